@@ -1,0 +1,187 @@
+// RegTop-k oracle: a plain, slow, single-threaded CPU statement of one
+// communication round of Regularized Top-k gradient sparsification for N
+// simulated workers plus the server-side aggregation.
+//
+// THIS IS TEST INFRASTRUCTURE. It is the parity reference for the HIP library
+// and the timed CPU baseline of the benchmark; nothing on the product path may
+// call it, and it shares no code, header, table or constant with the HIP path.
+//
+// What it follows (paper: "Regularized Top-k: A Bayesian Framework for
+// Gradient Sparsification"):
+//   * Algorithm 2 (RegTop-k sparsification at worker n): accumulate, posterior
+//     distortion, regularised Top_k mask, sparsified gradient, error update.
+//   * Algorithm 1 / the Top_k selector defined in the subsection "Top-k:
+//     Classical Sparsification Scheme": mask with exactly k ones on the k
+//     largest magnitudes.
+//   * The posterior-distortion equation (label eq:Delta_def) in "Characterizing
+//     the Likelihood".
+//   * The likelihood with tanh and the constant C = 1 (Section "RegTop-k
+//     Algorithm", display after the cumulative function u_mu, and its footnote).
+//   * The aggregation equation g^t = sum_n omega_n ghat_n^t right after
+//     Algorithm 1.
+//
+// Precision: every quantity is IEEE-754 binary32, round to nearest even, no
+// fused multiply-add, denormals kept (build with -ffp-contract=off and without
+// fast-math).  The one non-elementary step, tanh, is taken as the correctly
+// rounded binary32 value of the exact tanh of its binary32 argument; it is
+// realised here by evaluating tanhl in x87 extended precision (64-bit
+// significand) and rounding once to binary32.
+//
+// Readings where the paper leaves a choice (each is also listed in the design
+// document of the repository):
+//   R1  ties in Top_k: the lower index wins; always exactly k entries.
+//   R2  omega_n = 1/N for every worker, computed as 1.0f / (float)N.
+//   R3  entries not sent in the previous round get the factor 1 exactly
+//       (C = 1, i.e. the Q -> infinity limit); Q is never formed.
+//   R4  omega * a^t == 0 in the denominator of the distortion: factor 1
+//       (infinite distortion = no information).  A NaN argument: factor 1.
+//   R5  mu == 0 switches the regulariser off (plain Top-k, Algorithm 1).
+//   R6  round 0 has an empty previous mask, so it is plain Top-k.
+//   R7  operation order of the distortion: (gprev - w*aprev) / (w*a), then
+//       1 + D, abs, divide by mu, tanh, times |a|.
+//   R8  aggregation: start from +0 and add w * ghat_n[j] for n = 0..N-1 in
+//       ascending worker order.
+//   R9  the sent values are the un-weighted entries of a; the server applies w.
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <numeric>
+#include <vector>
+
+namespace {
+
+struct Oracle {
+    int32_t N;
+    int64_t d, k;
+    float mu;
+    float w;         // omega_n = 1/N  (R2)
+    int64_t t;       // rounds done so far
+    std::vector<float> e;        // [N*d] sparsification error eps_n
+    std::vector<float> a;        // [N*d] accumulated gradient of the last round
+    std::vector<float> a_prev;   // [N*d] accumulated gradient of the round before
+    std::vector<uint8_t> s_prev; // [N*d] previous mask s_n^{t-1}
+    std::vector<float> score;    // [N*d] selection score of the last round
+    std::vector<uint8_t> s;      // [N*d] mask of the last round
+    std::vector<float> ghat;     // [N*d] sparsified gradient of the last round
+};
+
+// tanh step: correctly rounded binary32 tanh (see header).
+float tanh32(float x) {
+    return (float)tanhl((long double)x);
+}
+
+// Likelihood factor for an entry that WAS sent in the previous round
+// (Algorithm 2, distortion line and the tanh in the mask line).  R4, R7.
+float likelihood_sent(float a_now, float a_before, float g_before, float w, float mu) {
+    float num = g_before - w * a_before;   // g^{t-1} - omega a^{t-1}
+    float den = w * a_now;                 // omega a^t
+    if (den == 0.0f) return 1.0f;
+    float D = num / den;                   // posterior distortion Delta
+    float r = std::fabs(1.0f + D);
+    float x = r / mu;
+    if (x != x) return 1.0f;
+    return tanh32(x);
+}
+
+// Top_k selector: mask with exactly k ones on the k largest scores, lower index
+// first among equal scores (R1).  Scores are non-negative and never NaN here.
+void topk_mask(const float* score, int64_t d, int64_t k, uint8_t* mask) {
+    std::vector<int64_t> order((size_t)d);
+    std::iota(order.begin(), order.end(), (int64_t)0);
+    auto before = [score](int64_t i, int64_t j) {
+        if (score[i] != score[j]) return score[i] > score[j];
+        return i < j;
+    };
+    if (k < d) std::nth_element(order.begin(), order.begin() + k, order.end(), before);
+    std::fill(mask, mask + d, (uint8_t)0);
+    for (int64_t i = 0; i < k; ++i) mask[order[(size_t)i]] = 1;
+}
+
+}  // namespace
+
+extern "C" {
+
+void* rtk_oracle_create(int32_t N, int64_t d, int64_t k, float mu) {
+    if (N < 1 || d < 1 || k < 1 || k > d || !(mu >= 0.0f)) return nullptr;
+    Oracle* o = new Oracle;
+    o->N = N; o->d = d; o->k = k; o->mu = mu;
+    o->w = 1.0f / (float)N;
+    o->t = 0;
+    size_t nd = (size_t)N * (size_t)d;
+    o->e.assign(nd, 0.0f);           // eps^0 = 0
+    o->a.assign(nd, 0.0f);
+    o->a_prev.assign(nd, 0.0f);
+    o->s_prev.assign(nd, 0);         // empty previous mask (R6)
+    o->score.assign(nd, 0.0f);
+    o->s.assign(nd, 0);
+    o->ghat.assign(nd, 0.0f);
+    return o;
+}
+
+void rtk_oracle_destroy(void* h) { delete (Oracle*)h; }
+
+// One round.  grads [N*d] row-major, gprev [d] (previous aggregate g^{t-1};
+// not read in round 0 and may then be NULL).  Outputs: idx [N*k] ascending per
+// worker, val [N*k] = a at those indices, agg [d].
+void rtk_oracle_step(void* h, const float* grads, const float* gprev,
+                     int32_t* idx, float* val, float* agg) {
+    Oracle* o = (Oracle*)h;
+    const int64_t d = o->d, k = o->k;
+    const float w = o->w, mu = o->mu;
+    for (int32_t n = 0; n < o->N; ++n) {
+        const size_t row = (size_t)n * (size_t)d;
+        float* e = &o->e[row];
+        float* a = &o->a[row];
+        float* ap = &o->a_prev[row];
+        uint8_t* sp = &o->s_prev[row];
+        float* sc = &o->score[row];
+        uint8_t* s = &o->s[row];
+        float* gh = &o->ghat[row];
+        const float* g = grads + row;
+        for (int64_t j = 0; j < d; ++j) {
+            a[j] = e[j] + g[j];                              // accumulate
+            float f = 1.0f;                                  // C = 1 (R3)
+            if (mu != 0.0f && sp[j])                         // R5, R6
+                f = likelihood_sent(a[j], ap[j], gprev[j], w, mu);
+            sc[j] = std::fabs(a[j]) * f;                     // |a . tanh(.)|
+        }
+        topk_mask(sc, d, k, s);                              // s^t = Top_k(.)
+        int64_t c = 0;
+        for (int64_t j = 0; j < d; ++j) {
+            gh[j] = (float)s[j] * a[j];                      // ghat = s . a
+            e[j] = a[j] - gh[j];                             // eps^{t+1} = a - ghat
+            if (s[j]) { idx[(size_t)n * k + c] = (int32_t)j; val[(size_t)n * k + c] = a[j]; ++c; }
+        }
+        std::memcpy(ap, a, sizeof(float) * (size_t)d);       // keep a^{t} for round t+1
+        std::memcpy(sp, s, (size_t)d);                       // keep s^{t}
+    }
+    for (int64_t j = 0; j < d; ++j) {                        // server: g = sum_n w ghat_n (R8)
+        float acc = 0.0f;
+        for (int32_t n = 0; n < o->N; ++n) acc = acc + w * o->ghat[(size_t)n * d + j];
+        agg[j] = acc;
+    }
+    o->t += 1;
+}
+
+// Read-only views for the tests (pointers stay valid until destroy).
+const float* rtk_oracle_e(void* h) { return ((Oracle*)h)->e.data(); }
+const float* rtk_oracle_a(void* h) { return ((Oracle*)h)->a.data(); }
+const float* rtk_oracle_score(void* h) { return ((Oracle*)h)->score.data(); }
+const uint8_t* rtk_oracle_mask(void* h) { return ((Oracle*)h)->s.data(); }
+int64_t rtk_oracle_round(void* h) { return ((Oracle*)h)->t; }
+
+// Single steps exposed so that the tests can pin them one by one.
+float rtk_oracle_tanh32(float x) { return tanh32(x); }
+float rtk_oracle_likelihood_sent(float a_now, float a_before, float g_before, float w, float mu) {
+    return likelihood_sent(a_now, a_before, g_before, w, mu);
+}
+void rtk_oracle_topk_mask(const float* score, int64_t d, int64_t k, uint8_t* mask) {
+    topk_mask(score, d, k, mask);
+}
+void rtk_oracle_tanh32_array(const float* x, float* y, int64_t n) {
+    for (int64_t i = 0; i < n; ++i) y[i] = tanh32(x[i]);
+}
+
+}  // extern "C"

@@ -1,0 +1,252 @@
+"""Pins for whole rounds of the CPU oracle (Algorithm 2 + aggregation):
+reduction to plain Top-k, conservation, the paper's toy example, k = d, and
+metamorphic relations.  The plain Top-k with error feedback used for comparison
+(Algorithm 1) is written here with numpy's sort, not with the oracle.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2501_05633_amd import workloads
+
+f32 = np.float32
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _topk_ef_numpy(grads_per_round, k):
+    """Algorithm 1 for every worker with a library sort; returns per-round index sets."""
+    N, d = grads_per_round[0].shape
+    e = np.zeros((N, d), dtype=np.float32)
+    out = []
+    for g in grads_per_round:
+        a = e + g
+        sets, agg = [], np.zeros(d, dtype=np.float64)
+        for n in range(N):
+            order = np.lexsort((np.arange(d), -np.abs(a[n]).astype(np.float64)))
+            sel = np.sort(order[:k])
+            sets.append(sel)
+            e[n] = a[n]
+            e[n, sel] = 0.0
+            agg[sel] += a[n, sel].astype(np.float64) / N
+        out.append((sets, a.copy(), agg))
+    return out
+
+
+def _tiny_rounds(T=6, N=4, d=2000, k=20, seed=None):
+    cfg = workloads.scaled(workloads.CONFIGS["tiny"], d=d, N=N, k=k)
+    wl = workloads.Workload(cfg, "cpu", seed=seed)
+    return [wl.grads(t).numpy() for t in range(T)]
+
+
+def _run(o, rounds):
+    res, agg = [], None
+    for g in rounds:
+        idx, val, agg = o.step(g, agg)
+        res.append((idx.copy(), val.copy(), agg.copy(), o.a, o.e, o.score, o.mask))
+    return res
+
+
+def test_round0_is_plain_topk():
+    # "The algorithm starts with applying standard Top-k in the initial round."
+    rounds = _tiny_rounds(T=1)
+    ref = _topk_ef_numpy(rounds, 20)
+    for mu in (0.1, 1.0, 10.0):
+        idx, val, agg = oracle.Oracle(4, 2000, 20, mu).step(rounds[0], None)
+        for n in range(4):
+            assert np.array_equal(idx[n], ref[0][0][n])
+        np.testing.assert_allclose(agg, ref[0][2], rtol=1e-6, atol=0)
+
+
+def test_mu_zero_is_algorithm1_for_all_rounds():
+    rounds = _tiny_rounds(T=6)
+    ref = _topk_ef_numpy(rounds, 20)
+    res = _run(oracle.Oracle(4, 2000, 20, 0.0), rounds)
+    for t in range(6):
+        for n in range(4):
+            assert np.array_equal(res[t][0][n], ref[t][0][n]), (t, n)
+        assert np.array_equal(res[t][3], ref[t][1])            # accumulated gradients
+        np.testing.assert_allclose(res[t][2], ref[t][2], rtol=2e-6, atol=1e-30)
+
+
+def test_tiny_positive_mu_equals_mu_zero_without_exact_cancellation():
+    rounds = _tiny_rounds(T=5)
+    r0 = _run(oracle.Oracle(4, 2000, 20, 0.0), rounds)
+    r1 = _run(oracle.Oracle(4, 2000, 20, 2.0 ** -100), rounds)
+    for t in range(5):
+        assert np.array_equal(r0[t][0], r1[t][0])
+        assert np.array_equal(r0[t][1], r1[t][1])
+
+
+def test_conservation_and_mask_shape():
+    # ghat = s . a and eps^{t+1} = a - ghat: a = ghat + eps exactly, eps in {0, a}.
+    rounds = _tiny_rounds(T=6)
+    o = oracle.Oracle(4, 2000, 20, 1.0)
+    agg = None
+    e_before = np.zeros((4, 2000), dtype=np.float32)
+    for g in rounds:
+        idx, val, agg = o.step(g, agg)
+        a, e, m = o.a, o.e, o.mask
+        assert np.array_equal(a, e_before + g)                 # one rounded add
+        assert np.all(m.sum(axis=1) == 20)
+        ghat = np.zeros_like(a)
+        for n in range(4):
+            assert np.all(np.diff(idx[n]) > 0)
+            assert np.array_equal(np.flatnonzero(m[n]), idx[n])
+            ghat[n, idx[n]] = val[n]
+            assert np.array_equal(val[n], a[n, idx[n]])
+        assert np.array_equal(ghat + e, a)
+        assert np.all((e == 0) | (e == a))
+        assert np.all(e[m == 1] == 0)
+        # aggregation: brute-force dense sum in the same worker order
+        acc = np.zeros(2000, dtype=np.float32)
+        for n in range(4):
+            acc = acc + f32(0.25) * ghat[n]
+        assert np.array_equal(acc, agg)
+        assert np.all(agg[m.sum(axis=0) == 0] == 0)
+        e_before = e
+
+
+def test_unsent_entries_keep_factor_one_and_scores_are_bounded():
+    rounds = _tiny_rounds(T=4)
+    o = oracle.Oracle(4, 2000, 20, 1.0)
+    agg, prev_mask = None, np.zeros((4, 2000), dtype=np.uint8)
+    changed = 0
+    for g in rounds:
+        idx, val, agg = o.step(g, agg)
+        a, sc = o.a, o.score
+        assert np.array_equal(sc[prev_mask == 0], np.abs(a)[prev_mask == 0])   # C = 1
+        assert np.all(sc >= 0) and np.all(sc <= np.abs(a))
+        changed += int((sc[prev_mask == 1] < np.abs(a)[prev_mask == 1]).sum())
+        # a previously sent entry restarts from zero error: a = g there
+        assert np.array_equal(a[prev_mask == 1], g[prev_mask == 1])
+        prev_mask = o.mask
+    assert changed > 0    # the regulariser did act
+
+
+def test_selection_invariant_on_regularised_rounds():
+    rounds = _tiny_rounds(T=5, d=5000, k=50)
+    o = oracle.Oracle(4, 5000, 50, 1.0)
+    agg = None
+    for g in rounds:
+        idx, val, agg = o.step(g, agg)
+        sc, m = o.score, o.mask
+        for n in range(4):
+            lo = sc[n][m[n] == 1].min()
+            hi = sc[n][m[n] == 0].max()
+            assert lo >= hi
+            if lo == hi:
+                tie_in = np.flatnonzero((sc[n] == lo) & (m[n] == 1))
+                tie_out = np.flatnonzero((sc[n] == lo) & (m[n] == 0))
+                assert tie_in.max() < tie_out.min()
+
+
+def test_k_equals_d_is_dense_averaging_for_any_mu():
+    # S = 1: Top-k, RegTop-k and the unsparsified run coincide.
+    rounds = _tiny_rounds(T=4, d=300, k=300)
+    ref = None
+    for mu in (0.0, 0.5, 4.0):
+        res = _run(oracle.Oracle(4, 300, 300, mu), rounds)
+        for t, g in enumerate(rounds):
+            assert np.all(res[t][4] == 0)                       # no residual
+            np.testing.assert_allclose(res[t][2], g.astype(np.float64).mean(axis=0), rtol=1e-6, atol=1e-7)
+        aggs = [r[2] for r in res]
+        if ref is not None:
+            for x, y in zip(ref, aggs):
+                assert np.array_equal(x, y)
+        ref = aggs
+
+
+def _read_gold(name):
+    out = {}
+    with open(os.path.join(GOLD, name)) as fh:
+        for line in fh:
+            line = line.split("#")[0].strip()
+            if "=" in line:
+                k, v = line.split("=")
+                out[k.strip()] = [float(x) for x in v.split()]
+    return out
+
+
+def _toy_grad(theta, xs):
+    z = np.exp(-(xs @ theta))
+    return (-(z / (1 + z))[:, None] * xs).astype(np.float32)
+
+
+def test_toy_example_first_two_rounds():
+    gold = _read_gold("toy_logistic.txt")
+    xs = np.array([gold["x1"], gold["x2"]])
+    theta = np.array(gold["theta0"])
+    c = gold["c"][0]
+    g = _toy_grad(theta, xs)
+    np.testing.assert_allclose(g, -c * xs, rtol=1e-6)
+    o = oracle.Oracle(2, 2, 1, 1.0)
+    idx, val, agg = o.step(g, None)
+    assert idx.ravel().tolist() == [0, 0]                       # both send the large entry
+    assert agg.tolist() == [0.0, 0.0]                           # which cancels exactly
+    np.testing.assert_allclose(o.e[:, 1], [-c, -c], rtol=1e-6)
+    # theta does not move (zero aggregate), so the gradient repeats
+    idx, val, agg = o.step(g, agg)
+    assert np.all(o.score[:, 0] == 0.0)                         # Delta = -1: damped to zero
+    assert idx.ravel().tolist() == [1, 1]
+    np.testing.assert_allclose(agg, [0.0, -2 * c], rtol=1e-6)
+
+
+def test_toy_example_closed_loop_stall():
+    gold = _read_gold("toy_logistic.txt")
+    xs = np.array([gold["x1"], gold["x2"]])
+    eta = gold["eta"][0]
+
+    def risk(theta):
+        return float(np.mean(np.log1p(np.exp(-(xs @ theta)))))
+
+    def run(mu, T):
+        theta = np.array(gold["theta0"])
+        o = oracle.Oracle(2, 2, 1, mu)
+        agg, first_move = None, None
+        for t in range(T):
+            idx, val, agg = o.step(_toy_grad(theta, xs), agg)
+            if first_move is None and np.any(agg != 0):
+                first_move = t
+            theta = theta - eta * agg.astype(np.float64)
+        return first_move, risk(theta)
+
+    stall = int(gold["stall_rounds_min"][0])
+    move_topk, risk_topk = run(0.0, stall)
+    assert move_topk is None
+    move_topk, _ = run(0.0, 110)
+    assert gold["stall_rounds_min"][0] <= move_topk <= gold["stall_rounds_max"][0]
+    move_reg, risk_reg = run(1.0, stall)
+    assert move_reg == 1
+    r0 = risk(np.array(gold["theta0"]))
+    assert abs(risk_topk - r0) < 1e-12          # no progress for about 100 iterations
+    assert risk_reg < 0.5 * r0
+
+
+def test_power_of_two_scaling_and_sign_flip_keep_the_masks():
+    rounds = _tiny_rounds(T=5)
+    base = _run(oracle.Oracle(4, 2000, 20, 1.0), rounds)
+    for factor in (2.0 ** 7, 2.0 ** -9, -1.0):
+        res = _run(oracle.Oracle(4, 2000, 20, 1.0), [g * f32(factor) for g in rounds])
+        for t in range(5):
+            assert np.array_equal(res[t][0], base[t][0])
+            assert np.array_equal(res[t][1], base[t][1] * f32(factor))
+            assert np.array_equal(res[t][2], base[t][2] * f32(factor))
+
+
+def test_worker_permutation_permutes_rows():
+    # N a power of two: w is exact, so the aggregate does not depend on the order
+    rounds = _tiny_rounds(T=1)
+    perm = [2, 0, 3, 1]
+    a = oracle.Oracle(4, 2000, 20, 1.0).step(rounds[0], None)
+    b = oracle.Oracle(4, 2000, 20, 1.0).step(rounds[0][perm], None)
+    assert np.array_equal(a[0][perm], b[0]) and np.array_equal(a[1][perm], b[1])
+
+
+def test_argument_checks():
+    for bad in ((0, 10, 1, 1.0), (2, 0, 1, 1.0), (2, 10, 0, 1.0), (2, 10, 11, 1.0), (2, 10, 1, -1.0),
+                (2, 10, 1, float("nan"))):
+        with pytest.raises(ValueError):
+            oracle.Oracle(*bad)
