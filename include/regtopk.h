@@ -1,0 +1,148 @@
+/*
+ * regtopk.h -- C ABI of the RegTop-k per-round hot path for AMD MI355X (gfx950).
+ *
+ * One context simulates N workers of a parameter-server round on one GPU.
+ * A call of regtopk_step() runs, for every worker n (rows of a [N,d] batch):
+ *
+ *   1. error-feedback accumulation  a_n = eps_n + g_n
+ *        (paper: Algorithm 1 line 3 / Algorithm 2, "accumulated gradient");
+ *   2. the posterior-regularised selection score
+ *        score_j = |a_j| * tanh(|1 + Delta_j| / mu)   for j sent in the previous round,
+ *        score_j = |a_j|                              otherwise (constant C = 1),
+ *        Delta_j = (gprev_j - w a^{t-1}_j) / (w a^t_j),  w = 1/N
+ *        (paper: posterior-distortion equation, label eq:Delta_def; likelihood
+ *        with tanh in the section "RegTop-k Algorithm"; Algorithm 2 mask line);
+ *   3. exact Top_k of the score, exactly k entries, the lower index winning
+ *        among equal scores (paper: Top_k selector of the subsection "Top-k:
+ *        Classical Sparsification Scheme");
+ *   4. compaction of the k (index, value) pairs, value = a_j, and the error
+ *        update eps_n <- a_n - s_n (.) a_n (paper: last three lines of
+ *        Algorithm 2);
+ *   5. the server's aggregation g = sum_n w * ghat_n into a dense vector
+ *        (paper: aggregation equation after Algorithm 1).
+ *
+ * Round 0 has no previous mask and is plain Top-k (first block of Algorithm 2).
+ * mu == 0 switches the regulariser off in every round (Algorithm 1).
+ *
+ * Arithmetic is IEEE binary32 without fused multiply-add, in this order:
+ *   a = eps + g;  num = gprev - w*aprev;  den = w*a;  if den == 0: f = 1, else
+ *   D = num/den;  r = |1 + D|;  x = r/mu;  f = tanh(x) correctly rounded to
+ *   binary32 (f = 1 when x is NaN);  score = |a| * f;
+ *   agg_j = (((+0 + w*v_n1) + w*v_n2) + ...) over the workers n1 < n2 < ...
+ *   that selected j.
+ *
+ * All pointers named *_dev are device memory of the GPU that was current when
+ * the context was created; the library never dereferences them on the host.
+ * Every call returns 0 on success or a negative REGTOPK_* code; nothing throws
+ * or aborts across this boundary.  regtopk_last_error() describes the last
+ * failure of the calling thread.
+ *
+ * A context may be driven from one thread / one stream at a time.
+ */
+#ifndef REGTOPK_H
+#define REGTOPK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define REGTOPK_OK            0
+#define REGTOPK_INVALID_ARG  -1   /* bad size, null pointer, misaligned pointer, mu < 0 or NaN */
+#define REGTOPK_BAD_STATE    -2   /* e.g. set_state with indices that are not ascending */
+#define REGTOPK_HIP_ERROR    -3   /* a HIP call or kernel launch failed */
+#define REGTOPK_NO_MEMORY    -4   /* arena too small / allocation failed */
+
+typedef struct regtopk_ctx regtopk_ctx;
+
+/* Result of one round.  Device pointers into the context's arena; they stay
+ * valid (and unchanged) until the next regtopk_step/reset/set_state/destroy on
+ * the same context.  Contents are defined once the stream has been
+ * synchronised. */
+typedef struct {
+  const int32_t* idx;  /* [N,k] selected indices of each worker, ascending          */
+  const float*   val;  /* [N,k] val[n,i] = a_n[idx[n,i]] (un-weighted, as sent)     */
+  const float*   agg;  /* [d]   aggregate g^t; +0 where no worker selected an entry */
+} regtopk_result;
+
+/* Per-worker diagnostics of the last round (host memory). */
+typedef struct {
+  uint32_t tau_lo_bits;   /* speculative lower bound on the k-th score used in pass 1 (bit pattern; 0xFFFFFFFF = none) */
+  uint32_t n_candidates;  /* entries handed to the exact selection                   */
+  uint32_t used_dense;    /* 1 if the dense (non-speculative) selection had to run   */
+  uint32_t tau_bits;      /* bit pattern of the k-th largest score                   */
+  uint32_t n_greater;     /* entries with score > tau                                */
+  uint32_t n_ties_taken;  /* entries with score == tau that were selected            */
+  uint32_t n_ties_total;  /* candidates with score == tau                            */
+  uint32_t overflow;      /* 1 if the speculative candidate buffer overflowed        */
+} regtopk_worker_stats;
+
+/* Bytes of device memory a context needs for (N, d, k).  0 on invalid sizes. */
+size_t regtopk_workspace_bytes(int32_t N, int64_t d, int64_t k);
+
+/* Creates a context: eps = 0, round counter 0, empty previous mask
+ * (initialisation line of Algorithm 2).
+ *   N >= 1 workers, 1 <= d < 2^31 entries per worker, 1 <= k <= d, mu >= 0.
+ * regtopk_create allocates its arena with hipMalloc on the current device and
+ * frees it in regtopk_destroy.  regtopk_create_in uses caller-owned device
+ * memory instead: arena_dev must be 256-byte aligned, at least
+ * regtopk_workspace_bytes(N,d,k) long, and must outlive the context; its
+ * contents are overwritten.  Both zero the state (create_in on `stream`, a
+ * hipStream_t, NULL = default stream) and wait for that to finish. */
+int regtopk_create(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu);
+int regtopk_create_in(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu,
+                      void* arena_dev, size_t arena_bytes, void* stream);
+
+/* One round (steps 1-5 above) enqueued on `stream`; no host synchronisation.
+ *   grads_dev          [N,d] row-major binary32 local gradients g_n^t; read only;
+ *                      finite values (otherwise the selection is undefined).
+ *   prev_aggregate_dev [d] aggregate of the previous round, g^{t-1} (normally
+ *                      the `agg` pointer of the previous result); read only;
+ *                      ignored (may be NULL) in round 0 and when mu == 0.
+ * Rows are read with 128-bit loads when d is a multiple of 4 and grads_dev is
+ * 16-byte aligned, otherwise with scalar loads. */
+int regtopk_step(regtopk_ctx* ctx, const float* grads_dev, const float* prev_aggregate_dev,
+                 void* stream, regtopk_result* out);
+
+int regtopk_destroy(regtopk_ctx* ctx);
+
+/* Back to the state after create (eps = 0, round 0, no previous mask). */
+int regtopk_reset(regtopk_ctx* ctx, void* stream);
+
+/* Copies the persistent state out / in (device buffers of the caller):
+ *   e_dev [N,d] error eps, pidx_dev [N,k] / pval_dev [N,k] previous round's
+ *   selected indices (ascending) and values, *t_host the round counter.
+ * Before round 1 the previous lists are empty and pidx/pval are not written /
+ * read.  Any of the output pointers of get_state may be NULL to skip it.
+ * set_state enqueues a check that every row of pidx is strictly ascending and
+ * within [0,d); a violation is reported by the next regtopk_get_stats /
+ * regtopk_check (REGTOPK_BAD_STATE) and the following rounds are undefined. */
+int regtopk_get_state(regtopk_ctx* ctx, float* e_dev, int32_t* pidx_dev, float* pval_dev,
+                      int64_t* t_host, void* stream);
+int regtopk_set_state(regtopk_ctx* ctx, const float* e_dev, const int32_t* pidx_dev,
+                      const float* pval_dev, int64_t t, void* stream);
+
+/* Synchronises `stream` and copies the per-worker diagnostics of the last
+ * round into stats_host[0..N).  Returns REGTOPK_BAD_STATE if a device-side
+ * consistency check failed (selected count != k, bad set_state input). */
+int regtopk_get_stats(regtopk_ctx* ctx, regtopk_worker_stats* stats_host, void* stream);
+
+/* Options (tuning and test hooks). */
+#define REGTOPK_OPT_FORCE_DENSE   1  /* value != 0: never speculate, always run the dense selection */
+#define REGTOPK_OPT_CAND_TARGET   2  /* speculative pass aims at value*k candidates (1 < value <= 3; default 1.5) */
+int regtopk_set_option(regtopk_ctx* ctx, int option, double value);
+
+/* The tanh step alone: y[i] = tanh(x[i]) correctly rounded to binary32 for
+ * x[i] >= 0 (device buffers of n floats).  Test hook for the exhaustive
+ * comparison of that step. */
+int regtopk_tanh_f32(const float* x_dev, float* y_dev, int64_t n, void* stream);
+
+/* Text of the last error on the calling thread ("" if none). */
+const char* regtopk_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REGTOPK_H */

@@ -1,0 +1,368 @@
+// C ABI of the RegTop-k round (see include/regtopk.h): context, arena layout
+// and the kernel sequence of one round.  Host code only enqueues; the only
+// host synchronisation is in regtopk_get_stats.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/regtopk.h"
+#include "kernels.h"
+
+using namespace rtk;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                   \
+  do {                                                                                  \
+    hipError_t e_ = (expr);                                                             \
+    if (e_ != hipSuccess)                                                               \
+      return fail(REGTOPK_HIP_ERROR, "%s failed: %s", #expr, hipGetErrorString(e_));    \
+  } while (0)
+
+constexpr size_t kAlign = 256;
+size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Layout {
+  uint32_t nc, regions, cap_r, cap_total;
+  size_t e, out_idx[2], out_val[2], agg[2], cand_idx, cand_val, cand_key;
+  size_t ch_off, ch_cnt, ch_gt, ch_tie, tie_off, sel_off[2], chist, fhist, ctl, total;
+};
+
+bool valid_sizes(int32_t N, int64_t d, int64_t k) {
+  return N >= 1 && N <= 65535 && d >= 1 && d < ((int64_t)1 << 31) && k >= 1 && k <= d;
+}
+
+Layout make_layout(int32_t N, int64_t d, int64_t k) {
+  Layout L{};
+  L.nc = (uint32_t)((d + kChunk - 1) / kChunk);
+  uint32_t R = L.nc / 64;
+  if (R < 1) R = 1;
+  if (R > 32) R = 32;
+  L.regions = R;
+  // Room for 4k candidates in total (the dense selection needs min(2k,d)),
+  // with a quarter of slack per region for uneven chunk populations.
+  uint64_t want = (uint64_t)4 * (uint64_t)k;
+  if (want < 1024) want = 1024;
+  uint64_t per = (want + R - 1) / R;
+  if (R > 1) per += per / 4;
+  per = (per + 63) / 64 * 64;
+  L.cap_r = (uint32_t)per;
+  L.cap_total = (uint32_t)(per * R);
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += up(bytes); return at; };
+  const size_t nd = (size_t)N * (size_t)d, nk = (size_t)N * (size_t)k;
+  const size_t ncand = (size_t)N * L.cap_total, nch = (size_t)N * L.nc;
+  L.e = take(nd * 4);
+  for (int b = 0; b < 2; ++b) { L.out_idx[b] = take(nk * 4); L.out_val[b] = take(nk * 4); L.agg[b] = take((size_t)d * 4); }
+  L.cand_idx = take(ncand * 4);
+  L.cand_val = take(ncand * 4);
+  L.cand_key = take(ncand * 4);
+  L.ch_off = take(nch * 4);
+  L.ch_cnt = take(nch * 4);
+  L.ch_gt = take(nch * 4);
+  L.ch_tie = take(nch * 4);
+  L.tie_off = take(nch * 4);
+  for (int b = 0; b < 2; ++b) L.sel_off[b] = take(((size_t)N * (L.nc + 1)) * 4);
+  L.chist = take((size_t)N * 3 * kL1Bins * 4);
+  L.fhist = take((size_t)N * 3 * kL1Bins * 4);
+  L.ctl = take((size_t)N * sizeof(WorkerCtl));
+  L.total = o;
+  return L;
+}
+
+}  // namespace
+
+struct regtopk_ctx {
+  int32_t N;
+  int64_t d, k;
+  float mu, w;
+  int64_t t;
+  bool have_prev;       // a previous mask exists (round >= 1 or set_state with t >= 1)
+  bool owns_arena;
+  int device;
+  int force_dense;
+  float cand_target;
+  char* arena;
+  Layout L;
+  template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(arena + off); }
+};
+
+namespace {
+
+int zero_state(regtopk_ctx* c, hipStream_t s) {
+  const size_t ne = (size_t)c->N * (size_t)c->d;
+  k_fill_u32<<<2048, 256, 0, s>>>(c->at<uint32_t>(c->L.e), ne, 0u);
+  for (int b = 0; b < 2; ++b)
+    k_fill_u32<<<256, 256, 0, s>>>(c->at<uint32_t>(c->L.sel_off[b]), (size_t)c->N * (c->L.nc + 1), 0u);
+  k_init_ctl<<<c->N, 256, 0, s>>>(c->at<WorkerCtl>(c->L.ctl));
+  HIP_TRY(hipGetLastError());
+  c->t = 0;
+  c->have_prev = false;
+  return REGTOPK_OK;
+}
+
+int create_common(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu, void* arena,
+                  size_t bytes, bool owns, hipStream_t s) {
+  regtopk_ctx* c = new (std::nothrow) regtopk_ctx;
+  if (!c) return fail(REGTOPK_NO_MEMORY, "out of host memory");
+  c->N = N; c->d = d; c->k = k; c->mu = mu;
+  c->w = 1.0f / (float)N;
+  c->owns_arena = owns;
+  c->force_dense = 0;
+  c->cand_target = 1.5f;
+  c->arena = static_cast<char*>(arena);
+  c->L = make_layout(N, d, k);
+  (void)bytes;
+  if (hipGetDevice(&c->device) != hipSuccess) { delete c; return fail(REGTOPK_HIP_ERROR, "hipGetDevice failed"); }
+  int rc = zero_state(c, s);
+  if (rc == REGTOPK_OK && hipStreamSynchronize(s) != hipSuccess) rc = fail(REGTOPK_HIP_ERROR, "zeroing the state failed");
+  if (rc != REGTOPK_OK) { delete c; return rc; }
+  *out = c;
+  return REGTOPK_OK;
+}
+
+int check_create_args(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu) {
+  if (!out) return fail(REGTOPK_INVALID_ARG, "out is NULL");
+  if (!valid_sizes(N, d, k))
+    return fail(REGTOPK_INVALID_ARG, "need 1 <= N <= 65535, 1 <= d < 2^31, 1 <= k <= d (N=%d d=%lld k=%lld)", N,
+                (long long)d, (long long)k);
+  if (!(mu >= 0.0f) || std::isinf(mu)) return fail(REGTOPK_INVALID_ARG, "mu must be finite and >= 0");
+  return REGTOPK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* regtopk_last_error(void) { return g_err; }
+
+size_t regtopk_workspace_bytes(int32_t N, int64_t d, int64_t k) {
+  if (!valid_sizes(N, d, k)) return 0;
+  return make_layout(N, d, k).total;
+}
+
+int regtopk_create(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu) {
+  int rc = check_create_args(out, N, d, k, mu);
+  if (rc) return rc;
+  const size_t bytes = make_layout(N, d, k).total;
+  void* p = nullptr;
+  if (hipMalloc(&p, bytes) != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(REGTOPK_NO_MEMORY, "hipMalloc of %zu bytes failed", bytes);
+  }
+  rc = create_common(out, N, d, k, mu, p, bytes, true, nullptr);
+  if (rc) (void)hipFree(p);
+  return rc;
+}
+
+int regtopk_create_in(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu, void* arena_dev,
+                      size_t arena_bytes, void* stream) {
+  int rc = check_create_args(out, N, d, k, mu);
+  if (rc) return rc;
+  if (!arena_dev) return fail(REGTOPK_INVALID_ARG, "arena_dev is NULL");
+  if (reinterpret_cast<uintptr_t>(arena_dev) % kAlign) return fail(REGTOPK_INVALID_ARG, "arena_dev must be 256-byte aligned");
+  const size_t need = make_layout(N, d, k).total;
+  if (arena_bytes < need) return fail(REGTOPK_NO_MEMORY, "arena has %zu bytes, %zu needed", arena_bytes, need);
+  return create_common(out, N, d, k, mu, arena_dev, arena_bytes, false, static_cast<hipStream_t>(stream));
+}
+
+int regtopk_destroy(regtopk_ctx* c) {
+  if (!c) return fail(REGTOPK_INVALID_ARG, "ctx is NULL");
+  int rc = REGTOPK_OK;
+  if (c->owns_arena && hipFree(c->arena) != hipSuccess) rc = fail(REGTOPK_HIP_ERROR, "hipFree failed");
+  delete c;
+  return rc;
+}
+
+int regtopk_reset(regtopk_ctx* c, void* stream) {
+  if (!c) return fail(REGTOPK_INVALID_ARG, "ctx is NULL");
+  return zero_state(c, static_cast<hipStream_t>(stream));
+}
+
+int regtopk_set_option(regtopk_ctx* c, int option, double value) {
+  if (!c) return fail(REGTOPK_INVALID_ARG, "ctx is NULL");
+  switch (option) {
+    case REGTOPK_OPT_FORCE_DENSE: c->force_dense = value != 0.0; return REGTOPK_OK;
+    case REGTOPK_OPT_CAND_TARGET:
+      if (!(value > 1.0 && value <= 3.0)) return fail(REGTOPK_INVALID_ARG, "candidate target must be in (1, 3]");
+      c->cand_target = (float)value;
+      return REGTOPK_OK;
+    default: return fail(REGTOPK_INVALID_ARG, "unknown option %d", option);
+  }
+}
+
+int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* stream, regtopk_result* out) {
+  if (!c || !grads || !out) return fail(REGTOPK_INVALID_ARG, "ctx, grads_dev and out must not be NULL");
+  const int use_reg = (c->have_prev && c->mu > 0.0f) ? 1 : 0;
+  if (use_reg && !gprev) return fail(REGTOPK_INVALID_ARG, "prev_aggregate_dev is required after round 0 when mu > 0");
+  if (reinterpret_cast<uintptr_t>(grads) % 4 || reinterpret_cast<uintptr_t>(gprev) % 4)
+    return fail(REGTOPK_INVALID_ARG, "device pointers must be 4-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const Layout& L = c->L;
+  const int32_t N = c->N;
+  const int64_t d = c->d, k = c->k;
+  const uint32_t nc = L.nc;
+  const int cur = (int)(c->t & 1), prv = cur ^ 1;
+  const bool vec = (d % 4 == 0) && (reinterpret_cast<uintptr_t>(grads) % 16 == 0);
+
+  WorkerCtl* ctl = c->at<WorkerCtl>(L.ctl);
+  float* e = c->at<float>(L.e);
+  int32_t* cand_idx = c->at<int32_t>(L.cand_idx);
+  float* cand_val = c->at<float>(L.cand_val);
+  uint32_t* cand_key = c->at<uint32_t>(L.cand_key);
+  uint32_t* ch_off = c->at<uint32_t>(L.ch_off);
+  uint32_t* ch_cnt = c->at<uint32_t>(L.ch_cnt);
+  uint32_t* ch_gt = c->at<uint32_t>(L.ch_gt);
+  uint32_t* ch_tie = c->at<uint32_t>(L.ch_tie);
+  uint32_t* tie_off = c->at<uint32_t>(L.tie_off);
+  uint32_t* chist = c->at<uint32_t>(L.chist);
+  uint32_t* fhist = c->at<uint32_t>(L.fhist);
+  int32_t* out_idx = c->at<int32_t>(L.out_idx[cur]);
+  float* out_val = c->at<float>(L.out_val[cur]);
+  float* agg = c->at<float>(L.agg[cur]);
+  const int32_t* prev_idx = c->at<int32_t>(L.out_idx[prv]);
+  const float* prev_val = c->at<float>(L.out_val[prv]);
+  uint32_t* sel_off = c->at<uint32_t>(L.sel_off[cur]);
+  const uint32_t* prev_sel_off = c->at<uint32_t>(L.sel_off[prv]);
+
+  const dim3 g_chunks(nc, N), g_waves((nc + 3) / 4, N);
+  uint32_t cb = (L.cap_total + kBlock * 4 - 1) / (kBlock * 4);
+  if (cb > 512) cb = 512;
+  if (cb < 1) cb = 1;
+  const dim3 g_cand(cb, N);
+  uint32_t db = (uint32_t)((d + kBlock * 16 - 1) / (kBlock * 16));
+  if (db > 1024) db = 1024;
+  const dim3 g_dense(db, N);
+
+  k_begin<<<N, kBlock, 0, s>>>(ctl, chist, fhist, c->force_dense);
+  if (vec)
+    k_accum_emit<true><<<g_chunks, kBlock, 0, s>>>(e, grads, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
+  else
+    k_accum_emit<false><<<g_chunks, kBlock, 0, s>>>(e, grads, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
+  k_score<<<g_cand, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_key, prev_idx, prev_val, prev_sel_off, gprev, chist, d, k, nc, L.cap_r, L.cap_total, c->w, c->mu, use_reg, 0);
+  k_validate<<<N, kBlock, 0, s>>>(ctl, chist, k, L.regions, c->force_dense);
+
+  // dense selection; every kernel returns at once for workers that do not need it
+  k_dense_hist<1><<<g_dense, kBlock, 0, s>>>(e, d, ctl, fhist);
+  k_select_scan<true, 1><<<N, kBlock, 0, s>>>(ctl, fhist, k, d, c->cand_target);
+  k_dense_hist<2><<<g_dense, kBlock, 0, s>>>(e, d, ctl, fhist);
+  k_select_scan<true, 2><<<N, kBlock, 0, s>>>(ctl, fhist, k, d, c->cand_target);
+  k_dense_hist<3><<<g_dense, kBlock, 0, s>>>(e, d, ctl, fhist);
+  k_select_scan<true, 3><<<N, kBlock, 0, s>>>(ctl, fhist, k, d, c->cand_target);
+  k_dense_count<<<g_chunks, kBlock, 0, s>>>(e, d, ctl, ch_gt, ch_tie, nc);
+  k_chunk_scan<true><<<N, kScanBlock, 0, s>>>(ctl, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, nc, k);
+  if (vec)
+    k_dense_emit<true><<<g_chunks, kBlock, 0, s>>>(e, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, tie_off, nc, L.cap_total);
+  else
+    k_dense_emit<false><<<g_chunks, kBlock, 0, s>>>(e, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, tie_off, nc, L.cap_total);
+  k_score<<<g_cand, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_key, prev_idx, prev_val, prev_sel_off, gprev, chist, d, k, nc, L.cap_r, L.cap_total, c->w, c->mu, use_reg, 1);
+
+  // exact k-th largest score among the candidates
+  k_select_scan<false, 1><<<N, kBlock, 0, s>>>(ctl, chist, k, d, c->cand_target);
+  k_cand_hist<2><<<g_cand, kBlock, 0, s>>>(ctl, cand_key, chist, L.cap_r, L.cap_total);
+  k_select_scan<false, 2><<<N, kBlock, 0, s>>>(ctl, chist, k, d, c->cand_target);
+  k_cand_hist<3><<<g_cand, kBlock, 0, s>>>(ctl, cand_key, chist, L.cap_r, L.cap_total);
+  k_select_scan<false, 3><<<N, kBlock, 0, s>>>(ctl, chist, k, d, c->cand_target);
+
+  // ordered compaction, error update, aggregation
+  k_chunk_count<<<g_waves, kBlock, 0, s>>>(ctl, cand_key, ch_off, ch_cnt, ch_gt, ch_tie, nc, L.cap_total);
+  k_chunk_scan<false><<<N, kScanBlock, 0, s>>>(ctl, ch_gt, ch_tie, sel_off, nullptr, tie_off, nc, k);
+  k_compact<<<g_waves, kBlock, 0, s>>>(ctl, cand_key, cand_idx, cand_val, ch_off, ch_cnt, sel_off, tie_off, out_idx, out_val, e, d, k, nc, L.cap_total);
+  k_aggregate<<<nc, kBlock, 0, s>>>(out_idx, out_val, sel_off, agg, d, k, nc, N, c->w);
+  HIP_TRY(hipGetLastError());
+
+  c->t += 1;
+  c->have_prev = true;
+  out->idx = out_idx;
+  out->val = out_val;
+  out->agg = agg;
+  return REGTOPK_OK;
+}
+
+int regtopk_get_state(regtopk_ctx* c, float* e_dev, int32_t* pidx_dev, float* pval_dev, int64_t* t_host, void* stream) {
+  if (!c) return fail(REGTOPK_INVALID_ARG, "ctx is NULL");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t nd = (size_t)c->N * (size_t)c->d, nk = (size_t)c->N * (size_t)c->k;
+  if (e_dev) k_copy_u32<<<2048, 256, 0, s>>>(reinterpret_cast<uint32_t*>(e_dev), c->at<uint32_t>(c->L.e), nd);
+  if (c->have_prev) {
+    const int prv = (int)((c->t & 1) ^ 1);
+    if (pidx_dev) k_copy_u32<<<512, 256, 0, s>>>(reinterpret_cast<uint32_t*>(pidx_dev), c->at<uint32_t>(c->L.out_idx[prv]), nk);
+    if (pval_dev) k_copy_u32<<<512, 256, 0, s>>>(reinterpret_cast<uint32_t*>(pval_dev), c->at<uint32_t>(c->L.out_val[prv]), nk);
+  }
+  HIP_TRY(hipGetLastError());
+  if (t_host) *t_host = c->t;
+  return REGTOPK_OK;
+}
+
+int regtopk_set_state(regtopk_ctx* c, const float* e_dev, const int32_t* pidx_dev, const float* pval_dev, int64_t t, void* stream) {
+  if (!c || !e_dev) return fail(REGTOPK_INVALID_ARG, "ctx and e_dev must not be NULL");
+  if (t < 0) return fail(REGTOPK_INVALID_ARG, "t must be >= 0");
+  if (t > 0 && (!pidx_dev || !pval_dev)) return fail(REGTOPK_INVALID_ARG, "previous lists are required when t > 0");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t nd = (size_t)c->N * (size_t)c->d, nk = (size_t)c->N * (size_t)c->k;
+  k_copy_u32<<<2048, 256, 0, s>>>(c->at<uint32_t>(c->L.e), reinterpret_cast<const uint32_t*>(e_dev), nd);
+  k_init_ctl<<<c->N, 256, 0, s>>>(c->at<WorkerCtl>(c->L.ctl));     // no speculative bound: next round selects densely
+  c->t = t;
+  c->have_prev = t > 0;
+  if (t > 0) {
+    const int prv = (int)((t & 1) ^ 1);
+    int32_t* pi = c->at<int32_t>(c->L.out_idx[prv]);
+    k_copy_u32<<<512, 256, 0, s>>>(reinterpret_cast<uint32_t*>(pi), reinterpret_cast<const uint32_t*>(pidx_dev), nk);
+    k_copy_u32<<<512, 256, 0, s>>>(c->at<uint32_t>(c->L.out_val[prv]), reinterpret_cast<const uint32_t*>(pval_dev), nk);
+    const dim3 g((c->L.nc + 1 + 255) / 256, c->N);
+    k_rebuild_sel_off<<<g, 256, 0, s>>>(pi, c->at<uint32_t>(c->L.sel_off[prv]), c->at<WorkerCtl>(c->L.ctl), c->d, c->k, c->L.nc);
+    const dim3 g2(64, c->N);
+    k_check_ascending<<<g2, 256, 0, s>>>(pi, c->at<WorkerCtl>(c->L.ctl), c->d, c->k);
+  }
+  HIP_TRY(hipGetLastError());
+  return REGTOPK_OK;
+}
+
+int regtopk_get_stats(regtopk_ctx* c, regtopk_worker_stats* st, void* stream) {
+  if (!c || !st) return fail(REGTOPK_INVALID_ARG, "ctx and stats_host must not be NULL");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  std::vector<WorkerCtl> h((size_t)c->N);
+  HIP_TRY(hipMemcpyAsync(h.data(), c->at<WorkerCtl>(c->L.ctl), sizeof(WorkerCtl) * (size_t)c->N, hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  uint32_t err = 0;
+  for (int32_t n = 0; n < c->N; ++n) {
+    const WorkerCtl& w = h[(size_t)n];
+    st[n].tau_lo_bits = w.tau_lo;
+    st[n].n_candidates = w.need_dense ? w.dense_total : w.n_cand;
+    st[n].used_dense = w.need_dense;
+    st[n].tau_bits = w.tau;
+    st[n].n_greater = w.n_gt;
+    st[n].n_ties_taken = w.budget;
+    st[n].n_ties_total = w.ties_total;
+    st[n].overflow = w.overflow;
+    err |= w.err;
+  }
+  if (err) return fail(REGTOPK_BAD_STATE, "device-side check failed (flags 0x%x)", err);
+  return REGTOPK_OK;
+}
+
+int regtopk_tanh_f32(const float* x_dev, float* y_dev, int64_t n, void* stream) {
+  if (n < 0 || (n > 0 && (!x_dev || !y_dev))) return fail(REGTOPK_INVALID_ARG, "bad arguments");
+  if (n == 0) return REGTOPK_OK;
+  k_tanh<<<2048, 256, 0, static_cast<hipStream_t>(stream)>>>(x_dev, y_dev, n);
+  HIP_TRY(hipGetLastError());
+  return REGTOPK_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,146 @@
+// tanh of a non-negative binary32 argument, rounded correctly to binary32.
+//
+// The selection score needs tanh to be the same function on every machine, so
+// it is defined as the correctly rounded value and computed here from IEEE
+// binary64 +, -, *, /, fma only (no device math library):
+//
+//   tanh(x) = E / (E + 2),  E = expm1(2x),  2x = n ln2 + r,  |r| <= ln2/2,
+//   expm1(r) by its Taylor series (degree 14; the remainder is below 2^-60 of
+//   the sum), E = 2^n expm1(r) + (2^n - 1).
+//
+// The binary64 result carries a relative error below 2^-49; when rounding it
+// to binary32 could depend on that error (the value lies within 2^-47 of a
+// rounding boundary) the same evaluation is repeated in double-double
+// arithmetic (about 100 bits), which settles it.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace rtk {
+
+struct dd { double hi, lo; };
+
+__device__ __forceinline__ dd dd_two_sum(double a, double b) {
+  double s = a + b;
+  double bb = s - a;
+  double err = (a - (s - bb)) + (b - bb);
+  return {s, err};
+}
+__device__ __forceinline__ dd dd_quick_two_sum(double a, double b) {  // |a| >= |b|
+  double s = a + b;
+  return {s, b - (s - a)};
+}
+__device__ __forceinline__ dd dd_two_prod(double a, double b) {
+  double p = a * b;
+  return {p, __fma_rn(a, b, -p)};
+}
+__device__ __forceinline__ dd dd_add(dd a, dd b) {
+  dd s = dd_two_sum(a.hi, b.hi);
+  dd t = dd_two_sum(a.lo, b.lo);
+  s.lo += t.hi;
+  s = dd_quick_two_sum(s.hi, s.lo);
+  s.lo += t.lo;
+  return dd_quick_two_sum(s.hi, s.lo);
+}
+__device__ __forceinline__ dd dd_add_d(dd a, double b) {
+  dd s = dd_two_sum(a.hi, b);
+  s.lo += a.lo;
+  return dd_quick_two_sum(s.hi, s.lo);
+}
+__device__ __forceinline__ dd dd_mul(dd a, dd b) {
+  dd p = dd_two_prod(a.hi, b.hi);
+  p.lo += a.hi * b.lo + a.lo * b.hi;
+  return dd_quick_two_sum(p.hi, p.lo);
+}
+__device__ __forceinline__ dd dd_mul_d(dd a, double b) {
+  dd p = dd_two_prod(a.hi, b);
+  p.lo += a.lo * b;
+  return dd_quick_two_sum(p.hi, p.lo);
+}
+__device__ __forceinline__ dd dd_div(dd a, dd b) {
+  double q1 = a.hi / b.hi;
+  dd r = dd_add(a, dd_mul_d(b, -q1));
+  double q2 = r.hi / b.hi;
+  r = dd_add(r, dd_mul_d(b, -q2));
+  double q3 = r.hi / b.hi;
+  dd q = dd_quick_two_sum(q1, q2);
+  return dd_add_d(q, q3);
+}
+
+// ln 2 split into three binary64 pieces (each the rounding of what is left).
+#define RTK_LN2_A 0x1.62e42fefa39efp-1
+#define RTK_LN2_B 0x1.abc9e3b39803fp-56
+#define RTK_LN2_C 0x1.7b57a079a1934p-111
+#define RTK_LOG2E 0x1.71547652b82fep+0
+
+// Slow, ~100-bit evaluation (only reached for arguments whose tanh lies
+// extremely close to the midpoint of two binary32 numbers).
+__device__ __noinline__ float tanh_f32_dd(float xf) {
+  const double t = 2.0 * (double)xf;                       // exact
+  const double n = rint(t * RTK_LOG2E);
+  // r = t - n ln2 in double-double
+  dd r = dd_two_prod(-n, RTK_LN2_A);
+  r = dd_add_d(r, t);
+  r = dd_add(r, dd_two_prod(-n, RTK_LN2_B));
+  r = dd_add_d(r, -n * RTK_LN2_C);
+  // expm1(r / 256) by its Taylor series in nested form
+  //   expm1(s) = s (1 + s/2 (1 + s/3 (1 + ... (1 + s/12)))),
+  // then 8 doublings  expm1(2u) = 2 expm1(u) + expm1(u)^2.
+  dd s = {r.hi * 0.00390625, r.lo * 0.00390625};
+  dd h = {1.0, 0.0};
+  for (int kk = 12; kk >= 2; --kk) {
+    dd kd = {(double)kk, 0.0};
+    h = dd_add_d(dd_div(dd_mul(s, h), kd), 1.0);
+  }
+  dd q = dd_mul(s, h);
+  for (int i = 0; i < 8; ++i) {
+    dd q2 = dd_mul(q, q);
+    q = dd_add(dd_mul_d(q, 2.0), q2);
+  }
+  // E = 2^n q + (2^n - 1),  tanh = E / (E + 2)
+  const double sc = ldexp(1.0, (int)n);
+  dd E = dd_add_d(dd_mul_d(q, sc), sc - 1.0);
+  dd y = dd_div(E, dd_add_d(E, 2.0));
+  // one rounding of hi + lo to binary32 (the argument is positive here)
+  float f = (float)y.hi;
+  const double fl = (double)f;
+  const double diff = (y.hi - fl) + y.lo;
+  if (diff > 0.0) {
+    float up = __uint_as_float(__float_as_uint(f) + 1u);
+    if (diff > 0.5 * ((double)up - fl)) f = up;
+  } else if (diff < 0.0) {
+    float dn = __uint_as_float(__float_as_uint(f) - 1u);
+    if (-diff > 0.5 * (fl - (double)dn)) f = dn;
+  }
+  return f;
+}
+
+__device__ __forceinline__ float tanh_f32_cr(float xf) {
+  if (!(xf < 9.02f)) return 1.0f;          // tanh(x) >= 1 - 2^-25 from x = 9.011 on
+  const double t = 2.0 * (double)xf;       // exact
+  const double n = rint(t * RTK_LOG2E);
+  double r = __fma_rn(-n, RTK_LN2_A, t);
+  r = __fma_rn(-n, RTK_LN2_B, r);
+  double p = 1.0 / 87178291200.0;                       // 1/14!
+  p = __fma_rn(p, r, 1.0 / 6227020800.0);               // 1/13!
+  p = __fma_rn(p, r, 1.0 / 479001600.0);
+  p = __fma_rn(p, r, 1.0 / 39916800.0);
+  p = __fma_rn(p, r, 1.0 / 3628800.0);
+  p = __fma_rn(p, r, 1.0 / 362880.0);
+  p = __fma_rn(p, r, 1.0 / 40320.0);
+  p = __fma_rn(p, r, 1.0 / 5040.0);
+  p = __fma_rn(p, r, 1.0 / 720.0);
+  p = __fma_rn(p, r, 1.0 / 120.0);
+  p = __fma_rn(p, r, 1.0 / 24.0);
+  p = __fma_rn(p, r, 1.0 / 6.0);
+  p = __fma_rn(p, r, 0.5);
+  const double q = __fma_rn(r * r, p, r);               // expm1(r)
+  const double sc = ldexp(1.0, (int)n);
+  const double E = __fma_rn(sc, q, sc - 1.0);           // expm1(2x)
+  const double y = E / (E + 2.0);
+  const float lo = (float)(y * (1.0 - 0x1p-47));
+  const float hi = (float)(y * (1.0 + 0x1p-47));
+  if (lo == hi) return lo;
+  return tanh_f32_dd(xf);
+}
+
+}  // namespace rtk

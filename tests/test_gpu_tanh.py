@@ -1,0 +1,49 @@
+"""The tanh step of the HIP path against the oracle's, for EVERY binary32
+argument from 0 up to beyond the saturation point (about 1.09e9 values), plus
+arguments above it.  Both must be the correctly rounded binary32 tanh."""
+import concurrent.futures as cf
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2501_05633_amd import binding
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _oracle_parallel(x: np.ndarray, threads=16) -> np.ndarray:
+    parts = np.array_split(x, threads)
+    with cf.ThreadPoolExecutor(threads) as ex:      # ctypes releases the GIL
+        outs = list(ex.map(orc.tanh32_array, parts))
+    return np.concatenate(outs)
+
+
+def test_tanh_exhaustive_up_to_saturation():
+    hi = int(np.float32(9.03).view(np.uint32))
+    slab = 1 << 26
+    mismatches = 0
+    for lo in range(0, hi + 1, slab):
+        n = min(slab, hi + 1 - lo)
+        bits = torch.arange(lo, lo + n, dtype=torch.int64, device=DEV).to(torch.int32)
+        x = bits.view(torch.float32)
+        y = binding.tanh_f32(x).cpu().numpy()
+        want = _oracle_parallel(x.cpu().numpy())
+        bad = np.flatnonzero(y.view(np.uint32) != want.view(np.uint32))
+        if bad.size:
+            print("slab %#x: %d mismatches, first x=%r got=%r want=%r" % (
+                lo, bad.size, x[int(bad[0])].item(), y[bad[0]], want[bad[0]]), flush=True)
+        mismatches += bad.size
+        print("slab %#x done" % lo, flush=True)
+    assert mismatches == 0
+
+
+def test_tanh_above_saturation_and_specials():
+    x = torch.tensor([9.0109, 9.011, 9.02, 9.03, 10.0, 88.0, 1e10, 3.4e38, float("inf"), 0.0, 1e-45, 1e-38],
+                     dtype=torch.float32, device=DEV)
+    y = binding.tanh_f32(x).cpu().numpy()
+    want = orc.tanh32_array(x.cpu().numpy())
+    assert np.array_equal(y.view(np.uint32), want.view(np.uint32))
+    assert y[4] == 1.0 and y[8] == 1.0 and y[9] == 0.0
