@@ -132,7 +132,15 @@ int regtopk_get_stats(regtopk_ctx* ctx, regtopk_worker_stats* stats_host, void* 
 /* Options (tuning and test hooks). */
 #define REGTOPK_OPT_FORCE_DENSE   1  /* value != 0: never speculate, always run the dense selection */
 #define REGTOPK_OPT_CAND_TARGET   2  /* speculative pass aims at value*k candidates (1 < value <= 3; default 1.5) */
+#define REGTOPK_OPT_PROFILE       3  /* value != 0: record HIP events on the step's stream around the stages of every
+                                        step (resets the recorded rounds); 0 switches it off */
 int regtopk_set_option(regtopk_ctx* ctx, int option, double value);
+
+/* Stage times of the last n <= min(max_rounds, 64) profiled rounds, oldest
+ * first, in milliseconds: out_host[4*i + 0] the dense sweep (accumulate + emit),
+ * + 1 scoring and selection, + 2 compaction, error update and aggregation,
+ * + 3 the whole round.  Waits for the recorded events. */
+int regtopk_get_timings(regtopk_ctx* ctx, float* out_host, int32_t max_rounds, int32_t* n_rounds);
 
 /* The tanh step alone: y[i] = tanh(x[i]) correctly rounded to binary32 for
  * x[i] >= 0 (device buffers of n floats).  Test hook for the exhaustive

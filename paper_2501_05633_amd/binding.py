@@ -15,13 +15,14 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libregtopk.so")
 
 OK, INVALID_ARG, BAD_STATE, HIP_ERROR, NO_MEMORY = 0, -1, -2, -3, -4
-OPT_FORCE_DENSE, OPT_CAND_TARGET = 1, 2
+OPT_FORCE_DENSE, OPT_CAND_TARGET, OPT_PROFILE = 1, 2, 3
 
 # every symbol include/regtopk.h declares
 SYMBOLS = [
     "regtopk_workspace_bytes", "regtopk_create", "regtopk_create_in", "regtopk_step",
     "regtopk_destroy", "regtopk_reset", "regtopk_get_state", "regtopk_set_state",
-    "regtopk_get_stats", "regtopk_set_option", "regtopk_tanh_f32", "regtopk_last_error",
+    "regtopk_get_stats", "regtopk_set_option", "regtopk_get_timings", "regtopk_tanh_f32",
+    "regtopk_last_error",
 ]
 
 
@@ -66,6 +67,7 @@ def load():
     lib.regtopk_set_state.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int64, c_void_p]
     lib.regtopk_get_stats.argtypes = [c_void_p, ctypes.POINTER(WorkerStats), c_void_p]
     lib.regtopk_set_option.argtypes = [c_void_p, c_int, c_double]
+    lib.regtopk_get_timings.argtypes = [c_void_p, ctypes.POINTER(c_float), c_int32, ctypes.POINTER(c_int32)]
     lib.regtopk_tanh_f32.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
     lib.regtopk_last_error.restype = c_char_p
     _lib = lib
@@ -205,6 +207,13 @@ class RegTopk:
         with torch.cuda.device(self.device):
             _check(self.lib.regtopk_set_state(self._h, c_void_p(e.data_ptr()), pi, pv, int(t), _stream_ptr(torch)))
             torch.cuda.current_stream().synchronize()   # inputs may be temporaries of the caller
+
+    def timings(self, max_rounds: int = 64):
+        """Per-round stage times in ms: rows of (sweep, select, compact+aggregate, total)."""
+        buf = (c_float * (4 * max_rounds))()
+        n = c_int32(0)
+        _check(self.lib.regtopk_get_timings(self._h, buf, max_rounds, ctypes.byref(n)))
+        return [tuple(buf[4 * i + j] for j in range(4)) for i in range(n.value)]
 
     def stats(self):
         arr = (WorkerStats * self.N)()

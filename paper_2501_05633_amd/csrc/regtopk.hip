@@ -88,6 +88,8 @@ Layout make_layout(int32_t N, int64_t d, int64_t k) {
 
 }  // namespace
 
+constexpr int kProfRounds = 64;
+
 struct regtopk_ctx {
   int32_t N;
   int64_t d, k;
@@ -98,6 +100,9 @@ struct regtopk_ctx {
   int device;
   int force_dense;
   float cand_target;
+  bool profile;                 // record stage events in every step
+  hipEvent_t ev[kProfRounds][4];
+  int64_t prof_rounds;          // steps recorded since profiling was switched on
   char* arena;
   Layout L;
   template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(arena + off); }
@@ -126,6 +131,8 @@ int create_common(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu, 
   c->owns_arena = owns;
   c->force_dense = 0;
   c->cand_target = 1.5f;
+  c->profile = false;
+  c->prof_rounds = 0;
   c->arena = static_cast<char*>(arena);
   c->L = make_layout(N, d, k);
   (void)bytes;
@@ -185,6 +192,8 @@ int regtopk_create_in(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float 
 int regtopk_destroy(regtopk_ctx* c) {
   if (!c) return fail(REGTOPK_INVALID_ARG, "ctx is NULL");
   int rc = REGTOPK_OK;
+  if (c->profile)
+    for (auto& row : c->ev) for (auto& e : row) (void)hipEventDestroy(e);
   if (c->owns_arena && hipFree(c->arena) != hipSuccess) rc = fail(REGTOPK_HIP_ERROR, "hipFree failed");
   delete c;
   return rc;
@@ -202,6 +211,17 @@ int regtopk_set_option(regtopk_ctx* c, int option, double value) {
     case REGTOPK_OPT_CAND_TARGET:
       if (!(value > 1.0 && value <= 3.0)) return fail(REGTOPK_INVALID_ARG, "candidate target must be in (1, 3]");
       c->cand_target = (float)value;
+      return REGTOPK_OK;
+    case REGTOPK_OPT_PROFILE:
+      if (value != 0.0 && !c->profile) {
+        for (auto& row : c->ev) for (auto& e : row) HIP_TRY(hipEventCreate(&e));
+        c->profile = true;
+      }
+      if (value == 0.0 && c->profile) {
+        for (auto& row : c->ev) for (auto& e : row) (void)hipEventDestroy(e);
+        c->profile = false;
+      }
+      c->prof_rounds = 0;
       return REGTOPK_OK;
     default: return fail(REGTOPK_INVALID_ARG, "unknown option %d", option);
   }
@@ -250,11 +270,14 @@ int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* s
   if (db > 1024) db = 1024;
   const dim3 g_dense(db, N);
 
+  hipEvent_t* ev = c->profile ? c->ev[c->prof_rounds % kProfRounds] : nullptr;
+  if (ev) HIP_TRY(hipEventRecord(ev[0], s));
   k_begin<<<N, kBlock, 0, s>>>(ctl, chist, fhist, c->force_dense);
   if (vec)
     k_accum_emit<true><<<g_chunks, kBlock, 0, s>>>(e, grads, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   else
     k_accum_emit<false><<<g_chunks, kBlock, 0, s>>>(e, grads, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
+  if (ev) HIP_TRY(hipEventRecord(ev[1], s));
   k_score<<<g_cand, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_key, prev_idx, prev_val, prev_sel_off, gprev, chist, d, k, nc, L.cap_r, L.cap_total, c->w, c->mu, use_reg, 0);
   k_validate<<<N, kBlock, 0, s>>>(ctl, chist, k, L.regions, c->force_dense);
 
@@ -281,10 +304,12 @@ int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* s
   k_select_scan<false, 3><<<N, kBlock, 0, s>>>(ctl, chist, k, d, c->cand_target);
 
   // ordered compaction, error update, aggregation
+  if (ev) HIP_TRY(hipEventRecord(ev[2], s));
   k_chunk_count<<<g_waves, kBlock, 0, s>>>(ctl, cand_key, ch_off, ch_cnt, ch_gt, ch_tie, nc, L.cap_total);
   k_chunk_scan<false><<<N, kScanBlock, 0, s>>>(ctl, ch_gt, ch_tie, sel_off, nullptr, tie_off, nc, k);
   k_compact<<<g_waves, kBlock, 0, s>>>(ctl, cand_key, cand_idx, cand_val, ch_off, ch_cnt, sel_off, tie_off, out_idx, out_val, e, d, k, nc, L.cap_total);
   k_aggregate<<<nc, kBlock, 0, s>>>(out_idx, out_val, sel_off, agg, d, k, nc, N, c->w);
+  if (ev) { HIP_TRY(hipEventRecord(ev[3], s)); c->prof_rounds += 1; }
   HIP_TRY(hipGetLastError());
 
   c->t += 1;
@@ -354,6 +379,24 @@ int regtopk_get_stats(regtopk_ctx* c, regtopk_worker_stats* st, void* stream) {
     err |= w.err;
   }
   if (err) return fail(REGTOPK_BAD_STATE, "device-side check failed (flags 0x%x)", err);
+  return REGTOPK_OK;
+}
+
+int regtopk_get_timings(regtopk_ctx* c, float* out, int32_t max_rounds, int32_t* n_rounds) {
+  if (!c || !out || !n_rounds || max_rounds < 0) return fail(REGTOPK_INVALID_ARG, "bad arguments");
+  if (!c->profile) return fail(REGTOPK_BAD_STATE, "profiling is off (REGTOPK_OPT_PROFILE)");
+  int64_t have = c->prof_rounds < kProfRounds ? c->prof_rounds : kProfRounds;
+  if (have > max_rounds) have = max_rounds;
+  for (int64_t i = 0; i < have; ++i) {
+    const int64_t r = c->prof_rounds - have + i;      // oldest first
+    hipEvent_t* ev = c->ev[r % kProfRounds];
+    HIP_TRY(hipEventSynchronize(ev[3]));
+    HIP_TRY(hipEventElapsedTime(&out[i * 4 + 0], ev[0], ev[1]));
+    HIP_TRY(hipEventElapsedTime(&out[i * 4 + 1], ev[1], ev[2]));
+    HIP_TRY(hipEventElapsedTime(&out[i * 4 + 2], ev[2], ev[3]));
+    HIP_TRY(hipEventElapsedTime(&out[i * 4 + 3], ev[0], ev[3]));
+  }
+  *n_rounds = (int32_t)have;
   return REGTOPK_OK;
 }
 
