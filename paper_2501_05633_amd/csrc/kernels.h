@@ -142,7 +142,10 @@ __device__ __forceinline__ ChunkPos ordered_positions(uint32_t flags, uint32_t* 
 }
 
 // ---------------------------------------------------------- k_accum_emit ----
-// grid (nc, N).  VEC: d % 4 == 0 and 16-byte aligned rows.
+// grid (nc, N).  VEC: d % 4 == 0 and 16-byte aligned rows.  The sweep touches
+// every byte exactly once, so it loads and stores with the non-temporal hint.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 template <bool VEC>
 __global__ void __launch_bounds__(kBlock)
 k_accum_emit(float* __restrict__ e, const float* __restrict__ g, int64_t d,
@@ -160,25 +163,25 @@ k_accum_emit(float* __restrict__ e, const float* __restrict__ g, int64_t d,
   float a[4][4];
   uint32_t flags = 0;
   if (VEC) {
-    float4 ev[4], gv[4];
+    f32x4 ev[4], gv[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int64_t j0 = base + i * 256;
       if (j0 < d) {
-        ev[i] = *reinterpret_cast<const float4*>(e + row + j0);
-        gv[i] = *reinterpret_cast<const float4*>(g + row + j0);
+        ev[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(e + row + j0));
+        gv[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(g + row + j0));
       } else {
-        ev[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        ev[i] = f32x4{0.f, 0.f, 0.f, 0.f};
         gv[i] = ev[i];
       }
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int64_t j0 = base + i * 256;
-      a[i][0] = ev[i].x + gv[i].x; a[i][1] = ev[i].y + gv[i].y;
-      a[i][2] = ev[i].z + gv[i].z; a[i][3] = ev[i].w + gv[i].w;
+      const f32x4 s4 = ev[i] + gv[i];
+      a[i][0] = s4.x; a[i][1] = s4.y; a[i][2] = s4.z; a[i][3] = s4.w;
       if (j0 < d) {
-        *reinterpret_cast<float4*>(e + row + j0) = make_float4(a[i][0], a[i][1], a[i][2], a[i][3]);
+        __builtin_nontemporal_store(s4, reinterpret_cast<f32x4*>(e + row + j0));
 #pragma unroll
         for (int q = 0; q < 4; ++q)
           if (key_of(a[i][q]) >= tau_lo) flags |= 1u << (i * 4 + q);
