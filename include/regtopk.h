@@ -77,6 +77,10 @@ typedef struct {
   uint32_t n_ties_taken;  /* entries with score == tau that were selected            */
   uint32_t n_ties_total;  /* candidates with score == tau                            */
   uint32_t overflow;      /* 1 if the speculative candidate buffer overflowed        */
+  uint32_t used_window;   /* 1 if the k-th score was found from the short boundary list */
+  uint32_t n_boundary;    /* candidates whose score fell into the window around the expected k-th score */
+  uint32_t n_valid;       /* candidates with score >= the speculative bound           */
+  uint32_t window_half;   /* half width of that window in binary32 bit patterns (0 = none) */
 } regtopk_worker_stats;
 
 /* Bytes of device memory a context needs for (N, d, k).  0 on invalid sizes. */
@@ -131,7 +135,7 @@ int regtopk_get_stats(regtopk_ctx* ctx, regtopk_worker_stats* stats_host, void* 
 
 /* Options (tuning and test hooks). */
 #define REGTOPK_OPT_FORCE_DENSE   1  /* value != 0: never speculate, always run the dense selection */
-#define REGTOPK_OPT_CAND_TARGET   2  /* speculative pass aims at value*k candidates (1 < value <= 3; default 1.5) */
+#define REGTOPK_OPT_CAND_TARGET   2  /* speculative pass aims at value*k candidates (1 < value <= 3; default 1.25) */
 #define REGTOPK_OPT_PROFILE       3  /* value != 0: record HIP events on the step's stream around the stages of every
                                         step (resets the recorded rounds); 0 switches it off */
 int regtopk_set_option(regtopk_ctx* ctx, int option, double value);

@@ -33,7 +33,8 @@ class Result(ctypes.Structure):
 class WorkerStats(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint32) for n in (
         "tau_lo_bits", "n_candidates", "used_dense", "tau_bits", "n_greater",
-        "n_ties_taken", "n_ties_total", "overflow")]
+        "n_ties_taken", "n_ties_total", "overflow", "used_window", "n_boundary", "n_valid",
+        "window_half")]
 
 
 class RegTopkError(RuntimeError):

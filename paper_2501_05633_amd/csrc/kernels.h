@@ -2,20 +2,25 @@
 //
 // Data flow of one round (all N workers batched; rows of length d):
 //
-//   k_begin         reset counters / histograms, load this round's speculative bound
+//   k_begin         reset counters, load this round's speculative bound and window
 //   k_accum_emit    a = eps + g written over eps (the one dense read/write sweep);
 //                   entries with |a| >= tau_lo are appended, in index order per
 //                   4096-entry chunk, to the worker's candidate list
 //   k_score         exact score of every candidate (regulariser for entries sent in
 //                   the previous round, found by binary search in that round's
-//                   index list) + level-1 histogram of the score bits
-//   k_validate      the speculation holds iff no overflow and >= k candidates have
-//                   score >= tau_lo; otherwise the worker is flagged for
-//   k_dense_*       the dense selection: exact radix select of the 2k largest |a|
-//                   (a superset of the true top-k, see below), count, scan and an
-//                   ordered emission of exactly those entries as the candidate list
-//   k_cand_hist     levels 2 and 3 of the radix select over the candidate scores
-//   k_select_scan   picks the histogram bin that holds the wanted rank
+//                   index list); scores inside a narrow window around the expected
+//                   k-th score are also copied to a short boundary list, those
+//                   above it are counted
+//   k_select        one block per worker: checks the speculation (no overflow and
+//                   >= k candidates scored >= tau_lo), then finds the k-th largest
+//                   score exactly - from the boundary list held in LDS when the
+//                   window contains it, otherwise by a three-level radix select
+//                   over all candidates - and derives next round's bound/window
+//   k_dense_*       for workers whose speculation failed (and in round 0): exact
+//                   radix select of the 2k largest |a| (a superset of the true
+//                   top-k, see below), count, scan and an ordered emission of
+//                   exactly those entries as the candidate list; then k_score and
+//                   k_select run again for those workers
 //   k_chunk_count / k_chunk_scan / k_compact
 //                   ordered compaction of the selected (index, value) pairs,
 //                   lowest-index ties first, and zeroing of eps on the mask
@@ -46,15 +51,24 @@ constexpr int kL1Shift = 19, kL1Bins = 4096;
 constexpr int kL2Shift = 8, kL2Bins = 2048;
 constexpr int kL3Bins = 256;
 
+// half width of the window around the predicted k-th score, in bit patterns
+constexpr uint32_t kWinMaxHalf = 1u << 22, kWinMinHalf = 1u << 10, kWinDefaultHalf = 1u << 16;
+
 struct WorkerCtl {
-  uint32_t tau_lo;        // speculative lower bound (bit pattern, multiple of 2^19) or kNoBound
+  uint32_t tau_lo;        // speculative lower bound on the k-th score (bit pattern) or kNoBound
   uint32_t next_tau_lo;   // bound for the next round
+  uint32_t win_lo;        // window [win_lo, win_hi) around the expected k-th score, or kNoBound
+  uint32_t win_hi;
+  uint32_t next_win_lo;
+  uint32_t next_win_hi;
   uint32_t overflow;      // a candidate region overflowed in k_accum_emit
   uint32_t need_dense;    // dense selection runs for this worker
   uint32_t n_cand;        // candidates handed to the exact selection
+  uint32_t n_valid;       // candidates with score >= tau_lo
+  uint32_t n_hi;          // candidates with score >= win_hi
+  uint32_t n_bnd;         // candidates with score inside the window (boundary list length)
   uint32_t dense_total;   // candidates written by the dense emission (compact from slot 0)
-  uint32_t c_prefix;      // radix-select state over candidate scores
-  uint32_t c_krem;
+  uint32_t used_window;   // 1 if the k-th score was found from the boundary list
   uint32_t tau;           // k-th largest score (bits)
   uint32_t n_gt;          // candidates with score > tau
   uint32_t budget;        // ties to take, lowest indices first
@@ -64,7 +78,11 @@ struct WorkerCtl {
   uint32_t f_tau;
   uint32_t f_budget;
   uint32_t err;           // bit 0: selected count != k, bit 1: bad set_state input
-  uint32_t pad[15];
+  uint32_t tau_prev;      // k-th score of the previous round or kNoBound
+  uint32_t centre;        // predicted k-th score of this round (window centre) or kNoBound
+  uint32_t err_prev;      // |prediction error| of the previous round
+  float margin_scale;     // widens the bound's safety margin after a failed speculation
+  uint32_t pad[5];
   uint32_t cursor[kMaxRegions];
 };
 
@@ -75,28 +93,64 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t ballot) {
 
 __device__ __forceinline__ uint32_t key_of(float a) { return __float_as_uint(a) & 0x7FFFFFFFu; }
 
-__device__ __forceinline__ bool slot_valid(const WorkerCtl& c, uint32_t p, uint32_t cap_r) {
-  if (c.need_dense) return p < c.dense_total;
-  const uint32_t r = p / cap_r;
-  const uint32_t cur = c.cursor[r] < cap_r ? c.cursor[r] : cap_r;
-  return (p - r * cap_r) < cur;
+// Number of valid candidate slots in region r of a worker's list.  The
+// speculative sweep fills every region from its own cursor; the dense emission
+// writes one compact run from slot 0 across the region boundaries.
+__device__ __forceinline__ uint32_t region_limit(const WorkerCtl& c, uint32_t r, uint32_t cap_r) {
+  if (c.need_dense) {
+    const uint32_t lo = r * cap_r;
+    if (c.dense_total <= lo) return 0;
+    const uint32_t left = c.dense_total - lo;
+    return left < cap_r ? left : cap_r;
+  }
+  const uint32_t cur = c.cursor[r];
+  return cur < cap_r ? cur : cap_r;
+}
+
+// Exclusive prefix sum over the 1024 threads of a block; *total gets the sum.
+constexpr int kScanBlock = 1024;
+
+__device__ __forceinline__ uint32_t block_excl_scan_1024(uint32_t v, uint32_t* s_w /*[16]*/,
+                                                         uint32_t* total) {
+  const uint32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  uint32_t x = v;
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t y = __shfl_up(x, o);
+    if (lane >= (uint32_t)o) x += y;
+  }
+  if (lane == 63) s_w[wv] = x;
+  __syncthreads();
+  uint32_t wb = 0, tot = 0;
+  for (uint32_t i = 0; i < 16; ++i) { const uint32_t t = s_w[i]; if (i < wv) wb += t; tot += t; }
+  __syncthreads();
+  *total = tot;
+  return wb + x - v;
 }
 
 // ---------------------------------------------------------------- k_begin ----
 __global__ void __launch_bounds__(kBlock)
-k_begin(WorkerCtl* ctl, uint32_t* chist, uint32_t* fhist, int force_dense) {
+k_begin(WorkerCtl* ctl, int force_dense) {
   const uint32_t n = blockIdx.x, tid = threadIdx.x;
-  uint32_t* ch = chist + (size_t)n * 3 * kL1Bins;
-  uint32_t* fh = fhist + (size_t)n * 3 * kL1Bins;
-  for (uint32_t i = tid; i < 3 * kL1Bins; i += kBlock) { ch[i] = 0; fh[i] = 0; }
   WorkerCtl& c = ctl[n];
   if (tid < kMaxRegions) c.cursor[tid] = 0;
   if (tid == 0) {
     c.tau_lo = force_dense ? kNoBound : c.next_tau_lo;
-    c.overflow = 0; c.need_dense = 0; c.n_cand = 0; c.dense_total = 0;
-    c.c_prefix = 0; c.c_krem = 0; c.tau = 0; c.n_gt = 0; c.budget = 0; c.ties_total = 0;
+    c.win_lo = force_dense ? kNoBound : c.next_win_lo;
+    c.win_hi = c.next_win_hi;
+    c.overflow = 0; c.need_dense = 0; c.n_cand = 0; c.n_valid = 0; c.n_hi = 0; c.n_bnd = 0;
+    c.dense_total = 0; c.used_window = 0;
+    c.tau = 0; c.n_gt = 0; c.budget = 0; c.ties_total = 0;
     c.f_prefix = 0; c.f_krem = 0; c.f_tau = 0; c.f_budget = 0;
   }
+}
+
+// grid (N): clears the histograms of the dense selection for flagged workers.
+__global__ void __launch_bounds__(kBlock)
+k_dense_begin(const WorkerCtl* __restrict__ ctl, uint32_t* fhist) {
+  const uint32_t n = blockIdx.x, tid = threadIdx.x;
+  if (!ctl[n].need_dense) return;
+  uint32_t* fh = fhist + (size_t)n * 3 * kL1Bins;
+  for (uint32_t i = tid; i < 3 * kL1Bins; i += kBlock) fh[i] = 0;
 }
 
 // ----------------------------------------------------- chunk in registers ----
@@ -250,28 +304,44 @@ __device__ __forceinline__ float likelihood_sent(float a_now, float a_before, fl
   return tanh_f32_cr(x);
 }
 
-// grid (blocks, N).  only_dense: second invocation, for the workers whose
-// candidate list was rebuilt by the dense selection.
+// grid (ceil(cap_r/1024), regions, N): a block covers 1024 consecutive slots of
+// one region, four per thread.  only_dense: second invocation, for the workers
+// whose candidate list was rebuilt by the dense selection (no window then).
+constexpr int kScoreSlots = 1024;
+
 __global__ void __launch_bounds__(kBlock)
-k_score(const WorkerCtl* __restrict__ ctl, const int32_t* __restrict__ cand_idx,
+k_score(WorkerCtl* __restrict__ ctl, const int32_t* __restrict__ cand_idx,
         const float* __restrict__ cand_val, uint32_t* __restrict__ cand_key,
-        const int32_t* __restrict__ prev_idx, const float* __restrict__ prev_val,
-        const uint32_t* __restrict__ prev_sel_off, const float* __restrict__ gprev,
-        uint32_t* __restrict__ chist, int64_t d, int64_t k, uint32_t nc, uint32_t cap_r,
-        uint32_t cap_total, float w, float mu, int use_reg, int only_dense) {
-  __shared__ uint32_t s_hist[kL1Bins];
-  const uint32_t n = blockIdx.y, tid = threadIdx.x;
-  const WorkerCtl& c = ctl[n];
+        uint32_t* __restrict__ bnd_key, const int32_t* __restrict__ prev_idx,
+        const float* __restrict__ prev_val, const uint32_t* __restrict__ prev_sel_off,
+        const float* __restrict__ gprev, int64_t d, int64_t k, uint32_t nc, uint32_t cap_r,
+        uint32_t cap_total, uint32_t bnd_cap, float w, float mu, int use_reg, int only_dense) {
+  __shared__ uint32_t s_stage[kScoreSlots];
+  __shared__ uint32_t s_cnt[3];       // boundary entries, valid, above window
+  __shared__ uint32_t s_base;
+  const uint32_t n = blockIdx.z, r = blockIdx.y, tid = threadIdx.x;
+  WorkerCtl& c = ctl[n];
   if (only_dense && !c.need_dense) return;
   if (!only_dense && c.overflow) return;      // list is incomplete; the dense selection rebuilds it
-  for (uint32_t i = tid; i < kL1Bins; i += kBlock) s_hist[i] = 0;
-  __syncthreads();
-  const size_t cbase = (size_t)n * cap_total;
+  const uint32_t lim = region_limit(c, r, cap_r);
+  const uint32_t p0 = blockIdx.x * kScoreSlots;
+  if (p0 >= lim) return;
+  const bool classify = !only_dense;
+  const uint32_t tau_lo = c.tau_lo, win_lo = c.win_lo, win_hi = c.win_hi;
+  const bool windowed = classify && win_lo != kNoBound;
+  if (classify) {
+    if (tid < 3) s_cnt[tid] = 0;
+    __syncthreads();
+  }
+  const size_t cbase = (size_t)n * cap_total + (size_t)r * cap_r;
   const int32_t* pi = prev_idx + (size_t)n * k;
   const float* pv = prev_val + (size_t)n * k;
   const uint32_t* so = prev_sel_off + (size_t)n * (nc + 1);
-  for (uint32_t p = blockIdx.x * kBlock + tid; p < cap_total; p += gridDim.x * kBlock) {
-    if (!slot_valid(c, p, cap_r)) continue;
+  uint32_t n_val = 0, n_hi = 0;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const uint32_t p = p0 + q * kBlock + tid;
+    if (p >= lim) continue;
     const int32_t j = cand_idx[cbase + p];
     if (j < 0 || (int64_t)j >= d) continue;
     const float a = cand_val[cbase + p];
@@ -279,56 +349,298 @@ k_score(const WorkerCtl* __restrict__ ctl, const int32_t* __restrict__ cand_idx,
     if (use_reg) {
       const uint32_t cj = (uint32_t)j >> kChunkLog;
       uint32_t lo = so[cj], hi = so[cj + 1];
+      const uint32_t end = hi;
       while (lo < hi) {                       // lower bound of j in the chunk's slice
         const uint32_t mid = (lo + hi) >> 1;
         if (pi[mid] < j) lo = mid + 1; else hi = mid;
       }
-      if (lo < so[cj + 1] && pi[lo] == j) f = likelihood_sent(a, pv[lo], gprev[j], w, mu);
+      if (lo < end && pi[lo] == j) f = likelihood_sent(a, pv[lo], gprev[j], w, mu);
     }
     const uint32_t key = __float_as_uint(__fmul_rn(fabsf(a), f));
     cand_key[cbase + p] = key;
-    atomicAdd(&s_hist[key >> kL1Shift], 1u);
+    if (classify) {
+      n_val += key >= tau_lo;
+      if (windowed) {
+        if (key >= win_hi) ++n_hi;
+        else if (key >= win_lo) s_stage[atomicAdd(&s_cnt[0], 1u)] = key;
+      }
+    }
+  }
+  if (!classify) return;
+  for (int o = 32; o > 0; o >>= 1) { n_val += __shfl_down(n_val, o); n_hi += __shfl_down(n_hi, o); }
+  if ((tid & 63) == 0) {
+    if (n_val) atomicAdd(&s_cnt[1], n_val);
+    if (n_hi) atomicAdd(&s_cnt[2], n_hi);
   }
   __syncthreads();
-  uint32_t* gh = chist + (size_t)n * 3 * kL1Bins;
-  for (uint32_t i = tid; i < kL1Bins; i += kBlock) {
-    const uint32_t v = s_hist[i];
-    if (v) atomicAdd(&gh[i], v);
+  const uint32_t nb = s_cnt[0];
+  if (tid == 0) {
+    if (s_cnt[1]) atomicAdd(&c.n_valid, s_cnt[1]);
+    if (s_cnt[2]) atomicAdd(&c.n_hi, s_cnt[2]);
+    uint32_t b = 0;
+    if (nb) b = atomicAdd(&c.n_bnd, nb);       // n_bnd > bnd_cap marks an overflow of the list
+    s_base = b;
+  }
+  __syncthreads();
+  if (nb == 0) return;
+  const uint32_t b = s_base;
+  if (b + nb > bnd_cap) return;
+  uint32_t* out = bnd_key + (size_t)n * bnd_cap + b;
+  for (uint32_t i = tid; i < nb; i += kBlock) out[i] = s_stage[i];
+}
+
+// -------------------------------------------------------------- k_select ----
+// One block of 1024 threads per worker.
+struct RankHit { uint32_t bin, above; };   // bin == kNoBound: rank not reached
+
+// Descending search in an LDS histogram: the bin b with
+//   count(bins > b) < want <= count(bins >= b);  above = count(bins > b).
+// nbins in {16, 512, 4096}.  All 1024 threads call it.
+__device__ __forceinline__ RankHit find_rank_desc(const uint32_t* hist, uint32_t nbins, uint32_t want,
+                                                  uint32_t* s_w, uint32_t* s_out) {
+  const uint32_t tid = threadIdx.x;
+  const uint32_t per = nbins >= (uint32_t)kScanBlock ? nbins / kScanBlock : 1u;
+  uint32_t loc[4];
+  uint32_t s = 0;
+#pragma unroll
+  for (uint32_t q = 0; q < 4; ++q) {
+    const uint32_t i = tid * per + q;
+    loc[q] = (q < per && i < nbins) ? hist[nbins - 1 - i] : 0u;
+    s += loc[q];
+  }
+  if (tid == 0) { s_out[0] = kNoBound; s_out[1] = 0; }
+  uint32_t total;
+  const uint32_t above = block_excl_scan_1024(s, s_w, &total);
+  if (above < want && want <= above + s) {
+    uint32_t run = above;
+#pragma unroll
+    for (uint32_t q = 0; q < 4; ++q) {
+      if (run < want && want <= run + loc[q]) { s_out[0] = nbins - 1 - (tid * per + q); s_out[1] = run; }
+      run += loc[q];
+    }
+  }
+  __syncthreads();
+  RankHit h{s_out[0], s_out[1]};
+  __syncthreads();
+  return h;
+}
+
+// Where the keys of a selection come from: the short boundary list (in LDS
+// when it fits, else in memory) or all candidate regions of the worker.
+struct KeySource {
+  const uint32_t* lds;      // non-null: count keys in LDS
+  const uint32_t* flat;     // non-null: count keys, contiguous in memory
+  const uint32_t* regions;  // else: candidate regions of cap_r slots each
+  uint32_t count, cap_r, n_regions;
+  const WorkerCtl* ctl;
+};
+
+// Calls f(key) for every key of the source; memory is read 128 bits at a time,
+// two loads in flight per thread.
+template <typename F>
+__device__ __forceinline__ void for_each_key(const KeySource& src, F f) {
+  const uint32_t tid = threadIdx.x;
+  if (src.lds) {
+    for (uint32_t i = tid; i < src.count; i += kScanBlock) f(src.lds[i]);
+    return;
+  }
+  const uint32_t nseg = src.flat ? 1u : src.n_regions;
+  for (uint32_t r = 0; r < nseg; ++r) {
+    const uint32_t lim = src.flat ? src.count : region_limit(*src.ctl, r, src.cap_r);
+    const uint32_t* base = src.flat ? src.flat : src.regions + (size_t)r * src.cap_r;
+    const uint4* b4 = reinterpret_cast<const uint4*>(base);
+    const uint32_t n4 = lim / 4;
+    uint32_t i = tid;
+    for (; i + kScanBlock < n4; i += 2 * kScanBlock) {
+      const uint4 x = b4[i], y = b4[i + kScanBlock];
+      f(x.x); f(x.y); f(x.z); f(x.w); f(y.x); f(y.y); f(y.z); f(y.w);
+    }
+    if (i < n4) { const uint4 x = b4[i]; f(x.x); f(x.y); f(x.z); f(x.w); }
+    if (tid < lim - n4 * 4) f(base[n4 * 4 + tid]);
   }
 }
 
-// ------------------------------------------------------------ k_validate ----
-// grid (N).  Decides whether the speculative candidate list is a superset of
-// the true top-k: no overflow and at least k candidates scored >= tau_lo.
-__global__ void __launch_bounds__(kBlock)
-k_validate(WorkerCtl* ctl, uint32_t* chist, int64_t k, uint32_t regions, int force_dense) {
-  __shared__ uint32_t s_red[kBlock];
-  __shared__ uint32_t s_need;
-  const uint32_t n = blockIdx.x, tid = threadIdx.x;
-  WorkerCtl& c = ctl[n];
-  uint32_t* h = chist + (size_t)n * 3 * kL1Bins;
-  const uint32_t tl = c.tau_lo;
-  const uint32_t first = (tl == kNoBound) ? kL1Bins : (tl >> kL1Shift);
-  uint32_t s = 0;
-  for (uint32_t i = tid; i < kL1Bins; i += kBlock)
-    if (i >= first) s += h[i];
-  s_red[tid] = s;
-  __syncthreads();
-  for (uint32_t o = kBlock / 2; o > 0; o >>= 1) {
-    if (tid < o) s_red[tid] += s_red[tid + o];
+// Exact `rank`-th largest key among the keys >= base of the source; at least
+// `rank` such keys must exist.  Three histogram levels over rel = key - base:
+// bits 24..13 (keys with rel >= 2^25 are counted apart; if the rank lies among
+// them the base moves up by 2^25 and the level is repeated), bits 12..4, bits
+// 3..0.  The fine first level spreads neighbouring scores over many bins, so
+// the LDS atomics rarely collide.  Returns tau; *budget = how many keys equal
+// to tau belong to the top `rank`; *ties = keys equal to tau.
+__device__ __forceinline__ uint32_t rel_select(const KeySource& src, uint32_t base, uint32_t rank,
+                                               uint32_t* s_hist, uint32_t* s_w, uint32_t* s_out,
+                                               uint32_t* budget, uint32_t* ties) {
+  const uint32_t tid = threadIdx.x;
+  uint32_t want = rank;
+  RankHit ha{0u, 0u};
+  for (int guard = 0; guard < 64; ++guard) {
+    for (uint32_t i = tid; i < kL1Bins; i += kScanBlock) s_hist[i] = 0;
+    __syncthreads();
+    uint32_t over = 0;
+    for_each_key(src, [&](uint32_t key) {
+      if (key < base) return;
+      const uint32_t rel = key - base;
+      if (rel >> 25) ++over;
+      else atomicAdd(&s_hist[rel >> 13], 1u);
+    });
+    uint32_t n_over;
+    (void)block_excl_scan_1024(over, s_w, &n_over);     // also orders the LDS atomics
+    if (want > n_over) {
+      want -= n_over;
+      ha = find_rank_desc(s_hist, kL1Bins, want, s_w, s_out);
+      break;
+    }
+    base += 1u << 25;                                   // the rank lies higher up
     __syncthreads();
   }
-  if (tid == 0) {
-    uint32_t tot = 0;
-    for (uint32_t r = 0; r < regions; ++r) tot += c.cursor[r];
-    const uint32_t need = (force_dense || c.overflow || (int64_t)s_red[0] < k) ? 1u : 0u;
-    c.n_cand = tot;
-    c.need_dense = need;
-    s_need = need;
+  want -= ha.above;
+  const uint32_t pa = ha.bin;
+  for (uint32_t i = tid; i < 512; i += kScanBlock) s_hist[i] = 0;
+  __syncthreads();
+  for_each_key(src, [&](uint32_t key) {
+    if (key < base) return;
+    const uint32_t rel = key - base;
+    if ((rel >> 13) == pa) atomicAdd(&s_hist[(rel >> 4) & 511u], 1u);
+  });
+  __syncthreads();
+  const RankHit hb = find_rank_desc(s_hist, 512, want, s_w, s_out);
+  want -= hb.above;
+  const uint32_t pb = (pa << 9) | hb.bin;
+  if (tid < 16) s_hist[tid] = 0;
+  __syncthreads();
+  for_each_key(src, [&](uint32_t key) {
+    if (key < base) return;
+    const uint32_t rel = key - base;
+    if ((rel >> 4) == pb) atomicAdd(&s_hist[rel & 15u], 1u);
+  });
+  __syncthreads();
+  const RankHit hc = find_rank_desc(s_hist, 16, want, s_w, s_out);
+  *budget = want - hc.above;
+  *ties = s_hist[hc.bin];
+  return base + ((pb << 4) | hc.bin);
+}
+
+constexpr uint32_t kLdsKeys = 11264;    // boundary keys held in LDS (longer lists are read from memory)
+
+// SECOND = false: first invocation, all workers (validates the speculation).
+// SECOND = true : after the dense selection, flagged workers only.
+template <bool SECOND>
+__global__ void __launch_bounds__(kScanBlock)
+k_select(WorkerCtl* ctl, const uint32_t* __restrict__ cand_key, const uint32_t* __restrict__ bnd_key,
+         int64_t k, uint32_t cap_r, uint32_t cap_total, uint32_t regions, uint32_t bnd_cap,
+         float cand_target, int force_dense) {
+  __shared__ uint32_t s_hist[kL1Bins];
+  __shared__ uint32_t s_keys[kLdsKeys];
+  __shared__ uint32_t s_w[16];
+  __shared__ uint32_t s_out[2];
+  const uint32_t n = blockIdx.x, tid = threadIdx.x;
+  WorkerCtl& c = ctl[n];
+  if (SECOND && !c.need_dense) return;
+  const uint32_t K = (uint32_t)k;
+  uint32_t n_tot = 0;
+  if (!SECOND) {
+    for (uint32_t r = 0; r < regions; ++r) n_tot += region_limit(c, r, cap_r);
+    const bool need = force_dense || c.overflow || c.tau_lo == kNoBound || c.n_valid < K;
+    if (tid == 0) { c.n_cand = n_tot; c.need_dense = need ? 1u : 0u; }
+    if (need) return;
+  } else {
+    n_tot = c.dense_total;
+    if (tid == 0) c.n_cand = n_tot;
+  }
+  const uint32_t win_lo = c.win_lo, win_hi = c.win_hi;
+  const uint32_t n_hi = c.n_hi, n_bnd = c.n_bnd;
+  const bool window = !SECOND && win_lo != kNoBound && n_bnd <= bnd_cap && n_hi < K && K <= n_hi + n_bnd;
+
+  KeySource src;
+  src.ctl = &c; src.cap_r = cap_r; src.n_regions = regions;
+  src.lds = nullptr; src.flat = nullptr; src.regions = cand_key + (size_t)n * cap_total; src.count = n_tot;
+  uint32_t base, rank;
+  if (window) {
+    // the k-th score lies inside the window: select among the boundary list only
+    const uint32_t* list = bnd_key + (size_t)n * bnd_cap;
+    src.count = n_bnd;
+    if (n_bnd <= kLdsKeys) {
+      for (uint32_t i = tid; i < n_bnd; i += kScanBlock) s_keys[i] = list[i];
+      src.lds = s_keys;
+    } else {
+      src.flat = list;
+    }
+    base = win_lo;
+    rank = K - n_hi;
+  } else {
+    // all candidates; only scores >= the bound can hold the k-th (at least k do)
+    // (dense list: the 2k-th largest |a| when the list has 2k entries; a shorter
+    // list is the whole row, whose scores may all be damped)
+    base = SECOND ? (c.dense_total >= 2 * K ? c.f_tau : 0u) : c.tau_lo;
+    rank = K;
   }
   __syncthreads();
-  if (s_need)
-    for (uint32_t i = tid; i < kL1Bins; i += kBlock) h[i] = 0;
+  uint32_t budget, ties;
+  const uint32_t tau = rel_select(src, base, rank, s_hist, s_w, s_out, &budget, &ties);
+
+  if (tid == 0) {
+    c.tau = tau;
+    c.budget = budget;
+    c.n_gt = K - budget;
+    c.ties_total = ties;
+    c.used_window = window ? 1u : 0u;
+    // ---- bound and window of the next round
+    // density of scores per bit pattern just below / around tau
+    double dens;
+    if (window) dens = (double)n_bnd / (double)(win_hi - win_lo);
+    else dens = tau > base ? (double)(n_tot - K + 1) / (double)(tau - base) : 1.0;
+    if (dens < 1e-7) dens = 1e-7;
+    // the k-th score drifts from round to round: extrapolate linearly
+    int64_t drift = 0;
+    if (c.tau_prev != kNoBound) drift = (int64_t)tau - (int64_t)c.tau_prev;
+    if (drift > (1 << 22)) drift = 1 << 22;
+    if (drift < -(1 << 22)) drift = -(1 << 22);
+    int64_t centre = (int64_t)tau + drift;
+    if (centre < 0) centre = 0;
+    if (centre > 0x7F000000) centre = 0x7F000000;
+    // how far this round's prediction was off
+    uint32_t err = kWinDefaultHalf;
+    if (c.centre != kNoBound) err = tau > c.centre ? tau - c.centre : c.centre - tau;
+    else if (c.tau_prev != kNoBound) err = (uint32_t)(drift < 0 ? -drift : drift);
+    if (err < c.err_prev / 2) err = c.err_prev / 2;
+    double half = 3.0 * (double)err + 1024.0;
+    const double by_count = 2500.0 / dens;                 // aims at about 5000 boundary entries
+    if (half < by_count) half = by_count;
+    const double cap_half = (double)bnd_cap / (2.5 * dens);
+    if (half > cap_half) half = cap_half;
+    if (half < (double)kWinMinHalf) half = (double)kWinMinHalf;
+    if (half > (double)kWinMaxHalf) half = (double)kWinMaxHalf;
+    const uint32_t h = (uint32_t)half;
+    // bound: below the (cautiously) predicted k-th score by a margin that aims at
+    // cand_target*k candidates and covers the prediction error.  An upward drift
+    // is only followed half way (it usually slows down; too low a bound merely
+    // costs candidates, too high a bound costs a dense selection).  After a
+    // failed speculation the margin grows if the bound was too high (fewer than
+    // k valid candidates) and shrinks if it was too low (overflow); it relaxes
+    // back afterwards.
+    float ms = c.margin_scale;
+    if (!(ms > 0.0f)) ms = 1.0f;
+    if (SECOND) {
+      if (c.overflow) ms = ms * 0.5f < 0.125f ? 0.125f : ms * 0.5f;
+      else if (c.tau_lo != kNoBound) ms = ms * 2.0f > 16.0f ? 16.0f : ms * 2.0f;
+    } else {
+      ms = ms > 1.0f ? 1.0f + (ms - 1.0f) * 0.7f : (ms * 1.3f > 1.0f ? 1.0f : ms * 1.3f);
+    }
+    c.margin_scale = ms;
+    double margin = ((double)cand_target - 1.0) * (double)K / dens;
+    if (margin < 2.0 * (double)err + 1024.0) margin = 2.0 * (double)err + 1024.0;
+    margin *= (double)ms;
+    if (margin > 16777216.0) margin = 16777216.0;
+    const int64_t anchor = drift > 0 ? (int64_t)tau + drift / 2 : centre;
+    const int64_t lo = anchor - (int64_t)margin;
+    const bool speculate = (int64_t)n_tot >= (int64_t)((double)cand_target * (double)K) || !SECOND;
+    c.next_tau_lo = speculate ? (uint32_t)(lo > 0 ? lo : 0) : kNoBound;
+    c.next_win_lo = speculate ? (uint32_t)(centre > (int64_t)h ? centre - (int64_t)h : 0) : kNoBound;
+    c.next_win_hi = (uint32_t)centre + h;
+    c.tau_prev = tau;
+    c.centre = speculate ? (uint32_t)centre : kNoBound;
+    c.err_prev = err;
+  }
 }
 
 // ---------------------------------------------------------- k_dense_hist ----
@@ -360,59 +672,24 @@ k_dense_hist(const float* __restrict__ a, int64_t d, const WorkerCtl* __restrict
   }
 }
 
-// ----------------------------------------------------------- k_cand_hist ----
-// grid (blocks, N).  Levels 2 and 3 over the candidate score bits.
+// ---------------------------------------------------------- k_dense_scan ----
+// grid (N), one block per flagged worker.  Level LEVEL of the radix select of
+// rank min(2k, d) over the |a| bits: finds, from the top bin downwards, the bin
+// in which the cumulative count reaches the wanted rank.
 template <int LEVEL>
 __global__ void __launch_bounds__(kBlock)
-k_cand_hist(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ cand_key,
-            uint32_t* __restrict__ chist, uint32_t cap_r, uint32_t cap_total) {
-  __shared__ uint32_t s_hist[kL2Bins];
-  const uint32_t n = blockIdx.y, tid = threadIdx.x;
-  const WorkerCtl& c = ctl[n];
-  constexpr uint32_t bins = LEVEL == 2 ? kL2Bins : kL3Bins;
-  for (uint32_t i = tid; i < bins; i += kBlock) s_hist[i] = 0;
-  __syncthreads();
-  const uint32_t prefix = c.c_prefix;
-  const size_t cbase = (size_t)n * cap_total;
-  for (uint32_t p = blockIdx.x * kBlock + tid; p < cap_total; p += gridDim.x * kBlock) {
-    if (!slot_valid(c, p, cap_r)) continue;
-    const uint32_t key = cand_key[cbase + p];
-    if (LEVEL == 2) { if ((key >> kL1Shift) == prefix) atomicAdd(&s_hist[(key >> kL2Shift) & (kL2Bins - 1)], 1u); }
-    else { if ((key >> kL2Shift) == prefix) atomicAdd(&s_hist[key & (kL3Bins - 1)], 1u); }
-  }
-  __syncthreads();
-  uint32_t* gh = chist + ((size_t)n * 3 + (LEVEL - 1)) * kL1Bins;
-  for (uint32_t i = tid; i < bins; i += kBlock) {
-    const uint32_t v = s_hist[i];
-    if (v) atomicAdd(&gh[i], v);
-  }
-}
-
-// --------------------------------------------------------- k_select_scan ----
-// grid (N), one block per worker.  Finds, from the top bin downwards, the bin
-// in which the cumulative count reaches the wanted rank.
-//   DENSE = false: radix select of rank k over candidate scores (levels 1..3);
-//                  level 1 also derives the next round's speculative bound.
-//   DENSE = true : radix select of rank min(2k, d) over |a| bits, flagged workers.
-template <bool DENSE, int LEVEL>
-__global__ void __launch_bounds__(kBlock)
-k_select_scan(WorkerCtl* ctl, const uint32_t* __restrict__ hist_all, int64_t k, int64_t d,
-              float cand_target) {
+k_dense_scan(WorkerCtl* ctl, const uint32_t* __restrict__ hist_all, int64_t k, int64_t d) {
   constexpr uint32_t bins = LEVEL == 1 ? kL1Bins : (LEVEL == 2 ? kL2Bins : kL3Bins);
   constexpr uint32_t per = bins / kBlock;            // bins per thread (16, 8, 1)
   __shared__ uint32_t s_sum[kBlock];
   __shared__ uint32_t s_scan[kBlock];
   const uint32_t n = blockIdx.x, tid = threadIdx.x;
   WorkerCtl& c = ctl[n];
-  if (DENSE && !c.need_dense) return;
+  if (!c.need_dense) return;
   const uint32_t* h = hist_all + ((size_t)n * 3 + (LEVEL - 1)) * kL1Bins;
   uint32_t want;
-  if (LEVEL == 1) {
-    int64_t r = DENSE ? (2 * k < d ? 2 * k : d) : k;
-    want = (uint32_t)r;
-  } else {
-    want = DENSE ? c.f_krem : c.c_krem;
-  }
+  if (LEVEL == 1) want = (uint32_t)(2 * k < d ? 2 * k : d);
+  else want = c.f_krem;
   // thread t owns bins [bins-1-t*per .. bins-(t+1)*per], i.e. descending order
   uint32_t loc[per];
   uint32_t s = 0;
@@ -433,57 +710,28 @@ k_select_scan(WorkerCtl* ctl, const uint32_t* __restrict__ hist_all, int64_t k, 
       if (run < want && want <= run + loc[q]) {
         const uint32_t bin = bins - 1 - (tid * per + q);
         const uint32_t krem = want - run;            // rank wanted inside this bin
-        if (DENSE) {
-          if (LEVEL == 1) { c.f_prefix = bin; c.f_krem = krem; }
-          else if (LEVEL == 2) { c.f_prefix = (c.f_prefix << 11) | bin; c.f_krem = krem; }
-          else { c.f_tau = (c.f_prefix << 8) | bin; c.f_budget = krem; }
-        } else {
-          if (LEVEL == 1) { c.c_prefix = bin; c.c_krem = krem; }
-          else if (LEVEL == 2) { c.c_prefix = (c.c_prefix << 11) | bin; c.c_krem = krem; }
-          else {
-            c.tau = (c.c_prefix << 8) | bin; c.budget = krem;
-            c.n_gt = (uint32_t)k - krem; c.ties_total = loc[q];
-          }
-        }
+        if (LEVEL == 1) { c.f_prefix = bin; c.f_krem = krem; }
+        else if (LEVEL == 2) { c.f_prefix = (c.f_prefix << 11) | bin; c.f_krem = krem; }
+        else { c.f_tau = (c.f_prefix << 8) | bin; c.f_budget = krem; }
       }
       run += loc[q];
-    }
-  }
-  if (!DENSE && LEVEL == 1) {
-    // next round's bound: the bin edge at which about cand_target*k candidates
-    // of this round lie above; if this round had fewer, two bins below its own.
-    const uint32_t tgt = (uint32_t)((double)cand_target * (double)k);
-    uint32_t total = 0;
-    if (tid == kBlock - 1) total = above + s;
-    if (above < tgt && tgt <= above + s) {
-      uint32_t run = above;
-#pragma unroll
-      for (uint32_t q = 0; q < per; ++q) {
-        if (run < tgt && tgt <= run + loc[q]) c.next_tau_lo = (bins - 1 - (tid * per + q)) << kL1Shift;
-        run += loc[q];
-      }
-    }
-    if (tid == kBlock - 1 && total < tgt) {
-      uint32_t lowest = 0;                            // lowest non-empty bin = this thread's region or above
-      const uint32_t tl = c.tau_lo;
-      uint32_t b = (tl == kNoBound) ? 0u : (tl >> kL1Shift);
-      lowest = b > 2 ? b - 2 : 0;
-      c.next_tau_lo = (tl == kNoBound) ? kNoBound : (lowest << kL1Shift);
     }
   }
 }
 
 // --------------------------------------------------------- k_dense_count ----
-// grid (nc, N).  Per chunk: entries with |a| bits > f_tau and == f_tau.
+// grid (min(nc, 1024), N), blocks stride over the chunks.  Per chunk: entries
+// with |a| bits > f_tau and == f_tau.
 __global__ void __launch_bounds__(kBlock)
 k_dense_count(const float* __restrict__ a, int64_t d, const WorkerCtl* __restrict__ ctl,
               uint32_t* __restrict__ ch_gt, uint32_t* __restrict__ ch_tie, uint32_t nc) {
   __shared__ uint32_t s_gt[4], s_tie[4];
-  const uint32_t c = blockIdx.x, n = blockIdx.y, tid = threadIdx.x;
+  const uint32_t n = blockIdx.y, tid = threadIdx.x;
   const WorkerCtl& w = ctl[n];
   if (!w.need_dense) return;
   const uint32_t tau = w.f_tau;
   const float* row = a + (size_t)n * (size_t)d;
+  for (uint32_t c = blockIdx.x; c < nc; c += gridDim.x) {
   uint32_t gt = 0, tie = 0;
   for (int i = 0; i < 16; ++i) {
     const int64_t j = (int64_t)c * kChunk + i * kBlock + tid;
@@ -500,6 +748,8 @@ k_dense_count(const float* __restrict__ a, int64_t d, const WorkerCtl* __restric
     ch_gt[(size_t)n * nc + c] = s_gt[0] + s_gt[1] + s_gt[2] + s_gt[3];
     ch_tie[(size_t)n * nc + c] = s_tie[0] + s_tie[1] + s_tie[2] + s_tie[3];
   }
+  __syncthreads();
+  }
 }
 
 // ---------------------------------------------------------- k_chunk_scan ----
@@ -511,25 +761,6 @@ k_dense_count(const float* __restrict__ a, int64_t d, const WorkerCtl* __restric
 // dense emission) and dense_total.  Otherwise budget = ctl.budget, sel_off goes
 // to the round's sel_off table and the total is checked against k.  tie_off is
 // written in both cases.
-constexpr int kScanBlock = 1024;
-
-__device__ __forceinline__ uint32_t block_excl_scan_1024(uint32_t v, uint32_t* s_w /*[16]*/,
-                                                         uint32_t* total) {
-  const uint32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  uint32_t x = v;
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t y = __shfl_up(x, o);
-    if (lane >= (uint32_t)o) x += y;
-  }
-  if (lane == 63) s_w[wv] = x;
-  __syncthreads();
-  uint32_t wb = 0, tot = 0;
-  for (uint32_t i = 0; i < 16; ++i) { const uint32_t t = s_w[i]; if (i < wv) wb += t; tot += t; }
-  __syncthreads();
-  *total = tot;
-  return wb + x - v;
-}
-
 template <bool DENSE>
 __global__ void __launch_bounds__(kScanBlock)
 k_chunk_scan(WorkerCtl* ctl, const uint32_t* __restrict__ ch_gt, const uint32_t* __restrict__ ch_tie,
@@ -574,7 +805,7 @@ k_chunk_scan(WorkerCtl* ctl, const uint32_t* __restrict__ ch_gt, const uint32_t*
 }
 
 // ---------------------------------------------------------- k_dense_emit ----
-// grid (nc, N).  Writes the 2k largest |a| (ties: lowest indices) of a flagged
+// grid (min(nc, 1024), N), blocks stride over the chunks.  Writes the 2k largest |a| (ties: lowest indices) of a flagged
 // worker as its candidate list, in index order, at the offsets of the scan.
 template <bool VEC>
 __global__ void __launch_bounds__(kBlock)
@@ -584,12 +815,13 @@ k_dense_emit(const float* __restrict__ a_rows, int64_t d, WorkerCtl* __restrict_
              const uint32_t* __restrict__ tie_off, uint32_t nc, uint32_t cap_total) {
   __shared__ uint32_t s_wtot[4];
   __shared__ uint32_t s_ttot[4];
-  const uint32_t c = blockIdx.x, n = blockIdx.y;
+  const uint32_t n = blockIdx.y;
   const uint32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const WorkerCtl& w = ctl[n];
   if (!w.need_dense) return;
+  for (uint32_t c = blockIdx.x; c < nc; c += gridDim.x) {
   const size_t tix = (size_t)n * nc + c;
-  if (ch_cnt[tix] == 0) return;
+  if (ch_cnt[tix] == 0) continue;
   const uint32_t tau = w.f_tau, budget = w.f_budget;
   const size_t row = (size_t)n * (size_t)d;
   const int64_t base = (int64_t)c * kChunk + (int64_t)wv * 1024 + lane * 4;
@@ -632,7 +864,6 @@ k_dense_emit(const float* __restrict__ a_rows, int64_t d, WorkerCtl* __restrict_
   }
   __syncthreads();
   const ChunkPos cp = ordered_positions(flags, s_wtot);
-  if (flags == 0) return;
   const size_t out = (size_t)n * cap_total + ch_off[tix] + cp.wave_base;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -645,6 +876,8 @@ k_dense_emit(const float* __restrict__ a_rows, int64_t d, WorkerCtl* __restrict_
         ++p;
       }
     }
+  }
+  __syncthreads();
   }
 }
 
@@ -720,25 +953,55 @@ k_compact(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ cand_k
 // ----------------------------------------------------------- k_aggregate ----
 // grid (nc).  agg tile of 4096 entries: +0, then + w*val of every worker in
 // ascending worker order (indices of one worker are distinct, so plain LDS
-// read-modify-write), written once.
+// read-modify-write), written once.  Workers are taken 32 at a time: wave v
+// prefetches the chunk's entries of its 8 workers, then the 32 workers are
+// applied to the tile one after the other.
 __global__ void __launch_bounds__(kBlock)
 k_aggregate(const int32_t* __restrict__ out_idx, const float* __restrict__ out_val,
             const uint32_t* __restrict__ sel_off, float* __restrict__ agg, int64_t d, int64_t k,
             uint32_t nc, int32_t N, float w) {
   __shared__ float s_tile[kChunk];
-  const uint32_t c = blockIdx.x, tid = threadIdx.x;
+  const uint32_t c = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   for (uint32_t i = tid; i < kChunk; i += kBlock) s_tile[i] = 0.0f;
-  __syncthreads();
   const int32_t jbase = (int32_t)(c << kChunkLog);
-  for (int32_t n = 0; n < N; ++n) {
-    const uint32_t s0 = sel_off[(size_t)n * (nc + 1) + c];
-    const uint32_t s1 = sel_off[(size_t)n * (nc + 1) + c + 1];
-    for (uint32_t p = s0 + tid; p < s1; p += kBlock) {
-      const int32_t j = out_idx[(size_t)n * k + p] - jbase;
-      if ((uint32_t)j < (uint32_t)kChunk)
-        s_tile[j] = __fadd_rn(s_tile[j], __fmul_rn(w, out_val[(size_t)n * k + p]));
+  for (int32_t b0 = 0; b0 < N; b0 += 32) {
+    uint32_t s0[8], len[8];
+    int32_t pj[8];
+    float pv[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int32_t n = b0 + (int32_t)wv * 8 + i;
+      s0[i] = 0; len[i] = 0;
+      if (n < N) {
+        s0[i] = sel_off[(size_t)n * (nc + 1) + c];
+        len[i] = sel_off[(size_t)n * (nc + 1) + c + 1] - s0[i];
+      }
     }
-    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int32_t n = b0 + (int32_t)wv * 8 + i;
+      pj[i] = -1; pv[i] = 0.0f;
+      if (lane < len[i]) {
+        pj[i] = out_idx[(size_t)n * k + s0[i] + lane] - jbase;
+        pv[i] = out_val[(size_t)n * k + s0[i] + lane];
+      }
+    }
+    __syncthreads();                       // tile zeroed / previous batch applied
+#pragma unroll
+    for (int o = 0; o < 32; ++o) {
+      if ((int)wv == o / 8) {
+        const int i = o % 8;
+        const int32_t n = b0 + o;
+        if ((uint32_t)pj[i] < (uint32_t)kChunk)
+          s_tile[pj[i]] = __fadd_rn(s_tile[pj[i]], __fmul_rn(w, pv[i]));
+        for (uint32_t p = 64 + lane; p < len[i]; p += 64) {     // more than 64 entries in this chunk
+          const int32_t j = out_idx[(size_t)n * k + s0[i] + p] - jbase;
+          if ((uint32_t)j < (uint32_t)kChunk)
+            s_tile[j] = __fadd_rn(s_tile[j], __fmul_rn(w, out_val[(size_t)n * k + s0[i] + p]));
+        }
+      }
+      __syncthreads();
+    }
   }
   const int64_t j0 = (int64_t)c * kChunk;
   for (uint32_t i = tid; i < kChunk; i += kBlock)
@@ -758,7 +1021,11 @@ __global__ void k_init_ctl(WorkerCtl* ctl) {
   uint32_t* p = reinterpret_cast<uint32_t*>(&ctl[blockIdx.x]);
   for (uint32_t i = threadIdx.x; i < sizeof(WorkerCtl) / 4; i += blockDim.x) p[i] = 0;
   __syncthreads();
-  if (threadIdx.x == 0) { ctl[blockIdx.x].tau_lo = kNoBound; ctl[blockIdx.x].next_tau_lo = kNoBound; }
+  if (threadIdx.x == 0) {
+    WorkerCtl& c = ctl[blockIdx.x];
+    c.tau_lo = kNoBound; c.next_tau_lo = kNoBound; c.win_lo = kNoBound; c.next_win_lo = kNoBound;
+    c.tau_prev = kNoBound; c.centre = kNoBound; c.margin_scale = 1.0f;
+  }
 }
 
 // set_state: rebuild the per-chunk offsets of a previous index list and check it.

@@ -39,9 +39,9 @@ constexpr size_t kAlign = 256;
 size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-  uint32_t nc, regions, cap_r, cap_total;
+  uint32_t nc, regions, cap_r, cap_total, bnd_cap;
   size_t e, out_idx[2], out_val[2], agg[2], cand_idx, cand_val, cand_key;
-  size_t ch_off, ch_cnt, ch_gt, ch_tie, tie_off, sel_off[2], chist, fhist, ctl, total;
+  size_t ch_off, ch_cnt, ch_gt, ch_tie, tie_off, sel_off[2], bnd_key, fhist, ctl, total;
 };
 
 bool valid_sizes(int32_t N, int64_t d, int64_t k) {
@@ -79,7 +79,8 @@ Layout make_layout(int32_t N, int64_t d, int64_t k) {
   L.ch_tie = take(nch * 4);
   L.tie_off = take(nch * 4);
   for (int b = 0; b < 2; ++b) L.sel_off[b] = take(((size_t)N * (L.nc + 1)) * 4);
-  L.chist = take((size_t)N * 3 * kL1Bins * 4);
+  L.bnd_cap = 65536;
+  L.bnd_key = take((size_t)N * L.bnd_cap * 4);
   L.fhist = take((size_t)N * 3 * kL1Bins * 4);
   L.ctl = take((size_t)N * sizeof(WorkerCtl));
   L.total = o;
@@ -130,7 +131,7 @@ int create_common(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu, 
   c->w = 1.0f / (float)N;
   c->owns_arena = owns;
   c->force_dense = 0;
-  c->cand_target = 1.5f;
+  c->cand_target = 1.25f;
   c->profile = false;
   c->prof_rounds = 0;
   c->arena = static_cast<char*>(arena);
@@ -251,7 +252,7 @@ int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* s
   uint32_t* ch_gt = c->at<uint32_t>(L.ch_gt);
   uint32_t* ch_tie = c->at<uint32_t>(L.ch_tie);
   uint32_t* tie_off = c->at<uint32_t>(L.tie_off);
-  uint32_t* chist = c->at<uint32_t>(L.chist);
+  uint32_t* bnd_key = c->at<uint32_t>(L.bnd_key);
   uint32_t* fhist = c->at<uint32_t>(L.fhist);
   int32_t* out_idx = c->at<int32_t>(L.out_idx[cur]);
   float* out_val = c->at<float>(L.out_val[cur]);
@@ -262,46 +263,41 @@ int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* s
   const uint32_t* prev_sel_off = c->at<uint32_t>(L.sel_off[prv]);
 
   const dim3 g_chunks(nc, N), g_waves((nc + 3) / 4, N);
-  uint32_t cb = (L.cap_total + kBlock * 4 - 1) / (kBlock * 4);
-  if (cb > 512) cb = 512;
-  if (cb < 1) cb = 1;
-  const dim3 g_cand(cb, N);
+  const dim3 g_score((L.cap_r + kScoreSlots - 1) / kScoreSlots, L.regions, N);
+  // the dense selection is rare: small grids that stride, so that the launches
+  // cost little when no worker needs them
+  const dim3 g_dense_chunks(nc < 1024 ? nc : 1024, N);
   uint32_t db = (uint32_t)((d + kBlock * 16 - 1) / (kBlock * 16));
   if (db > 1024) db = 1024;
   const dim3 g_dense(db, N);
 
   hipEvent_t* ev = c->profile ? c->ev[c->prof_rounds % kProfRounds] : nullptr;
   if (ev) HIP_TRY(hipEventRecord(ev[0], s));
-  k_begin<<<N, kBlock, 0, s>>>(ctl, chist, fhist, c->force_dense);
+  k_begin<<<N, kBlock, 0, s>>>(ctl, c->force_dense);
   if (vec)
     k_accum_emit<true><<<g_chunks, kBlock, 0, s>>>(e, grads, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   else
     k_accum_emit<false><<<g_chunks, kBlock, 0, s>>>(e, grads, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   if (ev) HIP_TRY(hipEventRecord(ev[1], s));
-  k_score<<<g_cand, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_key, prev_idx, prev_val, prev_sel_off, gprev, chist, d, k, nc, L.cap_r, L.cap_total, c->w, c->mu, use_reg, 0);
-  k_validate<<<N, kBlock, 0, s>>>(ctl, chist, k, L.regions, c->force_dense);
+  k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_key, bnd_key, prev_idx, prev_val, prev_sel_off, gprev, d, k, nc, L.cap_r, L.cap_total, L.bnd_cap, c->w, c->mu, use_reg, 0);
+  k_select<false><<<N, kScanBlock, 0, s>>>(ctl, cand_key, bnd_key, k, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->cand_target, c->force_dense);
 
   // dense selection; every kernel returns at once for workers that do not need it
+  k_dense_begin<<<N, kBlock, 0, s>>>(ctl, fhist);
   k_dense_hist<1><<<g_dense, kBlock, 0, s>>>(e, d, ctl, fhist);
-  k_select_scan<true, 1><<<N, kBlock, 0, s>>>(ctl, fhist, k, d, c->cand_target);
+  k_dense_scan<1><<<N, kBlock, 0, s>>>(ctl, fhist, k, d);
   k_dense_hist<2><<<g_dense, kBlock, 0, s>>>(e, d, ctl, fhist);
-  k_select_scan<true, 2><<<N, kBlock, 0, s>>>(ctl, fhist, k, d, c->cand_target);
+  k_dense_scan<2><<<N, kBlock, 0, s>>>(ctl, fhist, k, d);
   k_dense_hist<3><<<g_dense, kBlock, 0, s>>>(e, d, ctl, fhist);
-  k_select_scan<true, 3><<<N, kBlock, 0, s>>>(ctl, fhist, k, d, c->cand_target);
-  k_dense_count<<<g_chunks, kBlock, 0, s>>>(e, d, ctl, ch_gt, ch_tie, nc);
+  k_dense_scan<3><<<N, kBlock, 0, s>>>(ctl, fhist, k, d);
+  k_dense_count<<<g_dense_chunks, kBlock, 0, s>>>(e, d, ctl, ch_gt, ch_tie, nc);
   k_chunk_scan<true><<<N, kScanBlock, 0, s>>>(ctl, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, nc, k);
   if (vec)
-    k_dense_emit<true><<<g_chunks, kBlock, 0, s>>>(e, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, tie_off, nc, L.cap_total);
+    k_dense_emit<true><<<g_dense_chunks, kBlock, 0, s>>>(e, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, tie_off, nc, L.cap_total);
   else
-    k_dense_emit<false><<<g_chunks, kBlock, 0, s>>>(e, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, tie_off, nc, L.cap_total);
-  k_score<<<g_cand, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_key, prev_idx, prev_val, prev_sel_off, gprev, chist, d, k, nc, L.cap_r, L.cap_total, c->w, c->mu, use_reg, 1);
-
-  // exact k-th largest score among the candidates
-  k_select_scan<false, 1><<<N, kBlock, 0, s>>>(ctl, chist, k, d, c->cand_target);
-  k_cand_hist<2><<<g_cand, kBlock, 0, s>>>(ctl, cand_key, chist, L.cap_r, L.cap_total);
-  k_select_scan<false, 2><<<N, kBlock, 0, s>>>(ctl, chist, k, d, c->cand_target);
-  k_cand_hist<3><<<g_cand, kBlock, 0, s>>>(ctl, cand_key, chist, L.cap_r, L.cap_total);
-  k_select_scan<false, 3><<<N, kBlock, 0, s>>>(ctl, chist, k, d, c->cand_target);
+    k_dense_emit<false><<<g_dense_chunks, kBlock, 0, s>>>(e, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, tie_off, nc, L.cap_total);
+  k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_key, bnd_key, prev_idx, prev_val, prev_sel_off, gprev, d, k, nc, L.cap_r, L.cap_total, L.bnd_cap, c->w, c->mu, use_reg, 1);
+  k_select<true><<<N, kScanBlock, 0, s>>>(ctl, cand_key, bnd_key, k, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->cand_target, c->force_dense);
 
   // ordered compaction, error update, aggregation
   if (ev) HIP_TRY(hipEventRecord(ev[2], s));
@@ -376,6 +372,10 @@ int regtopk_get_stats(regtopk_ctx* c, regtopk_worker_stats* st, void* stream) {
     st[n].n_ties_taken = w.budget;
     st[n].n_ties_total = w.ties_total;
     st[n].overflow = w.overflow;
+    st[n].used_window = w.used_window;
+    st[n].n_boundary = w.n_bnd;
+    st[n].n_valid = w.n_valid;
+    st[n].window_half = w.win_lo == kNoBound ? 0u : (w.win_hi - w.win_lo) / 2;
     err |= w.err;
   }
   if (err) return fail(REGTOPK_BAD_STATE, "device-side check failed (flags 0x%x)", err);
