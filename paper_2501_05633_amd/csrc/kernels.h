@@ -4,11 +4,15 @@
 //
 //   k_begin         reset counters, load this round's speculative bound and window
 //   k_accum_emit    a = eps + g written over eps (the one dense read/write sweep);
+//                   eps is taken as 0 where the previous round's mask bit is set
+//                   (the sent entries are never zeroed in memory: one bit per
+//                   entry is read here instead of k scattered writes per worker);
 //                   entries with |a| >= tau_lo are appended, in index order per
 //                   4096-entry chunk, to the worker's candidate list
 //   k_score         exact score of every candidate (regulariser for entries sent in
-//                   the previous round, found by binary search in that round's
-//                   index list); scores inside a narrow window around the expected
+//                   the previous round; their rank in that round's value list
+//                   comes from the mask word and a per-word running count);
+//                   scores inside a narrow window around the expected
 //                   k-th score are also copied to a short boundary list, those
 //                   above it are counted
 //   k_select        one block per worker: checks the speculation (no overflow and
@@ -23,7 +27,8 @@
 //                   k_select run again for those workers
 //   k_chunk_count / k_chunk_scan / k_compact
 //                   ordered compaction of the selected (index, value) pairs,
-//                   lowest-index ties first, and zeroing of eps on the mask
+//                   lowest-index ties first; writes the round's mask (1 bit per
+//                   entry) and the running count of selected entries per word
 //   k_aggregate     per 4096-entry tile: LDS accumulation of w*value in ascending
 //                   worker order, tile written once (zero fill included)
 //
@@ -45,6 +50,8 @@ constexpr int kChunkLog = 12;
 constexpr int kBlock = 256;
 constexpr int kMaxRegions = 64;
 constexpr uint32_t kNoBound = 0xFFFFFFFFu;
+constexpr int kChunkWords = kChunk / 32;   // mask words per chunk
+constexpr uint32_t kSentFlag = 0x80000000u; // in a candidate's index: the entry was sent in the previous round
 
 // score bits (sign bit is always 0): level 1 = bits 30..19, level 2 = 18..8, level 3 = 7..0
 constexpr int kL1Shift = 19, kL1Bins = 4096;
@@ -202,8 +209,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 template <bool VEC>
 __global__ void __launch_bounds__(kBlock)
-k_accum_emit(float* __restrict__ e, const float* __restrict__ g, int64_t d,
-             WorkerCtl* __restrict__ ctl, int32_t* __restrict__ cand_idx,
+k_accum_emit(float* __restrict__ e, const float* __restrict__ g, const uint32_t* __restrict__ mask,
+             int64_t d, WorkerCtl* __restrict__ ctl, int32_t* __restrict__ cand_idx,
              float* __restrict__ cand_val, uint32_t* __restrict__ ch_off,
              uint32_t* __restrict__ ch_cnt, uint32_t nc, uint32_t cap_r, uint32_t cap_total,
              uint32_t regions) {
@@ -216,6 +223,14 @@ k_accum_emit(float* __restrict__ e, const float* __restrict__ g, int64_t d,
   const int64_t base = (int64_t)c * kChunk + (int64_t)wv * 1024 + lane * 4;
   float a[4][4];
   uint32_t flags = 0;
+  // previous round's mask: the 4 bits of entries j0..j0+3 lie in one word
+  const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
+  uint32_t mb[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int64_t j0 = base + i * 256;
+    mb[i] = j0 < d ? (mrow[j0 >> 5] >> (j0 & 31)) & 15u : 0u;
+  }
   if (VEC) {
     f32x4 ev[4], gv[4];
 #pragma unroll
@@ -232,6 +247,12 @@ k_accum_emit(float* __restrict__ e, const float* __restrict__ g, int64_t d,
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int64_t j0 = base + i * 256;
+      if (mb[i]) {                          // sent last round: the error restarts from zero
+        if (mb[i] & 1u) ev[i].x = 0.f;
+        if (mb[i] & 2u) ev[i].y = 0.f;
+        if (mb[i] & 4u) ev[i].z = 0.f;
+        if (mb[i] & 8u) ev[i].w = 0.f;
+      }
       const f32x4 s4 = ev[i] + gv[i];
       a[i][0] = s4.x; a[i][1] = s4.y; a[i][2] = s4.z; a[i][3] = s4.w;
       if (j0 < d) {
@@ -249,7 +270,8 @@ k_accum_emit(float* __restrict__ e, const float* __restrict__ g, int64_t d,
         const int64_t j = base + i * 256 + q;
         a[i][q] = 0.f;
         if (j < d) {
-          a[i][q] = e[row + j] + g[row + j];
+          const float eps = ((mb[i] >> q) & 1u) ? 0.f : e[row + j];
+          a[i][q] = eps + g[row + j];
           e[row + j] = a[i][q];
           if (key_of(a[i][q]) >= tau_lo) flags |= 1u << (i * 4 + q);
         }
@@ -282,7 +304,7 @@ k_accum_emit(float* __restrict__ e, const float* __restrict__ g, int64_t d,
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       if ((flags >> (i * 4 + q)) & 1u) {
-        cand_idx[out + p] = (int32_t)(base + i * 256 + q);
+        cand_idx[out + p] = (int32_t)((uint32_t)(base + i * 256 + q) | (((mb[i] >> q) & 1u) ? kSentFlag : 0u));
         cand_val[out + p] = a[i][q];
         ++p;
       }
@@ -312,8 +334,8 @@ constexpr int kScoreSlots = 1024;
 __global__ void __launch_bounds__(kBlock)
 k_score(WorkerCtl* __restrict__ ctl, const int32_t* __restrict__ cand_idx,
         const float* __restrict__ cand_val, uint32_t* __restrict__ cand_key,
-        uint32_t* __restrict__ bnd_key, const int32_t* __restrict__ prev_idx,
-        const float* __restrict__ prev_val, const uint32_t* __restrict__ prev_sel_off,
+        uint32_t* __restrict__ bnd_key, const uint32_t* __restrict__ mask,
+        const uint32_t* __restrict__ rankbase, const float* __restrict__ prev_val,
         const float* __restrict__ gprev, int64_t d, int64_t k, uint32_t nc, uint32_t cap_r,
         uint32_t cap_total, uint32_t bnd_cap, float w, float mu, int use_reg, int only_dense) {
   __shared__ uint32_t s_stage[kScoreSlots];
@@ -334,27 +356,24 @@ k_score(WorkerCtl* __restrict__ ctl, const int32_t* __restrict__ cand_idx,
     __syncthreads();
   }
   const size_t cbase = (size_t)n * cap_total + (size_t)r * cap_r;
-  const int32_t* pi = prev_idx + (size_t)n * k;
   const float* pv = prev_val + (size_t)n * k;
-  const uint32_t* so = prev_sel_off + (size_t)n * (nc + 1);
+  const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
+  const uint32_t* rrow = rankbase + (size_t)n * nc * kChunkWords;
   uint32_t n_val = 0, n_hi = 0;
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const uint32_t p = p0 + q * kBlock + tid;
     if (p >= lim) continue;
-    const int32_t j = cand_idx[cbase + p];
-    if (j < 0 || (int64_t)j >= d) continue;
+    const uint32_t raw = (uint32_t)cand_idx[cbase + p];
+    const uint32_t j = raw & ~kSentFlag;
+    if ((int64_t)j >= d) continue;
     const float a = cand_val[cbase + p];
     float f = 1.0f;
-    if (use_reg) {
-      const uint32_t cj = (uint32_t)j >> kChunkLog;
-      uint32_t lo = so[cj], hi = so[cj + 1];
-      const uint32_t end = hi;
-      while (lo < hi) {                       // lower bound of j in the chunk's slice
-        const uint32_t mid = (lo + hi) >> 1;
-        if (pi[mid] < j) lo = mid + 1; else hi = mid;
-      }
-      if (lo < end && pi[lo] == j) f = likelihood_sent(a, pv[lo], gprev[j], w, mu);
+    if (use_reg && (raw & kSentFlag)) {
+      // rank of j in the previous round's list: selected entries before its mask
+      // word plus the set bits below it inside the word
+      const uint32_t rank = rrow[j >> 5] + (uint32_t)__popc(mrow[j >> 5] & ((1u << (j & 31)) - 1u));
+      if ((int64_t)rank < k) f = likelihood_sent(a, pv[rank], gprev[j], w, mu);
     }
     const uint32_t key = __float_as_uint(__fmul_rn(fabsf(a), f));
     cand_key[cbase + p] = key;
@@ -809,8 +828,8 @@ k_chunk_scan(WorkerCtl* ctl, const uint32_t* __restrict__ ch_gt, const uint32_t*
 // worker as its candidate list, in index order, at the offsets of the scan.
 template <bool VEC>
 __global__ void __launch_bounds__(kBlock)
-k_dense_emit(const float* __restrict__ a_rows, int64_t d, WorkerCtl* __restrict__ ctl,
-             int32_t* __restrict__ cand_idx, float* __restrict__ cand_val,
+k_dense_emit(const float* __restrict__ a_rows, const uint32_t* __restrict__ mask, int64_t d,
+             WorkerCtl* __restrict__ ctl, int32_t* __restrict__ cand_idx, float* __restrict__ cand_val,
              const uint32_t* __restrict__ ch_off, const uint32_t* __restrict__ ch_cnt,
              const uint32_t* __restrict__ tie_off, uint32_t nc, uint32_t cap_total) {
   __shared__ uint32_t s_wtot[4];
@@ -819,6 +838,7 @@ k_dense_emit(const float* __restrict__ a_rows, int64_t d, WorkerCtl* __restrict_
   const uint32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const WorkerCtl& w = ctl[n];
   if (!w.need_dense) return;
+  const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
   for (uint32_t c = blockIdx.x; c < nc; c += gridDim.x) {
   const size_t tix = (size_t)n * nc + c;
   if (ch_cnt[tix] == 0) continue;
@@ -871,7 +891,9 @@ k_dense_emit(const float* __restrict__ a_rows, int64_t d, WorkerCtl* __restrict_
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       if ((flags >> (i * 4 + q)) & 1u) {
-        cand_idx[out + p] = (int32_t)(base + i * 256 + q);
+        const int64_t j = base + i * 256 + q;
+        const uint32_t sent = (mrow[j >> 5] >> (j & 31)) & 1u;
+        cand_idx[out + p] = (int32_t)((uint32_t)j | (sent ? kSentFlag : 0u));
         cand_val[out + p] = a[i][q];
         ++p;
       }
@@ -907,105 +929,152 @@ k_chunk_count(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ ca
 }
 
 // ------------------------------------------------------------- k_compact ----
+// Mask words and running counts of one chunk from its selected local indices.
+// s_m: 128 zeroed LDS words of the calling wave, in which the bits were set.
+// Lane l owns words 2l and 2l+1.  first = selected entries of the worker before
+// this chunk.
+__device__ __forceinline__ void write_chunk_mask(const uint32_t* s_m, uint32_t first,
+                                                 uint32_t* __restrict__ mask_chunk,
+                                                 uint32_t* __restrict__ rank_chunk) {
+  const uint32_t lane = threadIdx.x & 63;
+  const uint32_t m0 = s_m[2 * lane], m1 = s_m[2 * lane + 1];
+  const uint32_t c0 = (uint32_t)__popc(m0), c1 = (uint32_t)__popc(m1);
+  uint32_t x = c0 + c1;
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t y = __shfl_up(x, o);
+    if (lane >= (uint32_t)o) x += y;
+  }
+  const uint32_t before = first + x - (c0 + c1);
+  reinterpret_cast<uint2*>(mask_chunk)[lane] = make_uint2(m0, m1);
+  reinterpret_cast<uint2*>(rank_chunk)[lane] = make_uint2(before, before + c0);
+}
+
 // grid (ceil(nc/4), N): one wave per chunk.  Writes the selected pairs of the
-// chunk in index order at sel_off[c] and zeroes eps there.
+// chunk in index order at sel_off[c], and the chunk's words of the round's mask
+// (bit = entry selected) and of the running count of selected entries.
 __global__ void __launch_bounds__(kBlock)
 k_compact(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ cand_key,
           const int32_t* __restrict__ cand_idx, const float* __restrict__ cand_val,
           const uint32_t* __restrict__ ch_off, const uint32_t* __restrict__ ch_cnt,
           const uint32_t* __restrict__ sel_off, const uint32_t* __restrict__ tie_off,
-          int32_t* __restrict__ out_idx, float* __restrict__ out_val, float* __restrict__ e,
-          int64_t d, int64_t k, uint32_t nc, uint32_t cap_total) {
-  const uint32_t n = blockIdx.y, lane = threadIdx.x & 63;
-  const uint32_t c = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (c >= nc) return;
-  const size_t tix = (size_t)n * nc + c;
-  const uint32_t cnt = ch_cnt[tix];
-  if (cnt == 0) return;
-  const uint32_t off = ch_off[tix];
-  const uint32_t tau = ctl[n].tau, budget = ctl[n].budget;
-  const size_t cb = (size_t)n * cap_total + off;
-  uint32_t out = sel_off[(size_t)n * (nc + 1) + c];
-  uint32_t tie_run = tie_off[tix];
-  for (uint32_t p0 = 0; p0 < cnt; p0 += 64) {
-    const uint32_t p = p0 + lane;
-    uint32_t kk = 0;
-    bool in = p < cnt;
-    if (in) kk = cand_key[cb + p];
-    const bool is_tie = in && kk == tau;
-    const uint64_t tb = __ballot(is_tie);
-    const bool take = in && (kk > tau || (is_tie && tie_run + lanes_below(tb) < budget));
-    const uint64_t sb = __ballot(take);
-    if (take) {
-      const uint32_t o = out + lanes_below(sb);
-      if ((int64_t)o < k) {
-        const int32_t j = cand_idx[cb + p];
-        out_idx[(size_t)n * k + o] = j;
-        out_val[(size_t)n * k + o] = cand_val[cb + p];
-        e[(size_t)n * (size_t)d + j] = 0.0f;
+          int32_t* __restrict__ out_idx, float* __restrict__ out_val, uint32_t* __restrict__ mask,
+          uint32_t* __restrict__ rankbase, int64_t k, uint32_t nc, uint32_t cap_total) {
+  __shared__ uint32_t s_m[4][kChunkWords];
+  const uint32_t n = blockIdx.y, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const uint32_t c = blockIdx.x * 4 + wv;
+  const bool live = c < nc;
+  s_m[wv][lane] = 0;
+  s_m[wv][lane + 64] = 0;
+  __syncthreads();
+  uint32_t first = 0;
+  if (live) {
+    const size_t tix = (size_t)n * nc + c;
+    const uint32_t cnt = ch_cnt[tix];
+    const uint32_t off = ch_off[tix];
+    const uint32_t tau = ctl[n].tau, budget = ctl[n].budget;
+    const size_t cb = (size_t)n * cap_total + off;
+    first = sel_off[(size_t)n * (nc + 1) + c];
+    uint32_t out = first;
+    uint32_t tie_run = tie_off[tix];
+    for (uint32_t p0 = 0; p0 < cnt; p0 += 64) {
+      const uint32_t p = p0 + lane;
+      uint32_t kk = 0;
+      const bool in = p < cnt;
+      if (in) kk = cand_key[cb + p];
+      const bool is_tie = in && kk == tau;
+      const uint64_t tb = __ballot(is_tie);
+      const bool take = in && (kk > tau || (is_tie && tie_run + lanes_below(tb) < budget));
+      const uint64_t sb = __ballot(take);
+      if (take) {
+        const uint32_t o = out + lanes_below(sb);
+        if ((int64_t)o < k) {
+          const uint32_t j = (uint32_t)cand_idx[cb + p] & ~kSentFlag;
+          out_idx[(size_t)n * k + o] = (int32_t)j;
+          out_val[(size_t)n * k + o] = cand_val[cb + p];
+          const uint32_t jl = j & (kChunk - 1);
+          atomicOr(&s_m[wv][jl >> 5], 1u << (jl & 31));
+        }
       }
+      tie_run += (uint32_t)__popcll(tb);
+      out += (uint32_t)__popcll(sb);
     }
-    tie_run += (uint32_t)__popcll(tb);
-    out += (uint32_t)__popcll(sb);
+  }
+  __syncthreads();
+  if (live) {
+    const size_t wbase = ((size_t)n * nc + c) * kChunkWords;
+    write_chunk_mask(s_m[wv], first, mask + wbase, rankbase + wbase);
   }
 }
 
 // ----------------------------------------------------------- k_aggregate ----
 // grid (nc).  agg tile of 4096 entries: +0, then + w*val of every worker in
 // ascending worker order (indices of one worker are distinct, so plain LDS
-// read-modify-write), written once.  Workers are taken 32 at a time: wave v
-// prefetches the chunk's entries of its 8 workers, then the 32 workers are
-// applied to the tile one after the other.
+// read-modify-write), written once.  Workers are taken 32 at a time: the
+// chunk's selected entries of all 32 are first staged in LDS with independent
+// loads (so memory latency is paid once per batch), then applied to the tile
+// one worker after the other.
+constexpr uint32_t kAggStage = 2048;
+
 __global__ void __launch_bounds__(kBlock)
 k_aggregate(const int32_t* __restrict__ out_idx, const float* __restrict__ out_val,
             const uint32_t* __restrict__ sel_off, float* __restrict__ agg, int64_t d, int64_t k,
             uint32_t nc, int32_t N, float w) {
   __shared__ float s_tile[kChunk];
-  const uint32_t c = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  __shared__ uint32_t s_j[kAggStage];
+  __shared__ float s_v[kAggStage];
+  __shared__ uint32_t s_s0[32], s_pre[33];
+  const uint32_t c = blockIdx.x, tid = threadIdx.x;
   for (uint32_t i = tid; i < kChunk; i += kBlock) s_tile[i] = 0.0f;
   const int32_t jbase = (int32_t)(c << kChunkLog);
   for (int32_t b0 = 0; b0 < N; b0 += 32) {
-    uint32_t s0[8], len[8];
-    int32_t pj[8];
-    float pv[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int32_t n = b0 + (int32_t)wv * 8 + i;
-      s0[i] = 0; len[i] = 0;
-      if (n < N) {
-        s0[i] = sel_off[(size_t)n * (nc + 1) + c];
-        len[i] = sel_off[(size_t)n * (nc + 1) + c + 1] - s0[i];
-      }
+    const int32_t nb = N - b0 < 32 ? N - b0 : 32;
+    __syncthreads();                                  // previous batch applied, s_* free
+    if ((int32_t)tid < nb) {
+      const size_t o = (size_t)(b0 + tid) * (nc + 1) + c;
+      const uint32_t a0 = sel_off[o];
+      s_s0[tid] = a0;
+      s_pre[tid + 1] = sel_off[o + 1] - a0;            // length, turned into a prefix below
     }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int32_t n = b0 + (int32_t)wv * 8 + i;
-      pj[i] = -1; pv[i] = 0.0f;
-      if (lane < len[i]) {
-        pj[i] = out_idx[(size_t)n * k + s0[i] + lane] - jbase;
-        pv[i] = out_val[(size_t)n * k + s0[i] + lane];
-      }
+    __syncthreads();
+    if (tid == 0) {
+      uint32_t run = 0;
+      s_pre[0] = 0;
+      for (int32_t i = 0; i < nb; ++i) { run += s_pre[i + 1]; s_pre[i + 1] = run; }
     }
-    __syncthreads();                       // tile zeroed / previous batch applied
-#pragma unroll
-    for (int o = 0; o < 32; ++o) {
-      if ((int)wv == o / 8) {
-        const int i = o % 8;
-        const int32_t n = b0 + o;
-        if ((uint32_t)pj[i] < (uint32_t)kChunk)
-          s_tile[pj[i]] = __fadd_rn(s_tile[pj[i]], __fmul_rn(w, pv[i]));
-        for (uint32_t p = 64 + lane; p < len[i]; p += 64) {     // more than 64 entries in this chunk
-          const int32_t j = out_idx[(size_t)n * k + s0[i] + p] - jbase;
-          if ((uint32_t)j < (uint32_t)kChunk)
-            s_tile[j] = __fadd_rn(s_tile[j], __fmul_rn(w, out_val[(size_t)n * k + s0[i] + p]));
-        }
+    __syncthreads();
+    const uint32_t total = s_pre[nb];
+    for (uint32_t q0 = 0; q0 < total; q0 += kAggStage) {   // usually one pass
+      const uint32_t q1 = q0 + kAggStage < total ? q0 + kAggStage : total;
+      for (uint32_t q = q0 + tid; q < q1; q += kBlock) {
+        int32_t i = 0;
+        while (s_pre[i + 1] <= q) ++i;                 // worker of flattened entry q
+        const size_t src = (size_t)(b0 + i) * k + s_s0[i] + (q - s_pre[i]);
+        s_j[q - q0] = (uint32_t)(out_idx[src] - jbase);
+        s_v[q - q0] = out_val[src];
       }
       __syncthreads();
+      for (int32_t i = 0; i < nb; ++i) {               // ascending worker order
+        const uint32_t lo = s_pre[i] > q0 ? s_pre[i] : q0;
+        const uint32_t hi = s_pre[i + 1] < q1 ? s_pre[i + 1] : q1;
+        if (lo < hi) {                                 // uniform over the block
+          for (uint32_t q = lo + tid; q < hi; q += kBlock) {
+            const uint32_t j = s_j[q - q0];
+            if (j < (uint32_t)kChunk) s_tile[j] = __fadd_rn(s_tile[j], __fmul_rn(w, s_v[q - q0]));
+          }
+          __syncthreads();
+        }
+      }
     }
   }
+  __syncthreads();
   const int64_t j0 = (int64_t)c * kChunk;
-  for (uint32_t i = tid; i < kChunk; i += kBlock)
-    if (j0 + i < d) agg[j0 + i] = s_tile[i];
+  if (j0 + kChunk <= d && (d % 4) == 0) {
+    for (uint32_t i = tid * 4; i < kChunk; i += kBlock * 4)
+      *reinterpret_cast<float4*>(agg + j0 + i) = make_float4(s_tile[i], s_tile[i + 1], s_tile[i + 2], s_tile[i + 3]);
+  } else {
+    for (uint32_t i = tid; i < kChunk; i += kBlock)
+      if (j0 + i < d) agg[j0 + i] = s_tile[i];
+  }
 }
 
 // ------------------------------------------------------------- utilities ----
@@ -1028,19 +1097,50 @@ __global__ void k_init_ctl(WorkerCtl* ctl) {
   }
 }
 
-// set_state: rebuild the per-chunk offsets of a previous index list and check it.
-// grid (ceil((nc+1)/256), N)
-__global__ void k_rebuild_sel_off(const int32_t* __restrict__ pidx, uint32_t* __restrict__ sel_off,
-                                  WorkerCtl* ctl, int64_t d, int64_t k, uint32_t nc) {
-  const uint32_t n = blockIdx.y;
-  const uint32_t c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c > nc) return;
-  const int32_t* pi = pidx + (size_t)n * k;
-  const int64_t target = (int64_t)c * kChunk;
-  int64_t lo = 0, hi = k;
-  while (lo < hi) { const int64_t mid = (lo + hi) >> 1; if ((int64_t)pi[mid] < target) lo = mid + 1; else hi = mid; }
-  sel_off[(size_t)n * (nc + 1) + c] = (uint32_t)lo;
+// set_state: mask words and running counts from an ascending index list.
+// grid (ceil(nc/4), N): one wave per chunk.
+__global__ void __launch_bounds__(kBlock)
+k_build_mask(const int32_t* __restrict__ pidx, uint32_t* __restrict__ mask,
+             uint32_t* __restrict__ rankbase, int64_t k, uint32_t nc) {
+  __shared__ uint32_t s_m[4][kChunkWords];
+  const uint32_t n = blockIdx.y, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const uint32_t c = blockIdx.x * 4 + wv;
+  const bool live = c < nc;
+  s_m[wv][lane] = 0;
+  s_m[wv][lane + 64] = 0;
+  __syncthreads();
+  uint32_t first = 0;
+  if (live) {
+    const int32_t* pi = pidx + (size_t)n * k;
+    const int64_t t0 = (int64_t)c * kChunk, t1 = t0 + kChunk;
+    int64_t lo = 0, hi = k;
+    while (lo < hi) { const int64_t mid = (lo + hi) >> 1; if ((int64_t)pi[mid] < t0) lo = mid + 1; else hi = mid; }
+    first = (uint32_t)lo;
+    for (int64_t p = lo + lane; p < k; p += 64) {
+      const int64_t j = pi[p];
+      if (j >= t1 || j < t0) break;
+      const uint32_t jl = (uint32_t)(j - t0);
+      atomicOr(&s_m[wv][jl >> 5], 1u << (jl & 31));
+    }
+  }
+  __syncthreads();
+  if (live) {
+    const size_t wbase = ((size_t)n * nc + c) * kChunkWords;
+    write_chunk_mask(s_m[wv], first, mask + wbase, rankbase + wbase);
+  }
 }
+
+// get_state: eps as the method defines it (0 on the last round's mask).
+__global__ void k_export_eps(float* __restrict__ dst, const float* __restrict__ e,
+                             const uint32_t* __restrict__ mask, int64_t d, uint32_t nc, int32_t N) {
+  const size_t total = (size_t)N * (size_t)d;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const size_t n = i / (size_t)d, j = i - n * (size_t)d;
+    const uint32_t bit = (mask[n * nc * kChunkWords + (j >> 5)] >> (j & 31)) & 1u;
+    dst[i] = bit ? 0.0f : e[i];
+  }
+}
+
 // grid (blocks, N)
 __global__ void k_check_ascending(const int32_t* __restrict__ pidx, WorkerCtl* ctl, int64_t d, int64_t k) {
   const uint32_t n = blockIdx.y;

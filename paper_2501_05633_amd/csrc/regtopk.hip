@@ -41,7 +41,7 @@ size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct Layout {
   uint32_t nc, regions, cap_r, cap_total, bnd_cap;
   size_t e, out_idx[2], out_val[2], agg[2], cand_idx, cand_val, cand_key;
-  size_t ch_off, ch_cnt, ch_gt, ch_tie, tie_off, sel_off[2], bnd_key, fhist, ctl, total;
+  size_t ch_off, ch_cnt, ch_gt, ch_tie, tie_off, sel_off, mask, rankbase, bnd_key, fhist, ctl, total;
 };
 
 bool valid_sizes(int32_t N, int64_t d, int64_t k) {
@@ -78,7 +78,9 @@ Layout make_layout(int32_t N, int64_t d, int64_t k) {
   L.ch_gt = take(nch * 4);
   L.ch_tie = take(nch * 4);
   L.tie_off = take(nch * 4);
-  for (int b = 0; b < 2; ++b) L.sel_off[b] = take(((size_t)N * (L.nc + 1)) * 4);
+  L.sel_off = take(((size_t)N * (L.nc + 1)) * 4);
+  L.mask = take(nch * kChunkWords * 4);
+  L.rankbase = take(nch * kChunkWords * 4);
   L.bnd_cap = 65536;
   L.bnd_key = take((size_t)N * L.bnd_cap * 4);
   L.fhist = take((size_t)N * 3 * kL1Bins * 4);
@@ -114,8 +116,9 @@ namespace {
 int zero_state(regtopk_ctx* c, hipStream_t s) {
   const size_t ne = (size_t)c->N * (size_t)c->d;
   k_fill_u32<<<2048, 256, 0, s>>>(c->at<uint32_t>(c->L.e), ne, 0u);
-  for (int b = 0; b < 2; ++b)
-    k_fill_u32<<<256, 256, 0, s>>>(c->at<uint32_t>(c->L.sel_off[b]), (size_t)c->N * (c->L.nc + 1), 0u);
+  k_fill_u32<<<256, 256, 0, s>>>(c->at<uint32_t>(c->L.sel_off), (size_t)c->N * (c->L.nc + 1), 0u);
+  k_fill_u32<<<1024, 256, 0, s>>>(c->at<uint32_t>(c->L.mask), (size_t)c->N * c->L.nc * kChunkWords, 0u);
+  k_fill_u32<<<1024, 256, 0, s>>>(c->at<uint32_t>(c->L.rankbase), (size_t)c->N * c->L.nc * kChunkWords, 0u);
   k_init_ctl<<<c->N, 256, 0, s>>>(c->at<WorkerCtl>(c->L.ctl));
   HIP_TRY(hipGetLastError());
   c->t = 0;
@@ -257,10 +260,10 @@ int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* s
   int32_t* out_idx = c->at<int32_t>(L.out_idx[cur]);
   float* out_val = c->at<float>(L.out_val[cur]);
   float* agg = c->at<float>(L.agg[cur]);
-  const int32_t* prev_idx = c->at<int32_t>(L.out_idx[prv]);
   const float* prev_val = c->at<float>(L.out_val[prv]);
-  uint32_t* sel_off = c->at<uint32_t>(L.sel_off[cur]);
-  const uint32_t* prev_sel_off = c->at<uint32_t>(L.sel_off[prv]);
+  uint32_t* sel_off = c->at<uint32_t>(L.sel_off);
+  uint32_t* mask = c->at<uint32_t>(L.mask);
+  uint32_t* rankbase = c->at<uint32_t>(L.rankbase);
 
   const dim3 g_chunks(nc, N), g_waves((nc + 3) / 4, N);
   const dim3 g_score((L.cap_r + kScoreSlots - 1) / kScoreSlots, L.regions, N);
@@ -275,11 +278,11 @@ int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* s
   if (ev) HIP_TRY(hipEventRecord(ev[0], s));
   k_begin<<<N, kBlock, 0, s>>>(ctl, c->force_dense);
   if (vec)
-    k_accum_emit<true><<<g_chunks, kBlock, 0, s>>>(e, grads, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
+    k_accum_emit<true><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   else
-    k_accum_emit<false><<<g_chunks, kBlock, 0, s>>>(e, grads, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
+    k_accum_emit<false><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   if (ev) HIP_TRY(hipEventRecord(ev[1], s));
-  k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_key, bnd_key, prev_idx, prev_val, prev_sel_off, gprev, d, k, nc, L.cap_r, L.cap_total, L.bnd_cap, c->w, c->mu, use_reg, 0);
+  k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_key, bnd_key, mask, rankbase, prev_val, gprev, d, k, nc, L.cap_r, L.cap_total, L.bnd_cap, c->w, c->mu, use_reg, 0);
   k_select<false><<<N, kScanBlock, 0, s>>>(ctl, cand_key, bnd_key, k, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->cand_target, c->force_dense);
 
   // dense selection; every kernel returns at once for workers that do not need it
@@ -293,17 +296,17 @@ int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* s
   k_dense_count<<<g_dense_chunks, kBlock, 0, s>>>(e, d, ctl, ch_gt, ch_tie, nc);
   k_chunk_scan<true><<<N, kScanBlock, 0, s>>>(ctl, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, nc, k);
   if (vec)
-    k_dense_emit<true><<<g_dense_chunks, kBlock, 0, s>>>(e, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, tie_off, nc, L.cap_total);
+    k_dense_emit<true><<<g_dense_chunks, kBlock, 0, s>>>(e, mask, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, tie_off, nc, L.cap_total);
   else
-    k_dense_emit<false><<<g_dense_chunks, kBlock, 0, s>>>(e, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, tie_off, nc, L.cap_total);
-  k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_key, bnd_key, prev_idx, prev_val, prev_sel_off, gprev, d, k, nc, L.cap_r, L.cap_total, L.bnd_cap, c->w, c->mu, use_reg, 1);
+    k_dense_emit<false><<<g_dense_chunks, kBlock, 0, s>>>(e, mask, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, tie_off, nc, L.cap_total);
+  k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_key, bnd_key, mask, rankbase, prev_val, gprev, d, k, nc, L.cap_r, L.cap_total, L.bnd_cap, c->w, c->mu, use_reg, 1);
   k_select<true><<<N, kScanBlock, 0, s>>>(ctl, cand_key, bnd_key, k, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->cand_target, c->force_dense);
 
   // ordered compaction, error update, aggregation
   if (ev) HIP_TRY(hipEventRecord(ev[2], s));
   k_chunk_count<<<g_waves, kBlock, 0, s>>>(ctl, cand_key, ch_off, ch_cnt, ch_gt, ch_tie, nc, L.cap_total);
   k_chunk_scan<false><<<N, kScanBlock, 0, s>>>(ctl, ch_gt, ch_tie, sel_off, nullptr, tie_off, nc, k);
-  k_compact<<<g_waves, kBlock, 0, s>>>(ctl, cand_key, cand_idx, cand_val, ch_off, ch_cnt, sel_off, tie_off, out_idx, out_val, e, d, k, nc, L.cap_total);
+  k_compact<<<g_waves, kBlock, 0, s>>>(ctl, cand_key, cand_idx, cand_val, ch_off, ch_cnt, sel_off, tie_off, out_idx, out_val, mask, rankbase, k, nc, L.cap_total);
   k_aggregate<<<nc, kBlock, 0, s>>>(out_idx, out_val, sel_off, agg, d, k, nc, N, c->w);
   if (ev) { HIP_TRY(hipEventRecord(ev[3], s)); c->prof_rounds += 1; }
   HIP_TRY(hipGetLastError());
@@ -320,7 +323,8 @@ int regtopk_get_state(regtopk_ctx* c, float* e_dev, int32_t* pidx_dev, float* pv
   if (!c) return fail(REGTOPK_INVALID_ARG, "ctx is NULL");
   hipStream_t s = static_cast<hipStream_t>(stream);
   const size_t nd = (size_t)c->N * (size_t)c->d, nk = (size_t)c->N * (size_t)c->k;
-  if (e_dev) k_copy_u32<<<2048, 256, 0, s>>>(reinterpret_cast<uint32_t*>(e_dev), c->at<uint32_t>(c->L.e), nd);
+  (void)nd;
+  if (e_dev) k_export_eps<<<2048, 256, 0, s>>>(e_dev, c->at<float>(c->L.e), c->at<uint32_t>(c->L.mask), c->d, c->L.nc, c->N);
   if (c->have_prev) {
     const int prv = (int)((c->t & 1) ^ 1);
     if (pidx_dev) k_copy_u32<<<512, 256, 0, s>>>(reinterpret_cast<uint32_t*>(pidx_dev), c->at<uint32_t>(c->L.out_idx[prv]), nk);
@@ -341,13 +345,17 @@ int regtopk_set_state(regtopk_ctx* c, const float* e_dev, const int32_t* pidx_de
   k_init_ctl<<<c->N, 256, 0, s>>>(c->at<WorkerCtl>(c->L.ctl));     // no speculative bound: next round selects densely
   c->t = t;
   c->have_prev = t > 0;
+  if (t == 0) {
+    k_fill_u32<<<1024, 256, 0, s>>>(c->at<uint32_t>(c->L.mask), (size_t)c->N * c->L.nc * kChunkWords, 0u);
+    k_fill_u32<<<1024, 256, 0, s>>>(c->at<uint32_t>(c->L.rankbase), (size_t)c->N * c->L.nc * kChunkWords, 0u);
+  }
   if (t > 0) {
     const int prv = (int)((t & 1) ^ 1);
     int32_t* pi = c->at<int32_t>(c->L.out_idx[prv]);
     k_copy_u32<<<512, 256, 0, s>>>(reinterpret_cast<uint32_t*>(pi), reinterpret_cast<const uint32_t*>(pidx_dev), nk);
     k_copy_u32<<<512, 256, 0, s>>>(c->at<uint32_t>(c->L.out_val[prv]), reinterpret_cast<const uint32_t*>(pval_dev), nk);
-    const dim3 g((c->L.nc + 1 + 255) / 256, c->N);
-    k_rebuild_sel_off<<<g, 256, 0, s>>>(pi, c->at<uint32_t>(c->L.sel_off[prv]), c->at<WorkerCtl>(c->L.ctl), c->d, c->k, c->L.nc);
+    const dim3 g((c->L.nc + 3) / 4, c->N);
+    k_build_mask<<<g, kBlock, 0, s>>>(pi, c->at<uint32_t>(c->L.mask), c->at<uint32_t>(c->L.rankbase), c->k, c->L.nc);
     const dim3 g2(64, c->N);
     k_check_ascending<<<g2, 256, 0, s>>>(pi, c->at<WorkerCtl>(c->L.ctl), c->d, c->k);
   }
