@@ -4,7 +4,9 @@
 A step is one whole round (accumulate, score, exact top-k, compaction + error
 update, aggregation) for all N workers on fresh synthetic gradients that are
 already resident in HBM.  Default workload: N = 16, d = 25.6M, k = 1 % of d,
-mu = 1 (the "large CNN-sized" configuration).  Prints ONE JSON line.
+mu = 1 (the "large CNN-sized" configuration, 20 rounds from a zero error
+state): rounds 0..W-1 are the warm-up, rounds W..W+K-1 are timed.  Prints ONE
+JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--mu MU]
 """
@@ -29,9 +31,16 @@ def algorithmic_bytes(N, d, k):
     return 12 * N * d + 4 * d + 28 * N * k
 
 
-def cpu_baseline(cfg, wl, rounds=2, workers=2):
+# HBM bytes per launch of the sweep kernel measured with rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE (two runs), scaled by what the same counters read for
+# the 1 GiB reference copy; see profiles/regtopk_round_large_cnn_hbm_traffic.txt.
+MEASURED_SWEEP_TRAFFIC = {"large_cnn": 5021082512}
+
+
+def cpu_baseline(cfg, wl, rounds=3, workers=None):
     """The oracle, unchanged, single-threaded, on a bounded sample: the first
     `workers` rows of the same workload for `rounds` rounds."""
+    workers = cfg.N if workers is None else workers
     import numpy as np
     import torch
     from oracle import oracle as orc
@@ -56,7 +65,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="large_cnn")
     ap.add_argument("--mu", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -84,6 +93,13 @@ def main():
     n_buf = min(args.warmup + args.steps, args.max_buffers)
     grads = [wl.grads(t) for t in range(n_buf)]
     torch.cuda.synchronize()
+
+    # one plain copy of known size (256 Mi floats: 1 GiB read, 1 GiB written): the
+    # reference dispatch for scaling hardware traffic counters when profiling
+    ref = torch.empty(2, 1 << 28, dtype=torch.float32, device=dev)
+    binding.copy_f32(ref[1], ref[0])
+    torch.cuda.synchronize()
+    del ref
 
     r = binding.RegTopk(N, d, k, cfg.mu, device=dev)
     r.set_option(binding.OPT_PROFILE, 1)
@@ -130,9 +146,10 @@ def main():
                      "round_events": round_ms_events},
         "dense_fallback_workers_last_round": dense_rounds,
         "candidates_last_round": [w["n_candidates"] for w in st],
-        "roofline": {"bound": "hbm", "kernel": "k_accum_emit (+k_begin)", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "k_accum_emit", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None},
+                     "algorithmic_bytes_per_launch": sweep_bytes, "avg_launch_ms": sweep_ms,
+                     "traffic": MEASURED_SWEEP_TRAFFIC.get(cfg.name)},
     }
     r.close()
     del grads

@@ -141,7 +141,7 @@ int regtopk_get_stats(regtopk_ctx* ctx, regtopk_worker_stats* stats_host, void* 
 int regtopk_set_option(regtopk_ctx* ctx, int option, double value);
 
 /* Stage times of the last n <= min(max_rounds, 64) profiled rounds, oldest
- * first, in milliseconds: out_host[4*i + 0] the dense sweep (accumulate + emit),
+ * first, in milliseconds: out_host[4*i + 0] the dense sweep kernel (accumulate + emit),
  * + 1 scoring and selection, + 2 compaction, error update and aggregation,
  * + 3 the whole round.  Waits for the recorded events. */
 int regtopk_get_timings(regtopk_ctx* ctx, float* out_host, int32_t max_rounds, int32_t* n_rounds);
@@ -150,6 +150,11 @@ int regtopk_get_timings(regtopk_ctx* ctx, float* out_host, int32_t max_rounds, i
  * x[i] >= 0 (device buffers of n floats).  Test hook for the exhaustive
  * comparison of that step. */
 int regtopk_tanh_f32(const float* x_dev, float* y_dev, int64_t n, void* stream);
+
+/* Plain copy dst[i] = src[i] of n floats by one kernel (n*4 bytes read, n*4
+ * written): the known-size reference dispatch against which hardware traffic
+ * counters are scaled when profiling. */
+int regtopk_copy_f32(float* dst_dev, const float* src_dev, int64_t n, void* stream);
 
 /* Text of the last error on the calling thread ("" if none). */
 const char* regtopk_last_error(void);

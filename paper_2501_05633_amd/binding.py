@@ -22,6 +22,7 @@ SYMBOLS = [
     "regtopk_workspace_bytes", "regtopk_create", "regtopk_create_in", "regtopk_step",
     "regtopk_destroy", "regtopk_reset", "regtopk_get_state", "regtopk_set_state",
     "regtopk_get_stats", "regtopk_set_option", "regtopk_get_timings", "regtopk_tanh_f32",
+    "regtopk_copy_f32",
     "regtopk_last_error",
 ]
 
@@ -69,6 +70,7 @@ def load():
     lib.regtopk_get_stats.argtypes = [c_void_p, ctypes.POINTER(WorkerStats), c_void_p]
     lib.regtopk_set_option.argtypes = [c_void_p, c_int, c_double]
     lib.regtopk_get_timings.argtypes = [c_void_p, ctypes.POINTER(c_float), c_int32, ctypes.POINTER(c_int32)]
+    lib.regtopk_copy_f32.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
     lib.regtopk_tanh_f32.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
     lib.regtopk_last_error.restype = c_char_p
     _lib = lib
@@ -221,6 +223,14 @@ class RegTopk:
         with self._torch.cuda.device(self.device):
             _check(self.lib.regtopk_get_stats(self._h, arr, _stream_ptr(self._torch)))
         return [{f: getattr(s, f) for f, _ in WorkerStats._fields_} for s in arr]
+
+
+def copy_f32(dst, src):
+    """Plain copy kernel of known size (reference dispatch for traffic counters)."""
+    import torch
+    with torch.cuda.device(src.device):
+        _check(load().regtopk_copy_f32(c_void_p(dst.data_ptr()), c_void_p(src.data_ptr()), src.numel(),
+                                       _stream_ptr(torch)))
 
 
 def tanh_f32(x):

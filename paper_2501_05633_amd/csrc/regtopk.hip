@@ -104,7 +104,7 @@ struct regtopk_ctx {
   int force_dense;
   float cand_target;
   bool profile;                 // record stage events in every step
-  hipEvent_t ev[kProfRounds][4];
+  hipEvent_t ev[kProfRounds][5];
   int64_t prof_rounds;          // steps recorded since profiling was switched on
   char* arena;
   Layout L;
@@ -275,8 +275,9 @@ int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* s
   const dim3 g_dense(db, N);
 
   hipEvent_t* ev = c->profile ? c->ev[c->prof_rounds % kProfRounds] : nullptr;
-  if (ev) HIP_TRY(hipEventRecord(ev[0], s));
+  if (ev) HIP_TRY(hipEventRecord(ev[4], s));
   k_begin<<<N, kBlock, 0, s>>>(ctl, c->force_dense);
+  if (ev) HIP_TRY(hipEventRecord(ev[0], s));
   if (vec)
     k_accum_emit<true><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   else
@@ -402,9 +403,18 @@ int regtopk_get_timings(regtopk_ctx* c, float* out, int32_t max_rounds, int32_t*
     HIP_TRY(hipEventElapsedTime(&out[i * 4 + 0], ev[0], ev[1]));
     HIP_TRY(hipEventElapsedTime(&out[i * 4 + 1], ev[1], ev[2]));
     HIP_TRY(hipEventElapsedTime(&out[i * 4 + 2], ev[2], ev[3]));
-    HIP_TRY(hipEventElapsedTime(&out[i * 4 + 3], ev[0], ev[3]));
+    HIP_TRY(hipEventElapsedTime(&out[i * 4 + 3], ev[4], ev[3]));
   }
   *n_rounds = (int32_t)have;
+  return REGTOPK_OK;
+}
+
+int regtopk_copy_f32(float* dst_dev, const float* src_dev, int64_t n, void* stream) {
+  if (n < 0 || (n > 0 && (!dst_dev || !src_dev))) return fail(REGTOPK_INVALID_ARG, "bad arguments");
+  if (n == 0) return REGTOPK_OK;
+  k_copy_u32<<<2048, 256, 0, static_cast<hipStream_t>(stream)>>>(reinterpret_cast<uint32_t*>(dst_dev),
+                                                                   reinterpret_cast<const uint32_t*>(src_dev), (size_t)n);
+  HIP_TRY(hipGetLastError());
   return REGTOPK_OK;
 }
 
