@@ -20,11 +20,13 @@
 //                   score exactly - from the boundary list held in LDS when the
 //                   window contains it, otherwise by a three-level radix select
 //                   over all candidates - and derives next round's bound/window
-//   k_dense_*       for workers whose speculation failed (and in round 0): exact
+//   k_dense_all     for workers whose speculation failed (and in round 0): exact
 //                   radix select of the 2k largest |a| (a superset of the true
 //                   top-k, see below), count, scan and an ordered emission of
-//                   exactly those entries as the candidate list; then k_score and
-//                   k_select run again for those workers
+//                   exactly those entries as the candidate list, then their
+//                   scores and the exact k-th score; one kernel with grid
+//                   barriers between its phases, which returns at once when no
+//                   worker is flagged
 //   k_chunk_count / k_chunk_scan / k_compact
 //                   ordered compaction of the selected (index, value) pairs,
 //                   lowest-index ties first; writes the round's mask (1 bit per
@@ -114,11 +116,11 @@ __device__ __forceinline__ uint32_t region_limit(const WorkerCtl& c, uint32_t r,
   return cur < cap_r ? cur : cap_r;
 }
 
-// Exclusive prefix sum over the 1024 threads of a block; *total gets the sum.
+// Exclusive prefix sum over the NT threads of a block; *total gets the sum.
 constexpr int kScanBlock = 1024;
 
-__device__ __forceinline__ uint32_t block_excl_scan_1024(uint32_t v, uint32_t* s_w /*[16]*/,
-                                                         uint32_t* total) {
+template <int NT>
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t* s_w /*[16]*/, uint32_t* total) {
   const uint32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   uint32_t x = v;
   for (int o = 1; o < 64; o <<= 1) {
@@ -128,16 +130,53 @@ __device__ __forceinline__ uint32_t block_excl_scan_1024(uint32_t v, uint32_t* s
   if (lane == 63) s_w[wv] = x;
   __syncthreads();
   uint32_t wb = 0, tot = 0;
-  for (uint32_t i = 0; i < 16; ++i) { const uint32_t t = s_w[i]; if (i < wv) wb += t; tot += t; }
+  for (uint32_t i = 0; i < NT / 64; ++i) { const uint32_t t = s_w[i]; if (i < wv) wb += t; tot += t; }
   __syncthreads();
   *total = tot;
   return wb + x - v;
 }
 
+// State shared by all workers of a context.
+struct GlobalCtl {
+  uint32_t any_dense;     // some worker needs the dense selection this round
+  uint32_t bar_count;     // grid barrier of the dense selection: arrivals
+  uint32_t bar_gen;       //   and generation
+  uint32_t bar_err;       // a barrier wait ran into its spin limit (reported as an error)
+  uint32_t pad[60];
+};
+
+// Barrier across the (co-resident) blocks of the dense-selection kernel.  Every
+// wait is bounded: after kBarrierSpinLimit polls a block gives up, records the
+// fact and carries on, so the grid always drains.
+constexpr uint32_t kBarrierSpinLimit = 1u << 22;
+
+__device__ __forceinline__ void grid_barrier(GlobalCtl* g, uint32_t nblocks) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __threadfence();
+    const uint32_t gen = __hip_atomic_load(&g->bar_gen, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t arrived = atomicAdd(&g->bar_count, 1u) + 1u;
+    if (arrived == nblocks) {
+      __hip_atomic_store(&g->bar_count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __threadfence();
+      atomicAdd(&g->bar_gen, 1u);
+    } else {
+      uint32_t spins = 0;
+      while (__hip_atomic_load(&g->bar_gen, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) == gen) {
+        __builtin_amdgcn_s_sleep(8);
+        if (++spins > kBarrierSpinLimit) { atomicOr(&g->bar_err, 1u); break; }
+      }
+    }
+  }
+  __syncthreads();
+  __threadfence();
+}
+
 // ---------------------------------------------------------------- k_begin ----
 __global__ void __launch_bounds__(kBlock)
-k_begin(WorkerCtl* ctl, int force_dense) {
+k_begin(WorkerCtl* ctl, GlobalCtl* gctl, int force_dense) {
   const uint32_t n = blockIdx.x, tid = threadIdx.x;
+  if (n == 0 && tid == 0) gctl->any_dense = 0;
   WorkerCtl& c = ctl[n];
   if (tid < kMaxRegions) c.cursor[tid] = 0;
   if (tid == 0) {
@@ -149,15 +188,6 @@ k_begin(WorkerCtl* ctl, int force_dense) {
     c.tau = 0; c.n_gt = 0; c.budget = 0; c.ties_total = 0;
     c.f_prefix = 0; c.f_krem = 0; c.f_tau = 0; c.f_budget = 0;
   }
-}
-
-// grid (N): clears the histograms of the dense selection for flagged workers.
-__global__ void __launch_bounds__(kBlock)
-k_dense_begin(const WorkerCtl* __restrict__ ctl, uint32_t* fhist) {
-  const uint32_t n = blockIdx.x, tid = threadIdx.x;
-  if (!ctl[n].need_dense) return;
-  uint32_t* fh = fhist + (size_t)n * 3 * kL1Bins;
-  for (uint32_t i = tid; i < 3 * kL1Bins; i += kBlock) fh[i] = 0;
 }
 
 // ----------------------------------------------------- chunk in registers ----
@@ -326,9 +356,26 @@ __device__ __forceinline__ float likelihood_sent(float a_now, float a_before, fl
   return tanh_f32_cr(x);
 }
 
+// Score bits of one candidate (index word `raw` with the sent flag, value a).
+__device__ __forceinline__ uint32_t score_entry(uint32_t raw, float a, int use_reg,
+                                                const uint32_t* __restrict__ mrow,
+                                                const uint32_t* __restrict__ rrow,
+                                                const float* __restrict__ pv,
+                                                const float* __restrict__ gprev, int64_t k, float w,
+                                                float mu) {
+  float f = 1.0f;
+  if (use_reg && (raw & kSentFlag)) {
+    // rank of j in the previous round's list: selected entries before its mask
+    // word plus the set bits below it inside the word
+    const uint32_t j = raw & ~kSentFlag;
+    const uint32_t rank = rrow[j >> 5] + (uint32_t)__popc(mrow[j >> 5] & ((1u << (j & 31)) - 1u));
+    if ((int64_t)rank < k) f = likelihood_sent(a, pv[rank], gprev[j], w, mu);
+  }
+  return __float_as_uint(__fmul_rn(fabsf(a), f));
+}
+
 // grid (ceil(cap_r/1024), regions, N): a block covers 1024 consecutive slots of
-// one region, four per thread.  only_dense: second invocation, for the workers
-// whose candidate list was rebuilt by the dense selection (no window then).
+// one region of the speculative candidate list, four per thread.
 constexpr int kScoreSlots = 1024;
 
 __global__ void __launch_bounds__(kBlock)
@@ -337,24 +384,20 @@ k_score(WorkerCtl* __restrict__ ctl, const int32_t* __restrict__ cand_idx,
         uint32_t* __restrict__ bnd_key, const uint32_t* __restrict__ mask,
         const uint32_t* __restrict__ rankbase, const float* __restrict__ prev_val,
         const float* __restrict__ gprev, int64_t d, int64_t k, uint32_t nc, uint32_t cap_r,
-        uint32_t cap_total, uint32_t bnd_cap, float w, float mu, int use_reg, int only_dense) {
+        uint32_t cap_total, uint32_t bnd_cap, float w, float mu, int use_reg) {
   __shared__ uint32_t s_stage[kScoreSlots];
   __shared__ uint32_t s_cnt[3];       // boundary entries, valid, above window
   __shared__ uint32_t s_base;
   const uint32_t n = blockIdx.z, r = blockIdx.y, tid = threadIdx.x;
   WorkerCtl& c = ctl[n];
-  if (only_dense && !c.need_dense) return;
-  if (!only_dense && c.overflow) return;      // list is incomplete; the dense selection rebuilds it
+  if (c.overflow) return;                     // list is incomplete; the dense selection rebuilds it
   const uint32_t lim = region_limit(c, r, cap_r);
   const uint32_t p0 = blockIdx.x * kScoreSlots;
   if (p0 >= lim) return;
-  const bool classify = !only_dense;
   const uint32_t tau_lo = c.tau_lo, win_lo = c.win_lo, win_hi = c.win_hi;
-  const bool windowed = classify && win_lo != kNoBound;
-  if (classify) {
-    if (tid < 3) s_cnt[tid] = 0;
-    __syncthreads();
-  }
+  const bool windowed = win_lo != kNoBound;
+  if (tid < 3) s_cnt[tid] = 0;
+  __syncthreads();
   const size_t cbase = (size_t)n * cap_total + (size_t)r * cap_r;
   const float* pv = prev_val + (size_t)n * k;
   const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
@@ -368,24 +411,14 @@ k_score(WorkerCtl* __restrict__ ctl, const int32_t* __restrict__ cand_idx,
     const uint32_t j = raw & ~kSentFlag;
     if ((int64_t)j >= d) continue;
     const float a = cand_val[cbase + p];
-    float f = 1.0f;
-    if (use_reg && (raw & kSentFlag)) {
-      // rank of j in the previous round's list: selected entries before its mask
-      // word plus the set bits below it inside the word
-      const uint32_t rank = rrow[j >> 5] + (uint32_t)__popc(mrow[j >> 5] & ((1u << (j & 31)) - 1u));
-      if ((int64_t)rank < k) f = likelihood_sent(a, pv[rank], gprev[j], w, mu);
-    }
-    const uint32_t key = __float_as_uint(__fmul_rn(fabsf(a), f));
+    const uint32_t key = score_entry(raw, a, use_reg, mrow, rrow, pv, gprev, k, w, mu);
     cand_key[cbase + p] = key;
-    if (classify) {
-      n_val += key >= tau_lo;
-      if (windowed) {
-        if (key >= win_hi) ++n_hi;
-        else if (key >= win_lo) s_stage[atomicAdd(&s_cnt[0], 1u)] = key;
-      }
+    n_val += key >= tau_lo;
+    if (windowed) {
+      if (key >= win_hi) ++n_hi;
+      else if (key >= win_lo) s_stage[atomicAdd(&s_cnt[0], 1u)] = key;
     }
   }
-  if (!classify) return;
   for (int o = 32; o > 0; o >>= 1) { n_val += __shfl_down(n_val, o); n_hi += __shfl_down(n_hi, o); }
   if ((tid & 63) == 0) {
     if (n_val) atomicAdd(&s_cnt[1], n_val);
@@ -414,26 +447,28 @@ struct RankHit { uint32_t bin, above; };   // bin == kNoBound: rank not reached
 
 // Descending search in an LDS histogram: the bin b with
 //   count(bins > b) < want <= count(bins >= b);  above = count(bins > b).
-// nbins in {16, 512, 4096}.  All 1024 threads call it.
+// nbins in {16, 512, 4096}.  All NT threads of the block call it.
+template <int NT>
 __device__ __forceinline__ RankHit find_rank_desc(const uint32_t* hist, uint32_t nbins, uint32_t want,
                                                   uint32_t* s_w, uint32_t* s_out) {
   const uint32_t tid = threadIdx.x;
-  const uint32_t per = nbins >= (uint32_t)kScanBlock ? nbins / kScanBlock : 1u;
-  uint32_t loc[4];
+  const uint32_t per = nbins >= (uint32_t)NT ? nbins / NT : 1u;
+  constexpr uint32_t kMaxPer = 4096 / NT;
+  uint32_t loc[kMaxPer];
   uint32_t s = 0;
 #pragma unroll
-  for (uint32_t q = 0; q < 4; ++q) {
+  for (uint32_t q = 0; q < kMaxPer; ++q) {
     const uint32_t i = tid * per + q;
     loc[q] = (q < per && i < nbins) ? hist[nbins - 1 - i] : 0u;
     s += loc[q];
   }
   if (tid == 0) { s_out[0] = kNoBound; s_out[1] = 0; }
   uint32_t total;
-  const uint32_t above = block_excl_scan_1024(s, s_w, &total);
+  const uint32_t above = block_excl_scan<NT>(s, s_w, &total);
   if (above < want && want <= above + s) {
     uint32_t run = above;
 #pragma unroll
-    for (uint32_t q = 0; q < 4; ++q) {
+    for (uint32_t q = 0; q < kMaxPer; ++q) {
       if (run < want && want <= run + loc[q]) { s_out[0] = nbins - 1 - (tid * per + q); s_out[1] = run; }
       run += loc[q];
     }
@@ -456,11 +491,11 @@ struct KeySource {
 
 // Calls f(key) for every key of the source; memory is read 128 bits at a time,
 // two loads in flight per thread.
-template <typename F>
+template <int NT, typename F>
 __device__ __forceinline__ void for_each_key(const KeySource& src, F f) {
   const uint32_t tid = threadIdx.x;
   if (src.lds) {
-    for (uint32_t i = tid; i < src.count; i += kScanBlock) f(src.lds[i]);
+    for (uint32_t i = tid; i < src.count; i += NT) f(src.lds[i]);
     return;
   }
   const uint32_t nseg = src.flat ? 1u : src.n_regions;
@@ -470,8 +505,8 @@ __device__ __forceinline__ void for_each_key(const KeySource& src, F f) {
     const uint4* b4 = reinterpret_cast<const uint4*>(base);
     const uint32_t n4 = lim / 4;
     uint32_t i = tid;
-    for (; i + kScanBlock < n4; i += 2 * kScanBlock) {
-      const uint4 x = b4[i], y = b4[i + kScanBlock];
+    for (; i + NT < n4; i += 2 * NT) {
+      const uint4 x = b4[i], y = b4[i + NT];
       f(x.x); f(x.y); f(x.z); f(x.w); f(y.x); f(y.y); f(y.z); f(y.w);
     }
     if (i < n4) { const uint4 x = b4[i]; f(x.x); f(x.y); f(x.z); f(x.w); }
@@ -486,6 +521,7 @@ __device__ __forceinline__ void for_each_key(const KeySource& src, F f) {
 // 3..0.  The fine first level spreads neighbouring scores over many bins, so
 // the LDS atomics rarely collide.  Returns tau; *budget = how many keys equal
 // to tau belong to the top `rank`; *ties = keys equal to tau.
+template <int NT>
 __device__ __forceinline__ uint32_t rel_select(const KeySource& src, uint32_t base, uint32_t rank,
                                                uint32_t* s_hist, uint32_t* s_w, uint32_t* s_out,
                                                uint32_t* budget, uint32_t* ties) {
@@ -493,20 +529,20 @@ __device__ __forceinline__ uint32_t rel_select(const KeySource& src, uint32_t ba
   uint32_t want = rank;
   RankHit ha{0u, 0u};
   for (int guard = 0; guard < 64; ++guard) {
-    for (uint32_t i = tid; i < kL1Bins; i += kScanBlock) s_hist[i] = 0;
+    for (uint32_t i = tid; i < kL1Bins; i += NT) s_hist[i] = 0;
     __syncthreads();
     uint32_t over = 0;
-    for_each_key(src, [&](uint32_t key) {
+    for_each_key<NT>(src, [&](uint32_t key) {
       if (key < base) return;
       const uint32_t rel = key - base;
       if (rel >> 25) ++over;
       else atomicAdd(&s_hist[rel >> 13], 1u);
     });
     uint32_t n_over;
-    (void)block_excl_scan_1024(over, s_w, &n_over);     // also orders the LDS atomics
+    (void)block_excl_scan<NT>(over, s_w, &n_over);     // also orders the LDS atomics
     if (want > n_over) {
       want -= n_over;
-      ha = find_rank_desc(s_hist, kL1Bins, want, s_w, s_out);
+      ha = find_rank_desc<NT>(s_hist, kL1Bins, want, s_w, s_out);
       break;
     }
     base += 1u << 25;                                   // the rank lies higher up
@@ -514,26 +550,26 @@ __device__ __forceinline__ uint32_t rel_select(const KeySource& src, uint32_t ba
   }
   want -= ha.above;
   const uint32_t pa = ha.bin;
-  for (uint32_t i = tid; i < 512; i += kScanBlock) s_hist[i] = 0;
+  for (uint32_t i = tid; i < 512; i += NT) s_hist[i] = 0;
   __syncthreads();
-  for_each_key(src, [&](uint32_t key) {
+  for_each_key<NT>(src, [&](uint32_t key) {
     if (key < base) return;
     const uint32_t rel = key - base;
     if ((rel >> 13) == pa) atomicAdd(&s_hist[(rel >> 4) & 511u], 1u);
   });
   __syncthreads();
-  const RankHit hb = find_rank_desc(s_hist, 512, want, s_w, s_out);
+  const RankHit hb = find_rank_desc<NT>(s_hist, 512, want, s_w, s_out);
   want -= hb.above;
   const uint32_t pb = (pa << 9) | hb.bin;
   if (tid < 16) s_hist[tid] = 0;
   __syncthreads();
-  for_each_key(src, [&](uint32_t key) {
+  for_each_key<NT>(src, [&](uint32_t key) {
     if (key < base) return;
     const uint32_t rel = key - base;
     if ((rel >> 4) == pb) atomicAdd(&s_hist[rel & 15u], 1u);
   });
   __syncthreads();
-  const RankHit hc = find_rank_desc(s_hist, 16, want, s_w, s_out);
+  const RankHit hc = find_rank_desc<NT>(s_hist, 16, want, s_w, s_out);
   *budget = want - hc.above;
   *ties = s_hist[hc.bin];
   return base + ((pb << 4) | hc.bin);
@@ -543,16 +579,15 @@ constexpr uint32_t kLdsKeys = 11264;    // boundary keys held in LDS (longer lis
 
 // SECOND = false: first invocation, all workers (validates the speculation).
 // SECOND = true : after the dense selection, flagged workers only.
-template <bool SECOND>
-__global__ void __launch_bounds__(kScanBlock)
-k_select(WorkerCtl* ctl, const uint32_t* __restrict__ cand_key, const uint32_t* __restrict__ bnd_key,
-         int64_t k, uint32_t cap_r, uint32_t cap_total, uint32_t regions, uint32_t bnd_cap,
-         float cand_target, int force_dense) {
-  __shared__ uint32_t s_hist[kL1Bins];
-  __shared__ uint32_t s_keys[kLdsKeys];
-  __shared__ uint32_t s_w[16];
-  __shared__ uint32_t s_out[2];
-  const uint32_t n = blockIdx.x, tid = threadIdx.x;
+template <bool SECOND, int NT>
+__device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, GlobalCtl* gctl,
+                                              const uint32_t* __restrict__ cand_key,
+                                              const uint32_t* __restrict__ bnd_key, int64_t k,
+                                              uint32_t cap_r, uint32_t cap_total, uint32_t regions,
+                                              uint32_t bnd_cap, float cand_target, int force_dense,
+                                              uint32_t* s_hist, uint32_t* s_keys, uint32_t* s_w,
+                                              uint32_t* s_out) {
+  const uint32_t tid = threadIdx.x;
   WorkerCtl& c = ctl[n];
   if (SECOND && !c.need_dense) return;
   const uint32_t K = (uint32_t)k;
@@ -560,7 +595,11 @@ k_select(WorkerCtl* ctl, const uint32_t* __restrict__ cand_key, const uint32_t* 
   if (!SECOND) {
     for (uint32_t r = 0; r < regions; ++r) n_tot += region_limit(c, r, cap_r);
     const bool need = force_dense || c.overflow || c.tau_lo == kNoBound || c.n_valid < K;
-    if (tid == 0) { c.n_cand = n_tot; c.need_dense = need ? 1u : 0u; }
+    if (tid == 0) {
+      c.n_cand = n_tot;
+      c.need_dense = need ? 1u : 0u;
+      if (need) atomicOr(&gctl->any_dense, 1u);
+    }
     if (need) return;
   } else {
     n_tot = c.dense_total;
@@ -578,8 +617,8 @@ k_select(WorkerCtl* ctl, const uint32_t* __restrict__ cand_key, const uint32_t* 
     // the k-th score lies inside the window: select among the boundary list only
     const uint32_t* list = bnd_key + (size_t)n * bnd_cap;
     src.count = n_bnd;
-    if (n_bnd <= kLdsKeys) {
-      for (uint32_t i = tid; i < n_bnd; i += kScanBlock) s_keys[i] = list[i];
+    if (s_keys != nullptr && n_bnd <= kLdsKeys) {
+      for (uint32_t i = tid; i < n_bnd; i += NT) s_keys[i] = list[i];
       src.lds = s_keys;
     } else {
       src.flat = list;
@@ -595,7 +634,7 @@ k_select(WorkerCtl* ctl, const uint32_t* __restrict__ cand_key, const uint32_t* 
   }
   __syncthreads();
   uint32_t budget, ties;
-  const uint32_t tau = rel_select(src, base, rank, s_hist, s_w, s_out, &budget, &ties);
+  const uint32_t tau = rel_select<NT>(src, base, rank, s_hist, s_w, s_out, &budget, &ties);
 
   if (tid == 0) {
     c.tau = tau;
@@ -662,22 +701,105 @@ k_select(WorkerCtl* ctl, const uint32_t* __restrict__ cand_key, const uint32_t* 
   }
 }
 
-// ---------------------------------------------------------- k_dense_hist ----
-// grid (blocks, N).  Histogram of the |a| bits of flagged workers' rows.
-template <int LEVEL>
-__global__ void __launch_bounds__(kBlock)
-k_dense_hist(const float* __restrict__ a, int64_t d, const WorkerCtl* __restrict__ ctl,
-             uint32_t* __restrict__ fhist) {
+// grid (N), 1024 threads: the first selection of a round, for all workers.
+__global__ void __launch_bounds__(kScanBlock)
+k_select(WorkerCtl* ctl, GlobalCtl* gctl, const uint32_t* __restrict__ cand_key,
+         const uint32_t* __restrict__ bnd_key, int64_t k, uint32_t cap_r, uint32_t cap_total,
+         uint32_t regions, uint32_t bnd_cap, float cand_target, int force_dense) {
   __shared__ uint32_t s_hist[kL1Bins];
-  const uint32_t n = blockIdx.y, tid = threadIdx.x;
-  const WorkerCtl& c = ctl[n];
-  if (!c.need_dense) return;
+  __shared__ uint32_t s_keys[kLdsKeys];
+  __shared__ uint32_t s_w[16];
+  __shared__ uint32_t s_out[2];
+  select_worker<false, kScanBlock>(blockIdx.x, ctl, gctl, cand_key, bnd_key, k, cap_r, cap_total, regions,
+                                   bnd_cap, cand_target, force_dense, s_hist, s_keys, s_w, s_out);
+}
+
+// ---------------------------------------------------------- k_chunk_scan ----
+// One block of NT threads per worker.  Exclusive scans over the chunks of one worker:
+//   tie_off[c] = ties before chunk c;
+//   sel[c]     = gt[c] + clamp(budget - tie_off[c], 0, tie[c])   (lowest-index ties first);
+//   sel_off[c] = selected entries before chunk c  (nc+1 values).
+// DENSE: budget = f_budget, sel_off/sel go to ch_off/ch_cnt (placement of the
+// dense emission) and dense_total.  Otherwise budget = ctl.budget, sel_off goes
+// to the round's sel_off table and the total is checked against k.  tie_off is
+// written in both cases.
+template <bool DENSE, int NT>
+__device__ __forceinline__ void chunk_scan_worker(uint32_t n, WorkerCtl* ctl,
+                                                  const uint32_t* __restrict__ ch_gt,
+                                                  const uint32_t* __restrict__ ch_tie,
+                                                  uint32_t* __restrict__ out_off,
+                                                  uint32_t* __restrict__ out_cnt,
+                                                  uint32_t* __restrict__ out_tieoff, uint32_t nc,
+                                                  int64_t k, uint32_t* s_w) {
+  const uint32_t tid = threadIdx.x;
+  WorkerCtl& c = ctl[n];
+  const uint32_t budget = DENSE ? c.f_budget : c.budget;
+  const uint32_t* gt = ch_gt + (size_t)n * nc;
+  const uint32_t* tie = ch_tie + (size_t)n * nc;
+  uint32_t* off = out_off + (size_t)n * (DENSE ? nc : nc + 1);
+  uint32_t* cnt = DENSE ? out_cnt + (size_t)n * nc : nullptr;
+  uint32_t* tof = out_tieoff + (size_t)n * nc;
+  uint32_t tie_run = 0, sel_run = 0;
+  for (uint32_t base = 0; base < nc; base += NT) {
+    const uint32_t ci = base + tid;
+    const uint32_t t = ci < nc ? tie[ci] : 0;
+    const uint32_t g = ci < nc ? gt[ci] : 0;
+    uint32_t ttot, stot;
+    const uint32_t toff = tie_run + block_excl_scan<NT>(t, s_w, &ttot);
+    uint32_t take = 0;
+    if (toff < budget) { take = budget - toff; if (take > t) take = t; }
+    const uint32_t sel = g + take;
+    const uint32_t soff = sel_run + block_excl_scan<NT>(sel, s_w, &stot);
+    if (ci < nc) {
+      off[ci] = soff;
+      tof[ci] = toff;
+      if (DENSE) cnt[ci] = sel;
+    }
+    tie_run += ttot;
+    sel_run += stot;
+  }
+  if (tid == 0) {
+    if (DENSE) c.dense_total = sel_run;
+    else {
+      off[nc] = sel_run;
+      if ((int64_t)sel_run != k) c.err |= 1u;
+    }
+  }
+}
+
+
+// grid (N), 1024 threads: the scan of the final compaction.
+__global__ void __launch_bounds__(kScanBlock)
+k_chunk_scan(WorkerCtl* ctl, const uint32_t* __restrict__ ch_gt, const uint32_t* __restrict__ ch_tie,
+             uint32_t* __restrict__ sel_off, uint32_t* __restrict__ tie_off, uint32_t nc, int64_t k) {
+  __shared__ uint32_t s_w[16];
+  chunk_scan_worker<false, kScanBlock>(blockIdx.x, ctl, ch_gt, ch_tie, sel_off, nullptr, tie_off, nc, k, s_w);
+}
+
+// ------------------------------------------------------------ dense path ----
+// The dense selection of the workers whose speculation failed (and of every
+// worker in round 0) runs as ONE kernel, k_dense_all, whose phases are
+// separated by grid barriers: when no worker is flagged - the usual case - the
+// whole path costs a single launch that returns at once.  The grid is sized by
+// the host so that all blocks are resident together.
+//
+// Phases, for flagged workers only:
+//   clear histograms | 3 x (histogram of |a| bits, pick the bin of rank
+//   min(2k,d)) | per-chunk counts | chunk scan | ordered emission of the 2k
+//   largest |a| as the candidate list | scores | exact k-th score.
+
+// Histogram level LEVEL of worker n's row; block b of G covers a strided share.
+template <int LEVEL>
+__device__ __forceinline__ void dense_hist_worker(uint32_t n, uint32_t b, uint32_t G, const float* a,
+                                                  int64_t d, const WorkerCtl* ctl, uint32_t* fhist,
+                                                  uint32_t* s_hist) {
+  const uint32_t tid = threadIdx.x;
   constexpr uint32_t bins = LEVEL == 1 ? kL1Bins : (LEVEL == 2 ? kL2Bins : kL3Bins);
   for (uint32_t i = tid; i < bins; i += kBlock) s_hist[i] = 0;
   __syncthreads();
-  const uint32_t prefix = c.f_prefix;
+  const uint32_t prefix = ctl[n].f_prefix;
   const float* row = a + (size_t)n * (size_t)d;
-  for (int64_t j = (int64_t)blockIdx.x * kBlock + tid; j < d; j += (int64_t)gridDim.x * kBlock) {
+  for (int64_t j = (int64_t)b * kBlock + tid; j < d; j += (int64_t)G * kBlock) {
     const uint32_t key = key_of(row[j]);
     if (LEVEL == 1) atomicAdd(&s_hist[key >> kL1Shift], 1u);
     else if (LEVEL == 2) { if ((key >> kL1Shift) == prefix) atomicAdd(&s_hist[(key >> kL2Shift) & (kL2Bins - 1)], 1u); }
@@ -689,22 +811,20 @@ k_dense_hist(const float* __restrict__ a, int64_t d, const WorkerCtl* __restrict
     const uint32_t v = s_hist[i];
     if (v) atomicAdd(&gh[i], v);
   }
+  __syncthreads();
 }
 
-// ---------------------------------------------------------- k_dense_scan ----
-// grid (N), one block per flagged worker.  Level LEVEL of the radix select of
-// rank min(2k, d) over the |a| bits: finds, from the top bin downwards, the bin
-// in which the cumulative count reaches the wanted rank.
+// Level LEVEL of the radix select of rank min(2k, d) over the |a| bits of worker
+// n: finds, from the top bin downwards, the bin in which the cumulative count
+// reaches the wanted rank.  One block.
 template <int LEVEL>
-__global__ void __launch_bounds__(kBlock)
-k_dense_scan(WorkerCtl* ctl, const uint32_t* __restrict__ hist_all, int64_t k, int64_t d) {
+__device__ __forceinline__ void dense_scan_worker(uint32_t n, WorkerCtl* ctl, const uint32_t* hist_all,
+                                                  int64_t k, int64_t d, uint32_t* s_sum,
+                                                  uint32_t* s_scan) {
   constexpr uint32_t bins = LEVEL == 1 ? kL1Bins : (LEVEL == 2 ? kL2Bins : kL3Bins);
   constexpr uint32_t per = bins / kBlock;            // bins per thread (16, 8, 1)
-  __shared__ uint32_t s_sum[kBlock];
-  __shared__ uint32_t s_scan[kBlock];
-  const uint32_t n = blockIdx.x, tid = threadIdx.x;
+  const uint32_t tid = threadIdx.x;
   WorkerCtl& c = ctl[n];
-  if (!c.need_dense) return;
   const uint32_t* h = hist_all + ((size_t)n * 3 + (LEVEL - 1)) * kL1Bins;
   uint32_t want;
   if (LEVEL == 1) want = (uint32_t)(2 * k < d ? 2 * k : d);
@@ -736,21 +856,17 @@ k_dense_scan(WorkerCtl* ctl, const uint32_t* __restrict__ hist_all, int64_t k, i
       run += loc[q];
     }
   }
+  __syncthreads();
 }
 
-// --------------------------------------------------------- k_dense_count ----
-// grid (min(nc, 1024), N), blocks stride over the chunks.  Per chunk: entries
-// with |a| bits > f_tau and == f_tau.
-__global__ void __launch_bounds__(kBlock)
-k_dense_count(const float* __restrict__ a, int64_t d, const WorkerCtl* __restrict__ ctl,
-              uint32_t* __restrict__ ch_gt, uint32_t* __restrict__ ch_tie, uint32_t nc) {
-  __shared__ uint32_t s_gt[4], s_tie[4];
-  const uint32_t n = blockIdx.y, tid = threadIdx.x;
-  const WorkerCtl& w = ctl[n];
-  if (!w.need_dense) return;
-  const uint32_t tau = w.f_tau;
+// Chunk c of worker n: entries with |a| bits > f_tau and == f_tau.
+__device__ __forceinline__ void dense_count_chunk(uint32_t n, uint32_t c, const float* a, int64_t d,
+                                                  const WorkerCtl* ctl, uint32_t* ch_gt,
+                                                  uint32_t* ch_tie, uint32_t nc, uint32_t* s_gt,
+                                                  uint32_t* s_tie) {
+  const uint32_t tid = threadIdx.x;
+  const uint32_t tau = ctl[n].f_tau;
   const float* row = a + (size_t)n * (size_t)d;
-  for (uint32_t c = blockIdx.x; c < nc; c += gridDim.x) {
   uint32_t gt = 0, tie = 0;
   for (int i = 0; i < 16; ++i) {
     const int64_t j = (int64_t)c * kChunk + i * kBlock + tid;
@@ -768,81 +884,22 @@ k_dense_count(const float* __restrict__ a, int64_t d, const WorkerCtl* __restric
     ch_tie[(size_t)n * nc + c] = s_tie[0] + s_tie[1] + s_tie[2] + s_tie[3];
   }
   __syncthreads();
-  }
 }
 
-// ---------------------------------------------------------- k_chunk_scan ----
-// grid (N), 1024 threads.  Exclusive scans over the chunks of one worker:
-//   tie_off[c] = ties before chunk c;
-//   sel[c]     = gt[c] + clamp(budget - tie_off[c], 0, tie[c])   (lowest-index ties first);
-//   sel_off[c] = selected entries before chunk c  (nc+1 values).
-// DENSE: budget = f_budget, sel_off/sel go to ch_off/ch_cnt (placement of the
-// dense emission) and dense_total.  Otherwise budget = ctl.budget, sel_off goes
-// to the round's sel_off table and the total is checked against k.  tie_off is
-// written in both cases.
-template <bool DENSE>
-__global__ void __launch_bounds__(kScanBlock)
-k_chunk_scan(WorkerCtl* ctl, const uint32_t* __restrict__ ch_gt, const uint32_t* __restrict__ ch_tie,
-             uint32_t* __restrict__ out_off, uint32_t* __restrict__ out_cnt,
-             uint32_t* __restrict__ out_tieoff, uint32_t nc, int64_t k) {
-  __shared__ uint32_t s_w[16];
-  const uint32_t n = blockIdx.x, tid = threadIdx.x;
-  WorkerCtl& c = ctl[n];
-  if (DENSE && !c.need_dense) return;
-  const uint32_t budget = DENSE ? c.f_budget : c.budget;
-  const uint32_t* gt = ch_gt + (size_t)n * nc;
-  const uint32_t* tie = ch_tie + (size_t)n * nc;
-  uint32_t* off = out_off + (size_t)n * (DENSE ? nc : nc + 1);
-  uint32_t* cnt = DENSE ? out_cnt + (size_t)n * nc : nullptr;
-  uint32_t* tof = out_tieoff + (size_t)n * nc;
-  uint32_t tie_run = 0, sel_run = 0;
-  for (uint32_t base = 0; base < nc; base += kScanBlock) {
-    const uint32_t ci = base + tid;
-    const uint32_t t = ci < nc ? tie[ci] : 0;
-    const uint32_t g = ci < nc ? gt[ci] : 0;
-    uint32_t ttot, stot;
-    const uint32_t toff = tie_run + block_excl_scan_1024(t, s_w, &ttot);
-    uint32_t take = 0;
-    if (toff < budget) { take = budget - toff; if (take > t) take = t; }
-    const uint32_t sel = g + take;
-    const uint32_t soff = sel_run + block_excl_scan_1024(sel, s_w, &stot);
-    if (ci < nc) {
-      off[ci] = soff;
-      tof[ci] = toff;
-      if (DENSE) cnt[ci] = sel;
-    }
-    tie_run += ttot;
-    sel_run += stot;
-  }
-  if (tid == 0) {
-    if (DENSE) c.dense_total = sel_run;
-    else {
-      off[nc] = sel_run;
-      if ((int64_t)sel_run != k) c.err |= 1u;
-    }
-  }
-}
-
-// ---------------------------------------------------------- k_dense_emit ----
-// grid (min(nc, 1024), N), blocks stride over the chunks.  Writes the 2k largest |a| (ties: lowest indices) of a flagged
-// worker as its candidate list, in index order, at the offsets of the scan.
+// Chunk c of worker n: writes its share of the 2k largest |a| (ties: lowest
+// indices) to the candidate list, in index order, at the offsets of the scan.
 template <bool VEC>
-__global__ void __launch_bounds__(kBlock)
-k_dense_emit(const float* __restrict__ a_rows, const uint32_t* __restrict__ mask, int64_t d,
-             WorkerCtl* __restrict__ ctl, int32_t* __restrict__ cand_idx, float* __restrict__ cand_val,
-             const uint32_t* __restrict__ ch_off, const uint32_t* __restrict__ ch_cnt,
-             const uint32_t* __restrict__ tie_off, uint32_t nc, uint32_t cap_total) {
-  __shared__ uint32_t s_wtot[4];
-  __shared__ uint32_t s_ttot[4];
-  const uint32_t n = blockIdx.y;
+__device__ __forceinline__ void dense_emit_chunk(uint32_t n, uint32_t c, const float* a_rows,
+                                                 const uint32_t* mask, int64_t d, const WorkerCtl* ctl,
+                                                 int32_t* cand_idx, float* cand_val,
+                                                 const uint32_t* ch_off, const uint32_t* ch_cnt,
+                                                 const uint32_t* tie_off, uint32_t nc,
+                                                 uint32_t cap_total, uint32_t* s_wtot, uint32_t* s_ttot) {
   const uint32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const WorkerCtl& w = ctl[n];
-  if (!w.need_dense) return;
   const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
-  for (uint32_t c = blockIdx.x; c < nc; c += gridDim.x) {
   const size_t tix = (size_t)n * nc + c;
-  if (ch_cnt[tix] == 0) continue;
-  const uint32_t tau = w.f_tau, budget = w.f_budget;
+  if (ch_cnt[tix] == 0) return;
+  const uint32_t tau = ctl[n].f_tau, budget = ctl[n].f_budget;
   const size_t row = (size_t)n * (size_t)d;
   const int64_t base = (int64_t)c * kChunk + (int64_t)wv * 1024 + lane * 4;
   float a[4][4];
@@ -900,7 +957,79 @@ k_dense_emit(const float* __restrict__ a_rows, const uint32_t* __restrict__ mask
     }
   }
   __syncthreads();
+}
+
+// grid (G): G blocks resident together.  See the section header.
+template <bool VEC>
+__global__ void __launch_bounds__(kBlock)
+k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* rankbase, int64_t d, WorkerCtl* ctl,
+            GlobalCtl* gctl, uint32_t* fhist, uint32_t* ch_gt, uint32_t* ch_tie, uint32_t* ch_off,
+            uint32_t* ch_cnt, uint32_t* tie_off, int32_t* cand_idx, float* cand_val, uint32_t* cand_key,
+            const uint32_t* bnd_key, const float* prev_val, const float* gprev, int64_t k, uint32_t nc,
+            int32_t N, uint32_t cap_r, uint32_t cap_total, uint32_t regions, uint32_t bnd_cap, float w,
+            float mu, int use_reg, float cand_target) {
+  if (gctl->any_dense == 0) return;
+  __shared__ uint32_t s_hist[kL1Bins];
+  __shared__ uint32_t s_a[kBlock], s_b[kBlock];
+  __shared__ uint32_t s_w[16], s_out[2], s_x[4], s_y[4];
+  const uint32_t b = blockIdx.x, G = gridDim.x, tid = threadIdx.x;
+
+  for (int32_t n = 0; n < N; ++n) {
+    if (!ctl[n].need_dense) continue;
+    uint32_t* fh = fhist + (size_t)n * 3 * kL1Bins;
+    for (uint32_t i = b * kBlock + tid; i < 3 * kL1Bins; i += G * kBlock) fh[i] = 0;
   }
+  grid_barrier(gctl, G);
+
+  for (int32_t n = 0; n < N; ++n)
+    if (ctl[n].need_dense) dense_hist_worker<1>(n, b, G, a_rows, d, ctl, fhist, s_hist);
+  grid_barrier(gctl, G);
+  for (int32_t n = b; n < N; n += G)
+    if (ctl[n].need_dense) dense_scan_worker<1>(n, ctl, fhist, k, d, s_a, s_b);
+  grid_barrier(gctl, G);
+  for (int32_t n = 0; n < N; ++n)
+    if (ctl[n].need_dense) dense_hist_worker<2>(n, b, G, a_rows, d, ctl, fhist, s_hist);
+  grid_barrier(gctl, G);
+  for (int32_t n = b; n < N; n += G)
+    if (ctl[n].need_dense) dense_scan_worker<2>(n, ctl, fhist, k, d, s_a, s_b);
+  grid_barrier(gctl, G);
+  for (int32_t n = 0; n < N; ++n)
+    if (ctl[n].need_dense) dense_hist_worker<3>(n, b, G, a_rows, d, ctl, fhist, s_hist);
+  grid_barrier(gctl, G);
+  for (int32_t n = b; n < N; n += G)
+    if (ctl[n].need_dense) dense_scan_worker<3>(n, ctl, fhist, k, d, s_a, s_b);
+  grid_barrier(gctl, G);
+
+  for (int32_t n = 0; n < N; ++n) {
+    if (!ctl[n].need_dense) continue;
+    for (uint32_t c = b; c < nc; c += G) dense_count_chunk(n, c, a_rows, d, ctl, ch_gt, ch_tie, nc, s_x, s_y);
+  }
+  grid_barrier(gctl, G);
+  for (int32_t n = b; n < N; n += G)
+    if (ctl[n].need_dense) chunk_scan_worker<true, kBlock>(n, ctl, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, nc, k, s_w);
+  grid_barrier(gctl, G);
+  for (int32_t n = 0; n < N; ++n) {
+    if (!ctl[n].need_dense) continue;
+    for (uint32_t c = b; c < nc; c += G)
+      dense_emit_chunk<VEC>(n, c, a_rows, mask, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, tie_off, nc, cap_total, s_x, s_y);
+  }
+  grid_barrier(gctl, G);
+
+  for (int32_t n = 0; n < N; ++n) {
+    if (!ctl[n].need_dense) continue;
+    const uint32_t total = ctl[n].dense_total;
+    const size_t cb = (size_t)n * cap_total;
+    const float* pv = prev_val + (size_t)n * k;
+    const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
+    const uint32_t* rrow = rankbase + (size_t)n * nc * kChunkWords;
+    for (uint32_t p = b * kBlock + tid; p < total; p += G * kBlock)
+      cand_key[cb + p] = score_entry((uint32_t)cand_idx[cb + p], cand_val[cb + p], use_reg, mrow, rrow, pv, gprev, k, w, mu);
+  }
+  grid_barrier(gctl, G);
+  for (int32_t n = b; n < N; n += G)
+    if (ctl[n].need_dense)
+      select_worker<true, kBlock>(n, ctl, gctl, cand_key, bnd_key, k, cap_r, cap_total, regions, bnd_cap,
+                                  cand_target, 0, s_hist, nullptr, s_w, s_out);
 }
 
 // --------------------------------------------------------- k_chunk_count ----

@@ -41,7 +41,7 @@ size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct Layout {
   uint32_t nc, regions, cap_r, cap_total, bnd_cap;
   size_t e, out_idx[2], out_val[2], agg[2], cand_idx, cand_val, cand_key;
-  size_t ch_off, ch_cnt, ch_gt, ch_tie, tie_off, sel_off, mask, rankbase, bnd_key, fhist, ctl, total;
+  size_t ch_off, ch_cnt, ch_gt, ch_tie, tie_off, sel_off, mask, rankbase, bnd_key, fhist, ctl, gctl, total;
 };
 
 bool valid_sizes(int32_t N, int64_t d, int64_t k) {
@@ -85,6 +85,7 @@ Layout make_layout(int32_t N, int64_t d, int64_t k) {
   L.bnd_key = take((size_t)N * L.bnd_cap * 4);
   L.fhist = take((size_t)N * 3 * kL1Bins * 4);
   L.ctl = take((size_t)N * sizeof(WorkerCtl));
+  L.gctl = take(sizeof(GlobalCtl));
   L.total = o;
   return L;
 }
@@ -101,6 +102,7 @@ struct regtopk_ctx {
   bool have_prev;       // a previous mask exists (round >= 1 or set_state with t >= 1)
   bool owns_arena;
   int device;
+  int dense_blocks;     // grid of the dense-selection kernel: all blocks resident together
   int force_dense;
   float cand_target;
   bool profile;                 // record stage events in every step
@@ -120,6 +122,7 @@ int zero_state(regtopk_ctx* c, hipStream_t s) {
   k_fill_u32<<<1024, 256, 0, s>>>(c->at<uint32_t>(c->L.mask), (size_t)c->N * c->L.nc * kChunkWords, 0u);
   k_fill_u32<<<1024, 256, 0, s>>>(c->at<uint32_t>(c->L.rankbase), (size_t)c->N * c->L.nc * kChunkWords, 0u);
   k_init_ctl<<<c->N, 256, 0, s>>>(c->at<WorkerCtl>(c->L.ctl));
+  k_fill_u32<<<1, 64, 0, s>>>(c->at<uint32_t>(c->L.gctl), sizeof(GlobalCtl) / 4, 0u);
   HIP_TRY(hipGetLastError());
   c->t = 0;
   c->have_prev = false;
@@ -141,6 +144,12 @@ int create_common(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu, 
   c->L = make_layout(N, d, k);
   (void)bytes;
   if (hipGetDevice(&c->device) != hipSuccess) { delete c; return fail(REGTOPK_HIP_ERROR, "hipGetDevice failed"); }
+  int cus = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess || cus < 1) {
+    delete c;
+    return fail(REGTOPK_HIP_ERROR, "cannot query the number of compute units");
+  }
+  c->dense_blocks = 2 * cus;      // 256-thread blocks with 20 KB of LDS: at least 8 fit on a compute unit
   int rc = zero_state(c, s);
   if (rc == REGTOPK_OK && hipStreamSynchronize(s) != hipSuccess) rc = fail(REGTOPK_HIP_ERROR, "zeroing the state failed");
   if (rc != REGTOPK_OK) { delete c; return rc; }
@@ -246,6 +255,7 @@ int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* s
   const bool vec = (d % 4 == 0) && (reinterpret_cast<uintptr_t>(grads) % 16 == 0);
 
   WorkerCtl* ctl = c->at<WorkerCtl>(L.ctl);
+  GlobalCtl* gctl = c->at<GlobalCtl>(L.gctl);
   float* e = c->at<float>(L.e);
   int32_t* cand_idx = c->at<int32_t>(L.cand_idx);
   float* cand_val = c->at<float>(L.cand_val);
@@ -267,46 +277,27 @@ int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* s
 
   const dim3 g_chunks(nc, N), g_waves((nc + 3) / 4, N);
   const dim3 g_score((L.cap_r + kScoreSlots - 1) / kScoreSlots, L.regions, N);
-  // the dense selection is rare: small grids that stride, so that the launches
-  // cost little when no worker needs them
-  const dim3 g_dense_chunks(nc < 1024 ? nc : 1024, N);
-  uint32_t db = (uint32_t)((d + kBlock * 16 - 1) / (kBlock * 16));
-  if (db > 1024) db = 1024;
-  const dim3 g_dense(db, N);
-
   hipEvent_t* ev = c->profile ? c->ev[c->prof_rounds % kProfRounds] : nullptr;
   if (ev) HIP_TRY(hipEventRecord(ev[4], s));
-  k_begin<<<N, kBlock, 0, s>>>(ctl, c->force_dense);
+  k_begin<<<N, kBlock, 0, s>>>(ctl, gctl, c->force_dense);
   if (ev) HIP_TRY(hipEventRecord(ev[0], s));
   if (vec)
     k_accum_emit<true><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   else
     k_accum_emit<false><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   if (ev) HIP_TRY(hipEventRecord(ev[1], s));
-  k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_key, bnd_key, mask, rankbase, prev_val, gprev, d, k, nc, L.cap_r, L.cap_total, L.bnd_cap, c->w, c->mu, use_reg, 0);
-  k_select<false><<<N, kScanBlock, 0, s>>>(ctl, cand_key, bnd_key, k, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->cand_target, c->force_dense);
-
-  // dense selection; every kernel returns at once for workers that do not need it
-  k_dense_begin<<<N, kBlock, 0, s>>>(ctl, fhist);
-  k_dense_hist<1><<<g_dense, kBlock, 0, s>>>(e, d, ctl, fhist);
-  k_dense_scan<1><<<N, kBlock, 0, s>>>(ctl, fhist, k, d);
-  k_dense_hist<2><<<g_dense, kBlock, 0, s>>>(e, d, ctl, fhist);
-  k_dense_scan<2><<<N, kBlock, 0, s>>>(ctl, fhist, k, d);
-  k_dense_hist<3><<<g_dense, kBlock, 0, s>>>(e, d, ctl, fhist);
-  k_dense_scan<3><<<N, kBlock, 0, s>>>(ctl, fhist, k, d);
-  k_dense_count<<<g_dense_chunks, kBlock, 0, s>>>(e, d, ctl, ch_gt, ch_tie, nc);
-  k_chunk_scan<true><<<N, kScanBlock, 0, s>>>(ctl, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, nc, k);
+  k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_key, bnd_key, mask, rankbase, prev_val, gprev, d, k, nc, L.cap_r, L.cap_total, L.bnd_cap, c->w, c->mu, use_reg);
+  k_select<<<N, kScanBlock, 0, s>>>(ctl, gctl, cand_key, bnd_key, k, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->cand_target, c->force_dense);
+  // dense selection for the workers whose speculation failed; returns at once if there is none
   if (vec)
-    k_dense_emit<true><<<g_dense_chunks, kBlock, 0, s>>>(e, mask, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, tie_off, nc, L.cap_total);
+    k_dense_all<true><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, rankbase, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->w, c->mu, use_reg, c->cand_target);
   else
-    k_dense_emit<false><<<g_dense_chunks, kBlock, 0, s>>>(e, mask, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, tie_off, nc, L.cap_total);
-  k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_key, bnd_key, mask, rankbase, prev_val, gprev, d, k, nc, L.cap_r, L.cap_total, L.bnd_cap, c->w, c->mu, use_reg, 1);
-  k_select<true><<<N, kScanBlock, 0, s>>>(ctl, cand_key, bnd_key, k, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->cand_target, c->force_dense);
+    k_dense_all<false><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, rankbase, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->w, c->mu, use_reg, c->cand_target);
 
   // ordered compaction, error update, aggregation
   if (ev) HIP_TRY(hipEventRecord(ev[2], s));
   k_chunk_count<<<g_waves, kBlock, 0, s>>>(ctl, cand_key, ch_off, ch_cnt, ch_gt, ch_tie, nc, L.cap_total);
-  k_chunk_scan<false><<<N, kScanBlock, 0, s>>>(ctl, ch_gt, ch_tie, sel_off, nullptr, tie_off, nc, k);
+  k_chunk_scan<<<N, kScanBlock, 0, s>>>(ctl, ch_gt, ch_tie, sel_off, tie_off, nc, k);
   k_compact<<<g_waves, kBlock, 0, s>>>(ctl, cand_key, cand_idx, cand_val, ch_off, ch_cnt, sel_off, tie_off, out_idx, out_val, mask, rankbase, k, nc, L.cap_total);
   k_aggregate<<<nc, kBlock, 0, s>>>(out_idx, out_val, sel_off, agg, d, k, nc, N, c->w);
   if (ev) { HIP_TRY(hipEventRecord(ev[3], s)); c->prof_rounds += 1; }
@@ -368,9 +359,11 @@ int regtopk_get_stats(regtopk_ctx* c, regtopk_worker_stats* st, void* stream) {
   if (!c || !st) return fail(REGTOPK_INVALID_ARG, "ctx and stats_host must not be NULL");
   hipStream_t s = static_cast<hipStream_t>(stream);
   std::vector<WorkerCtl> h((size_t)c->N);
+  GlobalCtl hg;
   HIP_TRY(hipMemcpyAsync(h.data(), c->at<WorkerCtl>(c->L.ctl), sizeof(WorkerCtl) * (size_t)c->N, hipMemcpyDeviceToHost, s));
+  HIP_TRY(hipMemcpyAsync(&hg, c->at<GlobalCtl>(c->L.gctl), sizeof(GlobalCtl), hipMemcpyDeviceToHost, s));
   HIP_TRY(hipStreamSynchronize(s));
-  uint32_t err = 0;
+  uint32_t err = hg.bar_err ? 4u : 0u;
   for (int32_t n = 0; n < c->N; ++n) {
     const WorkerCtl& w = h[(size_t)n];
     st[n].tau_lo_bits = w.tau_lo;
