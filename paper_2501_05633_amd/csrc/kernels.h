@@ -91,7 +91,8 @@ struct WorkerCtl {
   uint32_t centre;        // predicted k-th score of this round (window centre) or kNoBound
   uint32_t err_prev;      // |prediction error| of the previous round
   float margin_scale;     // widens the bound's safety margin after a failed speculation
-  uint32_t pad[5];
+  uint32_t extrapolated;  // this round's prediction used the drift of two earlier rounds
+  uint32_t pad[4];
   uint32_t cursor[kMaxRegions];
 };
 
@@ -656,15 +657,18 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
     int64_t centre = (int64_t)tau + drift;
     if (centre < 0) centre = 0;
     if (centre > 0x7F000000) centre = 0x7F000000;
-    // how far this round's prediction was off
-    uint32_t err = kWinDefaultHalf;
-    if (c.centre != kNoBound) err = tau > c.centre ? tau - c.centre : c.centre - tau;
-    else if (c.tau_prev != kNoBound) err = (uint32_t)(drift < 0 ? -drift : drift);
-    if (err < c.err_prev / 2) err = c.err_prev / 2;
+    // expected error of that prediction: how far this round's prediction was off
+    // if it was an extrapolation (two earlier rounds known), else half the drift
+    const uint32_t adrift = (uint32_t)(drift < 0 ? -drift : drift);
+    uint32_t err;
+    if (c.centre != kNoBound && c.extrapolated) err = tau > c.centre ? tau - c.centre : c.centre - tau;
+    else if (c.tau_prev != kNoBound) err = adrift / 2;
+    else err = kWinDefaultHalf;
+    if ((double)err < 0.7 * (double)c.err_prev) err = (uint32_t)(0.7 * (double)c.err_prev);
     double half = 3.0 * (double)err + 1024.0;
-    const double by_count = 2500.0 / dens;                 // aims at about 5000 boundary entries
+    const double by_count = 10000.0 / dens;                // at least about 20000 boundary entries
     if (half < by_count) half = by_count;
-    const double cap_half = (double)bnd_cap / (2.5 * dens);
+    const double cap_half = (double)bnd_cap / (4.0 * dens);
     if (half > cap_half) half = cap_half;
     if (half < (double)kWinMinHalf) half = (double)kWinMinHalf;
     if (half > (double)kWinMaxHalf) half = (double)kWinMaxHalf;
@@ -686,7 +690,7 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
     }
     c.margin_scale = ms;
     double margin = ((double)cand_target - 1.0) * (double)K / dens;
-    if (margin < 2.0 * (double)err + 1024.0) margin = 2.0 * (double)err + 1024.0;
+    if (margin < (double)err + 1024.0) margin = (double)err + 1024.0;
     margin *= (double)ms;
     if (margin > 16777216.0) margin = 16777216.0;
     const int64_t anchor = drift > 0 ? (int64_t)tau + drift / 2 : centre;
@@ -698,6 +702,7 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
     c.tau_prev = tau;
     c.centre = speculate ? (uint32_t)centre : kNoBound;
     c.err_prev = err;
+    c.extrapolated = (speculate && drift != 0) ? 1u : 0u;
   }
 }
 
@@ -712,6 +717,69 @@ k_select(WorkerCtl* ctl, GlobalCtl* gctl, const uint32_t* __restrict__ cand_key,
   __shared__ uint32_t s_out[2];
   select_worker<false, kScanBlock>(blockIdx.x, ctl, gctl, cand_key, bnd_key, k, cap_r, cap_total, regions,
                                    bnd_cap, cand_target, force_dense, s_hist, s_keys, s_w, s_out);
+}
+
+// -------------------------------------------------------------- sampling ----
+// A round that starts without a bound from the previous one (round 0, after a
+// reset or set_state) gets one from a strided sample of a = eps + g: the level-1
+// histogram of the sample, from which k_sample_bound takes the bin edge above
+// which about 1.6k entries of the whole row are expected.  The bound is only a
+// guess - the selection verifies it like any other and falls back to the dense
+// selection if it was wrong.
+constexpr uint32_t kSampleMax = 1u << 20;     // sampled entries per worker (whole row if shorter)
+
+// grid (blocks, N).  Sample i is the group of 4 entries at 4*i*stride4.
+__global__ void __launch_bounds__(kBlock)
+k_sample_hist(const float* __restrict__ e, const float* __restrict__ g, const uint32_t* __restrict__ mask,
+              int64_t d, uint32_t nc, uint32_t* __restrict__ shist, uint32_t n_groups, uint32_t stride4) {
+  __shared__ uint32_t s_hist[kL1Bins];
+  const uint32_t n = blockIdx.y, tid = threadIdx.x;
+  for (uint32_t i = tid; i < kL1Bins; i += kBlock) s_hist[i] = 0;
+  __syncthreads();
+  const size_t row = (size_t)n * (size_t)d;
+  const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
+  for (uint32_t i = blockIdx.x * kBlock + tid; i < n_groups; i += gridDim.x * kBlock) {
+    const int64_t j0 = (int64_t)i * stride4 * 4;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int64_t j = j0 + q;
+      if (j < d) {
+        const uint32_t sent = (mrow[j >> 5] >> (j & 31)) & 1u;
+        const float a = (sent ? 0.0f : e[row + j]) + g[row + j];
+        atomicAdd(&s_hist[key_of(a) >> kL1Shift], 1u);
+      }
+    }
+  }
+  __syncthreads();
+  uint32_t* gh = shist + (size_t)n * 3 * kL1Bins;
+  for (uint32_t i = tid; i < kL1Bins; i += kBlock) {
+    const uint32_t v = s_hist[i];
+    if (v) atomicAdd(&gh[i], v);
+  }
+}
+
+// grid (N), 1024 threads.  Sets this round's bound from the sample histogram.
+__global__ void __launch_bounds__(kScanBlock)
+k_sample_bound(WorkerCtl* ctl, const uint32_t* __restrict__ shist, int64_t d, int64_t k,
+               uint32_t n_sampled) {
+  __shared__ uint32_t s_hist[kL1Bins];
+  __shared__ uint32_t s_w[16];
+  __shared__ uint32_t s_out[2];
+  const uint32_t n = blockIdx.x, tid = threadIdx.x;
+  const uint32_t* gh = shist + (size_t)n * 3 * kL1Bins;
+  for (uint32_t i = tid; i < kL1Bins; i += kScanBlock) s_hist[i] = gh[i];
+  __syncthreads();
+  // sample rank that corresponds to about 1.6k entries of the row, plus four
+  // standard deviations of the sampling noise
+  const double frac = (double)n_sampled / (double)d;
+  double want = 1.6 * (double)k * frac;
+  want += 4.0 * sqrt(want) + 1.0;
+  const RankHit h = want < (double)n_sampled ? find_rank_desc<kScanBlock>(s_hist, kL1Bins, (uint32_t)want, s_w, s_out)
+                                            : RankHit{kNoBound, 0u};
+  if (tid == 0 && h.bin != kNoBound && h.bin > 0) {
+    ctl[n].tau_lo = h.bin << kL1Shift;
+    ctl[n].win_lo = kNoBound;
+  }
 }
 
 // ---------------------------------------------------------- k_chunk_scan ----
@@ -789,7 +857,7 @@ k_chunk_scan(WorkerCtl* ctl, const uint32_t* __restrict__ ch_gt, const uint32_t*
 //   largest |a| as the candidate list | scores | exact k-th score.
 
 // Histogram level LEVEL of worker n's row; block b of G covers a strided share.
-template <int LEVEL>
+template <int LEVEL, bool VEC>
 __device__ __forceinline__ void dense_hist_worker(uint32_t n, uint32_t b, uint32_t G, const float* a,
                                                   int64_t d, const WorkerCtl* ctl, uint32_t* fhist,
                                                   uint32_t* s_hist) {
@@ -799,11 +867,21 @@ __device__ __forceinline__ void dense_hist_worker(uint32_t n, uint32_t b, uint32
   __syncthreads();
   const uint32_t prefix = ctl[n].f_prefix;
   const float* row = a + (size_t)n * (size_t)d;
-  for (int64_t j = (int64_t)b * kBlock + tid; j < d; j += (int64_t)G * kBlock) {
-    const uint32_t key = key_of(row[j]);
+  auto put = [&](float v) {
+    const uint32_t key = key_of(v);
     if (LEVEL == 1) atomicAdd(&s_hist[key >> kL1Shift], 1u);
     else if (LEVEL == 2) { if ((key >> kL1Shift) == prefix) atomicAdd(&s_hist[(key >> kL2Shift) & (kL2Bins - 1)], 1u); }
     else { if ((key >> kL2Shift) == prefix) atomicAdd(&s_hist[key & (kL3Bins - 1)], 1u); }
+  };
+  if (VEC) {
+    const float4* row4 = reinterpret_cast<const float4*>(row);
+    const int64_t d4 = d / 4;
+    for (int64_t j = (int64_t)b * kBlock + tid; j < d4; j += (int64_t)G * kBlock) {
+      const float4 v = row4[j];
+      put(v.x); put(v.y); put(v.z); put(v.w);
+    }
+  } else {
+    for (int64_t j = (int64_t)b * kBlock + tid; j < d; j += (int64_t)G * kBlock) put(row[j]);
   }
   __syncthreads();
   uint32_t* gh = fhist + ((size_t)n * 3 + (LEVEL - 1)) * kL1Bins;
@@ -860,6 +938,7 @@ __device__ __forceinline__ void dense_scan_worker(uint32_t n, WorkerCtl* ctl, co
 }
 
 // Chunk c of worker n: entries with |a| bits > f_tau and == f_tau.
+template <bool VEC>
 __device__ __forceinline__ void dense_count_chunk(uint32_t n, uint32_t c, const float* a, int64_t d,
                                                   const WorkerCtl* ctl, uint32_t* ch_gt,
                                                   uint32_t* ch_tie, uint32_t nc, uint32_t* s_gt,
@@ -868,12 +947,25 @@ __device__ __forceinline__ void dense_count_chunk(uint32_t n, uint32_t c, const 
   const uint32_t tau = ctl[n].f_tau;
   const float* row = a + (size_t)n * (size_t)d;
   uint32_t gt = 0, tie = 0;
-  for (int i = 0; i < 16; ++i) {
-    const int64_t j = (int64_t)c * kChunk + i * kBlock + tid;
-    if (j < d) {
-      const uint32_t key = key_of(row[j]);
-      gt += key > tau;
-      tie += key == tau;
+  if (VEC) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int64_t j = (int64_t)c * kChunk + (i * kBlock + tid) * 4;
+      if (j < d) {
+        const float4 v = *reinterpret_cast<const float4*>(row + j);
+        const uint32_t k0 = key_of(v.x), k1 = key_of(v.y), k2 = key_of(v.z), k3 = key_of(v.w);
+        gt += (k0 > tau) + (k1 > tau) + (k2 > tau) + (k3 > tau);
+        tie += (k0 == tau) + (k1 == tau) + (k2 == tau) + (k3 == tau);
+      }
+    }
+  } else {
+    for (int i = 0; i < 16; ++i) {
+      const int64_t j = (int64_t)c * kChunk + i * kBlock + tid;
+      if (j < d) {
+        const uint32_t key = key_of(row[j]);
+        gt += key > tau;
+        tie += key == tau;
+      }
     }
   }
   for (int o = 32; o > 0; o >>= 1) { gt += __shfl_down(gt, o); tie += __shfl_down(tie, o); }
@@ -982,19 +1074,19 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* rankbase,
   grid_barrier(gctl, G);
 
   for (int32_t n = 0; n < N; ++n)
-    if (ctl[n].need_dense) dense_hist_worker<1>(n, b, G, a_rows, d, ctl, fhist, s_hist);
+    if (ctl[n].need_dense) dense_hist_worker<1, VEC>(n, b, G, a_rows, d, ctl, fhist, s_hist);
   grid_barrier(gctl, G);
   for (int32_t n = b; n < N; n += G)
     if (ctl[n].need_dense) dense_scan_worker<1>(n, ctl, fhist, k, d, s_a, s_b);
   grid_barrier(gctl, G);
   for (int32_t n = 0; n < N; ++n)
-    if (ctl[n].need_dense) dense_hist_worker<2>(n, b, G, a_rows, d, ctl, fhist, s_hist);
+    if (ctl[n].need_dense) dense_hist_worker<2, VEC>(n, b, G, a_rows, d, ctl, fhist, s_hist);
   grid_barrier(gctl, G);
   for (int32_t n = b; n < N; n += G)
     if (ctl[n].need_dense) dense_scan_worker<2>(n, ctl, fhist, k, d, s_a, s_b);
   grid_barrier(gctl, G);
   for (int32_t n = 0; n < N; ++n)
-    if (ctl[n].need_dense) dense_hist_worker<3>(n, b, G, a_rows, d, ctl, fhist, s_hist);
+    if (ctl[n].need_dense) dense_hist_worker<3, VEC>(n, b, G, a_rows, d, ctl, fhist, s_hist);
   grid_barrier(gctl, G);
   for (int32_t n = b; n < N; n += G)
     if (ctl[n].need_dense) dense_scan_worker<3>(n, ctl, fhist, k, d, s_a, s_b);
@@ -1002,7 +1094,7 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* rankbase,
 
   for (int32_t n = 0; n < N; ++n) {
     if (!ctl[n].need_dense) continue;
-    for (uint32_t c = b; c < nc; c += G) dense_count_chunk(n, c, a_rows, d, ctl, ch_gt, ch_tie, nc, s_x, s_y);
+    for (uint32_t c = b; c < nc; c += G) dense_count_chunk<VEC>(n, c, a_rows, d, ctl, ch_gt, ch_tie, nc, s_x, s_y);
   }
   grid_barrier(gctl, G);
   for (int32_t n = b; n < N; n += G)

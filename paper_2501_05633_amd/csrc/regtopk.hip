@@ -81,7 +81,7 @@ Layout make_layout(int32_t N, int64_t d, int64_t k) {
   L.sel_off = take(((size_t)N * (L.nc + 1)) * 4);
   L.mask = take(nch * kChunkWords * 4);
   L.rankbase = take(nch * kChunkWords * 4);
-  L.bnd_cap = 65536;
+  L.bnd_cap = 262144;
   L.bnd_key = take((size_t)N * L.bnd_cap * 4);
   L.fhist = take((size_t)N * 3 * kL1Bins * 4);
   L.ctl = take((size_t)N * sizeof(WorkerCtl));
@@ -100,6 +100,7 @@ struct regtopk_ctx {
   float mu, w;
   int64_t t;
   bool have_prev;       // a previous mask exists (round >= 1 or set_state with t >= 1)
+  bool fresh;           // no bound carried over from a previous round: sample one
   bool owns_arena;
   int device;
   int dense_blocks;     // grid of the dense-selection kernel: all blocks resident together
@@ -126,6 +127,7 @@ int zero_state(regtopk_ctx* c, hipStream_t s) {
   HIP_TRY(hipGetLastError());
   c->t = 0;
   c->have_prev = false;
+  c->fresh = true;
   return REGTOPK_OK;
 }
 
@@ -149,7 +151,16 @@ int create_common(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu, 
     delete c;
     return fail(REGTOPK_HIP_ERROR, "cannot query the number of compute units");
   }
-  c->dense_blocks = 2 * cus;      // 256-thread blocks with 20 KB of LDS: at least 8 fit on a compute unit
+  // All blocks of the dense-selection kernel must be resident together (it
+  // synchronises them with grid barriers): stay one block per compute unit below
+  // what the occupancy calculator allows, at most 3 per unit.
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_dense_all<true>, kBlock, 0) != hipSuccess || per_cu < 1) {
+    delete c;
+    return fail(REGTOPK_HIP_ERROR, "cannot query the occupancy of the dense-selection kernel");
+  }
+  per_cu = per_cu - 1 < 1 ? 1 : (per_cu - 1 > 3 ? 3 : per_cu - 1);
+  c->dense_blocks = per_cu * cus;
   int rc = zero_state(c, s);
   if (rc == REGTOPK_OK && hipStreamSynchronize(s) != hipSuccess) rc = fail(REGTOPK_HIP_ERROR, "zeroing the state failed");
   if (rc != REGTOPK_OK) { delete c; return rc; }
@@ -280,6 +291,18 @@ int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* s
   hipEvent_t* ev = c->profile ? c->ev[c->prof_rounds % kProfRounds] : nullptr;
   if (ev) HIP_TRY(hipEventRecord(ev[4], s));
   k_begin<<<N, kBlock, 0, s>>>(ctl, gctl, c->force_dense);
+  if (c->fresh && !c->force_dense) {
+    // no bound from a previous round: take one from a strided sample of a = eps + g
+    const uint64_t groups_all = (uint64_t)((d + 3) / 4);
+    const uint32_t n_groups = (uint32_t)(groups_all < kSampleMax / 4 ? groups_all : kSampleMax / 4);
+    const uint32_t stride4 = (uint32_t)(groups_all / n_groups);
+    uint64_t n_sampled = (uint64_t)n_groups * 4;
+    if (n_sampled > (uint64_t)d) n_sampled = (uint64_t)d;
+    k_fill_u32<<<64, 256, 0, s>>>(fhist, (size_t)N * 3 * kL1Bins, 0u);
+    k_sample_hist<<<dim3((n_groups + 4 * kBlock - 1) / (4 * kBlock), N), kBlock, 0, s>>>(e, grads, mask, d, nc, fhist, n_groups, stride4);
+    k_sample_bound<<<N, kScanBlock, 0, s>>>(ctl, fhist, d, k, (uint32_t)n_sampled);
+  }
+  c->fresh = false;
   if (ev) HIP_TRY(hipEventRecord(ev[0], s));
   if (vec)
     k_accum_emit<true><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
@@ -337,6 +360,7 @@ int regtopk_set_state(regtopk_ctx* c, const float* e_dev, const int32_t* pidx_de
   k_init_ctl<<<c->N, 256, 0, s>>>(c->at<WorkerCtl>(c->L.ctl));     // no speculative bound: next round selects densely
   c->t = t;
   c->have_prev = t > 0;
+  c->fresh = true;
   if (t == 0) {
     k_fill_u32<<<1024, 256, 0, s>>>(c->at<uint32_t>(c->L.mask), (size_t)c->N * c->L.nc * kChunkWords, 0u);
     k_fill_u32<<<1024, 256, 0, s>>>(c->at<uint32_t>(c->L.rankbase), (size_t)c->N * c->L.nc * kChunkWords, 0u);

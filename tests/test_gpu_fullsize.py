@@ -29,7 +29,6 @@ def test_full_size_rounds(name, T):
     dense = [[w["used_dense"] for w in st] for st in stats]
     window = [[w["used_window"] for w in st] for st in stats]
     print("dense per round:", [sum(r) for r in dense], "window per round:", [sum(r) for r in window], flush=True)
-    assert all(x == 1 for x in dense[0])
     if name == "large_cnn":
         assert any(sum(r) == 0 for r in dense[1:])            # speculative rounds happened
         assert any(sum(r) == cfg.N for r in window)           # and the windowed selection

@@ -27,7 +27,8 @@ def test_tiny_config_all_rounds(mu):
     print("case tiny mu=%g" % mu, flush=True)
     stats, tol = run_both(cfg.N, cfg.d, cfg.k, mu, _wl_fn(cfg), cfg.T, label="tiny mu=%g" % mu)
     assert tol == 0
-    assert all(w["used_dense"] == 1 for w in stats[0])       # round 0 has no bound to speculate with
+    for st in stats:                                          # the speculation is either verified or replaced
+        assert all(w["used_dense"] == 1 or w["n_valid"] >= cfg.k for w in st)
 
 
 def test_linear_regression_closed_loop():
@@ -144,7 +145,7 @@ def test_state_roundtrip_and_reset():
     torch.cuda.synchronize()
     for x, y in zip(ra, rb):
         assert torch.equal(x, y)
-    assert all(w["used_dense"] == 1 for w in b.stats())      # no bound after set_state
+    assert all(w["used_window"] == 0 for w in b.stats())     # no history after set_state: sampled bound, no window
     a.reset()
     b.reset()
     g0 = wl.grads(0)
