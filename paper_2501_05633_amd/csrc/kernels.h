@@ -375,9 +375,9 @@ __device__ __forceinline__ uint32_t score_entry(uint32_t raw, float a, int use_r
   return __float_as_uint(__fmul_rn(fabsf(a), f));
 }
 
-// grid (ceil(cap_r/1024), regions, N): a block covers 1024 consecutive slots of
-// one region of the speculative candidate list, four per thread.
-constexpr int kScoreSlots = 1024;
+// grid (ceil(cap_r/4096), regions, N): a block covers 4096 consecutive slots of
+// one region of the speculative candidate list, sixteen per thread.
+constexpr int kScoreSlots = 4096;
 
 __global__ void __launch_bounds__(kBlock)
 k_score(WorkerCtl* __restrict__ ctl, const int32_t* __restrict__ cand_idx,
@@ -404,10 +404,10 @@ k_score(WorkerCtl* __restrict__ ctl, const int32_t* __restrict__ cand_idx,
   const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
   const uint32_t* rrow = rankbase + (size_t)n * nc * kChunkWords;
   uint32_t n_val = 0, n_hi = 0;
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {
+#pragma unroll 4
+  for (int q = 0; q < kScoreSlots / kBlock; ++q) {
     const uint32_t p = p0 + q * kBlock + tid;
-    if (p >= lim) continue;
+    if (p >= lim) break;
     const uint32_t raw = (uint32_t)cand_idx[cbase + p];
     const uint32_t j = raw & ~kSentFlag;
     if ((int64_t)j >= d) continue;
@@ -582,8 +582,8 @@ constexpr uint32_t kLdsKeys = 11264;    // boundary keys held in LDS (longer lis
 // SECOND = true : after the dense selection, flagged workers only.
 template <bool SECOND, int NT>
 __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, GlobalCtl* gctl,
-                                              const uint32_t* __restrict__ cand_key,
-                                              const uint32_t* __restrict__ bnd_key, int64_t k,
+                                              const uint32_t* cand_key,
+                                              const uint32_t* bnd_key, int64_t k,
                                               uint32_t cap_r, uint32_t cap_total, uint32_t regions,
                                               uint32_t bnd_cap, float cand_target, int force_dense,
                                               uint32_t* s_hist, uint32_t* s_keys, uint32_t* s_w,
@@ -791,13 +791,12 @@ k_sample_bound(WorkerCtl* ctl, const uint32_t* __restrict__ shist, int64_t d, in
 // dense emission) and dense_total.  Otherwise budget = ctl.budget, sel_off goes
 // to the round's sel_off table and the total is checked against k.  tie_off is
 // written in both cases.
+// (No __restrict__ here and in select_worker: inside k_dense_all these arrays
+// are written by other blocks in the phase before.)
 template <bool DENSE, int NT>
-__device__ __forceinline__ void chunk_scan_worker(uint32_t n, WorkerCtl* ctl,
-                                                  const uint32_t* __restrict__ ch_gt,
-                                                  const uint32_t* __restrict__ ch_tie,
-                                                  uint32_t* __restrict__ out_off,
-                                                  uint32_t* __restrict__ out_cnt,
-                                                  uint32_t* __restrict__ out_tieoff, uint32_t nc,
+__device__ __forceinline__ void chunk_scan_worker(uint32_t n, WorkerCtl* ctl, const uint32_t* ch_gt,
+                                                  const uint32_t* ch_tie, uint32_t* out_off,
+                                                  uint32_t* out_cnt, uint32_t* out_tieoff, uint32_t nc,
                                                   int64_t k, uint32_t* s_w) {
   const uint32_t tid = threadIdx.x;
   WorkerCtl& c = ctl[n];
@@ -807,25 +806,37 @@ __device__ __forceinline__ void chunk_scan_worker(uint32_t n, WorkerCtl* ctl,
   uint32_t* off = out_off + (size_t)n * (DENSE ? nc : nc + 1);
   uint32_t* cnt = DENSE ? out_cnt + (size_t)n * nc : nullptr;
   uint32_t* tof = out_tieoff + (size_t)n * nc;
-  uint32_t tie_run = 0, sel_run = 0;
-  for (uint32_t base = 0; base < nc; base += NT) {
-    const uint32_t ci = base + tid;
-    const uint32_t t = ci < nc ? tie[ci] : 0;
-    const uint32_t g = ci < nc ? gt[ci] : 0;
-    uint32_t ttot, stot;
-    const uint32_t toff = tie_run + block_excl_scan<NT>(t, s_w, &ttot);
+  // every thread owns a contiguous run of chunks: two block scans in all
+  const uint32_t per = (nc + NT - 1) / NT;
+  const uint32_t c0 = tid * per < nc ? tid * per : nc;
+  const uint32_t c1 = c0 + per < nc ? c0 + per : nc;
+  uint32_t tsum = 0;
+  for (uint32_t ci = c0; ci < c1; ++ci) tsum += tie[ci];
+  uint32_t ttot, stot;
+  const uint32_t tbase = block_excl_scan<NT>(tsum, s_w, &ttot);
+  uint32_t trun = tbase, ssum = 0;
+  for (uint32_t ci = c0; ci < c1; ++ci) {
+    const uint32_t t = tie[ci];
     uint32_t take = 0;
-    if (toff < budget) { take = budget - toff; if (take > t) take = t; }
-    const uint32_t sel = g + take;
-    const uint32_t soff = sel_run + block_excl_scan<NT>(sel, s_w, &stot);
-    if (ci < nc) {
-      off[ci] = soff;
-      tof[ci] = toff;
-      if (DENSE) cnt[ci] = sel;
-    }
-    tie_run += ttot;
-    sel_run += stot;
+    if (trun < budget) { take = budget - trun; if (take > t) take = t; }
+    ssum += gt[ci] + take;
+    trun += t;
   }
+  const uint32_t sbase = block_excl_scan<NT>(ssum, s_w, &stot);
+  trun = tbase;
+  uint32_t srun = sbase;
+  for (uint32_t ci = c0; ci < c1; ++ci) {
+    const uint32_t t = tie[ci];
+    uint32_t take = 0;
+    if (trun < budget) { take = budget - trun; if (take > t) take = t; }
+    const uint32_t sel = gt[ci] + take;
+    off[ci] = srun;
+    tof[ci] = trun;
+    if (DENSE) cnt[ci] = sel;
+    trun += t;
+    srun += sel;
+  }
+  const uint32_t sel_run = stot;
   if (tid == 0) {
     if (DENSE) c.dense_total = sel_run;
     else {
@@ -1234,7 +1245,7 @@ k_compact(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ cand_k
 // chunk's selected entries of all 32 are first staged in LDS with independent
 // loads (so memory latency is paid once per batch), then applied to the tile
 // one worker after the other.
-constexpr uint32_t kAggStage = 2048;
+constexpr uint32_t kAggStage = 1024;
 
 __global__ void __launch_bounds__(kBlock)
 k_aggregate(const int32_t* __restrict__ out_idx, const float* __restrict__ out_val,
