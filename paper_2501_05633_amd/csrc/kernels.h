@@ -241,7 +241,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 template <bool VEC>
 __global__ void __launch_bounds__(kBlock)
 k_accum_emit(float* __restrict__ e, const float* __restrict__ g, const uint32_t* __restrict__ mask,
-             int64_t d, WorkerCtl* __restrict__ ctl, int32_t* __restrict__ cand_idx,
+             const uint32_t* __restrict__ prev_sel_off, int64_t d, WorkerCtl* __restrict__ ctl,
+             int32_t* __restrict__ cand_idx,
              float* __restrict__ cand_val, uint32_t* __restrict__ ch_off,
              uint32_t* __restrict__ ch_cnt, uint32_t nc, uint32_t cap_r, uint32_t cap_total,
              uint32_t regions) {
@@ -255,12 +256,14 @@ k_accum_emit(float* __restrict__ e, const float* __restrict__ g, const uint32_t*
   float a[4][4];
   uint32_t flags = 0;
   // previous round's mask: the 4 bits of entries j0..j0+3 lie in one word
+  // (chunks from which nothing was sent have no mask bits: their words are not read)
   const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
+  const bool sent_any = prev_sel_off[(size_t)n * (nc + 1) + c + 1] != prev_sel_off[(size_t)n * (nc + 1) + c];
   uint32_t mb[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int64_t j0 = base + i * 256;
-    mb[i] = j0 < d ? (mrow[j0 >> 5] >> (j0 & 31)) & 15u : 0u;
+    mb[i] = (sent_any && j0 < d) ? (mrow[j0 >> 5] >> (j0 & 31)) & 15u : 0u;
   }
   if (VEC) {
     f32x4 ev[4], gv[4];
@@ -1188,9 +1191,10 @@ __global__ void __launch_bounds__(kBlock)
 k_compact(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ cand_key,
           const int32_t* __restrict__ cand_idx, const float* __restrict__ cand_val,
           const uint32_t* __restrict__ ch_off, const uint32_t* __restrict__ ch_cnt,
-          const uint32_t* __restrict__ sel_off, const uint32_t* __restrict__ tie_off,
-          int32_t* __restrict__ out_idx, float* __restrict__ out_val, uint32_t* __restrict__ mask,
-          uint32_t* __restrict__ rankbase, int64_t k, uint32_t nc, uint32_t cap_total) {
+          const uint32_t* __restrict__ sel_off, const uint32_t* __restrict__ prev_sel_off,
+          const uint32_t* __restrict__ tie_off, int32_t* __restrict__ out_idx,
+          float* __restrict__ out_val, uint32_t* __restrict__ mask, uint32_t* __restrict__ rankbase,
+          int64_t k, uint32_t nc, uint32_t cap_total) {
   __shared__ uint32_t s_m[4][kChunkWords];
   const uint32_t n = blockIdx.y, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const uint32_t c = blockIdx.x * 4 + wv;
@@ -1233,15 +1237,23 @@ k_compact(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ cand_k
   }
   __syncthreads();
   if (live) {
-    const size_t wbase = ((size_t)n * nc + c) * kChunkWords;
-    write_chunk_mask(s_m[wv], first, mask + wbase, rankbase + wbase);
+    // a chunk without selected entries in the previous round has all-zero mask
+    // words already: nothing to write if it has none now either
+    const size_t so = (size_t)n * (nc + 1) + c;
+    const bool was_empty = prev_sel_off[so + 1] == prev_sel_off[so];
+    const bool is_empty = sel_off[so + 1] == first;
+    if (!(was_empty && is_empty)) {
+      const size_t wbase = ((size_t)n * nc + c) * kChunkWords;
+      write_chunk_mask(s_m[wv], first, mask + wbase, rankbase + wbase);
+    }
   }
 }
 
 // ----------------------------------------------------------- k_aggregate ----
 // grid (nc).  agg tile of 4096 entries: +0, then + w*val of every worker in
 // ascending worker order (indices of one worker are distinct, so plain LDS
-// read-modify-write), written once.  Workers are taken 32 at a time: the
+// read-modify-write), written once (tiles that are zero and already hold zeros
+// are left alone).  Workers are taken 32 at a time: the
 // chunk's selected entries of all 32 are first staged in LDS with independent
 // loads (so memory latency is paid once per batch), then applied to the tile
 // one worker after the other.
@@ -1249,8 +1261,8 @@ constexpr uint32_t kAggStage = 1024;
 
 __global__ void __launch_bounds__(kBlock)
 k_aggregate(const int32_t* __restrict__ out_idx, const float* __restrict__ out_val,
-            const uint32_t* __restrict__ sel_off, float* __restrict__ agg, int64_t d, int64_t k,
-            uint32_t nc, int32_t N, float w) {
+            const uint32_t* __restrict__ sel_off, float* __restrict__ agg,
+            uint32_t* __restrict__ agg_hot, int64_t d, int64_t k, uint32_t nc, int32_t N, float w) {
   __shared__ float s_tile[kChunk];
   __shared__ uint32_t s_j[kAggStage];
   __shared__ float s_v[kAggStage];
@@ -1258,6 +1270,7 @@ k_aggregate(const int32_t* __restrict__ out_idx, const float* __restrict__ out_v
   const uint32_t c = blockIdx.x, tid = threadIdx.x;
   for (uint32_t i = tid; i < kChunk; i += kBlock) s_tile[i] = 0.0f;
   const int32_t jbase = (int32_t)(c << kChunkLog);
+  uint32_t any_entries = 0;
   for (int32_t b0 = 0; b0 < N; b0 += 32) {
     const int32_t nb = N - b0 < 32 ? N - b0 : 32;
     __syncthreads();                                  // previous batch applied, s_* free
@@ -1275,6 +1288,7 @@ k_aggregate(const int32_t* __restrict__ out_idx, const float* __restrict__ out_v
     }
     __syncthreads();
     const uint32_t total = s_pre[nb];
+    any_entries |= total;
     for (uint32_t q0 = 0; q0 < total; q0 += kAggStage) {   // usually one pass
       const uint32_t q1 = q0 + kAggStage < total ? q0 + kAggStage : total;
       for (uint32_t q = q0 + tid; q < q1; q += kBlock) {
@@ -1299,6 +1313,11 @@ k_aggregate(const int32_t* __restrict__ out_idx, const float* __restrict__ out_v
     }
   }
   __syncthreads();
+  // agg_hot[c] tells whether this tile of the output buffer holds anything but
+  // zeros: a tile no worker selected from is only written if it has to be cleared
+  const uint32_t was_hot = agg_hot[c];
+  if (!any_entries && !was_hot) return;
+  if (tid == 0) agg_hot[c] = any_entries ? 1u : 0u;
   const int64_t j0 = (int64_t)c * kChunk;
   if (j0 + kChunk <= d && (d % 4) == 0) {
     for (uint32_t i = tid * 4; i < kChunk; i += kBlock * 4)
@@ -1333,7 +1352,7 @@ __global__ void k_init_ctl(WorkerCtl* ctl) {
 // grid (ceil(nc/4), N): one wave per chunk.
 __global__ void __launch_bounds__(kBlock)
 k_build_mask(const int32_t* __restrict__ pidx, uint32_t* __restrict__ mask,
-             uint32_t* __restrict__ rankbase, int64_t k, uint32_t nc) {
+             uint32_t* __restrict__ rankbase, uint32_t* __restrict__ sel_off, int64_t k, uint32_t nc) {
   __shared__ uint32_t s_m[4][kChunkWords];
   const uint32_t n = blockIdx.y, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const uint32_t c = blockIdx.x * 4 + wv;
@@ -1348,6 +1367,10 @@ k_build_mask(const int32_t* __restrict__ pidx, uint32_t* __restrict__ mask,
     int64_t lo = 0, hi = k;
     while (lo < hi) { const int64_t mid = (lo + hi) >> 1; if ((int64_t)pi[mid] < t0) lo = mid + 1; else hi = mid; }
     first = (uint32_t)lo;
+    if (lane == 0) {
+      sel_off[(size_t)n * (nc + 1) + c] = first;
+      if (c == nc - 1) sel_off[(size_t)n * (nc + 1) + nc] = (uint32_t)k;
+    }
     for (int64_t p = lo + lane; p < k; p += 64) {
       const int64_t j = pi[p];
       if (j >= t1 || j < t0) break;
