@@ -729,7 +729,7 @@ k_select(WorkerCtl* ctl, GlobalCtl* gctl, const uint32_t* __restrict__ cand_key,
 // which about 1.6k entries of the whole row are expected.  The bound is only a
 // guess - the selection verifies it like any other and falls back to the dense
 // selection if it was wrong.
-constexpr uint32_t kSampleMax = 1u << 20;     // sampled entries per worker (whole row if shorter)
+constexpr uint32_t kSampleMax = 1u << 18;     // sampled entries per worker (whole row if shorter)
 
 // grid (blocks, N).  Sample i is the group of 4 entries at 4*i*stride4.
 __global__ void __launch_bounds__(kBlock)
