@@ -250,3 +250,33 @@ def test_argument_checks():
                 (2, 10, 1, float("nan"))):
         with pytest.raises(ValueError):
             oracle.Oracle(*bad)
+
+
+def test_masks_of_different_workers_coordinate_under_the_regulariser():
+    # Appendix "Comparing Sparsification Masks": with RegTop-k the workers, who all
+    # see the same previous aggregate, end up dropping the same entries, whereas
+    # Top-k workers sparsify independently.  Setting of the paper's linear
+    # regression (N = 20, J = 100, D_n = 500, eta = 1e-2, U = 0, sigma^2 = 5,
+    # h^2 = 1, eps^2 = 0.5), S = 0.9, measured once the iterates are near the optimum.
+    N, J, D, eta, k = 20, 100, 500, 1e-2, 90
+    rng = np.random.default_rng(0)
+    X = rng.standard_normal((N, D, J))
+    u = rng.normal(0.0, np.sqrt(5.0), N)
+    truth = u[:, None] + rng.standard_normal((N, J))
+    y = np.einsum("ndj,nj->nd", X, truth) + np.sqrt(0.5) * rng.standard_normal((N, D))
+
+    def unanimous(mu):
+        o = oracle.Oracle(N, J, k, mu)
+        theta, agg, acc = np.zeros(J), None, []
+        for it in range(420):
+            r = np.einsum("ndj,j->nd", X, theta) - y
+            g = (2.0 / D) * np.einsum("ndj,nd->nj", X, r)
+            _, _, agg = o.step(g.astype(np.float32), agg)
+            theta = theta - eta * agg.astype(np.float64)
+            if it >= 380:
+                cnt = o.mask.sum(axis=0)
+                acc.append(int(((cnt == 0) | (cnt == N)).sum()))     # entries all workers agree on
+        return float(np.mean(acc))
+
+    assert unanimous(1.0) > 70          # most of the 100 entries are kept or dropped by all workers
+    assert unanimous(0.0) < 35          # plain Top-k: hardly any agreement
