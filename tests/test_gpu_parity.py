@@ -192,3 +192,79 @@ def test_error_codes():
     with pytest.raises(ValueError):
         r.step(g[:, :999].contiguous(), None)
     r.close()
+
+
+def test_scale_shocks_force_both_kinds_of_failed_speculation():
+    # The gradient scale collapses (bound too high: fewer than k valid candidates)
+    # and later explodes (bound too low: the candidate buffer overflows): both
+    # must end in the dense selection and still match the oracle exactly.
+    cfg = workloads.scaled(workloads.CONFIGS["large_cnn"], d=600_000, N=3, k=6_000)
+    wl = workloads.Workload(cfg, DEV)
+    scale = {4: 1e-3, 5: 1e-3, 7: 1e4, 8: 1e4}
+
+    def fn(t, agg):
+        return (wl.grads(t) * scale.get(t, 1.0)).contiguous()
+
+    stats, tol = run_both(3, 600_000, 6_000, 1.0, fn, 10, label="shock", check_state_every=3)
+    assert tol == 0
+    dense = _used_dense(stats)
+    print("dense per round:", dense, "overflow:", [[w["overflow"] for w in st] for st in stats], flush=True)
+    assert any(all(x == 1 for x in row) for row in dense[4:6])        # collapse -> too few valid candidates
+    assert any(w["overflow"] == 1 for st in stats[7:9] for w in st)   # explosion -> overflow
+    assert all(x == 0 for x in dense[-1]) or all(x == 0 for x in dense[-2])   # and it recovers
+
+
+def test_more_than_32_workers_and_odd_sizes():
+    # 33 workers (two batches in the aggregation), d a multiple of 4 but not of 4096
+    N, d, k = 33, 70_004, 350
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(99)
+    shared = torch.randn(d, generator=gen, device=DEV)
+
+    def fn(t, agg):
+        return (shared + torch.randn(N, d, generator=gen, device=DEV)).contiguous()
+
+    stats, tol = run_both(N, d, k, 1.0, fn, 5, label="N=33")
+    assert tol == 0
+
+
+def test_windowed_selection_with_many_ties_at_the_threshold():
+    # Values on a coarse grid that hardly change from round to round: the k-th
+    # score is predictable (windowed selection) and massively tied.
+    N, d, k = 2, 200_000, 3_000
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(3)
+    base = torch.randint(-40, 41, (N, d), generator=gen, device=DEV).float() * 0.25
+
+    def fn(t, agg):
+        return base.clone()
+
+    stats, tol = run_both(N, d, k, 1.0, fn, 8, label="grid ties")
+    assert tol == 0
+    print("window per round:", [[w["used_window"] for w in st] for st in stats],
+          "ties:", [[(w["n_ties_taken"], w["n_ties_total"]) for w in st] for st in stats], flush=True)
+
+
+def test_caller_owned_previous_aggregate_and_two_contexts_on_two_streams():
+    cfg = workloads.scaled(workloads.CONFIGS["large_cnn"], d=300_000, N=2, k=3_000)
+    wl = workloads.Workload(cfg, DEV)
+    ref = binding.RegTopk(2, 300_000, 3_000, 1.0, device=DEV)
+    a = binding.RegTopk(2, 300_000, 3_000, 1.0, device=DEV)
+    b = binding.RegTopk(2, 300_000, 3_000, 1.0, device=DEV)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    agg_ref = agg_a = agg_b = None
+    for t in range(5):
+        g = wl.grads(t)
+        torch.cuda.synchronize()
+        r0 = [x.clone() for x in ref.step(g, agg_ref)]
+        agg_ref = r0[2]
+        with torch.cuda.stream(sa):
+            ra = a.step(g, agg_a)
+            agg_a = ra[2].clone()          # a copy owned by the caller is handed back next round
+        with torch.cuda.stream(sb):
+            rb = b.step(g, agg_b)
+            agg_b = rb[2].clone()
+        torch.cuda.synchronize()
+        for x, y, z in zip(r0, ra, rb):
+            assert torch.equal(x, y) and torch.equal(x, z)
+    ref.close(); a.close(); b.close()
