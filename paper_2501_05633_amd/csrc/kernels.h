@@ -526,8 +526,9 @@ __device__ __forceinline__ void for_each_key(const KeySource& src, F f) {
 // the LDS atomics rarely collide.  Returns tau; *budget = how many keys equal
 // to tau belong to the top `rank`; *ties = keys equal to tau.
 template <int NT>
-__device__ __forceinline__ uint32_t rel_select(const KeySource& src, uint32_t base, uint32_t rank,
+__device__ __forceinline__ uint32_t rel_select(KeySource src, uint32_t base, uint32_t rank,
                                                uint32_t* s_hist, uint32_t* s_w, uint32_t* s_out,
+                                               uint32_t* s_stash, uint32_t stash_cap,
                                                uint32_t* budget, uint32_t* ties) {
   const uint32_t tid = threadIdx.x;
   uint32_t want = rank;
@@ -554,6 +555,22 @@ __device__ __forceinline__ uint32_t rel_select(const KeySource& src, uint32_t ba
   }
   want -= ha.above;
   const uint32_t pa = ha.bin;
+  // the keys of that bin are usually few: gather them in LDS once, so that the
+  // two finer levels need no further pass over memory
+  const uint32_t in_bin = s_hist[pa];
+  __syncthreads();
+  if (!src.lds && s_stash != nullptr && in_bin <= stash_cap) {
+    if (tid == 0) s_out[0] = 0;
+    __syncthreads();
+    for_each_key<NT>(src, [&](uint32_t key) {
+      if (key < base) return;
+      if (((key - base) >> 13) == pa) s_stash[atomicAdd(&s_out[0], 1u)] = key;
+    });
+    __syncthreads();
+    src.lds = s_stash;
+    src.count = in_bin;
+    __syncthreads();
+  }
   for (uint32_t i = tid; i < 512; i += NT) s_hist[i] = 0;
   __syncthreads();
   for_each_key<NT>(src, [&](uint32_t key) {
@@ -638,7 +655,9 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
   }
   __syncthreads();
   uint32_t budget, ties;
-  const uint32_t tau = rel_select<NT>(src, base, rank, s_hist, s_w, s_out, &budget, &ties);
+  // (the key buffer in LDS is free for the gathering unless it holds the boundary list)
+  uint32_t* stash = (s_keys != nullptr && src.lds == nullptr) ? s_keys : nullptr;
+  const uint32_t tau = rel_select<NT>(src, base, rank, s_hist, s_w, s_out, stash, kLdsKeys, &budget, &ties);
 
   if (tid == 0) {
     c.tau = tau;
