@@ -50,6 +50,9 @@ def _load():
         f.argtypes = [c.c_void_p]
     lib.rtk_oracle_round.restype = c.c_int64
     lib.rtk_oracle_round.argtypes = [c.c_void_p]
+    lib.rtk_oracle_set_weights.argtypes = [c.c_void_p, c.c_void_p]
+    lib.rtk_oracle_mask_overlap.argtypes = [c.c_void_p, c.c_void_p]
+    lib.rtk_oracle_sgd_update.argtypes = [c.c_void_p, c.c_void_p, c.c_float, c.c_int64]
     lib.rtk_oracle_tanh32.restype = c.c_float
     lib.rtk_oracle_tanh32.argtypes = [c.c_float]
     lib.rtk_oracle_likelihood_sent.restype = c.c_float
@@ -105,6 +108,19 @@ class Oracle:
                                   idx.ctypes.data, val.ctypes.data, agg.ctypes.data)
         return idx, val, agg
 
+    def set_weights(self, w):
+        """Aggregation weights omega_n, one per worker (default 1/N each)."""
+        ws = _f32(w)
+        if ws.shape != (self.N,):
+            raise ValueError("weights must be [N]")
+        self._lib.rtk_oracle_set_weights(self._h, ws.ctypes.data)
+
+    def mask_overlap(self) -> np.ndarray:
+        """counts[c] = number of entries selected by exactly c workers in the last round."""
+        counts = np.zeros(self.N + 1, dtype=np.int64)
+        self._lib.rtk_oracle_mask_overlap(self._h, counts.ctypes.data)
+        return counts
+
     def _view(self, name, dtype):
         p = getattr(self._lib, "rtk_oracle_" + name)(self._h)
         n = self.N * self.d
@@ -154,3 +170,13 @@ def topk_mask(score, k: int) -> np.ndarray:
     mask = np.empty(s.size, dtype=np.uint8)
     _load().rtk_oracle_topk_mask(s.ctypes.data, s.size, int(k), mask.ctypes.data)
     return mask
+
+
+def sgd_update(theta, g, eta: float) -> np.ndarray:
+    """theta - eta * g in binary32 (returns a new array)."""
+    th = _f32(theta).copy()
+    gg = _f32(g)
+    if th.shape != gg.shape or th.ndim != 1:
+        raise ValueError("theta and g must be vectors of one length")
+    _load().rtk_oracle_sgd_update(th.ctypes.data, gg.ctypes.data, float(np.float32(eta)), th.size)
+    return th

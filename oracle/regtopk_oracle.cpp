@@ -30,7 +30,10 @@
 // Readings where the paper leaves a choice (each is also listed in the design
 // document of the repository):
 //   R1  ties in Top_k: the lower index wins; always exactly k entries.
-//   R2  omega_n = 1/N for every worker, computed as 1.0f / (float)N.
+//   R2  omega_n = 1/N for every worker, computed as 1.0f / (float)N, unless
+//       the caller sets other weights (the paper's general aggregation
+//       g = sum_n omega_n g_n of the introduction); worker n then uses its own
+//       omega_n in the distortion, as Algorithm 2 writes it.
 //   R3  entries not sent in the previous round get the factor 1 exactly
 //       (C = 1, i.e. the Q -> infinity limit); Q is never formed.
 //   R4  omega * a^t == 0 in the denominator of the distortion: factor 1
@@ -56,7 +59,7 @@ struct Oracle {
     int32_t N;
     int64_t d, k;
     float mu;
-    float w;         // omega_n = 1/N  (R2)
+    std::vector<float> w;        // [N] aggregation weights omega_n (R2)
     int64_t t;       // rounds done so far
     std::vector<float> e;        // [N*d] sparsification error eps_n
     std::vector<float> a;        // [N*d] accumulated gradient of the last round
@@ -107,7 +110,7 @@ void* rtk_oracle_create(int32_t N, int64_t d, int64_t k, float mu) {
     if (N < 1 || d < 1 || k < 1 || k > d || !(mu >= 0.0f)) return nullptr;
     Oracle* o = new Oracle;
     o->N = N; o->d = d; o->k = k; o->mu = mu;
-    o->w = 1.0f / (float)N;
+    o->w.assign((size_t)N, 1.0f / (float)N);
     o->t = 0;
     size_t nd = (size_t)N * (size_t)d;
     o->e.assign(nd, 0.0f);           // eps^0 = 0
@@ -129,8 +132,9 @@ void rtk_oracle_step(void* h, const float* grads, const float* gprev,
                      int32_t* idx, float* val, float* agg) {
     Oracle* o = (Oracle*)h;
     const int64_t d = o->d, k = o->k;
-    const float w = o->w, mu = o->mu;
+    const float mu = o->mu;
     for (int32_t n = 0; n < o->N; ++n) {
+        const float w = o->w[(size_t)n];
         const size_t row = (size_t)n * (size_t)d;
         float* e = &o->e[row];
         float* a = &o->a[row];
@@ -159,10 +163,40 @@ void rtk_oracle_step(void* h, const float* grads, const float* gprev,
     }
     for (int64_t j = 0; j < d; ++j) {                        // server: g = sum_n w ghat_n (R8)
         float acc = 0.0f;
-        for (int32_t n = 0; n < o->N; ++n) acc = acc + w * o->ghat[(size_t)n * d + j];
+        for (int32_t n = 0; n < o->N; ++n) acc = acc + o->w[(size_t)n] * o->ghat[(size_t)n * d + j];
         agg[j] = acc;
     }
     o->t += 1;
+}
+
+// Aggregation weights omega_n (introduction, aggregation equation with general
+// weights).  They apply from the next round on, to the distortion of worker n
+// and to its term of the aggregate.
+void rtk_oracle_set_weights(void* h, const float* w) {
+    Oracle* o = (Oracle*)h;
+    for (int32_t n = 0; n < o->N; ++n) o->w[(size_t)n] = w[n];
+}
+
+// How far the masks of the last round agree (appendix "Comparing Sparsification
+// Masks"): counts[c], c = 0..N, is the number of entries j that exactly c
+// workers selected.
+void rtk_oracle_mask_overlap(void* h, int64_t* counts) {
+    Oracle* o = (Oracle*)h;
+    for (int32_t c = 0; c <= o->N; ++c) counts[c] = 0;
+    for (int64_t j = 0; j < o->d; ++j) {
+        int32_t c = 0;
+        for (int32_t n = 0; n < o->N; ++n) c += o->s[(size_t)n * o->d + j];
+        counts[c] += 1;
+    }
+}
+
+// Model update of distributed SGD (introduction): theta <- theta - eta * g,
+// binary32, the product rounded before the subtraction.
+void rtk_oracle_sgd_update(float* theta, const float* g, float eta, int64_t d) {
+    for (int64_t j = 0; j < d; ++j) {
+        float step = eta * g[j];
+        theta[j] = theta[j] - step;
+    }
 }
 
 // Read-only views for the tests (pointers stay valid until destroy).
