@@ -9,7 +9,7 @@
  *   2. the posterior-regularised selection score
  *        score_j = |a_j| * tanh(|1 + Delta_j| / mu)   for j sent in the previous round,
  *        score_j = |a_j|                              otherwise (constant C = 1),
- *        Delta_j = (gprev_j - w a^{t-1}_j) / (w a^t_j),  w = 1/N
+ *        Delta_j = (gprev_j - w a^{t-1}_j) / (w a^t_j),  w = omega_n (1/N unless set)
  *        (paper: posterior-distortion equation, label eq:Delta_def; likelihood
  *        with tanh in the section "RegTop-k Algorithm"; Algorithm 2 mask line);
  *   3. exact Top_k of the score, exactly k entries, the lower index winning
@@ -18,8 +18,9 @@
  *   4. compaction of the k (index, value) pairs, value = a_j, and the error
  *        update eps_n <- a_n - s_n (.) a_n (paper: last three lines of
  *        Algorithm 2);
- *   5. the server's aggregation g = sum_n w * ghat_n into a dense vector
- *        (paper: aggregation equation after Algorithm 1).
+ *   5. the server's aggregation g = sum_n omega_n * ghat_n into a dense vector
+ *        (paper: aggregation equation after Algorithm 1; omega_n = 1/N, computed
+ *        as 1.0f/(float)N, unless regtopk_set_weights gave other weights).
  *
  * Round 0 has no previous mask and is plain Top-k (first block of Algorithm 2).
  * mu == 0 switches the regulariser off in every round (Algorithm 1).
@@ -132,6 +133,28 @@ int regtopk_set_state(regtopk_ctx* ctx, const float* e_dev, const int32_t* pidx_
  * round into stats_host[0..N).  Returns REGTOPK_BAD_STATE if a device-side
  * consistency check failed (selected count != k, bad set_state input). */
 int regtopk_get_stats(regtopk_ctx* ctx, regtopk_worker_stats* stats_host, void* stream);
+
+/* Aggregation weights omega_n of the N workers (paper: weighted average
+ * g = sum_n omega_n g_n of the introduction; omega_n in the distortion line of
+ * Algorithm 2).  weights_host[0..N) is HOST memory, finite values; worker n
+ * uses omega_n both in its posterior distortion and in its term of the
+ * aggregate, from the next regtopk_step on.  Copies synchronously (waits for
+ * `stream`).  Weights survive regtopk_reset and set_state. */
+int regtopk_set_weights(regtopk_ctx* ctx, const float* weights_host, void* stream);
+
+/* Agreement of the workers' masks in the last completed round (paper: appendix
+ * subsection "Comparing Sparsification Masks"): counts_dev[c], c = 0..N, device
+ * memory of N+1 int64 (8-byte aligned), receives the number of entries j in
+ * [0,d) that exactly c workers selected; all d entries fall into c = 0 before
+ * the first round.  Enqueued on `stream`. */
+int regtopk_mask_overlap(regtopk_ctx* ctx, int64_t* counts_dev, void* stream);
+
+/* Model update of distributed SGD (paper: introduction, theta^{t+1} = theta^t -
+ * eta^t g^t): theta_dev[j] <- theta_dev[j] - eta * g_dev[j] for j in [0,d),
+ * binary32, the product rounded before the subtraction (no fused multiply-add).
+ * Device buffers of d floats that must not overlap; g_dev is read only.
+ * Enqueued on `stream`.  No context is needed. */
+int regtopk_sgd_update(float* theta_dev, const float* g_dev, float eta, int64_t d, void* stream);
 
 /* Options (tuning and test hooks). */
 #define REGTOPK_OPT_FORCE_DENSE   1  /* value != 0: never speculate, always run the dense selection */

@@ -22,7 +22,7 @@ SYMBOLS = [
     "regtopk_workspace_bytes", "regtopk_create", "regtopk_create_in", "regtopk_step",
     "regtopk_destroy", "regtopk_reset", "regtopk_get_state", "regtopk_set_state",
     "regtopk_get_stats", "regtopk_set_option", "regtopk_get_timings", "regtopk_tanh_f32",
-    "regtopk_copy_f32",
+    "regtopk_copy_f32", "regtopk_set_weights", "regtopk_mask_overlap", "regtopk_sgd_update",
     "regtopk_last_error",
 ]
 
@@ -72,6 +72,9 @@ def load():
     lib.regtopk_get_timings.argtypes = [c_void_p, ctypes.POINTER(c_float), c_int32, ctypes.POINTER(c_int32)]
     lib.regtopk_copy_f32.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
     lib.regtopk_tanh_f32.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
+    lib.regtopk_set_weights.argtypes = [c_void_p, ctypes.POINTER(c_float), c_void_p]
+    lib.regtopk_mask_overlap.argtypes = [c_void_p, c_void_p, c_void_p]
+    lib.regtopk_sgd_update.argtypes = [c_void_p, c_void_p, c_float, c_int64, c_void_p]
     lib.regtopk_last_error.restype = c_char_p
     _lib = lib
     return lib
@@ -178,6 +181,23 @@ class RegTopk:
         with self._torch.cuda.device(self.device):
             _check(self.lib.regtopk_reset(self._h, _stream_ptr(self._torch)))
 
+    def set_weights(self, weights):
+        """Aggregation weights omega_n (sequence of N floats; default 1/N each)."""
+        ws = [float(x) for x in weights]
+        if len(ws) != self.N:
+            raise ValueError("need N weights")
+        arr = (c_float * self.N)(*ws)
+        with self._torch.cuda.device(self.device):
+            _check(self.lib.regtopk_set_weights(self._h, arr, _stream_ptr(self._torch)))
+
+    def mask_overlap(self):
+        """int64 [N+1] CUDA tensor: entry c = number of indices that exactly c workers selected last round."""
+        torch = self._torch
+        counts = torch.empty(self.N + 1, dtype=torch.int64, device=self.device)
+        with torch.cuda.device(self.device):
+            _check(self.lib.regtopk_mask_overlap(self._h, c_void_p(counts.data_ptr()), _stream_ptr(torch)))
+        return counts
+
     def set_option(self, option: int, value: float):
         _check(self.lib.regtopk_set_option(self._h, option, float(value)))
 
@@ -241,3 +261,15 @@ def tanh_f32(x):
         _check(load().regtopk_tanh_f32(c_void_p(x.data_ptr()), c_void_p(y.data_ptr()), x.numel(),
                                        _stream_ptr(torch)))
     return y
+
+
+def sgd_update(theta, g, eta: float):
+    """theta <- theta - eta * g in place (CUDA float32 vectors of one length)."""
+    import torch
+    if theta.dtype != torch.float32 or g.dtype != torch.float32 or theta.shape != g.shape or theta.dim() != 1 \
+            or not theta.is_contiguous() or not g.is_contiguous() or theta.device != g.device:
+        raise ValueError("theta and g must be contiguous float32 vectors of one length on one device")
+    with torch.cuda.device(theta.device):
+        _check(load().regtopk_sgd_update(c_void_p(theta.data_ptr()), c_void_p(g.data_ptr()), float(eta),
+                                         theta.numel(), _stream_ptr(torch)))
+    return theta

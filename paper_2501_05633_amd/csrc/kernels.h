@@ -388,7 +388,7 @@ k_score(WorkerCtl* __restrict__ ctl, const int32_t* __restrict__ cand_idx,
         uint32_t* __restrict__ bnd_key, const uint32_t* __restrict__ mask,
         const uint32_t* __restrict__ rankbase, const float* __restrict__ prev_val,
         const float* __restrict__ gprev, int64_t d, int64_t k, uint32_t nc, uint32_t cap_r,
-        uint32_t cap_total, uint32_t bnd_cap, float w, float mu, int use_reg) {
+        uint32_t cap_total, uint32_t bnd_cap, const float* __restrict__ omega, float mu, int use_reg) {
   __shared__ uint32_t s_stage[kScoreSlots];
   __shared__ uint32_t s_cnt[3];       // boundary entries, valid, above window
   __shared__ uint32_t s_base;
@@ -406,6 +406,7 @@ k_score(WorkerCtl* __restrict__ ctl, const int32_t* __restrict__ cand_idx,
   const float* pv = prev_val + (size_t)n * k;
   const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
   const uint32_t* rrow = rankbase + (size_t)n * nc * kChunkWords;
+  const float w = omega[n];
   uint32_t n_val = 0, n_hi = 0;
 #pragma unroll 4
   for (int q = 0; q < kScoreSlots / kBlock; ++q) {
@@ -1091,8 +1092,8 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* rankbase,
             GlobalCtl* gctl, uint32_t* fhist, uint32_t* ch_gt, uint32_t* ch_tie, uint32_t* ch_off,
             uint32_t* ch_cnt, uint32_t* tie_off, int32_t* cand_idx, float* cand_val, uint32_t* cand_key,
             const uint32_t* bnd_key, const float* prev_val, const float* gprev, int64_t k, uint32_t nc,
-            int32_t N, uint32_t cap_r, uint32_t cap_total, uint32_t regions, uint32_t bnd_cap, float w,
-            float mu, int use_reg, float cand_target) {
+            int32_t N, uint32_t cap_r, uint32_t cap_total, uint32_t regions, uint32_t bnd_cap,
+            const float* omega, float mu, int use_reg, float cand_target) {
   if (gctl->any_dense == 0) return;
   __shared__ uint32_t s_hist[kL1Bins];
   __shared__ uint32_t s_a[kBlock], s_b[kBlock];
@@ -1147,6 +1148,7 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* rankbase,
     const float* pv = prev_val + (size_t)n * k;
     const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
     const uint32_t* rrow = rankbase + (size_t)n * nc * kChunkWords;
+    const float w = omega[n];
     for (uint32_t p = b * kBlock + tid; p < total; p += G * kBlock)
       cand_key[cb + p] = score_entry((uint32_t)cand_idx[cb + p], cand_val[cb + p], use_reg, mrow, rrow, pv, gprev, k, w, mu);
   }
@@ -1269,7 +1271,7 @@ k_compact(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ cand_k
 }
 
 // ----------------------------------------------------------- k_aggregate ----
-// grid (nc).  agg tile of 4096 entries: +0, then + w*val of every worker in
+// grid (nc).  agg tile of 4096 entries: +0, then + omega_n*val of every worker in
 // ascending worker order (indices of one worker are distinct, so plain LDS
 // read-modify-write), written once (tiles that are zero and already hold zeros
 // are left alone).  Workers are taken 32 at a time: the
@@ -1281,11 +1283,13 @@ constexpr uint32_t kAggStage = 1024;
 __global__ void __launch_bounds__(kBlock)
 k_aggregate(const int32_t* __restrict__ out_idx, const float* __restrict__ out_val,
             const uint32_t* __restrict__ sel_off, float* __restrict__ agg,
-            uint32_t* __restrict__ agg_hot, int64_t d, int64_t k, uint32_t nc, int32_t N, float w) {
+            uint32_t* __restrict__ agg_hot, int64_t d, int64_t k, uint32_t nc, int32_t N,
+            const float* __restrict__ omega) {
   __shared__ float s_tile[kChunk];
   __shared__ uint32_t s_j[kAggStage];
   __shared__ float s_v[kAggStage];
   __shared__ uint32_t s_s0[32], s_pre[33];
+  __shared__ float s_w[32];
   const uint32_t c = blockIdx.x, tid = threadIdx.x;
   for (uint32_t i = tid; i < kChunk; i += kBlock) s_tile[i] = 0.0f;
   const int32_t jbase = (int32_t)(c << kChunkLog);
@@ -1297,6 +1301,7 @@ k_aggregate(const int32_t* __restrict__ out_idx, const float* __restrict__ out_v
       const size_t o = (size_t)(b0 + tid) * (nc + 1) + c;
       const uint32_t a0 = sel_off[o];
       s_s0[tid] = a0;
+      s_w[tid] = omega[b0 + tid];
       s_pre[tid + 1] = sel_off[o + 1] - a0;            // length, turned into a prefix below
     }
     __syncthreads();
@@ -1322,6 +1327,7 @@ k_aggregate(const int32_t* __restrict__ out_idx, const float* __restrict__ out_v
         const uint32_t lo = s_pre[i] > q0 ? s_pre[i] : q0;
         const uint32_t hi = s_pre[i + 1] < q1 ? s_pre[i + 1] : q1;
         if (lo < hi) {                                 // uniform over the block
+          const float w = s_w[i];
           for (uint32_t q = lo + tid; q < hi; q += kBlock) {
             const uint32_t j = s_j[q - q0];
             if (j < (uint32_t)kChunk) s_tile[j] = __fadd_rn(s_tile[j], __fmul_rn(w, s_v[q - q0]));
@@ -1344,6 +1350,89 @@ k_aggregate(const int32_t* __restrict__ out_idx, const float* __restrict__ out_v
   } else {
     for (uint32_t i = tid; i < kChunk; i += kBlock)
       if (j0 + i < d) agg[j0 + i] = s_tile[i];
+  }
+}
+
+// -------------------------------------------------------- k_mask_overlap ----
+// counts[c] += number of entries that exactly c workers selected in the last
+// round.  A thread takes one mask word position (32 entries) and adds the N
+// workers' words as bit-sliced counters: plane b holds bit b of the 32 column
+// sums.  Entries nobody selected (the bulk) are counted by population count,
+// the others one by one.  grid-stride over the ceil(d/32) word positions.
+constexpr int kOverlapPlanes = 16;          // N <= 65535
+constexpr uint32_t kOverlapBins = 1024;     // LDS histogram when N + 1 fits
+
+__global__ void __launch_bounds__(kBlock)
+k_mask_overlap(const uint32_t* __restrict__ mask, int64_t d, uint32_t nc, int32_t N, int planes,
+               unsigned long long* __restrict__ counts) {
+  __shared__ uint32_t s_hist[kOverlapBins];
+  const uint32_t tid = threadIdx.x;
+  const bool lds = (uint32_t)N + 1u <= kOverlapBins;
+  if (lds) for (uint32_t i = tid; i <= (uint32_t)N; i += kBlock) s_hist[i] = 0;
+  __syncthreads();
+  const size_t row_words = (size_t)nc * kChunkWords;
+  const size_t nw = (size_t)((d + 31) / 32);
+  uint32_t zeros = 0;
+  for (size_t wd = (size_t)blockIdx.x * kBlock + tid; wd < nw; wd += (size_t)gridDim.x * kBlock) {
+    uint32_t p[kOverlapPlanes];
+#pragma unroll
+    for (int b = 0; b < kOverlapPlanes; ++b) p[b] = 0;
+    for (int32_t n = 0; n < N; ++n) {
+      uint32_t carry = mask[(size_t)n * row_words + wd];
+#pragma unroll
+      for (int b = 0; b < kOverlapPlanes; ++b) {
+        if (b < planes) { const uint32_t t = p[b] & carry; p[b] ^= carry; carry = t; }
+      }
+    }
+    const int64_t left = d - (int64_t)wd * 32;
+    const uint32_t valid = left >= 32 ? 0xFFFFFFFFu : ((1u << (uint32_t)left) - 1u);
+    uint32_t any = 0;
+#pragma unroll
+    for (int b = 0; b < kOverlapPlanes; ++b) any |= p[b];
+    zeros += (uint32_t)__popc(~any & valid);
+    uint32_t todo = any & valid;
+    while (todo) {
+      const uint32_t i = (uint32_t)__ffs(todo) - 1u;
+      todo &= todo - 1u;
+      uint32_t c = 0;
+#pragma unroll
+      for (int b = 0; b < kOverlapPlanes; ++b) c |= ((p[b] >> i) & 1u) << b;
+      if (lds) atomicAdd(&s_hist[c], 1u);
+      else atomicAdd(&counts[c], 1ull);
+    }
+  }
+  for (int o = 32; o > 0; o >>= 1) zeros += __shfl_down(zeros, o);
+  if ((tid & 63) == 0 && zeros) {
+    if (lds) atomicAdd(&s_hist[0], zeros);
+    else atomicAdd(&counts[0], (unsigned long long)zeros);
+  }
+  __syncthreads();
+  if (lds)
+    for (uint32_t i = tid; i <= (uint32_t)N; i += kBlock)
+      if (s_hist[i]) atomicAdd(&counts[i], (unsigned long long)s_hist[i]);
+}
+
+// ---------------------------------------------------------- k_sgd_update ----
+// theta <- theta - eta * g, the product rounded before the subtraction.
+template <bool VEC>
+__global__ void __launch_bounds__(kBlock)
+k_sgd_update(float* __restrict__ theta, const float* __restrict__ g, float eta, int64_t d) {
+  const int64_t stride = (int64_t)gridDim.x * kBlock;
+  if (VEC) {
+    const int64_t n4 = d / 4;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += stride) {
+      const f32x4 t = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(theta) + i);
+      const f32x4 x = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(g) + i);
+      f32x4 o;
+      o.x = __fsub_rn(t.x, __fmul_rn(eta, x.x));
+      o.y = __fsub_rn(t.y, __fmul_rn(eta, x.y));
+      o.z = __fsub_rn(t.z, __fmul_rn(eta, x.z));
+      o.w = __fsub_rn(t.w, __fmul_rn(eta, x.w));
+      __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(theta) + i);
+    }
+  } else {
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < d; i += stride)
+      theta[i] = __fsub_rn(theta[i], __fmul_rn(eta, g[i]));
   }
 }
 

@@ -41,7 +41,7 @@ size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct Layout {
   uint32_t nc, regions, cap_r, cap_total, bnd_cap;
   size_t e, out_idx[2], out_val[2], agg[2], cand_idx, cand_val, cand_key;
-  size_t ch_off, ch_cnt, ch_gt, ch_tie, tie_off, sel_off[2], agg_hot[2], mask, rankbase, bnd_key, fhist, ctl, gctl, total;
+  size_t ch_off, ch_cnt, ch_gt, ch_tie, tie_off, sel_off[2], agg_hot[2], mask, rankbase, bnd_key, fhist, ctl, gctl, omega, total;
 };
 
 bool valid_sizes(int32_t N, int64_t d, int64_t k) {
@@ -86,6 +86,7 @@ Layout make_layout(int32_t N, int64_t d, int64_t k) {
   L.fhist = take((size_t)N * 3 * kL1Bins * 4);
   L.ctl = take((size_t)N * sizeof(WorkerCtl));
   L.gctl = take(sizeof(GlobalCtl));
+  L.omega = take((size_t)N * 4);
   L.total = o;
   return L;
 }
@@ -97,7 +98,7 @@ constexpr int kProfRounds = 64;
 struct regtopk_ctx {
   int32_t N;
   int64_t d, k;
-  float mu, w;
+  float mu;
   int64_t t;
   bool have_prev;       // a previous mask exists (round >= 1 or set_state with t >= 1)
   bool fresh;           // no bound carried over from a previous round: sample one
@@ -140,7 +141,6 @@ int create_common(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu, 
   regtopk_ctx* c = new (std::nothrow) regtopk_ctx;
   if (!c) return fail(REGTOPK_NO_MEMORY, "out of host memory");
   c->N = N; c->d = d; c->k = k; c->mu = mu;
-  c->w = 1.0f / (float)N;
   c->owns_arena = owns;
   c->force_dense = 0;
   c->cand_target = 1.25f;
@@ -165,6 +165,7 @@ int create_common(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu, 
   }
   per_cu = per_cu - 1 < 1 ? 1 : (per_cu - 1 > 3 ? 3 : per_cu - 1);
   c->dense_blocks = per_cu * cus;
+  k_fill_u32<<<1, 256, 0, s>>>(c->at<uint32_t>(c->L.omega), (size_t)N, __builtin_bit_cast(uint32_t, 1.0f / (float)N));
   int rc = zero_state(c, s);
   if (rc == REGTOPK_OK && hipStreamSynchronize(s) != hipSuccess) rc = fail(REGTOPK_HIP_ERROR, "zeroing the state failed");
   if (rc != REGTOPK_OK) { delete c; return rc; }
@@ -291,6 +292,7 @@ int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* s
   uint32_t* agg_hot = c->at<uint32_t>(L.agg_hot[cur]);
   uint32_t* mask = c->at<uint32_t>(L.mask);
   uint32_t* rankbase = c->at<uint32_t>(L.rankbase);
+  const float* omega = c->at<float>(L.omega);
 
   const dim3 g_chunks(nc, N), g_waves((nc + 3) / 4, N);
   const dim3 g_score((L.cap_r + kScoreSlots - 1) / kScoreSlots, L.regions, N);
@@ -315,20 +317,20 @@ int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* s
   else
     k_accum_emit<false><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, prev_sel_off, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   if (ev) HIP_TRY(hipEventRecord(ev[1], s));
-  k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_key, bnd_key, mask, rankbase, prev_val, gprev, d, k, nc, L.cap_r, L.cap_total, L.bnd_cap, c->w, c->mu, use_reg);
+  k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_key, bnd_key, mask, rankbase, prev_val, gprev, d, k, nc, L.cap_r, L.cap_total, L.bnd_cap, omega, c->mu, use_reg);
   k_select<<<N, kScanBlock, 0, s>>>(ctl, gctl, cand_key, bnd_key, k, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->cand_target, c->force_dense);
   // dense selection for the workers whose speculation failed; returns at once if there is none
   if (vec)
-    k_dense_all<true><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, rankbase, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->w, c->mu, use_reg, c->cand_target);
+    k_dense_all<true><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, rankbase, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, omega, c->mu, use_reg, c->cand_target);
   else
-    k_dense_all<false><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, rankbase, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->w, c->mu, use_reg, c->cand_target);
+    k_dense_all<false><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, rankbase, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, omega, c->mu, use_reg, c->cand_target);
 
   // ordered compaction, error update, aggregation
   if (ev) HIP_TRY(hipEventRecord(ev[2], s));
   k_chunk_count<<<g_waves, kBlock, 0, s>>>(ctl, cand_key, ch_off, ch_cnt, ch_gt, ch_tie, nc, L.cap_total);
   k_chunk_scan<<<N, kScanBlock, 0, s>>>(ctl, ch_gt, ch_tie, sel_off, tie_off, nc, k);
   k_compact<<<g_waves, kBlock, 0, s>>>(ctl, cand_key, cand_idx, cand_val, ch_off, ch_cnt, sel_off, prev_sel_off, tie_off, out_idx, out_val, mask, rankbase, k, nc, L.cap_total);
-  k_aggregate<<<nc, kBlock, 0, s>>>(out_idx, out_val, sel_off, agg, agg_hot, d, k, nc, N, c->w);
+  k_aggregate<<<nc, kBlock, 0, s>>>(out_idx, out_val, sel_off, agg, agg_hot, d, k, nc, N, omega);
   if (ev) { HIP_TRY(hipEventRecord(ev[3], s)); c->prof_rounds += 1; }
   HIP_TRY(hipGetLastError());
 
@@ -413,6 +415,47 @@ int regtopk_get_stats(regtopk_ctx* c, regtopk_worker_stats* st, void* stream) {
     err |= w.err;
   }
   if (err) return fail(REGTOPK_BAD_STATE, "device-side check failed (flags 0x%x)", err);
+  return REGTOPK_OK;
+}
+
+int regtopk_set_weights(regtopk_ctx* c, const float* w_host, void* stream) {
+  if (!c || !w_host) return fail(REGTOPK_INVALID_ARG, "ctx and weights_host must not be NULL");
+  for (int32_t n = 0; n < c->N; ++n)
+    if (!std::isfinite(w_host[n])) return fail(REGTOPK_INVALID_ARG, "weight %d is not finite", n);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  HIP_TRY(hipMemcpyAsync(c->at<float>(c->L.omega), w_host, (size_t)c->N * 4, hipMemcpyHostToDevice, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  return REGTOPK_OK;
+}
+
+int regtopk_mask_overlap(regtopk_ctx* c, int64_t* counts_dev, void* stream) {
+  if (!c || !counts_dev) return fail(REGTOPK_INVALID_ARG, "ctx and counts_dev must not be NULL");
+  if (reinterpret_cast<uintptr_t>(counts_dev) % 8) return fail(REGTOPK_INVALID_ARG, "counts_dev must be 8-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int planes = 1;
+  while ((1 << planes) <= c->N) ++planes;             // column sums reach N
+  const size_t nw = (size_t)((c->d + 31) / 32);
+  size_t blocks = (nw + kBlock - 1) / kBlock;
+  if (blocks > 4096) blocks = 4096;
+  k_fill_u32<<<1, 256, 0, s>>>(reinterpret_cast<uint32_t*>(counts_dev), 2 * ((size_t)c->N + 1), 0u);
+  k_mask_overlap<<<(uint32_t)blocks, kBlock, 0, s>>>(c->at<uint32_t>(c->L.mask), c->d, c->L.nc, c->N, planes,
+                                                      reinterpret_cast<unsigned long long*>(counts_dev));
+  HIP_TRY(hipGetLastError());
+  return REGTOPK_OK;
+}
+
+int regtopk_sgd_update(float* theta_dev, const float* g_dev, float eta, int64_t d, void* stream) {
+  if (d < 0 || (d > 0 && (!theta_dev || !g_dev))) return fail(REGTOPK_INVALID_ARG, "bad arguments");
+  if (reinterpret_cast<uintptr_t>(theta_dev) % 4 || reinterpret_cast<uintptr_t>(g_dev) % 4)
+    return fail(REGTOPK_INVALID_ARG, "device pointers must be 4-byte aligned");
+  if (d == 0) return REGTOPK_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const bool vec = d % 4 == 0 && reinterpret_cast<uintptr_t>(theta_dev) % 16 == 0 && reinterpret_cast<uintptr_t>(g_dev) % 16 == 0;
+  int64_t blocks = ((vec ? d / 4 : d) + kBlock - 1) / kBlock;
+  if (blocks > 8192) blocks = 8192;
+  if (vec) k_sgd_update<true><<<(uint32_t)blocks, kBlock, 0, s>>>(theta_dev, g_dev, eta, d);
+  else k_sgd_update<false><<<(uint32_t)blocks, kBlock, 0, s>>>(theta_dev, g_dev, eta, d);
+  HIP_TRY(hipGetLastError());
   return REGTOPK_OK;
 }
 

@@ -167,3 +167,39 @@ class LinRegWorkload:
     def grads(self, theta: torch.Tensor) -> torch.Tensor:
         r = torch.einsum("nrd,d->nr", self.X, theta) - self.y
         return torch.einsum("nrd,nr->nd", self.X, r).contiguous()
+
+
+class PaperLinReg:
+    """The paper's own linear-regression experiment (section "Linear Regression
+    Problem"): N workers with D_n data points each in J dimensions, rows
+    x ~ N(0, I_J), a ground truth t_n ~ N(u_n, h^2 I_J) per worker with
+    u_n ~ N(U, sigma^2), labels y_n = X_n t_n + e_n, e_n ~ N(0, eps^2 I).
+    Local loss F_n = |X_n theta - y_n|^2 / D_n, so the local gradient is
+    (2/D_n) X_n^T (X_n theta - y_n); the global optimum has the closed form
+    [sum_n X_n^T X_n]^{-1} sum_n X_n^T y_n.  Defaults: the heterogeneous setting
+    of the optimality-gap figures (N=20, J=100, D_n=500, U=0, sigma^2=5, h^2=1,
+    eps^2=0.5, learning rate 1e-2)."""
+
+    def __init__(self, device="cpu", N=20, J=100, D=500, U=0.0, sigma2=5.0, h2=1.0, eps2=0.5,
+                 eta=1e-2, seed: int = BASE_SEED + 100):
+        self.device = torch.device(device)
+        self.N, self.J, self.D, self.eta = N, J, D, eta
+        g0 = torch.Generator(device="cpu")
+        g0.manual_seed(seed)
+        X = torch.randn(N, D, J, generator=g0, dtype=torch.float64)
+        u = U + math.sqrt(sigma2) * torch.randn(N, generator=g0, dtype=torch.float64)
+        truth = u[:, None] + math.sqrt(h2) * torch.randn(N, J, generator=g0, dtype=torch.float64)
+        y = torch.einsum("ndj,nj->nd", X, truth) + math.sqrt(eps2) * torch.randn(N, D, generator=g0, dtype=torch.float64)
+        A = torch.einsum("ndj,ndk->jk", X, X)
+        b = torch.einsum("ndj,nd->j", X, y)
+        self.theta_star = torch.linalg.solve(A, b).to(self.device)           # float64
+        self.X = X.to(torch.float32).to(self.device)
+        self.y = y.to(torch.float32).to(self.device)
+
+    def grads(self, theta: torch.Tensor) -> torch.Tensor:
+        r = torch.einsum("ndj,j->nd", self.X, theta) - self.y
+        return ((2.0 / self.D) * torch.einsum("ndj,nd->nj", self.X, r)).contiguous()
+
+    def gap(self, theta: torch.Tensor) -> float:
+        """Optimality gap |theta - theta*|."""
+        return float(torch.linalg.norm(theta.to(torch.float64) - self.theta_star))

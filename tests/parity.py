@@ -64,11 +64,14 @@ def compare_round(o: orc.Oracle, res_gpu, res_cpu, label=""):
 
 
 def run_both(N, d, k, mu, grads_fn, T, device="cuda:0", force_dense=False, closed_loop=None,
-             label="", check_state_every=1, cand_target=None):
+             label="", check_state_every=1, cand_target=None, weights=None, check_overlap=False,
+             on_round=None):
     """grads_fn(t, agg_prev_or_None) -> [N,d] float32 tensor on the GPU.
 
     Each side feeds its own aggregate back as g^{t-1}.  Returns per-round stats
-    of the HIP path.
+    of the HIP path.  `weights`: aggregation weights omega_n for both sides;
+    `check_overlap`: also compare the mask-overlap counts of every round;
+    `on_round(t, res_gpu, res_cpu)`: hook after the comparison of round t.
     """
     dev = torch.device(device)
     o = orc.Oracle(N, d, k, mu)
@@ -77,6 +80,9 @@ def run_both(N, d, k, mu, grads_fn, T, device="cuda:0", force_dense=False, close
         r.set_option(binding.OPT_FORCE_DENSE, 1)
     if cand_target is not None:
         r.set_option(binding.OPT_CAND_TARGET, cand_target)
+    if weights is not None:
+        o.set_weights(np.asarray(weights, dtype=np.float32))
+        r.set_weights([float(np.float32(x)) for x in weights])
     agg_g = None
     agg_c = None
     stats = []
@@ -91,6 +97,12 @@ def run_both(N, d, k, mu, grads_fn, T, device="cuda:0", force_dense=False, close
         st = r.stats()
         stats.append(st)
         tolerated += compare_round(o, res_g, res_c, "%s round %d" % (label, t))
+        if check_overlap:
+            ov_g = r.mask_overlap().cpu().numpy()
+            assert np.array_equal(ov_g, o.mask_overlap()), "%s round %d: mask overlap %s vs %s" % (
+                label, t, ov_g, o.mask_overlap())
+        if on_round is not None:
+            on_round(t, res_g, res_c)
         agg_g = res_g[2].clone()
         agg_c = res_c[2]
         if check_state_every and (t % check_state_every == 0 or t == T - 1) and tolerated == 0:

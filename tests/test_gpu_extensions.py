@@ -1,0 +1,165 @@
+"""GPU parity of what goes beyond the uniform-weight round: general aggregation
+weights, the mask-overlap count, the SGD update, the paper's toy example and its
+linear-regression loop -- HIP path through the C ABI against the CPU oracle."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2501_05633_amd import binding, workloads
+from tests.parity import run_both
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+f32 = np.float32
+
+
+def _wl_fn(cfg):
+    wl = workloads.Workload(cfg, DEV)
+    return lambda t, agg: wl.grads(t)
+
+
+@pytest.mark.parametrize("N,d,k,mu,weights", [
+    (5, 200_003, 2_000, 1.0, [0.05, 0.4, 0.25, 0.2, 0.1]),
+    (3, 50_000, 500, 0.3, [0.5, 0.0, 0.5]),                       # a worker the server ignores
+    (4, 10_000, 100, 1.0, [1.0, 1.0, 1.0, 1.0]),                  # plain sum instead of the mean
+    (40, 20_000, 200, 1.0, None),                                  # more than one batch of 32 in the aggregation
+])
+def test_weighted_aggregation_and_distortion(N, d, k, mu, weights):
+    print("case weights N=%d d=%d" % (N, d), flush=True)
+    if weights is None:
+        rng = np.random.default_rng(5)
+        weights = rng.dirichlet(np.ones(N)).astype(f32)
+    cfg = workloads.scaled(workloads.CONFIGS["large_cnn"], d=d, N=N, k=k)
+    stats, tol = run_both(N, d, k, mu, _wl_fn(cfg), 6, label="weights N=%d" % N, weights=weights,
+                          check_overlap=True)
+    assert tol == 0
+
+
+def test_weights_survive_reset_and_reject_bad_input():
+    print("case weights reset", flush=True)
+    N, d, k = 3, 5_000, 50
+    cfg = workloads.scaled(workloads.CONFIGS["tiny"], d=d, N=N, k=k)
+    wl = workloads.Workload(cfg, DEV)
+    w = np.array([0.7, 0.2, 0.1], dtype=f32)
+    r = binding.RegTopk(N, d, k, 1.0, device=DEV)
+    with pytest.raises(binding.RegTopkError):
+        r.set_weights([0.1, float("nan"), 0.2])
+    with pytest.raises(ValueError):
+        r.set_weights([0.5, 0.5])
+    r.set_weights(w)
+    g = wl.grads(0)
+    _, _, a1 = r.step(g, None)
+    a1 = a1.clone()
+    r.reset()
+    _, _, a2 = r.step(g, None)
+    assert torch.equal(a1, a2)
+    o = orc.Oracle(N, d, k, 1.0)
+    o.set_weights(w)
+    _, _, ac = o.step(g.cpu().numpy(), None)
+    assert np.array_equal(a2.cpu().numpy(), ac)
+    r.close()
+
+
+@pytest.mark.parametrize("N,d,k", [(4, 10_000, 100), (33, 4_097, 41), (7, 31, 5), (1, 100_000, 1_000),
+                                   (1100, 300, 3)])
+def test_mask_overlap(N, d, k):
+    print("case overlap N=%d d=%d" % (N, d), flush=True)
+    cfg = workloads.scaled(workloads.CONFIGS["tiny"], d=d, N=N, k=k)
+    r = binding.RegTopk(N, d, k, 1.0, device=DEV)
+    before = r.mask_overlap().cpu().numpy()
+    assert before[0] == d and before[1:].sum() == 0
+    r.close()
+    stats, tol = run_both(N, d, k, 1.0, _wl_fn(cfg), 4, label="overlap N=%d" % N, check_overlap=True,
+                          check_state_every=0)
+    assert tol == 0
+
+
+@pytest.mark.parametrize("d", [1, 5, 4096, 1_000_003])
+def test_sgd_update_is_bit_equal(d):
+    print("case sgd d=%d" % d, flush=True)
+    gen = torch.Generator(device="cpu").manual_seed(17 + d)
+    theta = torch.randn(d, generator=gen)
+    g = torch.randn(d, generator=gen) * torch.pow(10.0, 6.0 * torch.rand(d, generator=gen) - 4.0)
+    for eta in (1e-2, 0.37, 0.0):
+        want = orc.sgd_update(theta.numpy(), g.numpy(), eta)
+        th = theta.to(DEV)
+        binding.sgd_update(th, g.to(DEV), eta)
+        assert np.array_equal(th.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    # views that are only 4-byte aligned take the scalar path
+    if d > 8:
+        th = torch.empty(d, device=DEV)[1:]
+        gg = torch.empty(d + 2, device=DEV)[3:]
+        th.copy_(theta[1:])
+        gg.copy_(g[1:])
+        binding.sgd_update(th, gg, 0.37)
+        want = orc.sgd_update(theta[1:].numpy(), g[1:].numpy(), 0.37)
+        assert np.array_equal(th.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    with pytest.raises(ValueError):
+        binding.sgd_update(torch.zeros(4, device=DEV), torch.zeros(5, device=DEV), 0.1)
+
+
+def _read_gold(name):
+    out = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", name)) as fh:
+        for line in fh:
+            line = line.split("#")[0].strip()
+            if "=" in line:
+                key, v = line.split("=")
+                out[key.strip()] = [float(x) for x in v.split()]
+    return out
+
+
+def test_toy_logistic_example_on_the_gpu():
+    # Section "A Toy Example": two workers whose first gradient entries cancel.  Top-1
+    # keeps sending them (aggregate stays 0); RegTop-1 damps them to score 0 in the
+    # second round and sends the small entries that add up.
+    print("case toy", flush=True)
+    gold = _read_gold("toy_logistic.txt")
+    xs = np.array([gold["x1"], gold["x2"]])
+    theta = np.array(gold["theta0"])
+    z = np.exp(-(xs @ theta))
+    g = (-(z / (1 + z))[:, None] * xs).astype(f32)                   # gradient of log(1 + exp(-<theta;x>))
+    gt = torch.from_numpy(g).to(DEV)
+    for mu, second in ((1.0, 1), (0.0, 0)):
+        r = binding.RegTopk(2, 2, 1, mu, device=DEV)
+        idx, val, agg = r.step(gt, None)
+        assert idx.cpu().tolist() == [[0], [0]]
+        assert agg.cpu().tolist() == [0.0, 0.0]
+        agg = agg.clone()
+        idx, val, agg = r.step(gt, agg)                              # model has not moved: same gradients
+        assert idx.cpu().tolist() == [[second], [second]]
+        if second == 1:
+            assert agg[0].item() == 0.0 and abs(agg[1].item() - 2 * g[0, 1]) < 1e-6
+            assert r.mask_overlap().cpu().tolist() == [1, 0, 1]
+        else:
+            assert agg.cpu().tolist() == [0.0, 0.0]
+        r.close()
+
+
+@pytest.mark.parametrize("mu,k", [(1.0, 60), (0.0, 60), (0.5, 90)])
+def test_paper_linear_regression_loop_with_sgd_update(mu, k):
+    # The paper's linear-regression experiment (N = 20, J = 100, D_n = 500, eta = 1e-2) as a
+    # closed loop: sparsified round, then theta <- theta - eta * g, both steps on the GPU; the
+    # oracle runs its own loop on its own aggregate and both trajectories must be bit-equal.
+    print("case paper linreg mu=%g k=%d" % (mu, k), flush=True)
+    wl = workloads.PaperLinReg(DEV)
+    theta_g = torch.zeros(wl.J, device=DEV)
+    theta_c = np.zeros(wl.J, dtype=f32)
+
+    def fn(t, agg):
+        return wl.grads(theta_g)
+
+    def after(t, res_g, res_c):
+        nonlocal theta_c
+        binding.sgd_update(theta_g, res_g[2], wl.eta)
+        theta_c = orc.sgd_update(theta_c, res_c[2], wl.eta)
+        assert np.array_equal(theta_g.cpu().numpy().view(np.uint32), theta_c.view(np.uint32)), "theta differs at t=%d" % t
+
+    gap0 = wl.gap(theta_g)
+    stats, tol = run_both(wl.N, wl.J, k, mu, fn, 150, label="paper linreg", check_state_every=50,
+                          on_round=after, check_overlap=True)
+    assert tol == 0
+    assert wl.gap(theta_g) < 0.2 * gap0                              # the loop does descend
