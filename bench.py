@@ -61,6 +61,28 @@ def cpu_baseline(cfg, wl, rounds=3, workers=None):
     }
 
 
+def time_extras(torch, binding, r, agg, N, d, reps=20):
+    """The two small kernels around the round, outside the timed region: the
+    mask-overlap count (reads the N mask rows: N*d/8 bytes) and the SGD update
+    of a d-vector (12 bytes per entry), timed with events on the current stream."""
+    theta = torch.zeros(d, dtype=torch.float32, device=agg.device)
+    g = agg.clone()
+    res = {}
+    for name, fn, nbytes in (("mask_overlap", lambda: r.mask_overlap(), N * d / 8.0),
+                             ("sgd_update", lambda: binding.sgd_update(theta, g, 1e-2), 12.0 * d)):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        res[name] = {"ms": ms, "GB/s": nbytes / (ms * 1e-3) / 1e9, "bytes": nbytes}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -151,6 +173,7 @@ def main():
                      "algorithmic_bytes_per_launch": sweep_bytes, "avg_launch_ms": sweep_ms,
                      "traffic": MEASURED_SWEEP_TRAFFIC.get(cfg.name)},
     }
+    out["extras"] = time_extras(torch, binding, r, agg, N, d)
     r.close()
     del grads
     torch.cuda.empty_cache()

@@ -1354,17 +1354,21 @@ k_aggregate(const int32_t* __restrict__ out_idx, const float* __restrict__ out_v
 }
 
 // -------------------------------------------------------- k_mask_overlap ----
-// counts[c] += number of entries that exactly c workers selected in the last
-// round.  A thread takes one mask word position (32 entries) and adds the N
+// Number of entries that exactly c workers selected in the last round,
+// c = 0..N.  A thread takes one mask word position (32 entries) and adds the N
 // workers' words as bit-sliced counters: plane b holds bit b of the 32 column
-// sums.  Entries nobody selected (the bulk) are counted by population count,
-// the others one by one.  grid-stride over the ceil(d/32) word positions.
+// sums.  Entries that at most three workers selected (the bulk) are counted
+// by population count, the others one by one.  grid-stride over the
+// ceil(d/32) word positions.  Same-address global atomics cost about 12 ns each
+// on this chip, so when N + 1 <= 1024 every block leaves its histogram in
+// partial[block][0..N] and k_overlap_sum adds the blocks up; larger N add to
+// counts directly (counts zeroed beforehand).
 constexpr int kOverlapPlanes = 16;          // N <= 65535
 constexpr uint32_t kOverlapBins = 1024;     // LDS histogram when N + 1 fits
 
 __global__ void __launch_bounds__(kBlock)
 k_mask_overlap(const uint32_t* __restrict__ mask, int64_t d, uint32_t nc, int32_t N, int planes,
-               unsigned long long* __restrict__ counts) {
+               unsigned long long* __restrict__ counts, uint32_t* __restrict__ partial) {
   __shared__ uint32_t s_hist[kOverlapBins];
   const uint32_t tid = threadIdx.x;
   const bool lds = (uint32_t)N + 1u <= kOverlapBins;
@@ -1372,25 +1376,35 @@ k_mask_overlap(const uint32_t* __restrict__ mask, int64_t d, uint32_t nc, int32_
   __syncthreads();
   const size_t row_words = (size_t)nc * kChunkWords;
   const size_t nw = (size_t)((d + 31) / 32);
-  uint32_t zeros = 0;
+  uint32_t small[4] = {0, 0, 0, 0};                     // column sums 0..3, counted by population count
   for (size_t wd = (size_t)blockIdx.x * kBlock + tid; wd < nw; wd += (size_t)gridDim.x * kBlock) {
     uint32_t p[kOverlapPlanes];
 #pragma unroll
     for (int b = 0; b < kOverlapPlanes; ++b) p[b] = 0;
-    for (int32_t n = 0; n < N; ++n) {
-      uint32_t carry = mask[(size_t)n * row_words + wd];
+    for (int32_t n0 = 0; n0 < N; n0 += 8) {           // eight independent loads in flight
+      uint32_t m[8];
 #pragma unroll
-      for (int b = 0; b < kOverlapPlanes; ++b) {
-        if (b < planes) { const uint32_t t = p[b] & carry; p[b] ^= carry; carry = t; }
+      for (int q = 0; q < 8; ++q) m[q] = n0 + q < N ? mask[(size_t)(n0 + q) * row_words + wd] : 0u;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        uint32_t carry = m[q];
+#pragma unroll
+        for (int b = 0; b < kOverlapPlanes; ++b) {
+          if (b < planes && carry) { const uint32_t t = p[b] & carry; p[b] ^= carry; carry = t; }
+        }
       }
     }
     const int64_t left = d - (int64_t)wd * 32;
     const uint32_t valid = left >= 32 ? 0xFFFFFFFFu : ((1u << (uint32_t)left) - 1u);
-    uint32_t any = 0;
+    uint32_t high = 0;                                   // column sum >= 4
 #pragma unroll
-    for (int b = 0; b < kOverlapPlanes; ++b) any |= p[b];
-    zeros += (uint32_t)__popc(~any & valid);
-    uint32_t todo = any & valid;
+    for (int b = 2; b < kOverlapPlanes; ++b) high |= p[b];
+    const uint32_t low = ~high & valid;
+    small[0] += (uint32_t)__popc(~p[1] & ~p[0] & low);
+    small[1] += (uint32_t)__popc(~p[1] & p[0] & low);
+    small[2] += (uint32_t)__popc(p[1] & ~p[0] & low);
+    small[3] += (uint32_t)__popc(p[1] & p[0] & low);
+    uint32_t todo = high & valid;
     while (todo) {
       const uint32_t i = (uint32_t)__ffs(todo) - 1u;
       todo &= todo - 1u;
@@ -1401,15 +1415,37 @@ k_mask_overlap(const uint32_t* __restrict__ mask, int64_t d, uint32_t nc, int32_
       else atomicAdd(&counts[c], 1ull);
     }
   }
-  for (int o = 32; o > 0; o >>= 1) zeros += __shfl_down(zeros, o);
-  if ((tid & 63) == 0 && zeros) {
-    if (lds) atomicAdd(&s_hist[0], zeros);
-    else atomicAdd(&counts[0], (unsigned long long)zeros);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    uint32_t v = small[q];
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o);
+    if ((tid & 63) == 0 && v && q <= N) {
+      if (lds) atomicAdd(&s_hist[q], v);
+      else atomicAdd(&counts[q], (unsigned long long)v);
+    }
   }
   __syncthreads();
   if (lds)
     for (uint32_t i = tid; i <= (uint32_t)N; i += kBlock)
-      if (s_hist[i]) atomicAdd(&counts[i], (unsigned long long)s_hist[i]);
+      partial[(size_t)blockIdx.x * ((uint32_t)N + 1u) + i] = s_hist[i];
+}
+
+// counts[c] = sum over the blocks of partial[block][c].  grid (N+1): one block per c.
+__global__ void __launch_bounds__(kBlock)
+k_overlap_sum(const uint32_t* __restrict__ partial, uint32_t blocks, int32_t N,
+              unsigned long long* __restrict__ counts) {
+  __shared__ unsigned long long s_part[kBlock / 64];
+  const uint32_t c = blockIdx.x, tid = threadIdx.x;
+  unsigned long long s = 0;
+  for (uint32_t b = tid; b < blocks; b += kBlock) s += partial[(size_t)b * ((uint32_t)N + 1u) + c];
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_down(s, o);
+  if ((tid & 63) == 0) s_part[tid >> 6] = s;
+  __syncthreads();
+  if (tid == 0) {
+    unsigned long long t = 0;
+    for (uint32_t i = 0; i < kBlock / 64; ++i) t += s_part[i];
+    counts[c] = t;
+  }
 }
 
 // ---------------------------------------------------------- k_sgd_update ----

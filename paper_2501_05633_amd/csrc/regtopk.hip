@@ -437,9 +437,15 @@ int regtopk_mask_overlap(regtopk_ctx* c, int64_t* counts_dev, void* stream) {
   const size_t nw = (size_t)((c->d + 31) / 32);
   size_t blocks = (nw + kBlock - 1) / kBlock;
   if (blocks > 4096) blocks = 4096;
-  k_fill_u32<<<1, 256, 0, s>>>(reinterpret_cast<uint32_t*>(counts_dev), 2 * ((size_t)c->N + 1), 0u);
-  k_mask_overlap<<<(uint32_t)blocks, kBlock, 0, s>>>(c->at<uint32_t>(c->L.mask), c->d, c->L.nc, c->N, planes,
-                                                      reinterpret_cast<unsigned long long*>(counts_dev));
+  unsigned long long* counts = reinterpret_cast<unsigned long long*>(counts_dev);
+  // Per-block histograms go through the histogram area of the dense selection,
+  // which is idle between rounds and cleared before each of its uses:
+  // 4096 * (N+1) words fit into its 3 * 4096 * N words for every N >= 1.
+  uint32_t* partial = c->at<uint32_t>(c->L.fhist);
+  const bool staged = (uint32_t)c->N + 1u <= kOverlapBins;
+  if (!staged) k_fill_u32<<<64, 256, 0, s>>>(reinterpret_cast<uint32_t*>(counts_dev), 2 * ((size_t)c->N + 1), 0u);
+  k_mask_overlap<<<(uint32_t)blocks, kBlock, 0, s>>>(c->at<uint32_t>(c->L.mask), c->d, c->L.nc, c->N, planes, counts, partial);
+  if (staged) k_overlap_sum<<<(uint32_t)c->N + 1u, kBlock, 0, s>>>(partial, (uint32_t)blocks, c->N, counts);
   HIP_TRY(hipGetLastError());
   return REGTOPK_OK;
 }
