@@ -243,7 +243,7 @@ __global__ void __launch_bounds__(kBlock)
 k_accum_emit(float* __restrict__ e, const float* __restrict__ g, const uint32_t* __restrict__ mask,
              const uint32_t* __restrict__ prev_sel_off, int64_t d, WorkerCtl* __restrict__ ctl,
              int32_t* __restrict__ cand_idx,
-             float* __restrict__ cand_val, uint32_t* __restrict__ ch_off,
+             float* __restrict__ cand_val, float* __restrict__ cand_prev, uint32_t* __restrict__ ch_off,
              uint32_t* __restrict__ ch_cnt, uint32_t nc, uint32_t cap_r, uint32_t cap_total,
              uint32_t regions) {
   __shared__ uint32_t s_wtot[4];
@@ -254,6 +254,7 @@ k_accum_emit(float* __restrict__ e, const float* __restrict__ g, const uint32_t*
   const uint32_t tau_lo = ctl[n].tau_lo;
   const int64_t base = (int64_t)c * kChunk + (int64_t)wv * 1024 + lane * 4;
   float a[4][4];
+  float eo[4][4];       // what the state held: a^{t-1} where the entry was sent, the error elsewhere
   uint32_t flags = 0;
   // previous round's mask: the 4 bits of entries j0..j0+3 lie in one word
   // (chunks from which nothing was sent have no mask bits: their words are not read)
@@ -281,13 +282,15 @@ k_accum_emit(float* __restrict__ e, const float* __restrict__ g, const uint32_t*
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int64_t j0 = base + i * 256;
+      eo[i][0] = ev[i].x; eo[i][1] = ev[i].y; eo[i][2] = ev[i].z; eo[i][3] = ev[i].w;
+      f32x4 z4 = ev[i];
       if (mb[i]) {                          // sent last round: the error restarts from zero
-        if (mb[i] & 1u) ev[i].x = 0.f;
-        if (mb[i] & 2u) ev[i].y = 0.f;
-        if (mb[i] & 4u) ev[i].z = 0.f;
-        if (mb[i] & 8u) ev[i].w = 0.f;
+        if (mb[i] & 1u) z4.x = 0.f;
+        if (mb[i] & 2u) z4.y = 0.f;
+        if (mb[i] & 4u) z4.z = 0.f;
+        if (mb[i] & 8u) z4.w = 0.f;
       }
-      const f32x4 s4 = ev[i] + gv[i];
+      const f32x4 s4 = z4 + gv[i];
       a[i][0] = s4.x; a[i][1] = s4.y; a[i][2] = s4.z; a[i][3] = s4.w;
       if (j0 < d) {
         __builtin_nontemporal_store(s4, reinterpret_cast<f32x4*>(e + row + j0));
@@ -303,8 +306,10 @@ k_accum_emit(float* __restrict__ e, const float* __restrict__ g, const uint32_t*
       for (int q = 0; q < 4; ++q) {
         const int64_t j = base + i * 256 + q;
         a[i][q] = 0.f;
+        eo[i][q] = 0.f;
         if (j < d) {
-          const float eps = ((mb[i] >> q) & 1u) ? 0.f : e[row + j];
+          eo[i][q] = e[row + j];
+          const float eps = ((mb[i] >> q) & 1u) ? 0.f : eo[i][q];
           a[i][q] = eps + g[row + j];
           e[row + j] = a[i][q];
           if (key_of(a[i][q]) >= tau_lo) flags |= 1u << (i * 4 + q);
@@ -340,6 +345,7 @@ k_accum_emit(float* __restrict__ e, const float* __restrict__ g, const uint32_t*
       if ((flags >> (i * 4 + q)) & 1u) {
         cand_idx[out + p] = (int32_t)((uint32_t)(base + i * 256 + q) | (((mb[i] >> q) & 1u) ? kSentFlag : 0u));
         cand_val[out + p] = a[i][q];
+        cand_prev[out + p] = eo[i][q];
         ++p;
       }
     }
@@ -360,21 +366,13 @@ __device__ __forceinline__ float likelihood_sent(float a_now, float a_before, fl
   return tanh_f32_cr(x);
 }
 
-// Score bits of one candidate (index word `raw` with the sent flag, value a).
-__device__ __forceinline__ uint32_t score_entry(uint32_t raw, float a, int use_reg,
-                                                const uint32_t* __restrict__ mrow,
-                                                const uint32_t* __restrict__ rrow,
-                                                const float* __restrict__ pv,
-                                                const float* __restrict__ gprev, int64_t k, float w,
-                                                float mu) {
+// Score bits of one candidate: index word `raw` with the sent flag, value a,
+// and a_before = the value the worker sent for this entry in the previous
+// round (read only when the flag is set).
+__device__ __forceinline__ uint32_t score_entry(uint32_t raw, float a, float a_before, int use_reg,
+                                                const float* __restrict__ gprev, float w, float mu) {
   float f = 1.0f;
-  if (use_reg && (raw & kSentFlag)) {
-    // rank of j in the previous round's list: selected entries before its mask
-    // word plus the set bits below it inside the word
-    const uint32_t j = raw & ~kSentFlag;
-    const uint32_t rank = rrow[j >> 5] + (uint32_t)__popc(mrow[j >> 5] & ((1u << (j & 31)) - 1u));
-    if ((int64_t)rank < k) f = likelihood_sent(a, pv[rank], gprev[j], w, mu);
-  }
+  if (use_reg && (raw & kSentFlag)) f = likelihood_sent(a, a_before, gprev[raw & ~kSentFlag], w, mu);
   return __float_as_uint(__fmul_rn(fabsf(a), f));
 }
 
@@ -384,10 +382,9 @@ constexpr int kScoreSlots = 4096;
 
 __global__ void __launch_bounds__(kBlock)
 k_score(WorkerCtl* __restrict__ ctl, const int32_t* __restrict__ cand_idx,
-        const float* __restrict__ cand_val, uint32_t* __restrict__ cand_key,
-        uint32_t* __restrict__ bnd_key, const uint32_t* __restrict__ mask,
-        const uint32_t* __restrict__ rankbase, const float* __restrict__ prev_val,
-        const float* __restrict__ gprev, int64_t d, int64_t k, uint32_t nc, uint32_t cap_r,
+        const float* __restrict__ cand_val, const float* __restrict__ cand_prev,
+        uint32_t* __restrict__ cand_key, uint32_t* __restrict__ bnd_key,
+        const float* __restrict__ gprev, int64_t d, uint32_t cap_r,
         uint32_t cap_total, uint32_t bnd_cap, const float* __restrict__ omega, float mu, int use_reg) {
   __shared__ uint32_t s_stage[kScoreSlots];
   __shared__ uint32_t s_cnt[3];       // boundary entries, valid, above window
@@ -403,9 +400,6 @@ k_score(WorkerCtl* __restrict__ ctl, const int32_t* __restrict__ cand_idx,
   if (tid < 3) s_cnt[tid] = 0;
   __syncthreads();
   const size_t cbase = (size_t)n * cap_total + (size_t)r * cap_r;
-  const float* pv = prev_val + (size_t)n * k;
-  const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
-  const uint32_t* rrow = rankbase + (size_t)n * nc * kChunkWords;
   const float w = omega[n];
   uint32_t n_val = 0, n_hi = 0;
 #pragma unroll 4
@@ -416,7 +410,8 @@ k_score(WorkerCtl* __restrict__ ctl, const int32_t* __restrict__ cand_idx,
     const uint32_t j = raw & ~kSentFlag;
     if ((int64_t)j >= d) continue;
     const float a = cand_val[cbase + p];
-    const uint32_t key = score_entry(raw, a, use_reg, mrow, rrow, pv, gprev, k, w, mu);
+    const float ab = (use_reg && (raw & kSentFlag)) ? cand_prev[cbase + p] : 0.0f;
+    const uint32_t key = score_entry(raw, a, ab, use_reg, gprev, w, mu);
     cand_key[cbase + p] = key;
     n_val += key >= tau_lo;
     if (windowed) {
@@ -1014,17 +1009,31 @@ __device__ __forceinline__ void dense_count_chunk(uint32_t n, uint32_t c, const 
 
 // Chunk c of worker n: writes its share of the 2k largest |a| (ties: lowest
 // indices) to the candidate list, in index order, at the offsets of the scan.
+// The sweep has overwritten the state by now, so the value sent in the previous
+// round is fetched from that round's list: its position there is the number of
+// mask bits before the entry (prev_sel_off[c] of them in lower chunks; s_mw /
+// s_rk, 128 words each, hold the chunk's mask words and their running counts).
 template <bool VEC>
 __device__ __forceinline__ void dense_emit_chunk(uint32_t n, uint32_t c, const float* a_rows,
                                                  const uint32_t* mask, int64_t d, const WorkerCtl* ctl,
-                                                 int32_t* cand_idx, float* cand_val,
+                                                 int32_t* cand_idx, float* cand_val, float* cand_prev,
                                                  const uint32_t* ch_off, const uint32_t* ch_cnt,
-                                                 const uint32_t* tie_off, uint32_t nc,
-                                                 uint32_t cap_total, uint32_t* s_wtot, uint32_t* s_ttot) {
+                                                 const uint32_t* tie_off, const uint32_t* prev_sel_off,
+                                                 const float* prev_val, int64_t k, uint32_t nc,
+                                                 uint32_t cap_total, uint32_t* s_wtot, uint32_t* s_ttot,
+                                                 uint32_t* s_mw, uint32_t* s_rk) {
   const uint32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
   const size_t tix = (size_t)n * nc + c;
   if (ch_cnt[tix] == 0) return;
+  if (tid < kChunkWords) s_mw[tid] = mrow[(size_t)c * kChunkWords + tid];
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t run = prev_sel_off[(size_t)n * (nc + 1) + c];
+    for (uint32_t i = 0; i < kChunkWords; ++i) { s_rk[i] = run; run += (uint32_t)__popc(s_mw[i]); }
+  }
+  __syncthreads();
+  const float* pv = prev_val + (size_t)n * k;
   const uint32_t tau = ctl[n].f_tau, budget = ctl[n].f_budget;
   const size_t row = (size_t)n * (size_t)d;
   const int64_t base = (int64_t)c * kChunk + (int64_t)wv * 1024 + lane * 4;
@@ -1075,9 +1084,16 @@ __device__ __forceinline__ void dense_emit_chunk(uint32_t n, uint32_t c, const f
     for (int q = 0; q < 4; ++q) {
       if ((flags >> (i * 4 + q)) & 1u) {
         const int64_t j = base + i * 256 + q;
-        const uint32_t sent = (mrow[j >> 5] >> (j & 31)) & 1u;
+        const uint32_t wl = (uint32_t)(j >> 5) & (kChunkWords - 1), bit = (uint32_t)j & 31u;
+        const uint32_t sent = (s_mw[wl] >> bit) & 1u;
+        float ab = 0.0f;
+        if (sent) {
+          const uint32_t rank = s_rk[wl] + (uint32_t)__popc(s_mw[wl] & ((1u << bit) - 1u));
+          if ((int64_t)rank < k) ab = pv[rank];
+        }
         cand_idx[out + p] = (int32_t)((uint32_t)j | (sent ? kSentFlag : 0u));
         cand_val[out + p] = a[i][q];
+        cand_prev[out + p] = ab;
         ++p;
       }
     }
@@ -1088,9 +1104,10 @@ __device__ __forceinline__ void dense_emit_chunk(uint32_t n, uint32_t c, const f
 // grid (G): G blocks resident together.  See the section header.
 template <bool VEC>
 __global__ void __launch_bounds__(kBlock)
-k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* rankbase, int64_t d, WorkerCtl* ctl,
+k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_off, int64_t d, WorkerCtl* ctl,
             GlobalCtl* gctl, uint32_t* fhist, uint32_t* ch_gt, uint32_t* ch_tie, uint32_t* ch_off,
-            uint32_t* ch_cnt, uint32_t* tie_off, int32_t* cand_idx, float* cand_val, uint32_t* cand_key,
+            uint32_t* ch_cnt, uint32_t* tie_off, int32_t* cand_idx, float* cand_val, float* cand_prev,
+            uint32_t* cand_key,
             const uint32_t* bnd_key, const float* prev_val, const float* gprev, int64_t k, uint32_t nc,
             int32_t N, uint32_t cap_r, uint32_t cap_total, uint32_t regions, uint32_t bnd_cap,
             const float* omega, float mu, int use_reg, float cand_target) {
@@ -1137,7 +1154,8 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* rankbase,
   for (int32_t n = 0; n < N; ++n) {
     if (!ctl[n].need_dense) continue;
     for (uint32_t c = b; c < nc; c += G)
-      dense_emit_chunk<VEC>(n, c, a_rows, mask, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, tie_off, nc, cap_total, s_x, s_y);
+      dense_emit_chunk<VEC>(n, c, a_rows, mask, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, tie_off,
+                            prev_sel_off, prev_val, k, nc, cap_total, s_x, s_y, s_a, s_b);
   }
   grid_barrier(gctl, G);
 
@@ -1145,12 +1163,9 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* rankbase,
     if (!ctl[n].need_dense) continue;
     const uint32_t total = ctl[n].dense_total;
     const size_t cb = (size_t)n * cap_total;
-    const float* pv = prev_val + (size_t)n * k;
-    const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
-    const uint32_t* rrow = rankbase + (size_t)n * nc * kChunkWords;
     const float w = omega[n];
     for (uint32_t p = b * kBlock + tid; p < total; p += G * kBlock)
-      cand_key[cb + p] = score_entry((uint32_t)cand_idx[cb + p], cand_val[cb + p], use_reg, mrow, rrow, pv, gprev, k, w, mu);
+      cand_key[cb + p] = score_entry((uint32_t)cand_idx[cb + p], cand_val[cb + p], cand_prev[cb + p], use_reg, gprev, w, mu);
   }
   grid_barrier(gctl, G);
   for (int32_t n = b; n < N; n += G)
@@ -1185,36 +1200,16 @@ k_chunk_count(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ ca
 }
 
 // ------------------------------------------------------------- k_compact ----
-// Mask words and running counts of one chunk from its selected local indices.
-// s_m: 128 zeroed LDS words of the calling wave, in which the bits were set.
-// Lane l owns words 2l and 2l+1.  first = selected entries of the worker before
-// this chunk.
-__device__ __forceinline__ void write_chunk_mask(const uint32_t* s_m, uint32_t first,
-                                                 uint32_t* __restrict__ mask_chunk,
-                                                 uint32_t* __restrict__ rank_chunk) {
-  const uint32_t lane = threadIdx.x & 63;
-  const uint32_t m0 = s_m[2 * lane], m1 = s_m[2 * lane + 1];
-  const uint32_t c0 = (uint32_t)__popc(m0), c1 = (uint32_t)__popc(m1);
-  uint32_t x = c0 + c1;
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t y = __shfl_up(x, o);
-    if (lane >= (uint32_t)o) x += y;
-  }
-  const uint32_t before = first + x - (c0 + c1);
-  reinterpret_cast<uint2*>(mask_chunk)[lane] = make_uint2(m0, m1);
-  reinterpret_cast<uint2*>(rank_chunk)[lane] = make_uint2(before, before + c0);
-}
-
 // grid (ceil(nc/4), N): one wave per chunk.  Writes the selected pairs of the
 // chunk in index order at sel_off[c], and the chunk's words of the round's mask
-// (bit = entry selected) and of the running count of selected entries.
+// (bit = entry selected).
 __global__ void __launch_bounds__(kBlock)
 k_compact(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ cand_key,
           const int32_t* __restrict__ cand_idx, const float* __restrict__ cand_val,
           const uint32_t* __restrict__ ch_off, const uint32_t* __restrict__ ch_cnt,
           const uint32_t* __restrict__ sel_off, const uint32_t* __restrict__ prev_sel_off,
           const uint32_t* __restrict__ tie_off, int32_t* __restrict__ out_idx,
-          float* __restrict__ out_val, uint32_t* __restrict__ mask, uint32_t* __restrict__ rankbase,
+          float* __restrict__ out_val, uint32_t* __restrict__ mask,
           int64_t k, uint32_t nc, uint32_t cap_total) {
   __shared__ uint32_t s_m[4][kChunkWords];
   const uint32_t n = blockIdx.y, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -1265,7 +1260,7 @@ k_compact(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ cand_k
     const bool is_empty = sel_off[so + 1] == first;
     if (!(was_empty && is_empty)) {
       const size_t wbase = ((size_t)n * nc + c) * kChunkWords;
-      write_chunk_mask(s_m[wv], first, mask + wbase, rankbase + wbase);
+      reinterpret_cast<uint2*>(mask + wbase)[lane] = make_uint2(s_m[wv][2 * lane], s_m[wv][2 * lane + 1]);
     }
   }
 }
@@ -1492,11 +1487,25 @@ __global__ void k_init_ctl(WorkerCtl* ctl) {
   }
 }
 
-// set_state: mask words and running counts from an ascending index list.
+// set_state: the state keeps, at the entries sent in the previous round, the
+// value that was sent (the sweep reads it from there and restarts the error at
+// zero): state[n][pidx[n][i]] = pval[n][i].  Indices outside [0,d) are skipped
+// (k_check_ascending reports them).
+__global__ void k_scatter_prev(float* __restrict__ e, const int32_t* __restrict__ pidx,
+                               const float* __restrict__ pval, int64_t d, int64_t k, int32_t N) {
+  const size_t total = (size_t)N * (size_t)k;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+    const size_t n = i / (size_t)k;
+    const int64_t j = pidx[i];
+    if (j >= 0 && j < d) e[n * (size_t)d + (size_t)j] = pval[i];
+  }
+}
+
+// set_state: mask words and per-chunk offsets from an ascending index list.
 // grid (ceil(nc/4), N): one wave per chunk.
 __global__ void __launch_bounds__(kBlock)
 k_build_mask(const int32_t* __restrict__ pidx, uint32_t* __restrict__ mask,
-             uint32_t* __restrict__ rankbase, uint32_t* __restrict__ sel_off, int64_t k, uint32_t nc) {
+             uint32_t* __restrict__ sel_off, int64_t k, uint32_t nc) {
   __shared__ uint32_t s_m[4][kChunkWords];
   const uint32_t n = blockIdx.y, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const uint32_t c = blockIdx.x * 4 + wv;
@@ -1525,7 +1534,7 @@ k_build_mask(const int32_t* __restrict__ pidx, uint32_t* __restrict__ mask,
   __syncthreads();
   if (live) {
     const size_t wbase = ((size_t)n * nc + c) * kChunkWords;
-    write_chunk_mask(s_m[wv], first, mask + wbase, rankbase + wbase);
+    reinterpret_cast<uint2*>(mask + wbase)[lane] = make_uint2(s_m[wv][2 * lane], s_m[wv][2 * lane + 1]);
   }
 }
 

@@ -41,7 +41,7 @@ size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct Layout {
   uint32_t nc, regions, cap_r, cap_total, bnd_cap;
   size_t e, out_idx[2], out_val[2], agg[2], cand_idx, cand_val, cand_key;
-  size_t ch_off, ch_cnt, ch_gt, ch_tie, tie_off, sel_off[2], agg_hot[2], mask, rankbase, bnd_key, fhist, ctl, gctl, omega, total;
+  size_t ch_off, ch_cnt, ch_gt, ch_tie, tie_off, sel_off[2], agg_hot[2], mask, cand_prev, bnd_key, fhist, ctl, gctl, omega, total;
 };
 
 bool valid_sizes(int32_t N, int64_t d, int64_t k) {
@@ -73,6 +73,7 @@ Layout make_layout(int32_t N, int64_t d, int64_t k) {
   L.cand_idx = take(ncand * 4);
   L.cand_val = take(ncand * 4);
   L.cand_key = take(ncand * 4);
+  L.cand_prev = take(ncand * 4);
   L.ch_off = take(nch * 4);
   L.ch_cnt = take(nch * 4);
   L.ch_gt = take(nch * 4);
@@ -80,7 +81,6 @@ Layout make_layout(int32_t N, int64_t d, int64_t k) {
   L.tie_off = take(nch * 4);
   for (int b = 0; b < 2; ++b) { L.sel_off[b] = take(((size_t)N * (L.nc + 1)) * 4); L.agg_hot[b] = take((size_t)L.nc * 4); }
   L.mask = take(nch * kChunkWords * 4);
-  L.rankbase = take(nch * kChunkWords * 4);
   L.bnd_cap = 262144;
   L.bnd_key = take((size_t)N * L.bnd_cap * 4);
   L.fhist = take((size_t)N * 3 * kL1Bins * 4);
@@ -126,7 +126,6 @@ int zero_state(regtopk_ctx* c, hipStream_t s) {
     k_fill_u32<<<1024, 256, 0, s>>>(c->at<uint32_t>(c->L.agg[b]), (size_t)c->d, 0u);     // agg_hot == 0 means zeros
   }
   k_fill_u32<<<1024, 256, 0, s>>>(c->at<uint32_t>(c->L.mask), (size_t)c->N * c->L.nc * kChunkWords, 0u);
-  k_fill_u32<<<1024, 256, 0, s>>>(c->at<uint32_t>(c->L.rankbase), (size_t)c->N * c->L.nc * kChunkWords, 0u);
   k_init_ctl<<<c->N, 256, 0, s>>>(c->at<WorkerCtl>(c->L.ctl));
   k_fill_u32<<<1, 64, 0, s>>>(c->at<uint32_t>(c->L.gctl), sizeof(GlobalCtl) / 4, 0u);
   HIP_TRY(hipGetLastError());
@@ -291,7 +290,7 @@ int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* s
   const uint32_t* prev_sel_off = c->at<uint32_t>(L.sel_off[prv]);
   uint32_t* agg_hot = c->at<uint32_t>(L.agg_hot[cur]);
   uint32_t* mask = c->at<uint32_t>(L.mask);
-  uint32_t* rankbase = c->at<uint32_t>(L.rankbase);
+  float* cand_prev = c->at<float>(L.cand_prev);
   const float* omega = c->at<float>(L.omega);
 
   const dim3 g_chunks(nc, N), g_waves((nc + 3) / 4, N);
@@ -313,23 +312,23 @@ int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* s
   c->fresh = false;
   if (ev) HIP_TRY(hipEventRecord(ev[0], s));
   if (vec)
-    k_accum_emit<true><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, prev_sel_off, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
+    k_accum_emit<true><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, prev_sel_off, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   else
-    k_accum_emit<false><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, prev_sel_off, d, ctl, cand_idx, cand_val, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
+    k_accum_emit<false><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, prev_sel_off, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   if (ev) HIP_TRY(hipEventRecord(ev[1], s));
-  k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_key, bnd_key, mask, rankbase, prev_val, gprev, d, k, nc, L.cap_r, L.cap_total, L.bnd_cap, omega, c->mu, use_reg);
+  k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_prev, cand_key, bnd_key, gprev, d, L.cap_r, L.cap_total, L.bnd_cap, omega, c->mu, use_reg);
   k_select<<<N, kScanBlock, 0, s>>>(ctl, gctl, cand_key, bnd_key, k, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->cand_target, c->force_dense);
   // dense selection for the workers whose speculation failed; returns at once if there is none
   if (vec)
-    k_dense_all<true><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, rankbase, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, omega, c->mu, use_reg, c->cand_target);
+    k_dense_all<true><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, prev_sel_off, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_prev, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, omega, c->mu, use_reg, c->cand_target);
   else
-    k_dense_all<false><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, rankbase, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, omega, c->mu, use_reg, c->cand_target);
+    k_dense_all<false><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, prev_sel_off, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_prev, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, omega, c->mu, use_reg, c->cand_target);
 
   // ordered compaction, error update, aggregation
   if (ev) HIP_TRY(hipEventRecord(ev[2], s));
   k_chunk_count<<<g_waves, kBlock, 0, s>>>(ctl, cand_key, ch_off, ch_cnt, ch_gt, ch_tie, nc, L.cap_total);
   k_chunk_scan<<<N, kScanBlock, 0, s>>>(ctl, ch_gt, ch_tie, sel_off, tie_off, nc, k);
-  k_compact<<<g_waves, kBlock, 0, s>>>(ctl, cand_key, cand_idx, cand_val, ch_off, ch_cnt, sel_off, prev_sel_off, tie_off, out_idx, out_val, mask, rankbase, k, nc, L.cap_total);
+  k_compact<<<g_waves, kBlock, 0, s>>>(ctl, cand_key, cand_idx, cand_val, ch_off, ch_cnt, sel_off, prev_sel_off, tie_off, out_idx, out_val, mask, k, nc, L.cap_total);
   k_aggregate<<<nc, kBlock, 0, s>>>(out_idx, out_val, sel_off, agg, agg_hot, d, k, nc, N, omega);
   if (ev) { HIP_TRY(hipEventRecord(ev[3], s)); c->prof_rounds += 1; }
   HIP_TRY(hipGetLastError());
@@ -373,7 +372,6 @@ int regtopk_set_state(regtopk_ctx* c, const float* e_dev, const int32_t* pidx_de
     for (int b = 0; b < 2; ++b)
       k_fill_u32<<<256, 256, 0, s>>>(c->at<uint32_t>(c->L.sel_off[b]), (size_t)c->N * (c->L.nc + 1), 0u);
     k_fill_u32<<<1024, 256, 0, s>>>(c->at<uint32_t>(c->L.mask), (size_t)c->N * c->L.nc * kChunkWords, 0u);
-    k_fill_u32<<<1024, 256, 0, s>>>(c->at<uint32_t>(c->L.rankbase), (size_t)c->N * c->L.nc * kChunkWords, 0u);
   }
   if (t > 0) {
     const int prv = (int)((t & 1) ^ 1);
@@ -381,7 +379,8 @@ int regtopk_set_state(regtopk_ctx* c, const float* e_dev, const int32_t* pidx_de
     k_copy_u32<<<512, 256, 0, s>>>(reinterpret_cast<uint32_t*>(pi), reinterpret_cast<const uint32_t*>(pidx_dev), nk);
     k_copy_u32<<<512, 256, 0, s>>>(c->at<uint32_t>(c->L.out_val[prv]), reinterpret_cast<const uint32_t*>(pval_dev), nk);
     const dim3 g((c->L.nc + 3) / 4, c->N);
-    k_build_mask<<<g, kBlock, 0, s>>>(pi, c->at<uint32_t>(c->L.mask), c->at<uint32_t>(c->L.rankbase), c->at<uint32_t>(c->L.sel_off[prv]), c->k, c->L.nc);
+    k_build_mask<<<g, kBlock, 0, s>>>(pi, c->at<uint32_t>(c->L.mask), c->at<uint32_t>(c->L.sel_off[prv]), c->k, c->L.nc);
+    k_scatter_prev<<<512, 256, 0, s>>>(c->at<float>(c->L.e), pi, c->at<float>(c->L.out_val[prv]), c->d, c->k, c->N);
     const dim3 g2(64, c->N);
     k_check_ascending<<<g2, 256, 0, s>>>(pi, c->at<WorkerCtl>(c->L.ctl), c->d, c->k);
   }
