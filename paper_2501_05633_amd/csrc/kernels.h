@@ -30,7 +30,7 @@
 //   k_chunk_count / k_chunk_scan / k_compact
 //                   ordered compaction of the selected (index, value) pairs,
 //                   lowest-index ties first; writes the round's mask (1 bit per
-//                   entry) and the running count of selected entries per word
+//                   entry)
 //   k_aggregate     per 4096-entry tile: LDS accumulation of w*value in ascending
 //                   worker order, tile written once (zero fill included)
 //
@@ -376,9 +376,9 @@ __device__ __forceinline__ uint32_t score_entry(uint32_t raw, float a, float a_b
   return __float_as_uint(__fmul_rn(fabsf(a), f));
 }
 
-// grid (ceil(cap_r/4096), regions, N): a block covers 4096 consecutive slots of
-// one region of the speculative candidate list, sixteen per thread.
-constexpr int kScoreSlots = 4096;
+// grid (ceil(cap_r/2048), regions, N): a block covers 2048 consecutive slots of
+// one region of the speculative candidate list, eight per thread.
+constexpr int kScoreSlots = 2048;
 
 __global__ void __launch_bounds__(kBlock)
 k_score(WorkerCtl* __restrict__ ctl, const int32_t* __restrict__ cand_idx,
@@ -402,16 +402,32 @@ k_score(WorkerCtl* __restrict__ ctl, const int32_t* __restrict__ cand_idx,
   const size_t cbase = (size_t)n * cap_total + (size_t)r * cap_r;
   const float w = omega[n];
   uint32_t n_val = 0, n_hi = 0;
-#pragma unroll 4
-  for (int q = 0; q < kScoreSlots / kBlock; ++q) {
+  // all loads of the thread's slots are issued before anything is computed, so
+  // the block pays the memory latency once per stage, not once per slot
+  constexpr int kPer = kScoreSlots / kBlock;
+  uint32_t raw[kPer];
+  float av[kPer], ab[kPer], gp[kPer];
+#pragma unroll
+  for (int q = 0; q < kPer; ++q) {
     const uint32_t p = p0 + q * kBlock + tid;
-    if (p >= lim) break;
-    const uint32_t raw = (uint32_t)cand_idx[cbase + p];
-    const uint32_t j = raw & ~kSentFlag;
-    if ((int64_t)j >= d) continue;
-    const float a = cand_val[cbase + p];
-    const float ab = (use_reg && (raw & kSentFlag)) ? cand_prev[cbase + p] : 0.0f;
-    const uint32_t key = score_entry(raw, a, ab, use_reg, gprev, w, mu);
+    const bool in = p < lim;
+    raw[q] = in ? (uint32_t)cand_idx[cbase + p] : 0xFFFFFFFFu;
+    av[q] = in ? cand_val[cbase + p] : 0.0f;
+    ab[q] = (in && use_reg) ? cand_prev[cbase + p] : 0.0f;
+  }
+#pragma unroll
+  for (int q = 0; q < kPer; ++q) {
+    const uint32_t j = raw[q] & ~kSentFlag;
+    if ((int64_t)j >= d) raw[q] = 0xFFFFFFFFu;               // empty slot
+    gp[q] = (use_reg && raw[q] != 0xFFFFFFFFu && (raw[q] & kSentFlag)) ? gprev[j] : 0.0f;
+  }
+#pragma unroll
+  for (int q = 0; q < kPer; ++q) {
+    if (raw[q] == 0xFFFFFFFFu) continue;
+    const uint32_t p = p0 + q * kBlock + tid;
+    float f = 1.0f;
+    if (use_reg && (raw[q] & kSentFlag)) f = likelihood_sent(av[q], ab[q], gp[q], w, mu);
+    const uint32_t key = __float_as_uint(__fmul_rn(fabsf(av[q]), f));
     cand_key[cbase + p] = key;
     n_val += key >= tau_lo;
     if (windowed) {
@@ -1176,7 +1192,9 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
 
 // --------------------------------------------------------- k_chunk_count ----
 // grid (ceil(nc/4), N): one wave per chunk.  Candidates of the chunk with
-// score > tau and == tau.
+// score > tau and == tau.  Most chunks are empty and a few hold hundreds of
+// candidates, so a lane takes eight at a time with all loads in flight together.
+constexpr int kLaneBatch = 8;
 __global__ void __launch_bounds__(kBlock)
 k_chunk_count(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ cand_key,
               const uint32_t* __restrict__ ch_off, const uint32_t* __restrict__ ch_cnt,
@@ -1190,10 +1208,19 @@ k_chunk_count(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ ca
   const uint32_t off = ch_off[tix], cnt = ch_cnt[tix];
   const uint32_t* key = cand_key + (size_t)n * cap_total + off;
   uint32_t gt = 0, tie = 0;
-  for (uint32_t p = lane; p < cnt; p += 64) {
-    const uint32_t kk = key[p];
-    gt += kk > tau;
-    tie += kk == tau;
+  for (uint32_t p0 = 0; p0 < cnt; p0 += 64 * kLaneBatch) {
+    uint32_t kk[kLaneBatch];
+#pragma unroll
+    for (int q = 0; q < kLaneBatch; ++q) {
+      const uint32_t p = p0 + q * 64 + lane;
+      kk[q] = p < cnt ? key[p] : 0u;
+    }
+#pragma unroll
+    for (int q = 0; q < kLaneBatch; ++q) {
+      const bool in = p0 + q * 64 + lane < cnt;
+      gt += in && kk[q] > tau;
+      tie += in && kk[q] == tau;
+    }
   }
   for (int o = 32; o > 0; o >>= 1) { gt += __shfl_down(gt, o); tie += __shfl_down(tie, o); }
   if (lane == 0) { ch_gt[tix] = gt; ch_tie[tix] = tie; }
@@ -1219,45 +1246,57 @@ k_compact(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ cand_k
   s_m[wv][lane + 64] = 0;
   __syncthreads();
   uint32_t first = 0;
+  bool was_empty = true, is_empty = true;
   if (live) {
     const size_t tix = (size_t)n * nc + c;
+    const size_t so = (size_t)n * (nc + 1) + c;
     const uint32_t cnt = ch_cnt[tix];
     const uint32_t off = ch_off[tix];
     const uint32_t tau = ctl[n].tau, budget = ctl[n].budget;
     const size_t cb = (size_t)n * cap_total + off;
-    first = sel_off[(size_t)n * (nc + 1) + c];
+    first = sel_off[so];
+    was_empty = prev_sel_off[so + 1] == prev_sel_off[so];
+    is_empty = sel_off[so + 1] == first;
     uint32_t out = first;
     uint32_t tie_run = tie_off[tix];
-    for (uint32_t p0 = 0; p0 < cnt; p0 += 64) {
-      const uint32_t p = p0 + lane;
-      uint32_t kk = 0;
-      const bool in = p < cnt;
-      if (in) kk = cand_key[cb + p];
-      const bool is_tie = in && kk == tau;
-      const uint64_t tb = __ballot(is_tie);
-      const bool take = in && (kk > tau || (is_tie && tie_run + lanes_below(tb) < budget));
-      const uint64_t sb = __ballot(take);
-      if (take) {
-        const uint32_t o = out + lanes_below(sb);
-        if ((int64_t)o < k) {
-          const uint32_t j = (uint32_t)cand_idx[cb + p] & ~kSentFlag;
-          out_idx[(size_t)n * k + o] = (int32_t)j;
-          out_val[(size_t)n * k + o] = cand_val[cb + p];
-          const uint32_t jl = j & (kChunk - 1);
-          atomicOr(&s_m[wv][jl >> 5], 1u << (jl & 31));
-        }
+    for (uint32_t p0 = 0; p0 < cnt; p0 += 64 * kLaneBatch) {
+      // keys, indices and values of eight candidates per lane, all loads in flight together
+      uint32_t kk[kLaneBatch], jj[kLaneBatch];
+      float vv[kLaneBatch];
+#pragma unroll
+      for (int q = 0; q < kLaneBatch; ++q) {
+        const uint32_t p = p0 + q * 64 + lane;
+        const bool in = p < cnt;
+        kk[q] = in ? cand_key[cb + p] : 0u;
+        jj[q] = in ? (uint32_t)cand_idx[cb + p] & ~kSentFlag : 0u;
+        vv[q] = in ? cand_val[cb + p] : 0.0f;
       }
-      tie_run += (uint32_t)__popcll(tb);
-      out += (uint32_t)__popcll(sb);
+#pragma unroll
+      for (int q = 0; q < kLaneBatch; ++q) {
+        if (p0 + q * 64 >= cnt) break;                       // uniform over the wave
+        const bool in = p0 + q * 64 + lane < cnt;
+        const bool is_tie = in && kk[q] == tau;
+        const uint64_t tb = __ballot(is_tie);
+        const bool take = in && (kk[q] > tau || (is_tie && tie_run + lanes_below(tb) < budget));
+        const uint64_t sb = __ballot(take);
+        if (take) {
+          const uint32_t o = out + lanes_below(sb);
+          if ((int64_t)o < k) {
+            out_idx[(size_t)n * k + o] = (int32_t)jj[q];
+            out_val[(size_t)n * k + o] = vv[q];
+            const uint32_t jl = jj[q] & (kChunk - 1);
+            atomicOr(&s_m[wv][jl >> 5], 1u << (jl & 31));
+          }
+        }
+        tie_run += (uint32_t)__popcll(tb);
+        out += (uint32_t)__popcll(sb);
+      }
     }
   }
   __syncthreads();
   if (live) {
     // a chunk without selected entries in the previous round has all-zero mask
     // words already: nothing to write if it has none now either
-    const size_t so = (size_t)n * (nc + 1) + c;
-    const bool was_empty = prev_sel_off[so + 1] == prev_sel_off[so];
-    const bool is_empty = sel_off[so + 1] == first;
     if (!(was_empty && is_empty)) {
       const size_t wbase = ((size_t)n * nc + c) * kChunkWords;
       reinterpret_cast<uint2*>(mask + wbase)[lane] = make_uint2(s_m[wv][2 * lane], s_m[wv][2 * lane + 1]);
