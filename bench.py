@@ -8,7 +8,7 @@ mu = 1 (the "large CNN-sized" configuration, 20 rounds from a zero error
 state): rounds 0..W-1 are the warm-up, rounds W..W+K-1 are timed.  Prints ONE
 JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--mu MU]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--mu MU] [--grad-dtype f32|bf16]
 """
 from __future__ import annotations
 
@@ -24,11 +24,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 
 
-def algorithmic_bytes(N, d, k):
+def algorithmic_bytes(N, d, k, g_bytes=4):
     """Bytes one round must move: read eps, read g, write eps; dense aggregate;
     index/value lists written, read back for the aggregate and for the next
     round's scores, plus the gathered previous aggregate."""
-    return 12 * N * d + 4 * d + 28 * N * k
+    return (8 + g_bytes) * N * d + 4 * d + 28 * N * k
 
 
 # HBM bytes per launch of the sweep kernel measured with rocprofv3 --pmc
@@ -37,7 +37,7 @@ def algorithmic_bytes(N, d, k):
 MEASURED_SWEEP_TRAFFIC = {"large_cnn": 4997008717}
 
 
-def cpu_baseline(cfg, wl, rounds=3, workers=None):
+def cpu_baseline(cfg, wl, rounds=3, workers=None, bf16=False):
     """The oracle, unchanged, single-threaded, on a bounded sample: the first
     `workers` rows of the same workload for `rounds` rounds."""
     workers = cfg.N if workers is None else workers
@@ -48,7 +48,10 @@ def cpu_baseline(cfg, wl, rounds=3, workers=None):
     agg = None
     elapsed = 0.0
     for t in range(rounds):
-        g = wl.grads(t)[:workers].contiguous().cpu().numpy()
+        g = wl.grads(t)[:workers].contiguous()
+        if bf16:
+            g = g.to(torch.bfloat16).float()
+        g = g.cpu().numpy()
         t0 = time.perf_counter()
         _, _, agg = o.step(g, agg)
         elapsed += time.perf_counter() - t0
@@ -90,6 +93,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="large_cnn")
     ap.add_argument("--mu", type=float, default=None)
+    ap.add_argument("--grad-dtype", choices=["f32", "bf16"], default="f32",
+                    help="storage type of the local gradients (bf16: widened exactly, arithmetic stays f32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--max-buffers", type=int, default=24,
                     help="rounds of gradients kept resident in HBM (cycled if steps+warmup is larger)")
@@ -114,6 +119,10 @@ def main():
 
     n_buf = min(args.warmup + args.steps, args.max_buffers)
     grads = [wl.grads(t) for t in range(n_buf)]
+    g_bytes = 4
+    if args.grad_dtype == "bf16":
+        grads = [g.to(torch.bfloat16).contiguous() for g in grads]
+        g_bytes = 2
     torch.cuda.synchronize()
 
     # one plain copy of known size (256 Mi floats: 1 GiB read, 1 GiB written): the
@@ -150,9 +159,9 @@ def main():
 
     entries = N * d
     value = entries / (ms_per_step * 1e-3)
-    sweep_bytes = 12 * N * d                      # read eps, read g, write eps
+    sweep_bytes = (8 + g_bytes) * N * d           # read eps, read g, write eps
     achieved = sweep_bytes / (sweep_ms * 1e-3) / 1e9
-    b_alg = algorithmic_bytes(N, d, k)
+    b_alg = algorithmic_bytes(N, d, k, g_bytes)
     out = {
         "metric": "gradient entries/sec per RegTop-k round (N*d)",
         "value": value, "unit": "gradient entries/s", "n_gpus": 1,
@@ -161,7 +170,8 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: N=%d workers, d=%d, k=%d, mu=%g, per-layer scales, %s entries, "
                                "30%% shared component" % (cfg.name, N, d, k, cfg.mu, cfg.marginal),
-                   "N": N, "d": d, "k": k, "mu": cfg.mu, "rounds_resident": n_buf},
+                   "N": N, "d": d, "k": k, "mu": cfg.mu, "rounds_resident": n_buf,
+                   "grad_dtype": args.grad_dtype},
         "hbm_frac_round": b_alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "algorithmic_bytes_per_round": b_alg,
         "stage_ms": {"sweep": sweep_ms, "select": select_ms, "compact_aggregate": tail_ms,
@@ -171,14 +181,14 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "k_accum_emit", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "algorithmic_bytes_per_launch": sweep_bytes, "avg_launch_ms": sweep_ms,
-                     "traffic": MEASURED_SWEEP_TRAFFIC.get(cfg.name)},
+                     "traffic": MEASURED_SWEEP_TRAFFIC.get(cfg.name) if args.grad_dtype == "f32" else None},
     }
     out["extras"] = time_extras(torch, binding, r, agg, N, d)
     r.close()
     del grads
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, wl)
+        out["cpu_baseline"] = cpu_baseline(cfg, wl, bf16=args.grad_dtype == "bf16")
     print(json.dumps(out))
 
 

@@ -111,6 +111,18 @@ int regtopk_create_in(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float 
 int regtopk_step(regtopk_ctx* ctx, const float* grads_dev, const float* prev_aggregate_dev,
                  void* stream, regtopk_result* out);
 
+/* The same round with the local gradients stored as bfloat16 (the upper 16
+ * bits of a binary32 pattern; reduced-precision gradient inputs with binary32
+ * state).  Each gradient is widened exactly to binary32 and everything else is
+ * as in regtopk_step (paper: Algorithm 2; the paper fixes no input precision),
+ * so the result equals regtopk_step on the widened values bit for bit, while
+ * the sweep reads 10 instead of 12 bytes per entry.  grads_bf16_dev [N,d]
+ * row-major, 2-byte aligned; read with 64-bit loads when d is a multiple of 4
+ * and the pointer is 8-byte aligned.  Calls with either gradient type may be
+ * mixed freely on one context. */
+int regtopk_step_bf16(regtopk_ctx* ctx, const uint16_t* grads_bf16_dev, const float* prev_aggregate_dev,
+                      void* stream, regtopk_result* out);
+
 int regtopk_destroy(regtopk_ctx* ctx);
 
 /* Back to the state after create (eps = 0, round 0, no previous mask). */

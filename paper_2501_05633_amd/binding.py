@@ -19,7 +19,7 @@ OPT_FORCE_DENSE, OPT_CAND_TARGET, OPT_PROFILE = 1, 2, 3
 
 # every symbol include/regtopk.h declares
 SYMBOLS = [
-    "regtopk_workspace_bytes", "regtopk_create", "regtopk_create_in", "regtopk_step",
+    "regtopk_workspace_bytes", "regtopk_create", "regtopk_create_in", "regtopk_step", "regtopk_step_bf16",
     "regtopk_destroy", "regtopk_reset", "regtopk_get_state", "regtopk_set_state",
     "regtopk_get_stats", "regtopk_set_option", "regtopk_get_timings", "regtopk_tanh_f32",
     "regtopk_copy_f32", "regtopk_set_weights", "regtopk_mask_overlap", "regtopk_sgd_update",
@@ -62,6 +62,7 @@ def load():
     lib.regtopk_create_in.argtypes = [ctypes.POINTER(c_void_p), c_int32, c_int64, c_int64, c_float,
                                       c_void_p, c_size_t, c_void_p]
     lib.regtopk_step.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, ctypes.POINTER(Result)]
+    lib.regtopk_step_bf16.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, ctypes.POINTER(Result)]
     lib.regtopk_destroy.argtypes = [c_void_p]
     lib.regtopk_reset.argtypes = [c_void_p, c_void_p]
     lib.regtopk_get_state.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p,
@@ -117,7 +118,7 @@ def _view(torch, ptr: int, shape, dtype, device, arena=None):
 class RegTopk:
     """regtopk_create / regtopk_step / regtopk_destroy with torch tensors.
 
-    ``step(grads, prev_aggregate)`` takes CUDA float32 tensors ([N,d] and [d])
+    ``step(grads, prev_aggregate)`` takes CUDA tensors ([N,d] float32 or bfloat16, and [d] float32)
     and returns ``(idx [N,k] int32, val [N,k] float32, agg [d] float32)`` as
     views into the context's memory, valid until the next step.
     """
@@ -159,9 +160,10 @@ class RegTopk:
 
     def step(self, grads, prev_aggregate=None):
         torch = self._torch
-        if grads.device != self.device or grads.dtype != torch.float32 or not grads.is_contiguous() \
-                or tuple(grads.shape) != (self.N, self.d):
-            raise ValueError("grads must be a contiguous float32 [N,d] tensor on %s" % self.device)
+        if grads.device != self.device or grads.dtype not in (torch.float32, torch.bfloat16) \
+                or not grads.is_contiguous() or tuple(grads.shape) != (self.N, self.d):
+            raise ValueError("grads must be a contiguous float32 or bfloat16 [N,d] tensor on %s" % self.device)
+        fn = self.lib.regtopk_step if grads.dtype == torch.float32 else self.lib.regtopk_step_bf16
         gp = c_void_p(0)
         if prev_aggregate is not None:
             if prev_aggregate.device != self.device or prev_aggregate.dtype != torch.float32 \
@@ -170,8 +172,7 @@ class RegTopk:
             gp = c_void_p(prev_aggregate.data_ptr())
         res = Result()
         with torch.cuda.device(self.device):
-            _check(self.lib.regtopk_step(self._h, c_void_p(grads.data_ptr()), gp, _stream_ptr(torch),
-                                         ctypes.byref(res)))
+            _check(fn(self._h, c_void_p(grads.data_ptr()), gp, _stream_ptr(torch), ctypes.byref(res)))
         idx = _view(torch, res.idx, (self.N, self.k), torch.int32, self.device, self._arena)
         val = _view(torch, res.val, (self.N, self.k), torch.float32, self.device, self._arena)
         agg = _view(torch, res.agg, (self.d,), torch.float32, self.device, self._arena)

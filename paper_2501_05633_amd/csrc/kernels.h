@@ -237,10 +237,32 @@ __device__ __forceinline__ ChunkPos ordered_positions(uint32_t flags, uint32_t* 
 // grid (nc, N).  VEC: d % 4 == 0 and 16-byte aligned rows.  The sweep touches
 // every byte exactly once, so it loads and stores with the non-temporal hint.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-template <bool VEC>
+// Local gradients arrive as binary32 or as bfloat16 (the upper half of a
+// binary32 pattern: widening is exact, the arithmetic stays binary32).
+struct bf16_t { uint16_t bits; };
+__device__ __forceinline__ float grad_at(const float* g, size_t i) { return g[i]; }
+__device__ __forceinline__ float grad_at(const bf16_t* g, size_t i) {
+  return __uint_as_float((uint32_t)g[i].bits << 16);
+}
+// four consecutive gradients from an address aligned to the four of them
+__device__ __forceinline__ f32x4 grad4_at(const float* g, size_t i) {
+  return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(g + i));
+}
+__device__ __forceinline__ f32x4 grad4_at(const bf16_t* g, size_t i) {
+  const u32x2 w = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(g + i));
+  f32x4 r;
+  r.x = __uint_as_float(w.x << 16);
+  r.y = __uint_as_float(w.x & 0xFFFF0000u);
+  r.z = __uint_as_float(w.y << 16);
+  r.w = __uint_as_float(w.y & 0xFFFF0000u);
+  return r;
+}
+
+template <bool VEC, typename G>
 __global__ void __launch_bounds__(kBlock)
-k_accum_emit(float* __restrict__ e, const float* __restrict__ g, const uint32_t* __restrict__ mask,
+k_accum_emit(float* __restrict__ e, const G* __restrict__ g, const uint32_t* __restrict__ mask,
              const uint32_t* __restrict__ prev_sel_off, int64_t d, WorkerCtl* __restrict__ ctl,
              int32_t* __restrict__ cand_idx,
              float* __restrict__ cand_val, float* __restrict__ cand_prev, uint32_t* __restrict__ ch_off,
@@ -273,7 +295,7 @@ k_accum_emit(float* __restrict__ e, const float* __restrict__ g, const uint32_t*
       const int64_t j0 = base + i * 256;
       if (j0 < d) {
         ev[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(e + row + j0));
-        gv[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(g + row + j0));
+        gv[i] = grad4_at(g, row + j0);
       } else {
         ev[i] = f32x4{0.f, 0.f, 0.f, 0.f};
         gv[i] = ev[i];
@@ -310,7 +332,7 @@ k_accum_emit(float* __restrict__ e, const float* __restrict__ g, const uint32_t*
         if (j < d) {
           eo[i][q] = e[row + j];
           const float eps = ((mb[i] >> q) & 1u) ? 0.f : eo[i][q];
-          a[i][q] = eps + g[row + j];
+          a[i][q] = eps + grad_at(g, row + j);
           e[row + j] = a[i][q];
           if (key_of(a[i][q]) >= tau_lo) flags |= 1u << (i * 4 + q);
         }
@@ -763,8 +785,9 @@ k_select(WorkerCtl* ctl, GlobalCtl* gctl, const uint32_t* __restrict__ cand_key,
 constexpr uint32_t kSampleMax = 1u << 18;     // sampled entries per worker (whole row if shorter)
 
 // grid (blocks, N).  Sample i is the group of 4 entries at 4*i*stride4.
+template <typename G>
 __global__ void __launch_bounds__(kBlock)
-k_sample_hist(const float* __restrict__ e, const float* __restrict__ g, const uint32_t* __restrict__ mask,
+k_sample_hist(const float* __restrict__ e, const G* __restrict__ g, const uint32_t* __restrict__ mask,
               int64_t d, uint32_t nc, uint32_t* __restrict__ shist, uint32_t n_groups, uint32_t stride4) {
   __shared__ uint32_t s_hist[kL1Bins];
   const uint32_t n = blockIdx.y, tid = threadIdx.x;
@@ -779,7 +802,7 @@ k_sample_hist(const float* __restrict__ e, const float* __restrict__ g, const ui
       const int64_t j = j0 + q;
       if (j < d) {
         const uint32_t sent = (mrow[j >> 5] >> (j & 31)) & 1u;
-        const float a = (sent ? 0.0f : e[row + j]) + g[row + j];
+        const float a = (sent ? 0.0f : e[row + j]) + grad_at(g, row + j);
         atomicAdd(&s_hist[key_of(a) >> kL1Shift], 1u);
       }
     }

@@ -255,19 +255,25 @@ int regtopk_set_option(regtopk_ctx* c, int option, double value) {
   }
 }
 
-int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* stream, regtopk_result* out) {
+}  // extern "C"
+
+namespace {
+
+// One round; G is the element type of the local gradients.
+template <typename G>
+int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, regtopk_result* out) {
   if (!c || !grads || !out) return fail(REGTOPK_INVALID_ARG, "ctx, grads_dev and out must not be NULL");
   const int use_reg = (c->have_prev && c->mu > 0.0f) ? 1 : 0;
   if (use_reg && !gprev) return fail(REGTOPK_INVALID_ARG, "prev_aggregate_dev is required after round 0 when mu > 0");
-  if (reinterpret_cast<uintptr_t>(grads) % 4 || reinterpret_cast<uintptr_t>(gprev) % 4)
-    return fail(REGTOPK_INVALID_ARG, "device pointers must be 4-byte aligned");
+  if (reinterpret_cast<uintptr_t>(grads) % sizeof(G) || reinterpret_cast<uintptr_t>(gprev) % 4)
+    return fail(REGTOPK_INVALID_ARG, "device pointers must be aligned to their element type");
   hipStream_t s = static_cast<hipStream_t>(stream);
   const Layout& L = c->L;
   const int32_t N = c->N;
   const int64_t d = c->d, k = c->k;
   const uint32_t nc = L.nc;
   const int cur = (int)(c->t & 1), prv = cur ^ 1;
-  const bool vec = (d % 4 == 0) && (reinterpret_cast<uintptr_t>(grads) % 16 == 0);
+  const bool vec = (d % 4 == 0) && (reinterpret_cast<uintptr_t>(grads) % (4 * sizeof(G)) == 0);
 
   WorkerCtl* ctl = c->at<WorkerCtl>(L.ctl);
   GlobalCtl* gctl = c->at<GlobalCtl>(L.gctl);
@@ -306,15 +312,15 @@ int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* s
     uint64_t n_sampled = (uint64_t)n_groups * 4;
     if (n_sampled > (uint64_t)d) n_sampled = (uint64_t)d;
     k_fill_u32<<<64, 256, 0, s>>>(fhist, (size_t)N * 3 * kL1Bins, 0u);
-    k_sample_hist<<<dim3((n_groups + 4 * kBlock - 1) / (4 * kBlock), N), kBlock, 0, s>>>(e, grads, mask, d, nc, fhist, n_groups, stride4);
+    k_sample_hist<G><<<dim3((n_groups + 4 * kBlock - 1) / (4 * kBlock), N), kBlock, 0, s>>>(e, grads, mask, d, nc, fhist, n_groups, stride4);
     k_sample_bound<<<N, kScanBlock, 0, s>>>(ctl, fhist, d, k, (uint32_t)n_sampled);
   }
   c->fresh = false;
   if (ev) HIP_TRY(hipEventRecord(ev[0], s));
   if (vec)
-    k_accum_emit<true><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, prev_sel_off, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
+    k_accum_emit<true, G><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, prev_sel_off, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   else
-    k_accum_emit<false><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, prev_sel_off, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
+    k_accum_emit<false, G><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, prev_sel_off, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   if (ev) HIP_TRY(hipEventRecord(ev[1], s));
   k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_prev, cand_key, bnd_key, gprev, d, L.cap_r, L.cap_total, L.bnd_cap, omega, c->mu, use_reg);
   k_select<<<N, kScanBlock, 0, s>>>(ctl, gctl, cand_key, bnd_key, k, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->cand_target, c->force_dense);
@@ -339,6 +345,18 @@ int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* s
   out->val = out_val;
   out->agg = agg;
   return REGTOPK_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* stream, regtopk_result* out) {
+  return step_impl<float>(c, grads, gprev, stream, out);
+}
+
+int regtopk_step_bf16(regtopk_ctx* c, const uint16_t* grads, const float* gprev, void* stream, regtopk_result* out) {
+  return step_impl<bf16_t>(c, reinterpret_cast<const bf16_t*>(grads), gprev, stream, out);
 }
 
 int regtopk_get_state(regtopk_ctx* c, float* e_dev, int32_t* pidx_dev, float* pval_dev, int64_t* t_host, void* stream) {

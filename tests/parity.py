@@ -65,13 +65,16 @@ def compare_round(o: orc.Oracle, res_gpu, res_cpu, label=""):
 
 def run_both(N, d, k, mu, grads_fn, T, device="cuda:0", force_dense=False, closed_loop=None,
              label="", check_state_every=1, cand_target=None, weights=None, check_overlap=False,
-             on_round=None):
+             on_round=None, grad_dtype=None):
     """grads_fn(t, agg_prev_or_None) -> [N,d] float32 tensor on the GPU.
 
     Each side feeds its own aggregate back as g^{t-1}.  Returns per-round stats
     of the HIP path.  `weights`: aggregation weights omega_n for both sides;
     `check_overlap`: also compare the mask-overlap counts of every round;
-    `on_round(t, res_gpu, res_cpu)`: hook after the comparison of round t.
+    `on_round(t, res_gpu, res_cpu)`: hook after the comparison of round t;
+    `grad_dtype`: torch.bfloat16 (or a function t -> dtype) rounds the generated
+    gradients to bfloat16 first and hands the HIP path the 16-bit tensor, the
+    oracle the same values widened to binary32.
     """
     dev = torch.device(device)
     o = orc.Oracle(N, d, k, mu)
@@ -90,7 +93,10 @@ def run_both(N, d, k, mu, grads_fn, T, device="cuda:0", force_dense=False, close
     for t in range(T):
         g = grads_fn(t, agg_g)
         assert g.is_cuda and g.dtype == torch.float32
-        g_host = g.cpu().numpy()
+        dt = grad_dtype(t) if callable(grad_dtype) else grad_dtype
+        if dt is not None and dt != torch.float32:
+            g = g.to(dt).contiguous()
+        g_host = g.float().cpu().numpy()
         res_g = r.step(g, agg_g)
         torch.cuda.synchronize(dev)
         res_c = o.step(g_host, agg_c)

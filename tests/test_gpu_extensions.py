@@ -163,3 +163,40 @@ def test_paper_linear_regression_loop_with_sgd_update(mu, k):
                           on_round=after, check_overlap=True)
     assert tol == 0
     assert wl.gap(theta_g) < 0.2 * gap0                              # the loop does descend
+
+
+@pytest.mark.parametrize("name,d,N,k,T,mixed", [
+    ("tiny", 10_000, 4, 100, 6, False),
+    ("large_cnn", 300_001, 3, 3_000, 5, False),      # ragged tail: scalar loads of 16-bit gradients
+    ("large_cnn", 1_000_000, 4, 10_000, 6, False),   # 64-bit loads
+    ("cnn", 400_000, 2, 400, 6, True),               # binary32 and bfloat16 rounds alternate on one context
+])
+def test_bfloat16_gradients(name, d, N, k, T, mixed):
+    print("case bf16 %s d=%d" % (name, d), flush=True)
+    cfg = workloads.scaled(workloads.CONFIGS[name], d=d, N=N, k=k)
+    dt = (lambda t: torch.bfloat16 if t % 2 else torch.float32) if mixed else torch.bfloat16
+    stats, tol = run_both(N, d, k, 1.0, _wl_fn(cfg), T, label="bf16 %s" % name, grad_dtype=dt)
+    assert tol == 0
+
+
+def test_bfloat16_gradients_unaligned_rows_and_forced_dense():
+    print("case bf16 unaligned", flush=True)
+    N, d, k = 2, 40_004, 400
+    cfg = workloads.scaled(workloads.CONFIGS["tiny"], d=d, N=N, k=k)
+    wl = workloads.Workload(cfg, DEV)
+    o = orc.Oracle(N, d, k, 1.0)
+    r = binding.RegTopk(N, d, k, 1.0, device=DEV)
+    agg_g = agg_c = None
+    for t in range(4):
+        if t == 2:
+            r.set_option(binding.OPT_FORCE_DENSE, 1)
+        buf = torch.empty(N * d + 1, dtype=torch.bfloat16, device=DEV)
+        g = buf[1:].view(N, d)                                   # 2-byte aligned only
+        g.copy_(wl.grads(t))
+        idx, val, agg_g = r.step(g, agg_g)
+        agg_g = agg_g.clone()
+        ic, vc, agg_c = o.step(g.float().cpu().numpy(), agg_c)
+        assert np.array_equal(idx.cpu().numpy(), ic)
+        assert np.array_equal(val.cpu().numpy(), vc)
+        assert np.array_equal(agg_g.cpu().numpy(), agg_c)
+    r.close()
