@@ -53,6 +53,12 @@ def _load():
     lib.rtk_oracle_set_weights.argtypes = [c.c_void_p, c.c_void_p]
     lib.rtk_oracle_mask_overlap.argtypes = [c.c_void_p, c.c_void_p]
     lib.rtk_oracle_sgd_update.argtypes = [c.c_void_p, c.c_void_p, c.c_float, c.c_int64]
+    lib.rtk_oracle_set_score_variant.restype = c.c_int
+    lib.rtk_oracle_set_score_variant.argtypes = [c.c_void_p, c.c_int, c.c_int]
+    lib.rtk_oracle_likelihood_sent_kind.restype = c.c_float
+    lib.rtk_oracle_likelihood_sent_kind.argtypes = [c.c_float] * 5 + [c.c_int]
+    lib.rtk_oracle_prior.restype = c.c_float
+    lib.rtk_oracle_prior.argtypes = [c.c_float, c.c_int]
     lib.rtk_oracle_tanh32.restype = c.c_float
     lib.rtk_oracle_tanh32.argtypes = [c.c_float]
     lib.rtk_oracle_likelihood_sent.restype = c.c_float
@@ -115,6 +121,11 @@ class Oracle:
             raise ValueError("weights must be [N]")
         self._lib.rtk_oracle_set_weights(self._h, ws.ctypes.data)
 
+    def set_score_variant(self, sqrt_steps: int = 0, likelihood: int = 0):
+        """Prior |a|^(2^-sqrt_steps) and likelihood kind (0 tanh, 1 clipped linear)."""
+        if self._lib.rtk_oracle_set_score_variant(self._h, int(sqrt_steps), int(likelihood)) != 0:
+            raise ValueError("sqrt_steps must be 0..3 and likelihood 0 or 1")
+
     def mask_overlap(self) -> np.ndarray:
         """counts[c] = number of entries selected by exactly c workers in the last round."""
         counts = np.zeros(self.N + 1, dtype=np.int64)
@@ -163,6 +174,16 @@ def likelihood_sent(a_now, a_before, g_before, w, mu) -> float:
     f = np.float32
     return float(_load().rtk_oracle_likelihood_sent(
         float(f(a_now)), float(f(a_before)), float(f(g_before)), float(f(w)), float(f(mu))))
+
+
+def likelihood_sent_kind(a_now, a_before, g_before, w, mu, kind: int) -> float:
+    f = np.float32
+    return float(_load().rtk_oracle_likelihood_sent_kind(
+        float(f(a_now)), float(f(a_before)), float(f(g_before)), float(f(w)), float(f(mu)), int(kind)))
+
+
+def prior(a, sqrt_steps: int) -> float:
+    return float(_load().rtk_oracle_prior(float(np.float32(a)), int(sqrt_steps)))
 
 
 def topk_mask(score, k: int) -> np.ndarray:

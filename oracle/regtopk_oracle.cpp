@@ -45,6 +45,13 @@
 //   R8  aggregation: start from +0 and add w * ghat_n[j] for n = 0..N-1 in
 //       ascending worker order.
 //   R9  the sent values are the un-weighted entries of a; the server applies w.
+//   R15 score variants of the appendix remark on sub-linear scaling and of the
+//       sentence that other cumulative functions u_mu may replace tanh:
+//       the prior |a|^y is offered for y = 2^-m, m = 0..3, and evaluated as m
+//       successive correctly rounded binary32 square roots of |a| (so that both
+//       sides of the parity check can take it bit for bit); besides tanh the
+//       likelihood may be the cumulative function of a uniform innovation,
+//       min(|1+Delta|/mu, 1).  The defaults (m = 0, tanh) are Algorithm 2.
 
 #include <algorithm>
 #include <cmath>
@@ -60,6 +67,8 @@ struct Oracle {
     int64_t d, k;
     float mu;
     std::vector<float> w;        // [N] aggregation weights omega_n (R2)
+    int sqrt_steps;              // prior |a|^y with y = 2^-sqrt_steps (R15)
+    int likelihood;              // 0: tanh(x), 1: min(x, 1) (R15)
     int64_t t;       // rounds done so far
     std::vector<float> e;        // [N*d] sparsification error eps_n
     std::vector<float> a;        // [N*d] accumulated gradient of the last round
@@ -77,7 +86,7 @@ float tanh32(float x) {
 
 // Likelihood factor for an entry that WAS sent in the previous round
 // (Algorithm 2, distortion line and the tanh in the mask line).  R4, R7.
-float likelihood_sent(float a_now, float a_before, float g_before, float w, float mu) {
+float likelihood_sent(float a_now, float a_before, float g_before, float w, float mu, int kind = 0) {
     float num = g_before - w * a_before;   // g^{t-1} - omega a^{t-1}
     float den = w * a_now;                 // omega a^t
     if (den == 0.0f) return 1.0f;
@@ -85,7 +94,15 @@ float likelihood_sent(float a_now, float a_before, float g_before, float w, floa
     float r = std::fabs(1.0f + D);
     float x = r / mu;
     if (x != x) return 1.0f;
+    if (kind == 1) return x < 1.0f ? x : 1.0f;   // uniform innovation on [0, mu]
     return tanh32(x);
+}
+
+// Prior |a|^y, y = 2^-m, as m correctly rounded square roots (R15).
+float prior(float a, int m) {
+    float p = std::fabs(a);
+    for (int i = 0; i < m; ++i) p = std::sqrt(p);
+    return p;
 }
 
 // Top_k selector: mask with exactly k ones on the k largest scores, lower index
@@ -112,6 +129,8 @@ void* rtk_oracle_create(int32_t N, int64_t d, int64_t k, float mu) {
     o->N = N; o->d = d; o->k = k; o->mu = mu;
     o->w.assign((size_t)N, 1.0f / (float)N);
     o->t = 0;
+    o->sqrt_steps = 0;
+    o->likelihood = 0;
     size_t nd = (size_t)N * (size_t)d;
     o->e.assign(nd, 0.0f);           // eps^0 = 0
     o->a.assign(nd, 0.0f);
@@ -148,8 +167,8 @@ void rtk_oracle_step(void* h, const float* grads, const float* gprev,
             a[j] = e[j] + g[j];                              // accumulate
             float f = 1.0f;                                  // C = 1 (R3)
             if (mu != 0.0f && sp[j])                         // R5, R6
-                f = likelihood_sent(a[j], ap[j], gprev[j], w, mu);
-            sc[j] = std::fabs(a[j]) * f;                     // |a . tanh(.)|
+                f = likelihood_sent(a[j], ap[j], gprev[j], w, mu, o->likelihood);
+            sc[j] = prior(a[j], o->sqrt_steps) * f;          // |a|^y . u(|1 + Delta|)
         }
         topk_mask(sc, d, k, s);                              // s^t = Top_k(.)
         int64_t c = 0;
@@ -175,6 +194,16 @@ void rtk_oracle_step(void* h, const float* grads, const float* gprev,
 void rtk_oracle_set_weights(void* h, const float* w) {
     Oracle* o = (Oracle*)h;
     for (int32_t n = 0; n < o->N; ++n) o->w[(size_t)n] = w[n];
+}
+
+// Score variant (R15): prior exponent y = 2^-sqrt_steps (0..3) and the kind of
+// likelihood (0 tanh, 1 clipped linear).  Returns 0 on success.
+int rtk_oracle_set_score_variant(void* h, int sqrt_steps, int likelihood) {
+    Oracle* o = (Oracle*)h;
+    if (sqrt_steps < 0 || sqrt_steps > 3 || likelihood < 0 || likelihood > 1) return -1;
+    o->sqrt_steps = sqrt_steps;
+    o->likelihood = likelihood;
+    return 0;
 }
 
 // How far the masks of the last round agree (appendix "Comparing Sparsification
@@ -211,6 +240,10 @@ float rtk_oracle_tanh32(float x) { return tanh32(x); }
 float rtk_oracle_likelihood_sent(float a_now, float a_before, float g_before, float w, float mu) {
     return likelihood_sent(a_now, a_before, g_before, w, mu);
 }
+float rtk_oracle_likelihood_sent_kind(float a_now, float a_before, float g_before, float w, float mu, int kind) {
+    return likelihood_sent(a_now, a_before, g_before, w, mu, kind);
+}
+float rtk_oracle_prior(float a, int sqrt_steps) { return prior(a, sqrt_steps); }
 void rtk_oracle_topk_mask(const float* score, int64_t d, int64_t k, uint8_t* mask) {
     topk_mask(score, d, k, mask);
 }

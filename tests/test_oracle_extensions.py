@@ -156,3 +156,139 @@ def test_sgd_update_exact_cases_and_rounding_order():
     assert out[0] == f32(0.0)
     with pytest.raises(ValueError):
         oracle.sgd_update(np.zeros(3, dtype=f32), np.zeros(4, dtype=f32), 0.1)
+
+
+# ------------------------------------------------------------ score variants ----
+def test_default_variant_is_algorithm_2():
+    rounds = _rounds(5, 4, 1500, 30)
+    a, b = oracle.Oracle(4, 1500, 30, 1.0), oracle.Oracle(4, 1500, 30, 1.0)
+    b.set_score_variant(0, 0)
+    ga = gb = None
+    for g in rounds:
+        ia, va, ga = a.step(g, ga)
+        ib, vb, gb = b.step(g, gb)
+        assert np.array_equal(ia, ib) and np.array_equal(va, vb) and np.array_equal(ga, gb)
+    with pytest.raises(ValueError):
+        b.set_score_variant(4, 0)
+    with pytest.raises(ValueError):
+        b.set_score_variant(0, 2)
+
+
+def test_prior_is_the_correctly_rounded_root():
+    # |a|^(1/2): the binary32 nearest to the exact root; |a|^(1/4), |a|^(1/8): that step repeated
+    mpmath.mp.prec = 200
+    rng = np.random.default_rng(21)
+    xs = np.concatenate([np.abs(rng.standard_normal(300)) * 10.0 ** rng.uniform(-30, 30, 300),
+                         [0.0, 1.0, 4.0, 2.0, 1e-45, 3.4e38]]).astype(f32)
+    for x in xs:
+        p = f32(oracle.prior(-x, 1))
+        assert p == f32(oracle.prior(x, 1))                               # magnitude only
+        exact = mpmath.sqrt(mpmath.mpf(float(x)))
+        lo, hi = np.nextafter(p, f32(-np.inf)), np.nextafter(p, f32(np.inf))
+        assert abs(mpmath.mpf(float(p)) - exact) <= abs(mpmath.mpf(float(lo)) - exact)
+        assert abs(mpmath.mpf(float(p)) - exact) <= abs(mpmath.mpf(float(hi)) - exact)
+        assert oracle.prior(x, 2) == oracle.prior(oracle.prior(x, 1), 1)
+        assert oracle.prior(x, 3) == oracle.prior(oracle.prior(x, 2), 1)
+        assert oracle.prior(x, 0) == float(x)
+    assert oracle.prior(16.0, 1) == 4.0 and oracle.prior(16.0, 2) == 2.0 and oracle.prior(256.0, 3) == 2.0
+
+
+def test_exponent_does_not_change_plain_topk():
+    # Remark on sub-linear scaling: without the regulariser the exponent does not affect the sorting.
+    rounds = _rounds(5, 3, 2500, 50)
+    ref = oracle.Oracle(3, 2500, 50, 0.0)
+    others = []
+    for m in (1, 2, 3):
+        o = oracle.Oracle(3, 2500, 50, 0.0)
+        o.set_score_variant(m, 0)
+        others.append(o)
+    for g in rounds:
+        i0, v0, a0 = ref.step(g, None)
+        for o in others:
+            i, v, a = o.step(g, None)
+            assert np.array_equal(i, i0) and np.array_equal(v, v0) and np.array_equal(a, a0)
+
+
+def test_exponent_scores_and_selection_invariant():
+    N, d, k = 3, 3000, 60
+    for m in (1, 2):
+        o = oracle.Oracle(N, d, k, 1.0)
+        o.set_score_variant(m, 0)
+        agg = None
+        for t, g in enumerate(_rounds(4, N, d, k)):
+            prev_mask = o.mask if t else np.zeros((N, d), dtype=np.uint8)
+            idx, val, agg = o.step(g, agg)
+            sc, a, msk = o.score, o.a, o.mask
+            root = np.abs(a)
+            for _ in range(m):
+                root = np.sqrt(root)                                  # numpy's binary32 sqrt is correctly rounded too
+            assert sc.dtype == np.float32 and np.all(sc <= root)
+            assert np.array_equal(sc[prev_mask == 0], root[prev_mask == 0])   # factor exactly 1 off the previous mask
+            if t:
+                assert np.any(sc[prev_mask == 1] < root[prev_mask == 1])
+            for n in range(N):
+                assert msk[n].sum() == k
+                assert sc[n][msk[n] == 1].min() >= sc[n][msk[n] == 0].max()
+
+
+def test_exponent_half_commutes_with_scaling_by_four():
+    # sqrt(4^p x) = 2^p sqrt(x) exactly, so scaling every gradient (and the fed-back
+    # aggregate) by a power of 4 leaves the masks of the y = 1/2 variant unchanged.
+    N, d, k = 3, 2000, 40
+    rounds = _rounds(4, N, d, k)
+    base, scaled = oracle.Oracle(N, d, k, 0.8), oracle.Oracle(N, d, k, 0.8)
+    base.set_score_variant(1, 0)
+    scaled.set_score_variant(1, 0)
+    ga = gb = None
+    for g in rounds:
+        ia, va, ga = base.step(g, ga)
+        ib, vb, gb = scaled.step(g * f32(16.0), gb)
+        assert np.array_equal(ia, ib)
+        assert np.array_equal(va * f32(16.0), vb) and np.array_equal(ga * f32(16.0), gb)
+
+
+def test_clipped_linear_likelihood():
+    # cumulative function of a uniform innovation: min(|1 + Delta| / mu, 1)
+    mpmath.mp.prec = 200
+    rng = np.random.default_rng(31)
+    for _ in range(300):
+        a_now, a_bef, g_bef = (f32(x) for x in rng.standard_normal(3))
+        w, mu = f32(rng.uniform(0.02, 1.0)), f32(rng.uniform(0.05, 5.0))
+        got = oracle.likelihood_sent_kind(a_now, a_bef, g_bef, w, mu, 1)
+        m = mpmath.mpf
+        den = m(float(w)) * m(float(a_now))
+        num = m(float(g_bef)) - m(float(w)) * m(float(a_bef))
+        x = abs(1 + num / den) / m(float(mu))
+        want = min(x, m(1))
+        # five roundings, conditioned by 1/|den| through the sum 1 + Delta
+        cond = (abs(num / den) + 1) / max(abs(1 + num / den), m(2) ** -60)
+        tol = float(want) * 2.0 ** -23 * (3 + 3 * float(cond)) + 1e-30
+        assert abs(got - float(want)) <= tol, (a_now, a_bef, g_bef, w, mu, got, float(want))
+        assert 0.0 <= got <= 1.0
+    # closed cases: cancelled entry, sole sender, saturation, monotone in |1 + Delta|
+    assert oracle.likelihood_sent_kind(2.0, 2.0, 0.0, 0.5, 1.0, 1) == 0.0
+    assert oracle.likelihood_sent_kind(2.0, 2.0, 1.0, 0.5, 4.0, 1) == 0.25
+    assert oracle.likelihood_sent_kind(2.0, 2.0, 1.0, 0.5, 0.5, 1) == 1.0
+    assert oracle.likelihood_sent_kind(0.0, 2.0, 1.0, 0.5, 1.0, 1) == 1.0      # zero denominator: no information
+    vals = [oracle.likelihood_sent_kind(1.0, 1.0, g, 1.0, 2.0, 1) for g in np.linspace(0.0, 3.0, 40)]
+    assert all(b >= a for a, b in zip(vals, vals[1:])) and vals[0] == 0.0 and vals[-1] == 1.0
+    # and the same kind argument with 0 is the tanh likelihood
+    assert oracle.likelihood_sent_kind(1.3, 0.7, 0.2, 0.25, 0.9, 0) == oracle.likelihood_sent(1.3, 0.7, 0.2, 0.25, 0.9)
+
+
+def test_clipped_linear_rounds_keep_the_invariants():
+    N, d, k = 4, 3000, 60
+    o = oracle.Oracle(N, d, k, 2.0)
+    o.set_score_variant(0, 1)
+    agg = None
+    damped = 0
+    for t, g in enumerate(_rounds(5, N, d, k)):
+        prev_mask = o.mask if t else np.zeros((N, d), dtype=np.uint8)
+        idx, val, agg = o.step(g, agg)
+        sc, a, msk, e = o.score, o.a, o.mask, o.e
+        assert np.all(sc <= np.abs(a)) and np.array_equal(sc[prev_mask == 0], np.abs(a)[prev_mask == 0])
+        damped += int((sc[prev_mask == 1] < np.abs(a)[prev_mask == 1]).sum())
+        for n in range(N):
+            assert msk[n].sum() == k and sc[n][msk[n] == 1].min() >= sc[n][msk[n] == 0].max()
+            assert np.array_equal(a[n][idx[n]], val[n]) and np.all(e[n][idx[n]] == 0)
+    assert damped > 0
