@@ -37,7 +37,7 @@ def algorithmic_bytes(N, d, k, g_bytes=4):
 MEASURED_SWEEP_TRAFFIC = {"large_cnn": 4997008717}
 
 
-def cpu_baseline(cfg, wl, rounds=3, workers=None, bf16=False):
+def cpu_baseline(cfg, wl, rounds=3, workers=None, bf16=False, variant=(0, 0)):
     """The oracle, unchanged, single-threaded, on a bounded sample: the first
     `workers` rows of the same workload for `rounds` rounds."""
     workers = cfg.N if workers is None else workers
@@ -45,6 +45,7 @@ def cpu_baseline(cfg, wl, rounds=3, workers=None, bf16=False):
     import torch
     from oracle import oracle as orc
     o = orc.Oracle(workers, cfg.d, cfg.k, cfg.mu)
+    o.set_score_variant(*variant)
     agg = None
     elapsed = 0.0
     for t in range(rounds):
@@ -95,6 +96,8 @@ def main():
     ap.add_argument("--mu", type=float, default=None)
     ap.add_argument("--grad-dtype", choices=["f32", "bf16"], default="f32",
                     help="storage type of the local gradients (bf16: widened exactly, arithmetic stays f32)")
+    ap.add_argument("--prior-roots", type=int, default=0, help="score variant: prior |a|^(2^-m)")
+    ap.add_argument("--likelihood", type=int, default=0, help="score variant: 0 tanh, 1 clipped linear")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--max-buffers", type=int, default=24,
                     help="rounds of gradients kept resident in HBM (cycled if steps+warmup is larger)")
@@ -134,6 +137,8 @@ def main():
 
     r = binding.RegTopk(N, d, k, cfg.mu, device=dev)
     r.set_option(binding.OPT_PROFILE, 1)
+    r.set_option(binding.OPT_PRIOR_ROOTS, args.prior_roots)
+    r.set_option(binding.OPT_LIKELIHOOD, args.likelihood)
     agg = None
     dense_rounds = 0
     for t in range(args.warmup):
@@ -171,7 +176,7 @@ def main():
         "config": {"workload": "%s: N=%d workers, d=%d, k=%d, mu=%g, per-layer scales, %s entries, "
                                "30%% shared component" % (cfg.name, N, d, k, cfg.mu, cfg.marginal),
                    "N": N, "d": d, "k": k, "mu": cfg.mu, "rounds_resident": n_buf,
-                   "grad_dtype": args.grad_dtype},
+                   "grad_dtype": args.grad_dtype, "prior_roots": args.prior_roots, "likelihood": args.likelihood},
         "hbm_frac_round": b_alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "algorithmic_bytes_per_round": b_alg,
         "stage_ms": {"sweep": sweep_ms, "select": select_ms, "compact_aggregate": tail_ms,
@@ -188,7 +193,8 @@ def main():
     del grads
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, wl, bf16=args.grad_dtype == "bf16")
+        out["cpu_baseline"] = cpu_baseline(cfg, wl, bf16=args.grad_dtype == "bf16",
+                                           variant=(args.prior_roots, args.likelihood))
     print(json.dumps(out))
 
 

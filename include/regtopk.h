@@ -173,6 +173,15 @@ int regtopk_sgd_update(float* theta_dev, const float* g_dev, float eta, int64_t 
 #define REGTOPK_OPT_CAND_TARGET   2  /* speculative pass aims at value*k candidates (1 < value <= 3; default 1.25) */
 #define REGTOPK_OPT_PROFILE       3  /* value != 0: record HIP events on the step's stream around the stages of every
                                         step (resets the recorded rounds); 0 switches it off */
+/* Score variants (paper: remark on sub-linear scaling in the appendix, score
+ * |a|^y * u(|1 + Delta|) with y <= 1; sentence after the tanh likelihood that
+ * other cumulative functions u_mu are admissible).  Defaults are Algorithm 2.
+ * They take effect from the next round; the bounds carried over from earlier
+ * rounds are dropped. */
+#define REGTOPK_OPT_PRIOR_ROOTS   4  /* value m in {0,1,2,3}: prior |a|^y with y = 2^-m, evaluated as m correctly
+                                        rounded binary32 square roots of |a| */
+#define REGTOPK_OPT_LIKELIHOOD    5  /* 0: tanh(|1+Delta|/mu);  1: min(|1+Delta|/mu, 1), the cumulative function
+                                        of an innovation uniform on [0, mu] */
 int regtopk_set_option(regtopk_ctx* ctx, int option, double value);
 
 /* Stage times of the last n <= min(max_rounds, 64) profiled rounds, oldest

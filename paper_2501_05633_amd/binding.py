@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libregtopk.so")
 
 OK, INVALID_ARG, BAD_STATE, HIP_ERROR, NO_MEMORY = 0, -1, -2, -3, -4
-OPT_FORCE_DENSE, OPT_CAND_TARGET, OPT_PROFILE = 1, 2, 3
+OPT_FORCE_DENSE, OPT_CAND_TARGET, OPT_PROFILE, OPT_PRIOR_ROOTS, OPT_LIKELIHOOD = 1, 2, 3, 4, 5
 
 # every symbol include/regtopk.h declares
 SYMBOLS = [

@@ -16,7 +16,7 @@ LIB = os.path.join(HERE, "libregtopk.so")
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # every binary32 operation of the score is a single IEEE rounding
-    "-ffp-contract=off", "-fno-fast-math",
+    "-ffp-contract=off", "-fno-fast-math", "-fhip-fp32-correctly-rounded-divide-sqrt",
     # no packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-function",

@@ -10,8 +10,8 @@
 //                   entries with |a| >= tau_lo are appended, in index order per
 //                   4096-entry chunk, to the worker's candidate list
 //   k_score         exact score of every candidate (regulariser for entries sent in
-//                   the previous round; their rank in that round's value list
-//                   comes from the mask word and a per-word running count);
+//                   the previous round; the value sent then travels with the
+//                   candidate: the sweep finds it in the state it overwrites);
 //                   scores inside a narrow window around the expected
 //                   k-th score are also copied to a short boundary list, those
 //                   above it are counted
@@ -92,7 +92,8 @@ struct WorkerCtl {
   uint32_t err_prev;      // |prediction error| of the previous round
   float margin_scale;     // widens the bound's safety margin after a failed speculation
   uint32_t extrapolated;  // this round's prediction used the drift of two earlier rounds
-  uint32_t pad[4];
+  uint32_t tau_lo_mag;    // smallest |a| bit pattern whose prior reaches tau_lo (= tau_lo for the plain prior)
+  uint32_t pad[3];
   uint32_t cursor[kMaxRegions];
 };
 
@@ -102,6 +103,29 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t ballot) {
 }
 
 __device__ __forceinline__ uint32_t key_of(float a) { return __float_as_uint(a) & 0x7FFFFFFFu; }
+
+// Prior |a|^y for y = 2^-roots, roots = 0..3 (appendix remark on sub-linear
+// scaling): `roots` correctly rounded binary32 square roots of |a|.
+__device__ __forceinline__ float prior_of(float a, int roots) {
+  float p = fabsf(a);
+  for (int i = 0; i < roots; ++i) p = sqrtf(p);      // correctly rounded (the __fsqrt_rn intrinsic is the approximate one here)
+  return p;
+}
+__device__ __forceinline__ uint32_t prior_key(float a, int roots) { return __float_as_uint(prior_of(a, roots)); }
+
+// Smallest |a| bit pattern whose prior reaches the score bound tau (bit
+// pattern): the sweep compares magnitudes, the bound lives in score space, and
+// the prior is monotone but not one-to-one.  kNoBound stays kNoBound; a bound
+// no finite magnitude reaches gives the pattern of +inf.
+__device__ __forceinline__ uint32_t magnitude_bound(uint32_t tau, int roots) {
+  if (roots == 0 || tau == 0xFFFFFFFFu) return tau;
+  uint32_t lo = 0, hi = 0x7F800000u;              // prior(hi) = +inf >= any finite tau
+  while (lo < hi) {
+    const uint32_t mid = lo + (hi - lo) / 2;
+    if (prior_key(__uint_as_float(mid), roots) >= tau) hi = mid; else lo = mid + 1;
+  }
+  return lo;
+}
 
 // Number of valid candidate slots in region r of a worker's list.  The
 // speculative sweep fills every region from its own cursor; the dense emission
@@ -175,13 +199,14 @@ __device__ __forceinline__ void grid_barrier(GlobalCtl* g, uint32_t nblocks) {
 
 // ---------------------------------------------------------------- k_begin ----
 __global__ void __launch_bounds__(kBlock)
-k_begin(WorkerCtl* ctl, GlobalCtl* gctl, int force_dense) {
+k_begin(WorkerCtl* ctl, GlobalCtl* gctl, int force_dense, int roots) {
   const uint32_t n = blockIdx.x, tid = threadIdx.x;
   if (n == 0 && tid == 0) gctl->any_dense = 0;
   WorkerCtl& c = ctl[n];
   if (tid < kMaxRegions) c.cursor[tid] = 0;
   if (tid == 0) {
     c.tau_lo = force_dense ? kNoBound : c.next_tau_lo;
+    c.tau_lo_mag = magnitude_bound(c.tau_lo, roots);
     c.win_lo = force_dense ? kNoBound : c.next_win_lo;
     c.win_hi = c.next_win_hi;
     c.overflow = 0; c.need_dense = 0; c.n_cand = 0; c.n_valid = 0; c.n_hi = 0; c.n_bnd = 0;
@@ -273,7 +298,7 @@ k_accum_emit(float* __restrict__ e, const G* __restrict__ g, const uint32_t* __r
   const uint32_t c = blockIdx.x, n = blockIdx.y;
   const uint32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const size_t row = (size_t)n * (size_t)d;
-  const uint32_t tau_lo = ctl[n].tau_lo;
+  const uint32_t tau_lo = ctl[n].tau_lo_mag;        // bound on |a|: the sweep never evaluates the prior
   const int64_t base = (int64_t)c * kChunk + (int64_t)wv * 1024 + lane * 4;
   float a[4][4];
   float eo[4][4];       // what the state held: a^{t-1} where the entry was sent, the error elsewhere
@@ -377,7 +402,7 @@ k_accum_emit(float* __restrict__ e, const G* __restrict__ g, const uint32_t* __r
 // --------------------------------------------------------------- k_score ----
 // Likelihood factor of an entry that was sent in the previous round.
 __device__ __forceinline__ float likelihood_sent(float a_now, float a_before, float g_before,
-                                                 float w, float mu) {
+                                                 float w, float mu, int kind) {
   const float num = __fsub_rn(g_before, __fmul_rn(w, a_before));
   const float den = __fmul_rn(w, a_now);
   if (den == 0.0f) return 1.0f;
@@ -385,17 +410,23 @@ __device__ __forceinline__ float likelihood_sent(float a_now, float a_before, fl
   const float r = fabsf(__fadd_rn(1.0f, D));
   const float x = __fdiv_rn(r, mu);
   if (x != x) return 1.0f;
+  if (kind == 1) return x < 1.0f ? x : 1.0f;     // cumulative function of a uniform innovation
   return tanh_f32_cr(x);
 }
+
+// What the score variants need: the number of square roots of the prior and
+// the kind of likelihood (0 tanh, 1 clipped linear).
+struct ScoreKind { int roots, likelihood; };
 
 // Score bits of one candidate: index word `raw` with the sent flag, value a,
 // and a_before = the value the worker sent for this entry in the previous
 // round (read only when the flag is set).
 __device__ __forceinline__ uint32_t score_entry(uint32_t raw, float a, float a_before, int use_reg,
-                                                const float* __restrict__ gprev, float w, float mu) {
+                                                const float* __restrict__ gprev, float w, float mu,
+                                                ScoreKind sk) {
   float f = 1.0f;
-  if (use_reg && (raw & kSentFlag)) f = likelihood_sent(a, a_before, gprev[raw & ~kSentFlag], w, mu);
-  return __float_as_uint(__fmul_rn(fabsf(a), f));
+  if (use_reg && (raw & kSentFlag)) f = likelihood_sent(a, a_before, gprev[raw & ~kSentFlag], w, mu, sk.likelihood);
+  return __float_as_uint(__fmul_rn(prior_of(a, sk.roots), f));
 }
 
 // grid (ceil(cap_r/2048), regions, N): a block covers 2048 consecutive slots of
@@ -407,7 +438,8 @@ k_score(WorkerCtl* __restrict__ ctl, const int32_t* __restrict__ cand_idx,
         const float* __restrict__ cand_val, const float* __restrict__ cand_prev,
         uint32_t* __restrict__ cand_key, uint32_t* __restrict__ bnd_key,
         const float* __restrict__ gprev, int64_t d, uint32_t cap_r,
-        uint32_t cap_total, uint32_t bnd_cap, const float* __restrict__ omega, float mu, int use_reg) {
+        uint32_t cap_total, uint32_t bnd_cap, const float* __restrict__ omega, float mu, int use_reg,
+        ScoreKind sk) {
   __shared__ uint32_t s_stage[kScoreSlots];
   __shared__ uint32_t s_cnt[3];       // boundary entries, valid, above window
   __shared__ uint32_t s_base;
@@ -448,8 +480,8 @@ k_score(WorkerCtl* __restrict__ ctl, const int32_t* __restrict__ cand_idx,
     if (raw[q] == 0xFFFFFFFFu) continue;
     const uint32_t p = p0 + q * kBlock + tid;
     float f = 1.0f;
-    if (use_reg && (raw[q] & kSentFlag)) f = likelihood_sent(av[q], ab[q], gp[q], w, mu);
-    const uint32_t key = __float_as_uint(__fmul_rn(fabsf(av[q]), f));
+    if (use_reg && (raw[q] & kSentFlag)) f = likelihood_sent(av[q], ab[q], gp[q], w, mu, sk.likelihood);
+    const uint32_t key = __float_as_uint(__fmul_rn(prior_of(av[q], sk.roots), f));
     cand_key[cbase + p] = key;
     n_val += key >= tau_lo;
     if (windowed) {
@@ -788,7 +820,8 @@ constexpr uint32_t kSampleMax = 1u << 18;     // sampled entries per worker (who
 template <typename G>
 __global__ void __launch_bounds__(kBlock)
 k_sample_hist(const float* __restrict__ e, const G* __restrict__ g, const uint32_t* __restrict__ mask,
-              int64_t d, uint32_t nc, uint32_t* __restrict__ shist, uint32_t n_groups, uint32_t stride4) {
+              int64_t d, uint32_t nc, uint32_t* __restrict__ shist, uint32_t n_groups, uint32_t stride4,
+              int roots) {
   __shared__ uint32_t s_hist[kL1Bins];
   const uint32_t n = blockIdx.y, tid = threadIdx.x;
   for (uint32_t i = tid; i < kL1Bins; i += kBlock) s_hist[i] = 0;
@@ -803,7 +836,7 @@ k_sample_hist(const float* __restrict__ e, const G* __restrict__ g, const uint32
       if (j < d) {
         const uint32_t sent = (mrow[j >> 5] >> (j & 31)) & 1u;
         const float a = (sent ? 0.0f : e[row + j]) + grad_at(g, row + j);
-        atomicAdd(&s_hist[key_of(a) >> kL1Shift], 1u);
+        atomicAdd(&s_hist[prior_key(a, roots) >> kL1Shift], 1u);
       }
     }
   }
@@ -818,7 +851,7 @@ k_sample_hist(const float* __restrict__ e, const G* __restrict__ g, const uint32
 // grid (N), 1024 threads.  Sets this round's bound from the sample histogram.
 __global__ void __launch_bounds__(kScanBlock)
 k_sample_bound(WorkerCtl* ctl, const uint32_t* __restrict__ shist, int64_t d, int64_t k,
-               uint32_t n_sampled) {
+               uint32_t n_sampled, int roots) {
   __shared__ uint32_t s_hist[kL1Bins];
   __shared__ uint32_t s_w[16];
   __shared__ uint32_t s_out[2];
@@ -835,6 +868,7 @@ k_sample_bound(WorkerCtl* ctl, const uint32_t* __restrict__ shist, int64_t d, in
                                             : RankHit{kNoBound, 0u};
   if (tid == 0 && h.bin != kNoBound && h.bin > 0) {
     ctl[n].tau_lo = h.bin << kL1Shift;
+    ctl[n].tau_lo_mag = magnitude_bound(h.bin << kL1Shift, roots);
     ctl[n].win_lo = kNoBound;
   }
 }
@@ -928,7 +962,7 @@ k_chunk_scan(WorkerCtl* ctl, const uint32_t* __restrict__ ch_gt, const uint32_t*
 template <int LEVEL, bool VEC>
 __device__ __forceinline__ void dense_hist_worker(uint32_t n, uint32_t b, uint32_t G, const float* a,
                                                   int64_t d, const WorkerCtl* ctl, uint32_t* fhist,
-                                                  uint32_t* s_hist) {
+                                                  uint32_t* s_hist, int roots) {
   const uint32_t tid = threadIdx.x;
   constexpr uint32_t bins = LEVEL == 1 ? kL1Bins : (LEVEL == 2 ? kL2Bins : kL3Bins);
   for (uint32_t i = tid; i < bins; i += kBlock) s_hist[i] = 0;
@@ -936,7 +970,7 @@ __device__ __forceinline__ void dense_hist_worker(uint32_t n, uint32_t b, uint32
   const uint32_t prefix = ctl[n].f_prefix;
   const float* row = a + (size_t)n * (size_t)d;
   auto put = [&](float v) {
-    const uint32_t key = key_of(v);
+    const uint32_t key = prior_key(v, roots);
     if (LEVEL == 1) atomicAdd(&s_hist[key >> kL1Shift], 1u);
     else if (LEVEL == 2) { if ((key >> kL1Shift) == prefix) atomicAdd(&s_hist[(key >> kL2Shift) & (kL2Bins - 1)], 1u); }
     else { if ((key >> kL2Shift) == prefix) atomicAdd(&s_hist[key & (kL3Bins - 1)], 1u); }
@@ -1010,7 +1044,7 @@ template <bool VEC>
 __device__ __forceinline__ void dense_count_chunk(uint32_t n, uint32_t c, const float* a, int64_t d,
                                                   const WorkerCtl* ctl, uint32_t* ch_gt,
                                                   uint32_t* ch_tie, uint32_t nc, uint32_t* s_gt,
-                                                  uint32_t* s_tie) {
+                                                  uint32_t* s_tie, int roots) {
   const uint32_t tid = threadIdx.x;
   const uint32_t tau = ctl[n].f_tau;
   const float* row = a + (size_t)n * (size_t)d;
@@ -1021,7 +1055,8 @@ __device__ __forceinline__ void dense_count_chunk(uint32_t n, uint32_t c, const 
       const int64_t j = (int64_t)c * kChunk + (i * kBlock + tid) * 4;
       if (j < d) {
         const float4 v = *reinterpret_cast<const float4*>(row + j);
-        const uint32_t k0 = key_of(v.x), k1 = key_of(v.y), k2 = key_of(v.z), k3 = key_of(v.w);
+        const uint32_t k0 = prior_key(v.x, roots), k1 = prior_key(v.y, roots), k2 = prior_key(v.z, roots),
+                       k3 = prior_key(v.w, roots);
         gt += (k0 > tau) + (k1 > tau) + (k2 > tau) + (k3 > tau);
         tie += (k0 == tau) + (k1 == tau) + (k2 == tau) + (k3 == tau);
       }
@@ -1030,7 +1065,7 @@ __device__ __forceinline__ void dense_count_chunk(uint32_t n, uint32_t c, const 
     for (int i = 0; i < 16; ++i) {
       const int64_t j = (int64_t)c * kChunk + i * kBlock + tid;
       if (j < d) {
-        const uint32_t key = key_of(row[j]);
+        const uint32_t key = prior_key(row[j], roots);
         gt += key > tau;
         tie += key == tau;
       }
@@ -1060,7 +1095,7 @@ __device__ __forceinline__ void dense_emit_chunk(uint32_t n, uint32_t c, const f
                                                  const uint32_t* tie_off, const uint32_t* prev_sel_off,
                                                  const float* prev_val, int64_t k, uint32_t nc,
                                                  uint32_t cap_total, uint32_t* s_wtot, uint32_t* s_ttot,
-                                                 uint32_t* s_mw, uint32_t* s_rk) {
+                                                 uint32_t* s_mw, uint32_t* s_rk, int roots) {
   const uint32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
   const size_t tix = (size_t)n * nc + c;
@@ -1092,7 +1127,7 @@ __device__ __forceinline__ void dense_emit_chunk(uint32_t n, uint32_t c, const f
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       if (j0 + q < d) {
-        const uint32_t key = key_of(a[i][q]);
+        const uint32_t key = prior_key(a[i][q], roots);
         if (key > tau) gtf |= 1u << (i * 4 + q);
         else if (key == tau) tief |= 1u << (i * 4 + q);
       }
@@ -1149,8 +1184,9 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
             uint32_t* cand_key,
             const uint32_t* bnd_key, const float* prev_val, const float* gprev, int64_t k, uint32_t nc,
             int32_t N, uint32_t cap_r, uint32_t cap_total, uint32_t regions, uint32_t bnd_cap,
-            const float* omega, float mu, int use_reg, float cand_target) {
+            const float* omega, float mu, int use_reg, float cand_target, ScoreKind sk) {
   if (gctl->any_dense == 0) return;
+  const int roots = sk.roots;
   __shared__ uint32_t s_hist[kL1Bins];
   __shared__ uint32_t s_a[kBlock], s_b[kBlock];
   __shared__ uint32_t s_w[16], s_out[2], s_x[4], s_y[4];
@@ -1164,19 +1200,19 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
   grid_barrier(gctl, G);
 
   for (int32_t n = 0; n < N; ++n)
-    if (ctl[n].need_dense) dense_hist_worker<1, VEC>(n, b, G, a_rows, d, ctl, fhist, s_hist);
+    if (ctl[n].need_dense) dense_hist_worker<1, VEC>(n, b, G, a_rows, d, ctl, fhist, s_hist, roots);
   grid_barrier(gctl, G);
   for (int32_t n = b; n < N; n += G)
     if (ctl[n].need_dense) dense_scan_worker<1>(n, ctl, fhist, k, d, s_a, s_b);
   grid_barrier(gctl, G);
   for (int32_t n = 0; n < N; ++n)
-    if (ctl[n].need_dense) dense_hist_worker<2, VEC>(n, b, G, a_rows, d, ctl, fhist, s_hist);
+    if (ctl[n].need_dense) dense_hist_worker<2, VEC>(n, b, G, a_rows, d, ctl, fhist, s_hist, roots);
   grid_barrier(gctl, G);
   for (int32_t n = b; n < N; n += G)
     if (ctl[n].need_dense) dense_scan_worker<2>(n, ctl, fhist, k, d, s_a, s_b);
   grid_barrier(gctl, G);
   for (int32_t n = 0; n < N; ++n)
-    if (ctl[n].need_dense) dense_hist_worker<3, VEC>(n, b, G, a_rows, d, ctl, fhist, s_hist);
+    if (ctl[n].need_dense) dense_hist_worker<3, VEC>(n, b, G, a_rows, d, ctl, fhist, s_hist, roots);
   grid_barrier(gctl, G);
   for (int32_t n = b; n < N; n += G)
     if (ctl[n].need_dense) dense_scan_worker<3>(n, ctl, fhist, k, d, s_a, s_b);
@@ -1184,7 +1220,7 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
 
   for (int32_t n = 0; n < N; ++n) {
     if (!ctl[n].need_dense) continue;
-    for (uint32_t c = b; c < nc; c += G) dense_count_chunk<VEC>(n, c, a_rows, d, ctl, ch_gt, ch_tie, nc, s_x, s_y);
+    for (uint32_t c = b; c < nc; c += G) dense_count_chunk<VEC>(n, c, a_rows, d, ctl, ch_gt, ch_tie, nc, s_x, s_y, roots);
   }
   grid_barrier(gctl, G);
   for (int32_t n = b; n < N; n += G)
@@ -1194,7 +1230,7 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
     if (!ctl[n].need_dense) continue;
     for (uint32_t c = b; c < nc; c += G)
       dense_emit_chunk<VEC>(n, c, a_rows, mask, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, tie_off,
-                            prev_sel_off, prev_val, k, nc, cap_total, s_x, s_y, s_a, s_b);
+                            prev_sel_off, prev_val, k, nc, cap_total, s_x, s_y, s_a, s_b, roots);
   }
   grid_barrier(gctl, G);
 
@@ -1204,7 +1240,7 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
     const size_t cb = (size_t)n * cap_total;
     const float w = omega[n];
     for (uint32_t p = b * kBlock + tid; p < total; p += G * kBlock)
-      cand_key[cb + p] = score_entry((uint32_t)cand_idx[cb + p], cand_val[cb + p], cand_prev[cb + p], use_reg, gprev, w, mu);
+      cand_key[cb + p] = score_entry((uint32_t)cand_idx[cb + p], cand_val[cb + p], cand_prev[cb + p], use_reg, gprev, w, mu, sk);
   }
   grid_barrier(gctl, G);
   for (int32_t n = b; n < N; n += G)
@@ -1544,7 +1580,7 @@ __global__ void k_init_ctl(WorkerCtl* ctl) {
   __syncthreads();
   if (threadIdx.x == 0) {
     WorkerCtl& c = ctl[blockIdx.x];
-    c.tau_lo = kNoBound; c.next_tau_lo = kNoBound; c.win_lo = kNoBound; c.next_win_lo = kNoBound;
+    c.tau_lo = kNoBound; c.tau_lo_mag = kNoBound; c.next_tau_lo = kNoBound; c.win_lo = kNoBound; c.next_win_lo = kNoBound;
     c.tau_prev = kNoBound; c.centre = kNoBound; c.margin_scale = 1.0f;
   }
 }

@@ -106,6 +106,9 @@ struct regtopk_ctx {
   int device;
   int dense_blocks;     // grid of the dense-selection kernel: all blocks resident together
   int force_dense;
+  int prior_roots;      // prior |a|^(2^-prior_roots)
+  int likelihood;       // 0 tanh, 1 clipped linear
+  bool reinit_ctl;      // the score space changed: drop the bounds carried over from earlier rounds
   float cand_target;
   bool profile;                 // record stage events in every step
   hipEvent_t ev[kProfRounds][5];
@@ -142,6 +145,9 @@ int create_common(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu, 
   c->N = N; c->d = d; c->k = k; c->mu = mu;
   c->owns_arena = owns;
   c->force_dense = 0;
+  c->prior_roots = 0;
+  c->likelihood = 0;
+  c->reinit_ctl = false;
   c->cand_target = 1.25f;
   c->profile = false;
   c->prof_rounds = 0;
@@ -240,6 +246,15 @@ int regtopk_set_option(regtopk_ctx* c, int option, double value) {
       if (!(value > 1.0 && value <= 3.0)) return fail(REGTOPK_INVALID_ARG, "candidate target must be in (1, 3]");
       c->cand_target = (float)value;
       return REGTOPK_OK;
+    case REGTOPK_OPT_PRIOR_ROOTS:
+      if (!(value == 0.0 || value == 1.0 || value == 2.0 || value == 3.0))
+        return fail(REGTOPK_INVALID_ARG, "prior roots must be 0, 1, 2 or 3");
+      if ((int)value != c->prior_roots) { c->prior_roots = (int)value; c->reinit_ctl = true; c->fresh = true; }
+      return REGTOPK_OK;
+    case REGTOPK_OPT_LIKELIHOOD:
+      if (!(value == 0.0 || value == 1.0)) return fail(REGTOPK_INVALID_ARG, "likelihood must be 0 (tanh) or 1 (clipped linear)");
+      if ((int)value != c->likelihood) { c->likelihood = (int)value; c->reinit_ctl = true; c->fresh = true; }
+      return REGTOPK_OK;
     case REGTOPK_OPT_PROFILE:
       if (value != 0.0 && !c->profile) {
         for (auto& row : c->ev) for (auto& e : row) HIP_TRY(hipEventCreate(&e));
@@ -303,7 +318,12 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
   const dim3 g_score((L.cap_r + kScoreSlots - 1) / kScoreSlots, L.regions, N);
   hipEvent_t* ev = c->profile ? c->ev[c->prof_rounds % kProfRounds] : nullptr;
   if (ev) HIP_TRY(hipEventRecord(ev[4], s));
-  k_begin<<<N, kBlock, 0, s>>>(ctl, gctl, c->force_dense);
+  const ScoreKind sk{c->prior_roots, c->likelihood};
+  if (c->reinit_ctl) {
+    k_init_ctl<<<N, 256, 0, s>>>(ctl);
+    c->reinit_ctl = false;
+  }
+  k_begin<<<N, kBlock, 0, s>>>(ctl, gctl, c->force_dense, sk.roots);
   if (c->fresh && !c->force_dense) {
     // no bound from a previous round: take one from a strided sample of a = eps + g
     const uint64_t groups_all = (uint64_t)((d + 3) / 4);
@@ -312,8 +332,8 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
     uint64_t n_sampled = (uint64_t)n_groups * 4;
     if (n_sampled > (uint64_t)d) n_sampled = (uint64_t)d;
     k_fill_u32<<<64, 256, 0, s>>>(fhist, (size_t)N * 3 * kL1Bins, 0u);
-    k_sample_hist<G><<<dim3((n_groups + 4 * kBlock - 1) / (4 * kBlock), N), kBlock, 0, s>>>(e, grads, mask, d, nc, fhist, n_groups, stride4);
-    k_sample_bound<<<N, kScanBlock, 0, s>>>(ctl, fhist, d, k, (uint32_t)n_sampled);
+    k_sample_hist<G><<<dim3((n_groups + 4 * kBlock - 1) / (4 * kBlock), N), kBlock, 0, s>>>(e, grads, mask, d, nc, fhist, n_groups, stride4, sk.roots);
+    k_sample_bound<<<N, kScanBlock, 0, s>>>(ctl, fhist, d, k, (uint32_t)n_sampled, sk.roots);
   }
   c->fresh = false;
   if (ev) HIP_TRY(hipEventRecord(ev[0], s));
@@ -322,13 +342,13 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
   else
     k_accum_emit<false, G><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, prev_sel_off, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   if (ev) HIP_TRY(hipEventRecord(ev[1], s));
-  k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_prev, cand_key, bnd_key, gprev, d, L.cap_r, L.cap_total, L.bnd_cap, omega, c->mu, use_reg);
+  k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_prev, cand_key, bnd_key, gprev, d, L.cap_r, L.cap_total, L.bnd_cap, omega, c->mu, use_reg, sk);
   k_select<<<N, kScanBlock, 0, s>>>(ctl, gctl, cand_key, bnd_key, k, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->cand_target, c->force_dense);
   // dense selection for the workers whose speculation failed; returns at once if there is none
   if (vec)
-    k_dense_all<true><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, prev_sel_off, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_prev, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, omega, c->mu, use_reg, c->cand_target);
+    k_dense_all<true><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, prev_sel_off, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_prev, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, omega, c->mu, use_reg, c->cand_target, sk);
   else
-    k_dense_all<false><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, prev_sel_off, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_prev, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, omega, c->mu, use_reg, c->cand_target);
+    k_dense_all<false><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, prev_sel_off, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_prev, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, omega, c->mu, use_reg, c->cand_target, sk);
 
   // ordered compaction, error update, aggregation
   if (ev) HIP_TRY(hipEventRecord(ev[2], s));

@@ -65,7 +65,7 @@ def compare_round(o: orc.Oracle, res_gpu, res_cpu, label=""):
 
 def run_both(N, d, k, mu, grads_fn, T, device="cuda:0", force_dense=False, closed_loop=None,
              label="", check_state_every=1, cand_target=None, weights=None, check_overlap=False,
-             on_round=None, grad_dtype=None):
+             on_round=None, grad_dtype=None, prior_roots=0, likelihood=0):
     """grads_fn(t, agg_prev_or_None) -> [N,d] float32 tensor on the GPU.
 
     Each side feeds its own aggregate back as g^{t-1}.  Returns per-round stats
@@ -83,6 +83,10 @@ def run_both(N, d, k, mu, grads_fn, T, device="cuda:0", force_dense=False, close
         r.set_option(binding.OPT_FORCE_DENSE, 1)
     if cand_target is not None:
         r.set_option(binding.OPT_CAND_TARGET, cand_target)
+    if prior_roots or likelihood:
+        o.set_score_variant(prior_roots, likelihood)
+        r.set_option(binding.OPT_PRIOR_ROOTS, prior_roots)
+        r.set_option(binding.OPT_LIKELIHOOD, likelihood)
     if weights is not None:
         o.set_weights(np.asarray(weights, dtype=np.float32))
         r.set_weights([float(np.float32(x)) for x in weights])

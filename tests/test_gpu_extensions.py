@@ -200,3 +200,56 @@ def test_bfloat16_gradients_unaligned_rows_and_forced_dense():
         assert np.array_equal(val.cpu().numpy(), vc)
         assert np.array_equal(agg_g.cpu().numpy(), agg_c)
     r.close()
+
+
+@pytest.mark.parametrize("roots,likelihood,mu", [(1, 0, 1.0), (2, 0, 1.0), (3, 0, 0.3), (0, 1, 2.0), (1, 1, 0.5), (1, 0, 0.0)])
+@pytest.mark.parametrize("name,d,N,k", [("tiny", 10_000, 4, 100), ("large_cnn", 500_003, 3, 5_000)])
+def test_score_variants(name, d, N, k, roots, likelihood, mu):
+    print("case variant %s roots=%d likelihood=%d mu=%g" % (name, roots, likelihood, mu), flush=True)
+    cfg = workloads.scaled(workloads.CONFIGS[name], d=d, N=N, k=k)
+    stats, tol = run_both(N, d, k, mu, _wl_fn(cfg), 6, label="variant", prior_roots=roots, likelihood=likelihood)
+    assert tol == 0
+    if name == "large_cnn":                       # the speculation also works in the transformed score space
+        fallbacks = sum(w["used_dense"] for st in stats[2:] for w in st)
+        # (the eighth root packs the scores 8 times denser: while the k-th score still moves by
+        # tens of per cent per round one overflow of the candidate buffer may happen)
+        assert fallbacks == 0 if roots < 3 else fallbacks <= N
+
+
+def test_score_variant_with_forced_dense_selection_and_ties():
+    # square roots collapse neighbouring magnitudes onto one score: many ties at the threshold
+    print("case variant dense ties", flush=True)
+    N, d, k = 2, 50_000, 5_000
+    rng = np.random.default_rng(9)
+    base = (1.0 + rng.integers(0, 64, size=(N, d)) * 2.0 ** -23).astype(f32)      # 64 adjacent binary32 values
+    sign = rng.choice([-1.0, 1.0], size=(N, d)).astype(f32)
+    gs = [torch.from_numpy(base * sign * f32(1 + t)).to(DEV) for t in range(3)]
+    for force in (False, True):
+        stats, tol = run_both(N, d, k, 1.0, lambda t, agg: gs[t], 3, label="variant ties", prior_roots=2,
+                              force_dense=force)
+        assert tol == 0
+
+
+def test_switching_the_variant_between_rounds():
+    print("case variant switch", flush=True)
+    N, d, k = 3, 200_000, 2_000
+    cfg = workloads.scaled(workloads.CONFIGS["large_cnn"], d=d, N=N, k=k)
+    wl = workloads.Workload(cfg, DEV)
+    o = orc.Oracle(N, d, k, 1.0)
+    r = binding.RegTopk(N, d, k, 1.0, device=DEV)
+    with pytest.raises(binding.RegTopkError):
+        r.set_option(binding.OPT_PRIOR_ROOTS, 4)
+    with pytest.raises(binding.RegTopkError):
+        r.set_option(binding.OPT_LIKELIHOOD, 2)
+    agg_g = agg_c = None
+    for t, (roots, lk) in enumerate([(0, 0), (0, 0), (1, 0), (1, 0), (1, 1), (0, 0), (0, 0)]):
+        o.set_score_variant(roots, lk)
+        r.set_option(binding.OPT_PRIOR_ROOTS, roots)
+        r.set_option(binding.OPT_LIKELIHOOD, lk)
+        g = wl.grads(t)
+        idx, val, agg_g = r.step(g, agg_g)
+        agg_g = agg_g.clone()
+        ic, vc, agg_c = o.step(g.cpu().numpy(), agg_c)
+        assert np.array_equal(idx.cpu().numpy(), ic), t
+        assert np.array_equal(val.cpu().numpy(), vc) and np.array_equal(agg_g.cpu().numpy(), agg_c)
+    r.close()
