@@ -44,6 +44,7 @@ def _load():
     lib.rtk_oracle_create.argtypes = [c.c_int32, c.c_int64, c.c_int64, c.c_float]
     lib.rtk_oracle_destroy.argtypes = [c.c_void_p]
     lib.rtk_oracle_step.argtypes = [c.c_void_p] + [c.c_void_p] * 5
+    lib.rtk_oracle_step_global.argtypes = [c.c_void_p] + [c.c_void_p] * 4
     for name in ("e", "a", "score", "mask"):
         f = getattr(lib, "rtk_oracle_" + name)
         f.restype = c.c_void_p
@@ -112,6 +113,19 @@ class Oracle:
         agg = np.empty(self.d, dtype=np.float32)
         self._lib.rtk_oracle_step(self._h, g.ctypes.data, gp.ctypes.data,
                                   idx.ctypes.data, val.ctypes.data, agg.ctypes.data)
+        return idx, val, agg
+
+    def step_global(self, grads):
+        """One round of the genie-aided global Top-k (all workers share the mask
+        of the k largest entries of the unsparsified aggregate).  Returns like step."""
+        g = _f32(grads)
+        if g.shape != (self.N, self.d):
+            raise ValueError("grads must be [N,d]")
+        idx = np.empty((self.N, self.k), dtype=np.int32)
+        val = np.empty((self.N, self.k), dtype=np.float32)
+        agg = np.empty(self.d, dtype=np.float32)
+        self._lib.rtk_oracle_step_global(self._h, g.ctypes.data, idx.ctypes.data, val.ctypes.data,
+                                         agg.ctypes.data)
         return idx, val, agg
 
     def set_weights(self, w):

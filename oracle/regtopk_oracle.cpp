@@ -228,6 +228,49 @@ void rtk_oracle_sgd_update(float* theta, const float* g, float eta, int64_t d) {
     }
 }
 
+// One round of the idealised "global Top-k" of the subsection "Statistical
+// Global Top-k": a genie tells every worker the aggregate of the accumulated
+// gradients without sparsification, abar_j = sum_n omega_n a_{n,j}, and all
+// workers apply Top_k to it, i.e. they share one mask, the k largest |abar_j|
+// (lower index first among equals).  Everything else is Algorithm 1: a = eps +
+// g, ghat = s . a, eps <- a - ghat, g = sum_n omega_n ghat_n.  abar is summed
+// like the aggregate (R8: from +0, + omega_n a_n in ascending worker order).
+// Outputs as in rtk_oracle_step (the N index rows are equal).
+void rtk_oracle_step_global(void* h, const float* grads, int32_t* idx, float* val, float* agg) {
+    Oracle* o = (Oracle*)h;
+    const int64_t d = o->d, k = o->k;
+    const size_t nd = (size_t)o->N * (size_t)d;
+    for (size_t i = 0; i < nd; ++i) o->a[i] = o->e[i] + grads[i];      // accumulate
+    std::vector<float> mag((size_t)d);
+    for (int64_t j = 0; j < d; ++j) {
+        float acc = 0.0f;
+        for (int32_t n = 0; n < o->N; ++n) acc = acc + o->w[(size_t)n] * o->a[(size_t)n * d + j];
+        mag[(size_t)j] = std::fabs(acc);                              // what the genie reveals
+    }
+    std::vector<uint8_t> s((size_t)d);
+    topk_mask(mag.data(), d, k, s.data());
+    for (int32_t n = 0; n < o->N; ++n) {
+        const size_t row = (size_t)n * (size_t)d;
+        int64_t c = 0;
+        for (int64_t j = 0; j < d; ++j) {
+            const float a = o->a[row + j];
+            o->score[row + j] = mag[(size_t)j];
+            o->s[row + j] = s[(size_t)j];
+            o->ghat[row + j] = (float)s[(size_t)j] * a;
+            o->e[row + j] = a - o->ghat[row + j];
+            if (s[(size_t)j]) { idx[(size_t)n * k + c] = (int32_t)j; val[(size_t)n * k + c] = a; ++c; }
+        }
+    }
+    o->a_prev = o->a;
+    o->s_prev = o->s;
+    for (int64_t j = 0; j < d; ++j) {
+        float acc = 0.0f;
+        for (int32_t n = 0; n < o->N; ++n) acc = acc + o->w[(size_t)n] * o->ghat[(size_t)n * d + j];
+        agg[j] = acc;
+    }
+    o->t += 1;
+}
+
 // Read-only views for the tests (pointers stay valid until destroy).
 const float* rtk_oracle_e(void* h) { return ((Oracle*)h)->e.data(); }
 const float* rtk_oracle_a(void* h) { return ((Oracle*)h)->a.data(); }

@@ -292,3 +292,78 @@ def test_clipped_linear_rounds_keep_the_invariants():
             assert msk[n].sum() == k and sc[n][msk[n] == 1].min() >= sc[n][msk[n] == 0].max()
             assert np.array_equal(a[n][idx[n]], val[n]) and np.all(e[n][idx[n]] == 0)
     assert damped > 0
+
+
+# ------------------------------------------------------------ global Top-k ----
+def test_global_topk_selects_the_largest_entries_of_the_unsparsified_aggregate():
+    # "Statistical Global Top-k": the genie-aided workers apply Top-k to the aggregated accumulated
+    # gradient.  Brute force in binary64 on data whose magnitudes are far apart compared to rounding.
+    N, d, k = 5, 3000, 75
+    w = np.array([0.3, 0.1, 0.2, 0.25, 0.15], dtype=f32)
+    o = oracle.Oracle(N, d, k, 1.0)
+    o.set_weights(w)
+    e = np.zeros((N, d))
+    for g in _rounds(5, N, d, k):
+        idx, val, agg = o.step_global(g)
+        a = e + g.astype(np.float64)
+        abar = (w.astype(np.float64)[:, None] * a).sum(axis=0)
+        order = np.lexsort((np.arange(d), -np.abs(abar)))
+        gap = np.abs(abar)[order[k - 1]] - np.abs(abar)[order[k]]
+        assert gap > 1e-5                                              # no near-tie at the threshold in this data
+        want = np.sort(order[:k])
+        for n in range(N):
+            assert np.array_equal(idx[n], want)                        # one mask for all workers
+            np.testing.assert_allclose(val[n], a[n, want], rtol=1e-5, atol=1e-6)
+        ref = np.zeros(d)
+        ref[want] = abar[want]
+        np.testing.assert_allclose(agg, ref, rtol=1e-5, atol=1e-6)
+        assert np.all(agg[np.setdiff1d(np.arange(d), want)] == 0)
+        e = a.copy()
+        e[:, want] = 0.0
+        np.testing.assert_allclose(o.e, e, rtol=1e-5, atol=1e-6)
+        assert list(o.mask_overlap()) == [d - k] + [0] * (N - 1) + [k]
+
+
+def test_global_topk_exact_conservation_and_special_cases():
+    N, d, k = 3, 1000, 40
+    rounds = _rounds(3, N, d, k)
+    o = oracle.Oracle(N, d, k, 0.0)
+    for g in rounds:
+        e_old = o.e
+        idx, val, agg = o.step_global(g)
+        a, e, m = o.a, o.e, o.mask
+        assert np.array_equal(a, e_old + g)                            # single rounded add
+        assert np.array_equal(np.where(m == 1, f32(0), a), e)          # eps = a off the mask, +0 on it
+        for n in range(N):
+            assert np.array_equal(a[n][idx[n]], val[n])
+    # identical workers: the aggregate is each worker's own vector, so global Top-k is their Top-k
+    g = np.tile(np.random.default_rng(4).standard_normal(500).astype(f32), (4, 1))
+    a_, b_ = oracle.Oracle(4, 500, 25, 0.0), oracle.Oracle(4, 500, 25, 0.0)
+    i1, v1, g1 = a_.step_global(g)
+    i2, v2, g2 = b_.step(g, None)
+    assert np.array_equal(i1, i2) and np.array_equal(v1, v2) and np.array_equal(g1, g2)
+    # k = d: nothing is dropped
+    o = oracle.Oracle(3, 200, 200, 1.0)
+    gg = _rounds(1, 3, 200, 200)[0]
+    _, _, agg = o.step_global(gg)
+    np.testing.assert_allclose(agg, gg.astype(np.float64).mean(axis=0), rtol=1e-6, atol=1e-7)
+    assert np.all(o.e == 0)
+    # cancelling workers (the toy example's situation): the genie sees the cancellation at once
+    g = np.array([[100.0, 1.0, 0.5], [-100.0, 1.0, 0.25]], dtype=f32)
+    o = oracle.Oracle(2, 3, 1, 1.0)
+    idx, val, agg = o.step_global(g)
+    assert idx.ravel().tolist() == [1, 1] and agg.tolist() == [0.0, 1.0, 0.0]
+
+
+def test_global_and_local_rounds_share_their_state():
+    # a local RegTop-k round after a global one regularises with the global mask as previous mask
+    N, d, k = 3, 1500, 30
+    rounds = _rounds(4, N, d, k)
+    o = oracle.Oracle(N, d, k, 1.0)
+    _, _, agg = o.step_global(rounds[0])
+    prev = o.mask
+    idx, val, agg = o.step(rounds[1], agg)
+    sc, a = o.score, o.a
+    assert np.array_equal(sc[prev == 0], np.abs(a)[prev == 0])
+    assert np.any(sc[prev == 1] < np.abs(a)[prev == 1])
+    assert o.round == 2
