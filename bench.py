@@ -37,7 +37,7 @@ def algorithmic_bytes(N, d, k, g_bytes=4):
 MEASURED_SWEEP_TRAFFIC = {"large_cnn": 5020582394}
 
 
-def cpu_baseline(cfg, wl, rounds=3, workers=None, bf16=False, variant=(0, 0)):
+def cpu_baseline(cfg, wl, rounds=3, workers=None, bf16=False, variant=(0, 0), glob=False):
     """The oracle, unchanged, single-threaded, on a bounded sample: the first
     `workers` rows of the same workload for `rounds` rounds."""
     workers = cfg.N if workers is None else workers
@@ -54,7 +54,7 @@ def cpu_baseline(cfg, wl, rounds=3, workers=None, bf16=False, variant=(0, 0)):
             g = g.to(torch.bfloat16).float()
         g = g.cpu().numpy()
         t0 = time.perf_counter()
-        _, _, agg = o.step(g, agg)
+        _, _, agg = o.step_global(g) if glob else o.step(g, agg)
         elapsed += time.perf_counter() - t0
     o.close()
     entries = workers * cfg.d * rounds
@@ -98,6 +98,8 @@ def main():
                     help="storage type of the local gradients (bf16: widened exactly, arithmetic stays f32)")
     ap.add_argument("--prior-roots", type=int, default=0, help="score variant: prior |a|^(2^-m)")
     ap.add_argument("--likelihood", type=int, default=0, help="score variant: 0 tanh, 1 clipped linear")
+    ap.add_argument("--mode", choices=["regtopk", "global"], default="regtopk",
+                    help="global: the genie-aided global Top-k baseline instead of the RegTop-k round")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--max-buffers", type=int, default=24,
                     help="rounds of gradients kept resident in HBM (cycled if steps+warmup is larger)")
@@ -141,15 +143,16 @@ def main():
     r.set_option(binding.OPT_LIKELIHOOD, args.likelihood)
     agg = None
     dense_rounds = 0
+    glob = args.mode == "global"
     for t in range(args.warmup):
-        _, _, agg = r.step(grads[t % n_buf], agg)
+        _, _, agg = r.step_global(grads[t % n_buf]) if glob else r.step(grads[t % n_buf], agg)
     torch.cuda.synchronize()
     r.set_option(binding.OPT_PROFILE, 1)          # restart the event ring for the timed region
 
     t0 = time.perf_counter()
     for i in range(args.steps):
         t = args.warmup + i
-        _, _, agg = r.step(grads[t % n_buf], agg)
+        _, _, agg = r.step_global(grads[t % n_buf]) if glob else r.step(grads[t % n_buf], agg)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
 
@@ -176,17 +179,17 @@ def main():
         "config": {"workload": "%s: N=%d workers, d=%d, k=%d, mu=%g, per-layer scales, %s entries, "
                                "30%% shared component" % (cfg.name, N, d, k, cfg.mu, cfg.marginal),
                    "N": N, "d": d, "k": k, "mu": cfg.mu, "rounds_resident": n_buf,
-                   "grad_dtype": args.grad_dtype, "prior_roots": args.prior_roots, "likelihood": args.likelihood},
+                   "grad_dtype": args.grad_dtype, "prior_roots": args.prior_roots, "likelihood": args.likelihood, "mode": args.mode},
         "hbm_frac_round": b_alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "algorithmic_bytes_per_round": b_alg,
         "stage_ms": {"sweep": sweep_ms, "select": select_ms, "compact_aggregate": tail_ms,
                      "round_events": round_ms_events},
         "dense_fallback_workers_last_round": dense_rounds,
         "candidates_last_round": [w["n_candidates"] for w in st],
-        "roofline": {"bound": "hbm", "kernel": "k_accum_emit", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "k_global_accum" if glob else "k_accum_emit", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "algorithmic_bytes_per_launch": sweep_bytes, "avg_launch_ms": sweep_ms,
-                     "traffic": MEASURED_SWEEP_TRAFFIC.get(cfg.name) if args.grad_dtype == "f32" else None},
+                     "traffic": MEASURED_SWEEP_TRAFFIC.get(cfg.name) if args.grad_dtype == "f32" and not glob else None},
     }
     out["extras"] = time_extras(torch, binding, r, agg, N, d)
     r.close()
@@ -194,7 +197,7 @@ def main():
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, wl, bf16=args.grad_dtype == "bf16",
-                                           variant=(args.prior_roots, args.likelihood))
+                                           variant=(args.prior_roots, args.likelihood), glob=glob)
     print(json.dumps(out))
 
 

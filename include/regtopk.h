@@ -123,6 +123,20 @@ int regtopk_step(regtopk_ctx* ctx, const float* grads_dev, const float* prev_agg
 int regtopk_step_bf16(regtopk_ctx* ctx, const uint16_t* grads_bf16_dev, const float* prev_aggregate_dev,
                       void* stream, regtopk_result* out);
 
+/* One round of the idealised "global Top-k" baseline (paper: subsection
+ * "Statistical Global Top-k"): a genie reveals abar = sum_n omega_n a_n, the
+ * aggregate of the accumulated gradients a_n = eps_n + g_n without
+ * sparsification, and every worker keeps the k entries of largest |abar_j|
+ * (lower index first among equals), so all N index rows are equal;
+ * val[n,i] = a_n[idx[i]], eps_n <- a_n off that mask, agg = sum_n omega_n ghat_n.
+ * abar is summed like the aggregate: from +0, + omega_n * a_n in ascending
+ * worker order.  Shares the state with regtopk_step (rounds of both kinds may
+ * alternate; a following regtopk_step regularises with this round's mask).
+ * The first call allocates a selector context for one row of d entries and a
+ * d-vector with hipMalloc (freed by regtopk_destroy); out->agg lives in that
+ * selector and stays valid until the next regtopk_step_global. */
+int regtopk_step_global(regtopk_ctx* ctx, const float* grads_dev, void* stream, regtopk_result* out);
+
 int regtopk_destroy(regtopk_ctx* ctx);
 
 /* Back to the state after create (eps = 0, round 0, no previous mask). */

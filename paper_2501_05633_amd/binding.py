@@ -19,7 +19,7 @@ OPT_FORCE_DENSE, OPT_CAND_TARGET, OPT_PROFILE, OPT_PRIOR_ROOTS, OPT_LIKELIHOOD =
 
 # every symbol include/regtopk.h declares
 SYMBOLS = [
-    "regtopk_workspace_bytes", "regtopk_create", "regtopk_create_in", "regtopk_step", "regtopk_step_bf16",
+    "regtopk_workspace_bytes", "regtopk_create", "regtopk_create_in", "regtopk_step", "regtopk_step_bf16", "regtopk_step_global",
     "regtopk_destroy", "regtopk_reset", "regtopk_get_state", "regtopk_set_state",
     "regtopk_get_stats", "regtopk_set_option", "regtopk_get_timings", "regtopk_tanh_f32",
     "regtopk_copy_f32", "regtopk_set_weights", "regtopk_mask_overlap", "regtopk_sgd_update",
@@ -63,6 +63,7 @@ def load():
                                       c_void_p, c_size_t, c_void_p]
     lib.regtopk_step.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, ctypes.POINTER(Result)]
     lib.regtopk_step_bf16.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, ctypes.POINTER(Result)]
+    lib.regtopk_step_global.argtypes = [c_void_p, c_void_p, c_void_p, ctypes.POINTER(Result)]
     lib.regtopk_destroy.argtypes = [c_void_p]
     lib.regtopk_reset.argtypes = [c_void_p, c_void_p]
     lib.regtopk_get_state.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p,
@@ -176,6 +177,21 @@ class RegTopk:
         idx = _view(torch, res.idx, (self.N, self.k), torch.int32, self.device, self._arena)
         val = _view(torch, res.val, (self.N, self.k), torch.float32, self.device, self._arena)
         agg = _view(torch, res.agg, (self.d,), torch.float32, self.device, self._arena)
+        return idx, val, agg
+
+    def step_global(self, grads):
+        """One round of the genie-aided global Top-k baseline; returns like ``step``."""
+        torch = self._torch
+        if grads.device != self.device or grads.dtype != torch.float32 or not grads.is_contiguous() \
+                or tuple(grads.shape) != (self.N, self.d):
+            raise ValueError("grads must be a contiguous float32 [N,d] tensor on %s" % self.device)
+        res = Result()
+        with torch.cuda.device(self.device):
+            _check(self.lib.regtopk_step_global(self._h, c_void_p(grads.data_ptr()), _stream_ptr(torch),
+                                                ctypes.byref(res)))
+        idx = _view(torch, res.idx, (self.N, self.k), torch.int32, self.device, self._arena)
+        val = _view(torch, res.val, (self.N, self.k), torch.float32, self.device, self._arena)
+        agg = _view(torch, res.agg, (self.d,), torch.float32, self.device, None)
         return idx, val, agg
 
     def reset(self):

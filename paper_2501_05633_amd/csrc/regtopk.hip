@@ -113,6 +113,8 @@ struct regtopk_ctx {
   bool profile;                 // record stage events in every step
   hipEvent_t ev[kProfRounds][5];
   int64_t prof_rounds;          // steps recorded since profiling was switched on
+  regtopk_ctx* gsel;    // global Top-k: a one-row context that selects over the unsparsified aggregate
+  float* abar;          // global Top-k: that aggregate, [d]
   char* arena;
   Layout L;
   template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(arena + off); }
@@ -148,6 +150,8 @@ int create_common(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu, 
   c->prior_roots = 0;
   c->likelihood = 0;
   c->reinit_ctl = false;
+  c->gsel = nullptr;
+  c->abar = nullptr;
   c->cand_target = 1.25f;
   c->profile = false;
   c->prof_rounds = 0;
@@ -228,6 +232,8 @@ int regtopk_destroy(regtopk_ctx* c) {
   int rc = REGTOPK_OK;
   if (c->profile)
     for (auto& row : c->ev) for (auto& e : row) (void)hipEventDestroy(e);
+  if (c->gsel && regtopk_destroy(c->gsel) != REGTOPK_OK) rc = REGTOPK_HIP_ERROR;
+  if (c->abar && hipFree(c->abar) != hipSuccess) rc = fail(REGTOPK_HIP_ERROR, "hipFree failed");
   if (c->owns_arena && hipFree(c->arena) != hipSuccess) rc = fail(REGTOPK_HIP_ERROR, "hipFree failed");
   delete c;
   return rc;
@@ -373,6 +379,60 @@ extern "C" {
 
 int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* stream, regtopk_result* out) {
   return step_impl<float>(c, grads, gprev, stream, out);
+}
+
+int regtopk_step_global(regtopk_ctx* c, const float* grads, void* stream, regtopk_result* out) {
+  if (!c || !grads || !out) return fail(REGTOPK_INVALID_ARG, "ctx, grads_dev and out must not be NULL");
+  if (reinterpret_cast<uintptr_t>(grads) % 4) return fail(REGTOPK_INVALID_ARG, "grads_dev must be 4-byte aligned");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (!c->gsel) {
+    // first use: the selector over the aggregate (one row, plain Top-k) and the aggregate itself
+    regtopk_ctx* g = nullptr;
+    int rc = regtopk_create(&g, 1, c->d, c->k, 0.0f);
+    if (rc != REGTOPK_OK) return rc;
+    void* p = nullptr;
+    if (hipMalloc(&p, (size_t)c->d * 4) != hipSuccess) {
+      (void)hipGetLastError();
+      (void)regtopk_destroy(g);
+      return fail(REGTOPK_NO_MEMORY, "hipMalloc of %zu bytes failed", (size_t)c->d * 4);
+    }
+    c->gsel = g;
+    c->abar = static_cast<float*>(p);
+  }
+  regtopk_ctx* g = c->gsel;
+  const Layout& L = c->L;
+  const int cur = (int)(c->t & 1), prv = cur ^ 1;
+  const bool vec = (c->d % 4 == 0) && (reinterpret_cast<uintptr_t>(grads) % 16 == 0);
+  float* e = c->at<float>(L.e);
+  uint32_t* mask = c->at<uint32_t>(L.mask);
+  const uint32_t* prev_sel_off = c->at<uint32_t>(L.sel_off[prv]);
+  hipEvent_t* ev = c->profile ? c->ev[c->prof_rounds % kProfRounds] : nullptr;
+  if (ev) { HIP_TRY(hipEventRecord(ev[4], s)); HIP_TRY(hipEventRecord(ev[0], s)); }
+  if (vec) k_global_accum<true><<<L.nc, kBlock, 0, s>>>(e, grads, mask, prev_sel_off, c->d, L.nc, c->N, c->at<float>(L.omega), c->abar);
+  else k_global_accum<false><<<L.nc, kBlock, 0, s>>>(e, grads, mask, prev_sel_off, c->d, L.nc, c->N, c->at<float>(L.omega), c->abar);
+  if (ev) HIP_TRY(hipEventRecord(ev[1], s));
+  // the selector must see abar alone: its own error state restarts at zero every round
+  // (its bounds and window carry over: the k-th magnitude of abar moves slowly)
+  k_fill_u32<<<2048, 256, 0, s>>>(g->at<uint32_t>(g->L.e), (size_t)c->d, 0u);
+  HIP_TRY(hipGetLastError());
+  regtopk_result sel;
+  const int gcur = (int)(g->t & 1);
+  int rc = regtopk_step(g, c->abar, nullptr, stream, &sel);
+  if (rc != REGTOPK_OK) return rc;
+  if (ev) HIP_TRY(hipEventRecord(ev[2], s));
+  const dim3 g_waves((L.nc + 3) / 4, c->N);
+  k_global_apply<<<g_waves, kBlock, 0, s>>>(e, sel.idx, g->at<uint32_t>(g->L.sel_off[gcur]), g->at<uint32_t>(g->L.mask),
+                                              prev_sel_off, c->at<int32_t>(L.out_idx[cur]), c->at<float>(L.out_val[cur]),
+                                              c->at<uint32_t>(L.sel_off[cur]), mask, c->d, c->k, L.nc);
+  if (ev) { HIP_TRY(hipEventRecord(ev[3], s)); c->prof_rounds += 1; }
+  HIP_TRY(hipGetLastError());
+  c->t += 1;
+  c->have_prev = true;
+  c->fresh = true;               // bounds of earlier local rounds do not describe the next one
+  out->idx = c->at<int32_t>(L.out_idx[cur]);
+  out->val = c->at<float>(L.out_val[cur]);
+  out->agg = sel.agg;
+  return REGTOPK_OK;
 }
 
 int regtopk_step_bf16(regtopk_ctx* c, const uint16_t* grads, const float* gprev, void* stream, regtopk_result* out) {

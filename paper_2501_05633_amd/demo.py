@@ -9,7 +9,8 @@ Example"): Top-1 keeps sending the cancelling first entries and the model does
 not move for about 100 iterations, RegTop-1 damps them after the first round.
 `linreg` is the paper's linear-regression experiment as a closed loop (sparsified
 round, then theta <- theta - eta * g): it prints the optimality gap
-|theta - theta*| of the unsparsified run, Top-k and RegTop-k, and how many of
+|theta - theta*| of the unsparsified run, Top-k, RegTop-k and the genie-aided
+global Top-k, and how many of
 the J entries all workers agree on (kept by all or dropped by all).
 Everything the method computes runs in the library's kernels; torch only
 produces the local gradients.
@@ -50,15 +51,15 @@ def toy(iters: int = 120, mu: float = 1.0, eta: float = 0.9, device="cuda:0"):
 def linreg(S: float, mu: float, iters: int, N: int, J: int, device="cuda:0", every: int = 250, quiet=False):
     wl = workloads.PaperLinReg(device, N=N, J=J, D=5 * J)
     k = max(1, int(round(S * J)))
-    runs = {"dense": (0.0, J), "Top-k": (0.0, k), "RegTop-k": (mu, k)}
+    runs = {"dense": (0.0, J), "Top-k": (0.0, k), "RegTop-k": (mu, k), "global Top-k": (None, k)}
     res = {}
     for name, (m, kk) in runs.items():
-        r = binding.RegTopk(N, J, kk, m, device=device)
+        r = binding.RegTopk(N, J, kk, 0.0 if m is None else m, device=device)
         theta = torch.zeros(J, device=device)
         agg, gaps, agree = None, [], []
         for t in range(iters):
             g = wl.grads(theta)
-            _, _, agg = r.step(g, agg)
+            _, _, agg = r.step_global(g) if m is None else r.step(g, agg)
             agg = agg.clone()
             binding.sgd_update(theta, agg, wl.eta)
             if t % every == every - 1 or t == iters - 1:
@@ -69,10 +70,12 @@ def linreg(S: float, mu: float, iters: int, N: int, J: int, device="cuda:0", eve
         res[name] = (gaps, agree)
     if not quiet:
         print("linear regression N=%d J=%d D_n=%d eta=%g S=%.2f (k=%d) mu=%g" % (N, J, 5 * J, wl.eta, S, k, mu))
-        print("%8s %14s %14s %14s   entries all workers agree on (Top-k / RegTop-k)" % ("iter", "gap dense", "gap Top-k", "gap RegTop-k"))
+        print("%8s %14s %14s %14s %14s   entries all workers agree on (Top-k / RegTop-k)" % (
+            "iter", "gap dense", "gap Top-k", "gap RegTop-k", "gap global"))
         for i, (t, gd) in enumerate(res["dense"][0]):
-            print("%8d %14.3e %14.3e %14.3e   %d / %d" % (t, gd, res["Top-k"][0][i][1], res["RegTop-k"][0][i][1],
-                                                        res["Top-k"][1][i], res["RegTop-k"][1][i]))
+            print("%8d %14.3e %14.3e %14.3e %14.3e   %d / %d" % (
+                t, gd, res["Top-k"][0][i][1], res["RegTop-k"][0][i][1], res["global Top-k"][0][i][1],
+                res["Top-k"][1][i], res["RegTop-k"][1][i]))
     return res
 
 

@@ -253,3 +253,78 @@ def test_switching_the_variant_between_rounds():
         assert np.array_equal(idx.cpu().numpy(), ic), t
         assert np.array_equal(val.cpu().numpy(), vc) and np.array_equal(agg_g.cpu().numpy(), agg_c)
     r.close()
+
+
+def _compare_exact(res_g, res_c, label):
+    idx, val, agg = (x.cpu().numpy() for x in res_g)
+    assert np.array_equal(idx, res_c[0]), label + " idx"
+    assert np.array_equal(val.view(np.uint32), res_c[1].view(np.uint32)), label + " val"
+    np.testing.assert_allclose(agg, res_c[2], rtol=1e-6, atol=0, err_msg=label + " agg")
+
+
+@pytest.mark.parametrize("name,d,N,k,weights", [
+    ("tiny", 10_000, 4, 100, None),
+    ("large_cnn", 300_001, 3, 3_000, [0.5, 0.3, 0.2]),       # ragged tail, general weights
+    ("large_cnn", 1_000_000, 5, 10_000, None),
+    ("cnn", 4_097, 33, 41, None),
+])
+def test_global_topk_rounds(name, d, N, k, weights):
+    print("case global %s d=%d N=%d" % (name, d, N), flush=True)
+    cfg = workloads.scaled(workloads.CONFIGS[name], d=d, N=N, k=k)
+    wl = workloads.Workload(cfg, DEV)
+    o = orc.Oracle(N, d, k, 1.0)
+    r = binding.RegTopk(N, d, k, 1.0, device=DEV)
+    if weights is not None:
+        o.set_weights(np.asarray(weights, dtype=f32))
+        r.set_weights(weights)
+    for t in range(5):
+        g = wl.grads(t)
+        res_g = r.step_global(g)
+        torch.cuda.synchronize()
+        res_c = o.step_global(g.cpu().numpy())
+        _compare_exact(res_g, res_c, "global round %d" % t)
+        assert np.array_equal(r.mask_overlap().cpu().numpy(), o.mask_overlap())
+        e_g, pidx, pval, tt = r.get_state()
+        assert tt == t + 1 and np.array_equal(e_g.cpu().numpy(), o.e) and np.array_equal(pidx.cpu().numpy(), res_c[0])
+    r.close()
+
+
+def test_global_and_local_rounds_alternate_on_one_context():
+    print("case global mixed", flush=True)
+    N, d, k = 4, 200_000, 2_000
+    cfg = workloads.scaled(workloads.CONFIGS["large_cnn"], d=d, N=N, k=k)
+    wl = workloads.Workload(cfg, DEV)
+    o = orc.Oracle(N, d, k, 1.0)
+    r = binding.RegTopk(N, d, k, 1.0, device=DEV)
+    agg_g = agg_c = None
+    for t, kind in enumerate("LGLLGGL"):
+        g = wl.grads(t)
+        if kind == "G":
+            res_g = r.step_global(g)
+            res_c = o.step_global(g.cpu().numpy())
+        else:
+            res_g = r.step(g, agg_g)
+            res_c = o.step(g.cpu().numpy(), agg_c)
+        torch.cuda.synchronize()
+        _compare_exact(res_g, res_c, "mixed round %d (%s)" % (t, kind))
+        agg_g, agg_c = res_g[2].clone(), res_c[2]
+    r.close()
+
+
+def test_global_topk_on_cancelling_workers_and_ties():
+    print("case global ties", flush=True)
+    g = torch.tensor([[100.0, 1.0, 0.5], [-100.0, 1.0, 0.25]], device=DEV)
+    r = binding.RegTopk(2, 3, 1, 1.0, device=DEV)
+    idx, val, agg = r.step_global(g)
+    assert idx.cpu().tolist() == [[1], [1]] and agg.cpu().tolist() == [0.0, 1.0, 0.0]
+    r.close()
+    # all aggregates equal: the lowest indices win
+    N, d, k = 3, 9_000, 450
+    gg = torch.ones(N, d, device=DEV)
+    r = binding.RegTopk(N, d, k, 0.0, device=DEV)
+    o = orc.Oracle(N, d, k, 0.0)
+    for t in range(3):
+        res_g = r.step_global(gg)
+        res_c = o.step_global(gg.cpu().numpy())
+        _compare_exact(res_g, res_c, "ties round %d" % t)
+    r.close()
