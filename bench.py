@@ -100,6 +100,8 @@ def main():
     ap.add_argument("--likelihood", type=int, default=0, help="score variant: 0 tanh, 1 clipped linear")
     ap.add_argument("--mode", choices=["regtopk", "global"], default="regtopk",
                     help="global: the genie-aided global Top-k baseline instead of the RegTop-k round")
+    ap.add_argument("--force-dense", action="store_true",
+                    help="never speculate: every round takes the dense selection (the cost of a failed speculation)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--max-buffers", type=int, default=24,
                     help="rounds of gradients kept resident in HBM (cycled if steps+warmup is larger)")
@@ -139,6 +141,7 @@ def main():
 
     r = binding.RegTopk(N, d, k, cfg.mu, device=dev)
     r.set_option(binding.OPT_PROFILE, 1)
+    r.set_option(binding.OPT_FORCE_DENSE, 1 if args.force_dense else 0)
     r.set_option(binding.OPT_PRIOR_ROOTS, args.prior_roots)
     r.set_option(binding.OPT_LIKELIHOOD, args.likelihood)
     agg = None
@@ -179,7 +182,7 @@ def main():
         "config": {"workload": "%s: N=%d workers, d=%d, k=%d, mu=%g, per-layer scales, %s entries, "
                                "30%% shared component" % (cfg.name, N, d, k, cfg.mu, cfg.marginal),
                    "N": N, "d": d, "k": k, "mu": cfg.mu, "rounds_resident": n_buf,
-                   "grad_dtype": args.grad_dtype, "prior_roots": args.prior_roots, "likelihood": args.likelihood, "mode": args.mode},
+                   "grad_dtype": args.grad_dtype, "prior_roots": args.prior_roots, "likelihood": args.likelihood, "mode": args.mode, "force_dense": args.force_dense},
         "hbm_frac_round": b_alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "algorithmic_bytes_per_round": b_alg,
         "stage_ms": {"sweep": sweep_ms, "select": select_ms, "compact_aggregate": tail_ms,

@@ -187,8 +187,10 @@ __device__ __forceinline__ void grid_barrier(GlobalCtl* g, uint32_t nblocks) {
       atomicAdd(&g->bar_gen, 1u);
     } else {
       uint32_t spins = 0;
-      while (__hip_atomic_load(&g->bar_gen, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) == gen) {
-        __builtin_amdgcn_s_sleep(8);
+      // relaxed polls with a pause: an acquiring load per poll makes the hundreds of waiting blocks
+      // slow down the few that work in the one-block-per-worker phases (the fence below orders the exit)
+      while (__hip_atomic_load(&g->bar_gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gen) {
+        __builtin_amdgcn_s_sleep(32);
         if (++spins > kBarrierSpinLimit) { atomicOr(&g->bar_err, 1u); break; }
       }
     }
@@ -978,7 +980,17 @@ __device__ __forceinline__ void dense_hist_worker(uint32_t n, uint32_t b, uint32
   if (VEC) {
     const float4* row4 = reinterpret_cast<const float4*>(row);
     const int64_t d4 = d / 4;
-    for (int64_t j = (int64_t)b * kBlock + tid; j < d4; j += (int64_t)G * kBlock) {
+    // four loads in flight per thread: the few resident blocks must cover the memory latency themselves
+    const int64_t step = (int64_t)G * kBlock;
+    int64_t j = (int64_t)b * kBlock + tid;
+    for (; j + 3 * step < d4; j += 4 * step) {
+      const float4 v0 = row4[j], v1 = row4[j + step], v2 = row4[j + 2 * step], v3 = row4[j + 3 * step];
+      put(v0.x); put(v0.y); put(v0.z); put(v0.w);
+      put(v1.x); put(v1.y); put(v1.z); put(v1.w);
+      put(v2.x); put(v2.y); put(v2.z); put(v2.w);
+      put(v3.x); put(v3.y); put(v3.z); put(v3.w);
+    }
+    for (; j < d4; j += step) {
       const float4 v = row4[j];
       put(v.x); put(v.y); put(v.z); put(v.w);
     }
@@ -1102,9 +1114,16 @@ __device__ __forceinline__ void dense_emit_chunk(uint32_t n, uint32_t c, const f
   if (ch_cnt[tix] == 0) return;
   if (tid < kChunkWords) s_mw[tid] = mrow[(size_t)c * kChunkWords + tid];
   __syncthreads();
-  if (tid == 0) {
-    uint32_t run = prev_sel_off[(size_t)n * (nc + 1) + c];
-    for (uint32_t i = 0; i < kChunkWords; ++i) { s_rk[i] = run; run += (uint32_t)__popc(s_mw[i]); }
+  if (tid < 64) {                                    // wave 0: running count of mask bits, two words per lane
+    const uint32_t c0 = (uint32_t)__popc(s_mw[2 * tid]), c1 = (uint32_t)__popc(s_mw[2 * tid + 1]);
+    uint32_t x = c0 + c1;
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t y = __shfl_up(x, o);
+      if (tid >= (uint32_t)o) x += y;
+    }
+    const uint32_t before = prev_sel_off[(size_t)n * (nc + 1) + c] + x - (c0 + c1);
+    s_rk[2 * tid] = before;
+    s_rk[2 * tid + 1] = before + c0;
   }
   __syncthreads();
   const float* pv = prev_val + (size_t)n * k;
@@ -1175,6 +1194,37 @@ __device__ __forceinline__ void dense_emit_chunk(uint32_t n, uint32_t c, const f
   __syncthreads();
 }
 
+// The r-th flagged worker (ascending), found by the whole block: thread t
+// counts the flags of a contiguous range of workers, a block scan places the
+// ranges, the thread whose range holds rank r walks it.  Returns N if r is past
+// the last flagged worker; *n_flagged gets their number.  s_w [16], s_out [2].
+__device__ __forceinline__ uint32_t flagged_worker(const WorkerCtl* ctl, int32_t N, uint32_t r,
+                                                   uint32_t* n_flagged, uint32_t* s_w, uint32_t* s_out) {
+  const uint32_t tid = threadIdx.x;
+  const uint32_t per = ((uint32_t)N + kBlock - 1) / kBlock;
+  const uint32_t n0 = tid * per < (uint32_t)N ? tid * per : (uint32_t)N;
+  const uint32_t n1 = n0 + per < (uint32_t)N ? n0 + per : (uint32_t)N;
+  uint32_t mine = 0;
+  for (uint32_t n = n0; n < n1; ++n) mine += ctl[n].need_dense != 0;
+  if (tid == 0) s_out[0] = (uint32_t)N;
+  uint32_t total;
+  const uint32_t before = block_excl_scan<kBlock>(mine, s_w, &total);
+  if (r >= before && r < before + mine) {
+    uint32_t seen = before;
+    for (uint32_t n = n0; n < n1; ++n) {
+      if (ctl[n].need_dense != 0) {
+        if (seen == r) { s_out[0] = n; break; }
+        ++seen;
+      }
+    }
+  }
+  __syncthreads();
+  const uint32_t hit = s_out[0];
+  __syncthreads();
+  *n_flagged = total;
+  return hit;
+}
+
 // grid (G): G blocks resident together.  See the section header.
 template <bool VEC>
 __global__ void __launch_bounds__(kBlock)
@@ -1199,20 +1249,36 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
   }
   grid_barrier(gctl, G);
 
-  for (int32_t n = 0; n < N; ++n)
-    if (ctl[n].need_dense) dense_hist_worker<1, VEC>(n, b, G, a_rows, d, ctl, fhist, s_hist, roots);
+  // The histogram passes give every flagged worker its own group of blocks (all
+  // workers at once, each histogram fed by G / n_flagged blocks), so that the
+  // blocks' final adds do not all queue on the same few words.
+  uint32_t n_flagged;
+  (void)flagged_worker(ctl, N, 0xFFFFFFFFu, &n_flagged, s_w, s_out);
+  if (n_flagged == 0) return;                                   // every block sees the same flags
+  const uint32_t groups = n_flagged < G ? n_flagged : G;
+  const uint32_t grp = b % groups, sub = b / groups;
+  const uint32_t sub_cnt = (G - grp + groups - 1) / groups;     // blocks of this group
+  const uint32_t first_worker = flagged_worker(ctl, N, grp, &n_flagged, s_w, s_out);
+  for (uint32_t r = grp; r < n_flagged; r += groups) {
+    const uint32_t n = r == grp ? first_worker : flagged_worker(ctl, N, r, &n_flagged, s_w, s_out);
+    if (n < (uint32_t)N) dense_hist_worker<1, VEC>(n, sub, sub_cnt, a_rows, d, ctl, fhist, s_hist, roots);
+  }
   grid_barrier(gctl, G);
   for (int32_t n = b; n < N; n += G)
     if (ctl[n].need_dense) dense_scan_worker<1>(n, ctl, fhist, k, d, s_a, s_b);
   grid_barrier(gctl, G);
-  for (int32_t n = 0; n < N; ++n)
-    if (ctl[n].need_dense) dense_hist_worker<2, VEC>(n, b, G, a_rows, d, ctl, fhist, s_hist, roots);
+  for (uint32_t r = grp; r < n_flagged; r += groups) {
+    const uint32_t n = r == grp ? first_worker : flagged_worker(ctl, N, r, &n_flagged, s_w, s_out);
+    if (n < (uint32_t)N) dense_hist_worker<2, VEC>(n, sub, sub_cnt, a_rows, d, ctl, fhist, s_hist, roots);
+  }
   grid_barrier(gctl, G);
   for (int32_t n = b; n < N; n += G)
     if (ctl[n].need_dense) dense_scan_worker<2>(n, ctl, fhist, k, d, s_a, s_b);
   grid_barrier(gctl, G);
-  for (int32_t n = 0; n < N; ++n)
-    if (ctl[n].need_dense) dense_hist_worker<3, VEC>(n, b, G, a_rows, d, ctl, fhist, s_hist, roots);
+  for (uint32_t r = grp; r < n_flagged; r += groups) {
+    const uint32_t n = r == grp ? first_worker : flagged_worker(ctl, N, r, &n_flagged, s_w, s_out);
+    if (n < (uint32_t)N) dense_hist_worker<3, VEC>(n, sub, sub_cnt, a_rows, d, ctl, fhist, s_hist, roots);
+  }
   grid_barrier(gctl, G);
   for (int32_t n = b; n < N; n += G)
     if (ctl[n].need_dense) dense_scan_worker<3>(n, ctl, fhist, k, d, s_a, s_b);
