@@ -739,9 +739,23 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
     if (window) dens = (double)n_bnd / (double)(win_hi - win_lo);
     else dens = tau > base ? (double)(n_tot - K + 1) / (double)(tau - base) : 1.0;
     if (dens < 1e-7) dens = 1e-7;
+    // After a failed speculation the history may say nothing about the next
+    // round.  The bound was too high (fewer than k valid candidates): the k-th
+    // score fell, which a drift never does - restart from this round's value.
+    // The bound was too low (overflow): a shock if the k-th score is more than
+    // twice what was expected; anything less can be the growth of the first
+    // rounds (the accumulated gradient of an unsent entry doubles from round 0
+    // to round 1, then grows by 3/2, 4/3, ...), an upward drift that was
+    // underestimated and that the extrapolation below keeps following.
+    bool shock = false;
+    if (SECOND && c.tau_lo != kNoBound) {
+      const uint32_t ref = c.centre != kNoBound ? c.centre : c.tau_prev;
+      if (!c.overflow) shock = true;
+      else if (ref != kNoBound && tau > ref && tau - ref > (1u << 23)) shock = true;
+    }
     // the k-th score drifts from round to round: extrapolate linearly
     int64_t drift = 0;
-    if (c.tau_prev != kNoBound) drift = (int64_t)tau - (int64_t)c.tau_prev;
+    if (!shock && c.tau_prev != kNoBound) drift = (int64_t)tau - (int64_t)c.tau_prev;
     if (drift > (1 << 22)) drift = 1 << 22;
     if (drift < -(1 << 22)) drift = -(1 << 22);
     int64_t centre = (int64_t)tau + drift;
@@ -751,10 +765,11 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
     // if it was an extrapolation (two earlier rounds known), else half the drift
     const uint32_t adrift = (uint32_t)(drift < 0 ? -drift : drift);
     uint32_t err;
-    if (c.centre != kNoBound && c.extrapolated) err = tau > c.centre ? tau - c.centre : c.centre - tau;
+    if (shock) err = kWinDefaultHalf;
+    else if (c.centre != kNoBound && c.extrapolated) err = tau > c.centre ? tau - c.centre : c.centre - tau;
     else if (c.tau_prev != kNoBound) err = adrift / 2;
     else err = kWinDefaultHalf;
-    if ((double)err < 0.7 * (double)c.err_prev) err = (uint32_t)(0.7 * (double)c.err_prev);
+    if (!shock && (double)err < 0.7 * (double)c.err_prev) err = (uint32_t)(0.7 * (double)c.err_prev);
     double half = 3.0 * (double)err + 1024.0;
     const double by_count = 10000.0 / dens;                // at least about 20000 boundary entries
     if (half < by_count) half = by_count;
@@ -784,7 +799,19 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
     margin *= (double)ms;
     if (margin > 16777216.0) margin = 16777216.0;
     const int64_t anchor = drift > 0 ? (int64_t)tau + drift / 2 : centre;
-    const int64_t lo = anchor - (int64_t)margin;
+    int64_t lo = anchor - (int64_t)margin;
+    if (shock && c.dense_total >= 2 * K) {
+      // The dense selection's list is exactly the 2k entries of largest prior,
+      // ending at f_tau.  Whether the new level persists (the k-th score stays
+      // near tau) or the residuals of this round dominate the next one - after a
+      // single spike, or when the gradients have collapsed - so that its k-th
+      // score is this round's 2k-th, about f_tau: a bound half a list's spacing
+      // below f_tau holds about 2.5k candidates, inside the buffer, and at
+      // least k valid ones.
+      const double below = 0.5 * (double)(tau > c.f_tau ? tau - c.f_tau : 0u) * (double)(ms > 1.0f ? ms : 1.0f);
+      const int64_t lo2 = (int64_t)c.f_tau - (int64_t)(below < 16777216.0 ? below : 16777216.0) - 1024;
+      if (lo2 < lo) lo = lo2;
+    }
     const bool speculate = (int64_t)n_tot >= (int64_t)((double)cand_target * (double)K) || !SECOND;
     c.next_tau_lo = speculate ? (uint32_t)(lo > 0 ? lo : 0) : kNoBound;
     c.next_win_lo = speculate ? (uint32_t)(centre > (int64_t)h ? centre - (int64_t)h : 0) : kNoBound;
