@@ -857,8 +857,24 @@ k_sample_hist(const float* __restrict__ e, const G* __restrict__ g, const uint32
   __syncthreads();
   const size_t row = (size_t)n * (size_t)d;
   const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
+  const bool vec = (d % 4 == 0) && (reinterpret_cast<uintptr_t>(g) % (4 * sizeof(G)) == 0);
   for (uint32_t i = blockIdx.x * kBlock + tid; i < n_groups; i += gridDim.x * kBlock) {
     const int64_t j0 = (int64_t)i * stride4 * 4;
+    if (vec && j0 + 4 <= d) {                           // one 128-bit load of the state, one of the gradients
+      const uint32_t mb = (mrow[j0 >> 5] >> (j0 & 31)) & 15u;
+      f32x4 ev = *reinterpret_cast<const f32x4*>(e + row + j0);
+      const f32x4 gv = grad4_at(g, row + j0);
+      if (mb & 1u) ev.x = 0.f;
+      if (mb & 2u) ev.y = 0.f;
+      if (mb & 4u) ev.z = 0.f;
+      if (mb & 8u) ev.w = 0.f;
+      const f32x4 a4 = ev + gv;
+      atomicAdd(&s_hist[prior_key(a4.x, roots) >> kL1Shift], 1u);
+      atomicAdd(&s_hist[prior_key(a4.y, roots) >> kL1Shift], 1u);
+      atomicAdd(&s_hist[prior_key(a4.z, roots) >> kL1Shift], 1u);
+      atomicAdd(&s_hist[prior_key(a4.w, roots) >> kL1Shift], 1u);
+      continue;
+    }
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int64_t j = j0 + q;

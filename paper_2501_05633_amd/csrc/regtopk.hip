@@ -338,7 +338,11 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
     uint64_t n_sampled = (uint64_t)n_groups * 4;
     if (n_sampled > (uint64_t)d) n_sampled = (uint64_t)d;
     k_fill_u32<<<64, 256, 0, s>>>(fhist, (size_t)N * 3 * kL1Bins, 0u);
-    k_sample_hist<G><<<dim3((n_groups + 4 * kBlock - 1) / (4 * kBlock), N), kBlock, 0, s>>>(e, grads, mask, d, nc, fhist, n_groups, stride4, sk.roots);
+    // few blocks per worker: every block ends with one global add per occupied histogram bin, and adds
+    // of many blocks to the same few words queue up (about 12 ns each)
+    uint32_t sample_blocks = (n_groups + 4 * kBlock - 1) / (4 * kBlock);
+    if (sample_blocks > 16) sample_blocks = 16;
+    k_sample_hist<G><<<dim3(sample_blocks, N), kBlock, 0, s>>>(e, grads, mask, d, nc, fhist, n_groups, stride4, sk.roots);
     k_sample_bound<<<N, kScanBlock, 0, s>>>(ctl, fhist, d, k, (uint32_t)n_sampled, sk.roots);
   }
   c->fresh = false;
