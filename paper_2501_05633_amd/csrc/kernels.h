@@ -933,8 +933,9 @@ template <bool DENSE, int NT>
 __device__ __forceinline__ void chunk_scan_worker(uint32_t n, WorkerCtl* ctl, const uint32_t* ch_gt,
                                                   const uint32_t* ch_tie, uint32_t* out_off,
                                                   uint32_t* out_cnt, uint32_t* out_tieoff, uint32_t nc,
-                                                  int64_t k, uint32_t* s_w) {
-  const uint32_t tid = threadIdx.x;
+                                                  int64_t k, uint32_t* s_w /*[>= 2 * NT / 64]*/) {
+  constexpr uint32_t W = NT / 64;
+  const uint32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   WorkerCtl& c = ctl[n];
   const uint32_t budget = DENSE ? c.f_budget : c.budget;
   const uint32_t* gt = ch_gt + (size_t)n * nc;
@@ -942,38 +943,53 @@ __device__ __forceinline__ void chunk_scan_worker(uint32_t n, WorkerCtl* ctl, co
   uint32_t* off = out_off + (size_t)n * (DENSE ? nc : nc + 1);
   uint32_t* cnt = DENSE ? out_cnt + (size_t)n * nc : nullptr;
   uint32_t* tof = out_tieoff + (size_t)n * nc;
-  // every thread owns a contiguous run of chunks: two block scans in all
-  const uint32_t per = (nc + NT - 1) / NT;
-  const uint32_t c0 = tid * per < nc ? tid * per : nc;
-  const uint32_t c1 = c0 + per < nc ? c0 + per : nc;
-  uint32_t tsum = 0;
-  for (uint32_t ci = c0; ci < c1; ++ci) tsum += tie[ci];
-  uint32_t ttot, stot;
-  const uint32_t tbase = block_excl_scan<NT>(tsum, s_w, &ttot);
-  uint32_t trun = tbase, ssum = 0;
-  for (uint32_t ci = c0; ci < c1; ++ci) {
-    const uint32_t t = tie[ci];
-    uint32_t take = 0;
-    if (trun < budget) { take = budget - trun; if (take > t) take = t; }
-    ssum += gt[ci] + take;
-    trun += t;
+  // The ties taken before chunk c number min(budget, ties before c), so the two
+  // running sums of gt and tie give everything.  Every wave owns a contiguous
+  // run of 64-chunk tiles (coalesced loads): first its totals, then, after the
+  // waves' totals are placed, the running sums and the outputs.
+  const uint32_t tiles = (nc + 63) / 64;
+  const uint32_t per = (tiles + W - 1) / W;
+  const uint32_t t0 = wv * per < tiles ? wv * per : tiles;
+  const uint32_t t1 = t0 + per < tiles ? t0 + per : tiles;
+  uint32_t gsum = 0, tsum = 0;
+#pragma unroll 8
+  for (uint32_t t = t0; t < t1; ++t) {
+    const uint32_t ci = t * 64 + lane;
+    if (ci < nc) { gsum += gt[ci]; tsum += tie[ci]; }
   }
-  const uint32_t sbase = block_excl_scan<NT>(ssum, s_w, &stot);
-  trun = tbase;
-  uint32_t srun = sbase;
-  for (uint32_t ci = c0; ci < c1; ++ci) {
-    const uint32_t t = tie[ci];
-    uint32_t take = 0;
-    if (trun < budget) { take = budget - trun; if (take > t) take = t; }
-    const uint32_t sel = gt[ci] + take;
-    off[ci] = srun;
-    tof[ci] = trun;
-    if (DENSE) cnt[ci] = sel;
-    trun += t;
-    srun += sel;
+  for (int o = 32; o > 0; o >>= 1) { gsum += __shfl_down(gsum, o); tsum += __shfl_down(tsum, o); }
+  if (lane == 0) { s_w[wv] = gsum; s_w[W + wv] = tsum; }
+  __syncthreads();
+  uint32_t grun = 0, trun = 0, gtot = 0, ttot = 0;
+  for (uint32_t i = 0; i < W; ++i) {
+    const uint32_t g = s_w[i], t = s_w[W + i];
+    if (i < wv) { grun += g; trun += t; }
+    gtot += g; ttot += t;
   }
-  const uint32_t sel_run = stot;
+  __syncthreads();
+#pragma unroll 4
+  for (uint32_t t = t0; t < t1; ++t) {
+    const uint32_t ci = t * 64 + lane;
+    const uint32_t g = ci < nc ? gt[ci] : 0u, ti = ci < nc ? tie[ci] : 0u;
+    uint32_t gx = g, tx = ti;                            // inclusive running sums inside the tile
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t gy = __shfl_up(gx, o), ty = __shfl_up(tx, o);
+      if (lane >= (uint32_t)o) { gx += gy; tx += ty; }
+    }
+    const uint32_t g_before = grun + gx - g, t_before = trun + tx - ti;
+    if (ci < nc) {
+      const uint32_t taken_before = t_before < budget ? t_before : budget;
+      uint32_t take = 0;
+      if (t_before < budget) { take = budget - t_before; if (take > ti) take = ti; }
+      off[ci] = g_before + taken_before;
+      tof[ci] = t_before;
+      if (DENSE) cnt[ci] = g + take;
+    }
+    grun += __shfl(gx, 63);
+    trun += __shfl(tx, 63);
+  }
   if (tid == 0) {
+    const uint32_t sel_run = gtot + (ttot < budget ? ttot : budget);
     if (DENSE) c.dense_total = sel_run;
     else {
       off[nc] = sel_run;
@@ -987,7 +1003,7 @@ __device__ __forceinline__ void chunk_scan_worker(uint32_t n, WorkerCtl* ctl, co
 __global__ void __launch_bounds__(kScanBlock)
 k_chunk_scan(WorkerCtl* ctl, const uint32_t* __restrict__ ch_gt, const uint32_t* __restrict__ ch_tie,
              uint32_t* __restrict__ sel_off, uint32_t* __restrict__ tie_off, uint32_t nc, int64_t k) {
-  __shared__ uint32_t s_w[16];
+  __shared__ uint32_t s_w[2 * kScanBlock / 64];
   chunk_scan_worker<false, kScanBlock>(blockIdx.x, ctl, ch_gt, ch_tie, sel_off, nullptr, tie_off, nc, k, s_w);
 }
 
