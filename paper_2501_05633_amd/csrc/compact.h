@@ -1,0 +1,204 @@
+// Ordered compaction of the selected pairs (k_chunk_count, k_compact) and the aggregation (k_aggregate).
+#pragma once
+#include "dense.h"
+
+namespace rtk {
+
+// --------------------------------------------------------- k_chunk_count ----
+// grid (ceil(nc/4), N): one wave per chunk.  Candidates of the chunk with
+// score > tau and == tau.  Most chunks are empty and a few hold hundreds of
+// candidates, so a lane takes eight at a time with all loads in flight together.
+constexpr int kLaneBatch = 8;
+__global__ void __launch_bounds__(kBlock)
+k_chunk_count(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ cand_key,
+              const uint32_t* __restrict__ ch_off, const uint32_t* __restrict__ ch_cnt,
+              uint32_t* __restrict__ ch_gt, uint32_t* __restrict__ ch_tie, uint32_t nc,
+              uint32_t cap_total) {
+  const uint32_t n = blockIdx.y, lane = threadIdx.x & 63;
+  const uint32_t c = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (c >= nc) return;
+  const size_t tix = (size_t)n * nc + c;
+  const uint32_t tau = ctl[n].tau;
+  const uint32_t off = ch_off[tix], cnt = ch_cnt[tix];
+  const uint32_t* key = cand_key + (size_t)n * cap_total + off;
+  uint32_t gt = 0, tie = 0;
+  for (uint32_t p0 = 0; p0 < cnt; p0 += 64 * kLaneBatch) {
+    uint32_t kk[kLaneBatch];
+#pragma unroll
+    for (int q = 0; q < kLaneBatch; ++q) {
+      const uint32_t p = p0 + q * 64 + lane;
+      kk[q] = p < cnt ? key[p] : 0u;
+    }
+#pragma unroll
+    for (int q = 0; q < kLaneBatch; ++q) {
+      const bool in = p0 + q * 64 + lane < cnt;
+      gt += in && kk[q] > tau;
+      tie += in && kk[q] == tau;
+    }
+  }
+  for (int o = 32; o > 0; o >>= 1) { gt += __shfl_down(gt, o); tie += __shfl_down(tie, o); }
+  if (lane == 0) { ch_gt[tix] = gt; ch_tie[tix] = tie; }
+}
+
+// ------------------------------------------------------------- k_compact ----
+// grid (ceil(nc/4), N): one wave per chunk.  Writes the selected pairs of the
+// chunk in index order at sel_off[c], and the chunk's words of the round's mask
+// (bit = entry selected).
+__global__ void __launch_bounds__(kBlock)
+k_compact(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ cand_key,
+          const int32_t* __restrict__ cand_idx, const float* __restrict__ cand_val,
+          const uint32_t* __restrict__ ch_off, const uint32_t* __restrict__ ch_cnt,
+          const uint32_t* __restrict__ sel_off, const uint32_t* __restrict__ prev_sel_off,
+          const uint32_t* __restrict__ tie_off, int32_t* __restrict__ out_idx,
+          float* __restrict__ out_val, uint32_t* __restrict__ mask,
+          int64_t k, uint32_t nc, uint32_t cap_total) {
+  __shared__ uint32_t s_m[4][kChunkWords];
+  const uint32_t n = blockIdx.y, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const uint32_t c = blockIdx.x * 4 + wv;
+  const bool live = c < nc;
+  s_m[wv][lane] = 0;
+  s_m[wv][lane + 64] = 0;
+  __syncthreads();
+  uint32_t first = 0;
+  bool was_empty = true, is_empty = true;
+  if (live) {
+    const size_t tix = (size_t)n * nc + c;
+    const size_t so = (size_t)n * (nc + 1) + c;
+    const uint32_t cnt = ch_cnt[tix];
+    const uint32_t off = ch_off[tix];
+    const uint32_t tau = ctl[n].tau, budget = ctl[n].budget;
+    const size_t cb = (size_t)n * cap_total + off;
+    first = sel_off[so];
+    was_empty = prev_sel_off[so + 1] == prev_sel_off[so];
+    is_empty = sel_off[so + 1] == first;
+    uint32_t out = first;
+    uint32_t tie_run = tie_off[tix];
+    for (uint32_t p0 = 0; p0 < cnt; p0 += 64 * kLaneBatch) {
+      // keys, indices and values of eight candidates per lane, all loads in flight together
+      uint32_t kk[kLaneBatch], jj[kLaneBatch];
+      float vv[kLaneBatch];
+#pragma unroll
+      for (int q = 0; q < kLaneBatch; ++q) {
+        const uint32_t p = p0 + q * 64 + lane;
+        const bool in = p < cnt;
+        kk[q] = in ? cand_key[cb + p] : 0u;
+        jj[q] = in ? (uint32_t)cand_idx[cb + p] & ~kSentFlag : 0u;
+        vv[q] = in ? cand_val[cb + p] : 0.0f;
+      }
+#pragma unroll
+      for (int q = 0; q < kLaneBatch; ++q) {
+        if (p0 + q * 64 >= cnt) break;                       // uniform over the wave
+        const bool in = p0 + q * 64 + lane < cnt;
+        const bool is_tie = in && kk[q] == tau;
+        const uint64_t tb = __ballot(is_tie);
+        const bool take = in && (kk[q] > tau || (is_tie && tie_run + lanes_below(tb) < budget));
+        const uint64_t sb = __ballot(take);
+        if (take) {
+          const uint32_t o = out + lanes_below(sb);
+          if ((int64_t)o < k) {
+            out_idx[(size_t)n * k + o] = (int32_t)jj[q];
+            out_val[(size_t)n * k + o] = vv[q];
+            const uint32_t jl = jj[q] & (kChunk - 1);
+            atomicOr(&s_m[wv][jl >> 5], 1u << (jl & 31));
+          }
+        }
+        tie_run += (uint32_t)__popcll(tb);
+        out += (uint32_t)__popcll(sb);
+      }
+    }
+  }
+  __syncthreads();
+  if (live) {
+    // a chunk without selected entries in the previous round has all-zero mask
+    // words already: nothing to write if it has none now either
+    if (!(was_empty && is_empty)) {
+      const size_t wbase = ((size_t)n * nc + c) * kChunkWords;
+      reinterpret_cast<uint2*>(mask + wbase)[lane] = make_uint2(s_m[wv][2 * lane], s_m[wv][2 * lane + 1]);
+    }
+  }
+}
+
+// ----------------------------------------------------------- k_aggregate ----
+// grid (nc).  agg tile of 4096 entries: +0, then + omega_n*val of every worker in
+// ascending worker order (indices of one worker are distinct, so plain LDS
+// read-modify-write), written once (tiles that are zero and already hold zeros
+// are left alone).  Workers are taken 32 at a time: the
+// chunk's selected entries of all 32 are first staged in LDS with independent
+// loads (so memory latency is paid once per batch), then applied to the tile
+// one worker after the other.
+constexpr uint32_t kAggStage = 1024;
+
+__global__ void __launch_bounds__(kBlock)
+k_aggregate(const int32_t* __restrict__ out_idx, const float* __restrict__ out_val,
+            const uint32_t* __restrict__ sel_off, float* __restrict__ agg,
+            uint32_t* __restrict__ agg_hot, int64_t d, int64_t k, uint32_t nc, int32_t N,
+            const float* __restrict__ omega) {
+  __shared__ float s_tile[kChunk];
+  __shared__ uint32_t s_j[kAggStage];
+  __shared__ float s_v[kAggStage];
+  __shared__ uint32_t s_s0[32], s_pre[33];
+  __shared__ float s_w[32];
+  const uint32_t c = blockIdx.x, tid = threadIdx.x;
+  for (uint32_t i = tid; i < kChunk; i += kBlock) s_tile[i] = 0.0f;
+  const int32_t jbase = (int32_t)(c << kChunkLog);
+  uint32_t any_entries = 0;
+  for (int32_t b0 = 0; b0 < N; b0 += 32) {
+    const int32_t nb = N - b0 < 32 ? N - b0 : 32;
+    __syncthreads();                                  // previous batch applied, s_* free
+    if ((int32_t)tid < nb) {
+      const size_t o = (size_t)(b0 + tid) * (nc + 1) + c;
+      const uint32_t a0 = sel_off[o];
+      s_s0[tid] = a0;
+      s_w[tid] = omega[b0 + tid];
+      s_pre[tid + 1] = sel_off[o + 1] - a0;            // length, turned into a prefix below
+    }
+    __syncthreads();
+    if (tid == 0) {
+      uint32_t run = 0;
+      s_pre[0] = 0;
+      for (int32_t i = 0; i < nb; ++i) { run += s_pre[i + 1]; s_pre[i + 1] = run; }
+    }
+    __syncthreads();
+    const uint32_t total = s_pre[nb];
+    any_entries |= total;
+    for (uint32_t q0 = 0; q0 < total; q0 += kAggStage) {   // usually one pass
+      const uint32_t q1 = q0 + kAggStage < total ? q0 + kAggStage : total;
+      for (uint32_t q = q0 + tid; q < q1; q += kBlock) {
+        int32_t i = 0;
+        while (s_pre[i + 1] <= q) ++i;                 // worker of flattened entry q
+        const size_t src = (size_t)(b0 + i) * k + s_s0[i] + (q - s_pre[i]);
+        s_j[q - q0] = (uint32_t)(out_idx[src] - jbase);
+        s_v[q - q0] = out_val[src];
+      }
+      __syncthreads();
+      for (int32_t i = 0; i < nb; ++i) {               // ascending worker order
+        const uint32_t lo = s_pre[i] > q0 ? s_pre[i] : q0;
+        const uint32_t hi = s_pre[i + 1] < q1 ? s_pre[i + 1] : q1;
+        if (lo < hi) {                                 // uniform over the block
+          const float w = s_w[i];
+          for (uint32_t q = lo + tid; q < hi; q += kBlock) {
+            const uint32_t j = s_j[q - q0];
+            if (j < (uint32_t)kChunk) s_tile[j] = __fadd_rn(s_tile[j], __fmul_rn(w, s_v[q - q0]));
+          }
+          __syncthreads();
+        }
+      }
+    }
+  }
+  __syncthreads();
+  // agg_hot[c] tells whether this tile of the output buffer holds anything but
+  // zeros: a tile no worker selected from is only written if it has to be cleared
+  const uint32_t was_hot = agg_hot[c];
+  if (!any_entries && !was_hot) return;
+  if (tid == 0) agg_hot[c] = any_entries ? 1u : 0u;
+  const int64_t j0 = (int64_t)c * kChunk;
+  if (j0 + kChunk <= d && (d % 4) == 0) {
+    for (uint32_t i = tid * 4; i < kChunk; i += kBlock * 4)
+      *reinterpret_cast<float4*>(agg + j0 + i) = make_float4(s_tile[i], s_tile[i + 1], s_tile[i + 2], s_tile[i + 3]);
+  } else {
+    for (uint32_t i = tid; i < kChunk; i += kBlock)
+      if (j0 + i < d) agg[j0 + i] = s_tile[i];
+  }
+}
+
+}  // namespace rtk

@@ -1,0 +1,374 @@
+// The dense selection of workers whose speculation failed: one kernel with grid barriers (k_dense_all).
+#pragma once
+#include "select.h"
+
+namespace rtk {
+
+// ------------------------------------------------------------ dense path ----
+// The dense selection of the workers whose speculation failed (and of every
+// worker in round 0) runs as ONE kernel, k_dense_all, whose phases are
+// separated by grid barriers: when no worker is flagged - the usual case - the
+// whole path costs a single launch that returns at once.  The grid is sized by
+// the host so that all blocks are resident together.
+//
+// Phases, for flagged workers only:
+//   clear histograms | 3 x (histogram of |a| bits, pick the bin of rank
+//   min(2k,d)) | per-chunk counts | chunk scan | ordered emission of the 2k
+//   largest |a| as the candidate list | scores | exact k-th score.
+
+// Histogram level LEVEL of worker n's row; block b of G covers a strided share.
+template <int LEVEL, bool VEC>
+__device__ __forceinline__ void dense_hist_worker(uint32_t n, uint32_t b, uint32_t G, const float* a,
+                                                  int64_t d, const WorkerCtl* ctl, uint32_t* fhist,
+                                                  uint32_t* s_hist, int roots) {
+  const uint32_t tid = threadIdx.x;
+  constexpr uint32_t bins = LEVEL == 1 ? kL1Bins : (LEVEL == 2 ? kL2Bins : kL3Bins);
+  for (uint32_t i = tid; i < bins; i += kBlock) s_hist[i] = 0;
+  __syncthreads();
+  const uint32_t prefix = ctl[n].f_prefix;
+  const float* row = a + (size_t)n * (size_t)d;
+  auto put = [&](float v) {
+    const uint32_t key = prior_key(v, roots);
+    if (LEVEL == 1) atomicAdd(&s_hist[key >> kL1Shift], 1u);
+    else if (LEVEL == 2) { if ((key >> kL1Shift) == prefix) atomicAdd(&s_hist[(key >> kL2Shift) & (kL2Bins - 1)], 1u); }
+    else { if ((key >> kL2Shift) == prefix) atomicAdd(&s_hist[key & (kL3Bins - 1)], 1u); }
+  };
+  if (VEC) {
+    const float4* row4 = reinterpret_cast<const float4*>(row);
+    const int64_t d4 = d / 4;
+    // four loads in flight per thread: the few resident blocks must cover the memory latency themselves
+    const int64_t step = (int64_t)G * kBlock;
+    int64_t j = (int64_t)b * kBlock + tid;
+    for (; j + 3 * step < d4; j += 4 * step) {
+      const float4 v0 = row4[j], v1 = row4[j + step], v2 = row4[j + 2 * step], v3 = row4[j + 3 * step];
+      put(v0.x); put(v0.y); put(v0.z); put(v0.w);
+      put(v1.x); put(v1.y); put(v1.z); put(v1.w);
+      put(v2.x); put(v2.y); put(v2.z); put(v2.w);
+      put(v3.x); put(v3.y); put(v3.z); put(v3.w);
+    }
+    for (; j < d4; j += step) {
+      const float4 v = row4[j];
+      put(v.x); put(v.y); put(v.z); put(v.w);
+    }
+  } else {
+    for (int64_t j = (int64_t)b * kBlock + tid; j < d; j += (int64_t)G * kBlock) put(row[j]);
+  }
+  __syncthreads();
+  uint32_t* gh = fhist + ((size_t)n * 3 + (LEVEL - 1)) * kL1Bins;
+  for (uint32_t i = tid; i < bins; i += kBlock) {
+    const uint32_t v = s_hist[i];
+    if (v) atomicAdd(&gh[i], v);
+  }
+  __syncthreads();
+}
+
+// Level LEVEL of the radix select of rank min(2k, d) over the |a| bits of worker
+// n: finds, from the top bin downwards, the bin in which the cumulative count
+// reaches the wanted rank.  One block.
+template <int LEVEL>
+__device__ __forceinline__ void dense_scan_worker(uint32_t n, WorkerCtl* ctl, const uint32_t* hist_all,
+                                                  int64_t k, int64_t d, uint32_t* s_sum,
+                                                  uint32_t* s_scan) {
+  constexpr uint32_t bins = LEVEL == 1 ? kL1Bins : (LEVEL == 2 ? kL2Bins : kL3Bins);
+  constexpr uint32_t per = bins / kBlock;            // bins per thread (16, 8, 1)
+  const uint32_t tid = threadIdx.x;
+  WorkerCtl& c = ctl[n];
+  const uint32_t* h = hist_all + ((size_t)n * 3 + (LEVEL - 1)) * kL1Bins;
+  uint32_t want;
+  if (LEVEL == 1) want = (uint32_t)(2 * k < d ? 2 * k : d);
+  else want = c.f_krem;
+  // thread t owns bins [bins-1-t*per .. bins-(t+1)*per], i.e. descending order
+  uint32_t loc[per];
+  uint32_t s = 0;
+#pragma unroll
+  for (uint32_t q = 0; q < per; ++q) { loc[q] = h[bins - 1 - (tid * per + q)]; s += loc[q]; }
+  s_sum[tid] = s;
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t run = 0;
+    for (uint32_t i = 0; i < kBlock; ++i) { s_scan[i] = run; run += s_sum[i]; }
+  }
+  __syncthreads();
+  const uint32_t above = s_scan[tid];               // count in bins above this thread's
+  if (above < want && want <= above + s) {
+    uint32_t run = above;
+#pragma unroll
+    for (uint32_t q = 0; q < per; ++q) {
+      if (run < want && want <= run + loc[q]) {
+        const uint32_t bin = bins - 1 - (tid * per + q);
+        const uint32_t krem = want - run;            // rank wanted inside this bin
+        if (LEVEL == 1) { c.f_prefix = bin; c.f_krem = krem; }
+        else if (LEVEL == 2) { c.f_prefix = (c.f_prefix << 11) | bin; c.f_krem = krem; }
+        else { c.f_tau = (c.f_prefix << 8) | bin; c.f_budget = krem; }
+      }
+      run += loc[q];
+    }
+  }
+  __syncthreads();
+}
+
+// Chunk c of worker n: entries with |a| bits > f_tau and == f_tau.
+template <bool VEC>
+__device__ __forceinline__ void dense_count_chunk(uint32_t n, uint32_t c, const float* a, int64_t d,
+                                                  const WorkerCtl* ctl, uint32_t* ch_gt,
+                                                  uint32_t* ch_tie, uint32_t nc, uint32_t* s_gt,
+                                                  uint32_t* s_tie, int roots) {
+  const uint32_t tid = threadIdx.x;
+  const uint32_t tau = ctl[n].f_tau;
+  const float* row = a + (size_t)n * (size_t)d;
+  uint32_t gt = 0, tie = 0;
+  if (VEC) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int64_t j = (int64_t)c * kChunk + (i * kBlock + tid) * 4;
+      if (j < d) {
+        const float4 v = *reinterpret_cast<const float4*>(row + j);
+        const uint32_t k0 = prior_key(v.x, roots), k1 = prior_key(v.y, roots), k2 = prior_key(v.z, roots),
+                       k3 = prior_key(v.w, roots);
+        gt += (k0 > tau) + (k1 > tau) + (k2 > tau) + (k3 > tau);
+        tie += (k0 == tau) + (k1 == tau) + (k2 == tau) + (k3 == tau);
+      }
+    }
+  } else {
+    for (int i = 0; i < 16; ++i) {
+      const int64_t j = (int64_t)c * kChunk + i * kBlock + tid;
+      if (j < d) {
+        const uint32_t key = prior_key(row[j], roots);
+        gt += key > tau;
+        tie += key == tau;
+      }
+    }
+  }
+  for (int o = 32; o > 0; o >>= 1) { gt += __shfl_down(gt, o); tie += __shfl_down(tie, o); }
+  if ((tid & 63) == 0) { s_gt[tid >> 6] = gt; s_tie[tid >> 6] = tie; }
+  __syncthreads();
+  if (tid == 0) {
+    ch_gt[(size_t)n * nc + c] = s_gt[0] + s_gt[1] + s_gt[2] + s_gt[3];
+    ch_tie[(size_t)n * nc + c] = s_tie[0] + s_tie[1] + s_tie[2] + s_tie[3];
+  }
+  __syncthreads();
+}
+
+// Chunk c of worker n: writes its share of the 2k largest |a| (ties: lowest
+// indices) to the candidate list, in index order, at the offsets of the scan.
+// The sweep has overwritten the state by now, so the value sent in the previous
+// round is fetched from that round's list: its position there is the number of
+// mask bits before the entry (prev_sel_off[c] of them in lower chunks; s_mw /
+// s_rk, 128 words each, hold the chunk's mask words and their running counts).
+template <bool VEC>
+__device__ __forceinline__ void dense_emit_chunk(uint32_t n, uint32_t c, const float* a_rows,
+                                                 const uint32_t* mask, int64_t d, const WorkerCtl* ctl,
+                                                 int32_t* cand_idx, float* cand_val, float* cand_prev,
+                                                 const uint32_t* ch_off, const uint32_t* ch_cnt,
+                                                 const uint32_t* tie_off, const uint32_t* prev_sel_off,
+                                                 const float* prev_val, int64_t k, uint32_t nc,
+                                                 uint32_t cap_total, uint32_t* s_wtot, uint32_t* s_ttot,
+                                                 uint32_t* s_mw, uint32_t* s_rk, int roots) {
+  const uint32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
+  const size_t tix = (size_t)n * nc + c;
+  if (ch_cnt[tix] == 0) return;
+  if (tid < kChunkWords) s_mw[tid] = mrow[(size_t)c * kChunkWords + tid];
+  __syncthreads();
+  if (tid < 64) {                                    // wave 0: running count of mask bits, two words per lane
+    const uint32_t c0 = (uint32_t)__popc(s_mw[2 * tid]), c1 = (uint32_t)__popc(s_mw[2 * tid + 1]);
+    uint32_t x = c0 + c1;
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t y = __shfl_up(x, o);
+      if (tid >= (uint32_t)o) x += y;
+    }
+    const uint32_t before = prev_sel_off[(size_t)n * (nc + 1) + c] + x - (c0 + c1);
+    s_rk[2 * tid] = before;
+    s_rk[2 * tid + 1] = before + c0;
+  }
+  __syncthreads();
+  const float* pv = prev_val + (size_t)n * k;
+  const uint32_t tau = ctl[n].f_tau, budget = ctl[n].f_budget;
+  const size_t row = (size_t)n * (size_t)d;
+  const int64_t base = (int64_t)c * kChunk + (int64_t)wv * 1024 + lane * 4;
+  float a[4][4];
+  uint32_t gtf = 0, tief = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int64_t j0 = base + i * 256;
+    if (VEC) {
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (j0 < d) v = *reinterpret_cast<const float4*>(a_rows + row + j0);
+      a[i][0] = v.x; a[i][1] = v.y; a[i][2] = v.z; a[i][3] = v.w;
+    } else {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) a[i][q] = (j0 + q < d) ? a_rows[row + j0 + q] : 0.f;
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if (j0 + q < d) {
+        const uint32_t key = prior_key(a[i][q], roots);
+        if (key > tau) gtf |= 1u << (i * 4 + q);
+        else if (key == tau) tief |= 1u << (i * 4 + q);
+      }
+    }
+  }
+  // rank of every tie within the chunk (index order) decides which ties are taken
+  const uint32_t tie_before = tie_off[tix];          // ties in lower chunks
+  ChunkPos tp = ordered_positions(tief, s_ttot);
+  uint32_t flags = gtf;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    uint32_t p = tie_before + tp.wave_base + tp.lane_base[i];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if ((tief >> (i * 4 + q)) & 1u) {
+        if (p < budget) flags |= 1u << (i * 4 + q);
+        ++p;
+      }
+    }
+  }
+  __syncthreads();
+  const ChunkPos cp = ordered_positions(flags, s_wtot);
+  const size_t out = (size_t)n * cap_total + ch_off[tix] + cp.wave_base;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    uint32_t p = cp.lane_base[i];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if ((flags >> (i * 4 + q)) & 1u) {
+        const int64_t j = base + i * 256 + q;
+        const uint32_t wl = (uint32_t)(j >> 5) & (kChunkWords - 1), bit = (uint32_t)j & 31u;
+        const uint32_t sent = (s_mw[wl] >> bit) & 1u;
+        float ab = 0.0f;
+        if (sent) {
+          const uint32_t rank = s_rk[wl] + (uint32_t)__popc(s_mw[wl] & ((1u << bit) - 1u));
+          if ((int64_t)rank < k) ab = pv[rank];
+        }
+        cand_idx[out + p] = (int32_t)((uint32_t)j | (sent ? kSentFlag : 0u));
+        cand_val[out + p] = a[i][q];
+        cand_prev[out + p] = ab;
+        ++p;
+      }
+    }
+  }
+  __syncthreads();
+}
+
+// The r-th flagged worker (ascending), found by the whole block: thread t
+// counts the flags of a contiguous range of workers, a block scan places the
+// ranges, the thread whose range holds rank r walks it.  Returns N if r is past
+// the last flagged worker; *n_flagged gets their number.  s_w [16], s_out [2].
+__device__ __forceinline__ uint32_t flagged_worker(const WorkerCtl* ctl, int32_t N, uint32_t r,
+                                                   uint32_t* n_flagged, uint32_t* s_w, uint32_t* s_out) {
+  const uint32_t tid = threadIdx.x;
+  const uint32_t per = ((uint32_t)N + kBlock - 1) / kBlock;
+  const uint32_t n0 = tid * per < (uint32_t)N ? tid * per : (uint32_t)N;
+  const uint32_t n1 = n0 + per < (uint32_t)N ? n0 + per : (uint32_t)N;
+  uint32_t mine = 0;
+  for (uint32_t n = n0; n < n1; ++n) mine += ctl[n].need_dense != 0;
+  if (tid == 0) s_out[0] = (uint32_t)N;
+  uint32_t total;
+  const uint32_t before = block_excl_scan<kBlock>(mine, s_w, &total);
+  if (r >= before && r < before + mine) {
+    uint32_t seen = before;
+    for (uint32_t n = n0; n < n1; ++n) {
+      if (ctl[n].need_dense != 0) {
+        if (seen == r) { s_out[0] = n; break; }
+        ++seen;
+      }
+    }
+  }
+  __syncthreads();
+  const uint32_t hit = s_out[0];
+  __syncthreads();
+  *n_flagged = total;
+  return hit;
+}
+
+// grid (G): G blocks resident together.  See the section header.
+template <bool VEC>
+__global__ void __launch_bounds__(kBlock)
+k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_off, int64_t d, WorkerCtl* ctl,
+            GlobalCtl* gctl, uint32_t* fhist, uint32_t* ch_gt, uint32_t* ch_tie, uint32_t* ch_off,
+            uint32_t* ch_cnt, uint32_t* tie_off, int32_t* cand_idx, float* cand_val, float* cand_prev,
+            uint32_t* cand_key,
+            const uint32_t* bnd_key, const float* prev_val, const float* gprev, int64_t k, uint32_t nc,
+            int32_t N, uint32_t cap_r, uint32_t cap_total, uint32_t regions, uint32_t bnd_cap,
+            const float* omega, float mu, int use_reg, float cand_target, ScoreKind sk) {
+  if (gctl->any_dense == 0) return;
+  const int roots = sk.roots;
+  __shared__ uint32_t s_hist[kL1Bins];
+  __shared__ uint32_t s_a[kBlock], s_b[kBlock];
+  __shared__ uint32_t s_w[16], s_out[2], s_x[4], s_y[4];
+  const uint32_t b = blockIdx.x, G = gridDim.x, tid = threadIdx.x;
+
+  for (int32_t n = 0; n < N; ++n) {
+    if (!ctl[n].need_dense) continue;
+    uint32_t* fh = fhist + (size_t)n * 3 * kL1Bins;
+    for (uint32_t i = b * kBlock + tid; i < 3 * kL1Bins; i += G * kBlock) fh[i] = 0;
+  }
+  grid_barrier(gctl, G);
+
+  // The histogram passes give every flagged worker its own group of blocks (all
+  // workers at once, each histogram fed by G / n_flagged blocks), so that the
+  // blocks' final adds do not all queue on the same few words.
+  uint32_t n_flagged;
+  (void)flagged_worker(ctl, N, 0xFFFFFFFFu, &n_flagged, s_w, s_out);
+  if (n_flagged == 0) return;                                   // every block sees the same flags
+  const uint32_t groups = n_flagged < G ? n_flagged : G;
+  const uint32_t grp = b % groups, sub = b / groups;
+  const uint32_t sub_cnt = (G - grp + groups - 1) / groups;     // blocks of this group
+  const uint32_t first_worker = flagged_worker(ctl, N, grp, &n_flagged, s_w, s_out);
+  for (uint32_t r = grp; r < n_flagged; r += groups) {
+    const uint32_t n = r == grp ? first_worker : flagged_worker(ctl, N, r, &n_flagged, s_w, s_out);
+    if (n < (uint32_t)N) dense_hist_worker<1, VEC>(n, sub, sub_cnt, a_rows, d, ctl, fhist, s_hist, roots);
+  }
+  grid_barrier(gctl, G);
+  for (int32_t n = b; n < N; n += G)
+    if (ctl[n].need_dense) dense_scan_worker<1>(n, ctl, fhist, k, d, s_a, s_b);
+  grid_barrier(gctl, G);
+  for (uint32_t r = grp; r < n_flagged; r += groups) {
+    const uint32_t n = r == grp ? first_worker : flagged_worker(ctl, N, r, &n_flagged, s_w, s_out);
+    if (n < (uint32_t)N) dense_hist_worker<2, VEC>(n, sub, sub_cnt, a_rows, d, ctl, fhist, s_hist, roots);
+  }
+  grid_barrier(gctl, G);
+  for (int32_t n = b; n < N; n += G)
+    if (ctl[n].need_dense) dense_scan_worker<2>(n, ctl, fhist, k, d, s_a, s_b);
+  grid_barrier(gctl, G);
+  for (uint32_t r = grp; r < n_flagged; r += groups) {
+    const uint32_t n = r == grp ? first_worker : flagged_worker(ctl, N, r, &n_flagged, s_w, s_out);
+    if (n < (uint32_t)N) dense_hist_worker<3, VEC>(n, sub, sub_cnt, a_rows, d, ctl, fhist, s_hist, roots);
+  }
+  grid_barrier(gctl, G);
+  for (int32_t n = b; n < N; n += G)
+    if (ctl[n].need_dense) dense_scan_worker<3>(n, ctl, fhist, k, d, s_a, s_b);
+  grid_barrier(gctl, G);
+
+  for (int32_t n = 0; n < N; ++n) {
+    if (!ctl[n].need_dense) continue;
+    for (uint32_t c = b; c < nc; c += G) dense_count_chunk<VEC>(n, c, a_rows, d, ctl, ch_gt, ch_tie, nc, s_x, s_y, roots);
+  }
+  grid_barrier(gctl, G);
+  for (int32_t n = b; n < N; n += G)
+    if (ctl[n].need_dense) chunk_scan_worker<true, kBlock>(n, ctl, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, nc, k, s_w);
+  grid_barrier(gctl, G);
+  for (int32_t n = 0; n < N; ++n) {
+    if (!ctl[n].need_dense) continue;
+    for (uint32_t c = b; c < nc; c += G)
+      dense_emit_chunk<VEC>(n, c, a_rows, mask, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, tie_off,
+                            prev_sel_off, prev_val, k, nc, cap_total, s_x, s_y, s_a, s_b, roots);
+  }
+  grid_barrier(gctl, G);
+
+  for (int32_t n = 0; n < N; ++n) {
+    if (!ctl[n].need_dense) continue;
+    const uint32_t total = ctl[n].dense_total;
+    const size_t cb = (size_t)n * cap_total;
+    const float w = omega[n];
+    for (uint32_t p = b * kBlock + tid; p < total; p += G * kBlock)
+      cand_key[cb + p] = score_entry((uint32_t)cand_idx[cb + p], cand_val[cb + p], cand_prev[cb + p], use_reg, gprev, w, mu, sk);
+  }
+  grid_barrier(gctl, G);
+  for (int32_t n = b; n < N; n += G)
+    if (ctl[n].need_dense)
+      select_worker<true, kBlock>(n, ctl, gctl, cand_key, bnd_key, k, cap_r, cap_total, regions, bnd_cap,
+                                  cand_target, 0, s_hist, nullptr, s_w, s_out);
+}
+
+}  // namespace rtk

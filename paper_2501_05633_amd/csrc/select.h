@@ -1,0 +1,501 @@
+// Exact k-th score per worker: rank search in histograms, relative radix select, the controller of the next round's bound (k_select), the sampled bound of rounds without history, and the chunk scan.
+#pragma once
+#include "score.h"
+
+namespace rtk {
+
+// -------------------------------------------------------------- k_select ----
+// One block of 1024 threads per worker.
+struct RankHit { uint32_t bin, above; };   // bin == kNoBound: rank not reached
+
+// Descending search in an LDS histogram: the bin b with
+//   count(bins > b) < want <= count(bins >= b);  above = count(bins > b).
+// nbins in {16, 512, 4096}.  All NT threads of the block call it.
+template <int NT>
+__device__ __forceinline__ RankHit find_rank_desc(const uint32_t* hist, uint32_t nbins, uint32_t want,
+                                                  uint32_t* s_w, uint32_t* s_out) {
+  const uint32_t tid = threadIdx.x;
+  const uint32_t per = nbins >= (uint32_t)NT ? nbins / NT : 1u;
+  constexpr uint32_t kMaxPer = 4096 / NT;
+  uint32_t loc[kMaxPer];
+  uint32_t s = 0;
+#pragma unroll
+  for (uint32_t q = 0; q < kMaxPer; ++q) {
+    const uint32_t i = tid * per + q;
+    loc[q] = (q < per && i < nbins) ? hist[nbins - 1 - i] : 0u;
+    s += loc[q];
+  }
+  if (tid == 0) { s_out[0] = kNoBound; s_out[1] = 0; }
+  uint32_t total;
+  const uint32_t above = block_excl_scan<NT>(s, s_w, &total);
+  if (above < want && want <= above + s) {
+    uint32_t run = above;
+#pragma unroll
+    for (uint32_t q = 0; q < kMaxPer; ++q) {
+      if (run < want && want <= run + loc[q]) { s_out[0] = nbins - 1 - (tid * per + q); s_out[1] = run; }
+      run += loc[q];
+    }
+  }
+  __syncthreads();
+  RankHit h{s_out[0], s_out[1]};
+  __syncthreads();
+  return h;
+}
+
+// Where the keys of a selection come from: the short boundary list (in LDS
+// when it fits, else in memory) or all candidate regions of the worker.
+struct KeySource {
+  const uint32_t* lds;      // non-null: count keys in LDS
+  const uint32_t* flat;     // non-null: count keys, contiguous in memory
+  const uint32_t* regions;  // else: candidate regions of cap_r slots each
+  uint32_t count, cap_r, n_regions;
+  const WorkerCtl* ctl;
+};
+
+// Calls f(key) for every key of the source; memory is read 128 bits at a time,
+// two loads in flight per thread.
+template <int NT, typename F>
+__device__ __forceinline__ void for_each_key(const KeySource& src, F f) {
+  const uint32_t tid = threadIdx.x;
+  if (src.lds) {
+    for (uint32_t i = tid; i < src.count; i += NT) f(src.lds[i]);
+    return;
+  }
+  const uint32_t nseg = src.flat ? 1u : src.n_regions;
+  for (uint32_t r = 0; r < nseg; ++r) {
+    const uint32_t lim = src.flat ? src.count : region_limit(*src.ctl, r, src.cap_r);
+    const uint32_t* base = src.flat ? src.flat : src.regions + (size_t)r * src.cap_r;
+    const uint4* b4 = reinterpret_cast<const uint4*>(base);
+    const uint32_t n4 = lim / 4;
+    uint32_t i = tid;
+    for (; i + NT < n4; i += 2 * NT) {
+      const uint4 x = b4[i], y = b4[i + NT];
+      f(x.x); f(x.y); f(x.z); f(x.w); f(y.x); f(y.y); f(y.z); f(y.w);
+    }
+    if (i < n4) { const uint4 x = b4[i]; f(x.x); f(x.y); f(x.z); f(x.w); }
+    if (tid < lim - n4 * 4) f(base[n4 * 4 + tid]);
+  }
+}
+
+// Exact `rank`-th largest key among the keys >= base of the source; at least
+// `rank` such keys must exist.  Three histogram levels over rel = key - base:
+// bits 24..13 (keys with rel >= 2^25 are counted apart; if the rank lies among
+// them the base moves up by 2^25 and the level is repeated), bits 12..4, bits
+// 3..0.  The fine first level spreads neighbouring scores over many bins, so
+// the LDS atomics rarely collide.  Returns tau; *budget = how many keys equal
+// to tau belong to the top `rank`; *ties = keys equal to tau.
+template <int NT>
+__device__ __forceinline__ uint32_t rel_select(KeySource src, uint32_t base, uint32_t rank,
+                                               uint32_t* s_hist, uint32_t* s_w, uint32_t* s_out,
+                                               uint32_t* s_stash, uint32_t stash_cap,
+                                               uint32_t* budget, uint32_t* ties) {
+  const uint32_t tid = threadIdx.x;
+  uint32_t want = rank;
+  RankHit ha{0u, 0u};
+  for (int guard = 0; guard < 64; ++guard) {
+    for (uint32_t i = tid; i < kL1Bins; i += NT) s_hist[i] = 0;
+    __syncthreads();
+    uint32_t over = 0;
+    for_each_key<NT>(src, [&](uint32_t key) {
+      if (key < base) return;
+      const uint32_t rel = key - base;
+      if (rel >> 25) ++over;
+      else atomicAdd(&s_hist[rel >> 13], 1u);
+    });
+    uint32_t n_over;
+    (void)block_excl_scan<NT>(over, s_w, &n_over);     // also orders the LDS atomics
+    if (want > n_over) {
+      want -= n_over;
+      ha = find_rank_desc<NT>(s_hist, kL1Bins, want, s_w, s_out);
+      break;
+    }
+    base += 1u << 25;                                   // the rank lies higher up
+    __syncthreads();
+  }
+  want -= ha.above;
+  const uint32_t pa = ha.bin;
+  // the keys of that bin are usually few: gather them in LDS once, so that the
+  // two finer levels need no further pass over memory
+  const uint32_t in_bin = s_hist[pa];
+  __syncthreads();
+  if (!src.lds && s_stash != nullptr && in_bin <= stash_cap) {
+    if (tid == 0) s_out[0] = 0;
+    __syncthreads();
+    for_each_key<NT>(src, [&](uint32_t key) {
+      if (key < base) return;
+      if (((key - base) >> 13) == pa) s_stash[atomicAdd(&s_out[0], 1u)] = key;
+    });
+    __syncthreads();
+    src.lds = s_stash;
+    src.count = in_bin;
+    __syncthreads();
+  }
+  for (uint32_t i = tid; i < 512; i += NT) s_hist[i] = 0;
+  __syncthreads();
+  for_each_key<NT>(src, [&](uint32_t key) {
+    if (key < base) return;
+    const uint32_t rel = key - base;
+    if ((rel >> 13) == pa) atomicAdd(&s_hist[(rel >> 4) & 511u], 1u);
+  });
+  __syncthreads();
+  const RankHit hb = find_rank_desc<NT>(s_hist, 512, want, s_w, s_out);
+  want -= hb.above;
+  const uint32_t pb = (pa << 9) | hb.bin;
+  if (tid < 16) s_hist[tid] = 0;
+  __syncthreads();
+  for_each_key<NT>(src, [&](uint32_t key) {
+    if (key < base) return;
+    const uint32_t rel = key - base;
+    if ((rel >> 4) == pb) atomicAdd(&s_hist[rel & 15u], 1u);
+  });
+  __syncthreads();
+  const RankHit hc = find_rank_desc<NT>(s_hist, 16, want, s_w, s_out);
+  *budget = want - hc.above;
+  *ties = s_hist[hc.bin];
+  return base + ((pb << 4) | hc.bin);
+}
+
+constexpr uint32_t kLdsKeys = 11264;    // boundary keys held in LDS (longer lists are read from memory)
+
+// SECOND = false: first invocation, all workers (validates the speculation).
+// SECOND = true : after the dense selection, flagged workers only.
+template <bool SECOND, int NT>
+__device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, GlobalCtl* gctl,
+                                              const uint32_t* cand_key,
+                                              const uint32_t* bnd_key, int64_t k,
+                                              uint32_t cap_r, uint32_t cap_total, uint32_t regions,
+                                              uint32_t bnd_cap, float cand_target, int force_dense,
+                                              uint32_t* s_hist, uint32_t* s_keys, uint32_t* s_w,
+                                              uint32_t* s_out) {
+  const uint32_t tid = threadIdx.x;
+  WorkerCtl& c = ctl[n];
+  if (SECOND && !c.need_dense) return;
+  const uint32_t K = (uint32_t)k;
+  uint32_t n_tot = 0;
+  if (!SECOND) {
+    for (uint32_t r = 0; r < regions; ++r) n_tot += region_limit(c, r, cap_r);
+    const bool need = force_dense || c.overflow || c.tau_lo == kNoBound || c.n_valid < K;
+    if (tid == 0) {
+      c.n_cand = n_tot;
+      c.need_dense = need ? 1u : 0u;
+      if (need) atomicOr(&gctl->any_dense, 1u);
+    }
+    if (need) return;
+  } else {
+    n_tot = c.dense_total;
+    if (tid == 0) c.n_cand = n_tot;
+  }
+  const uint32_t win_lo = c.win_lo, win_hi = c.win_hi;
+  const uint32_t n_hi = c.n_hi, n_bnd = c.n_bnd;
+  const bool window = !SECOND && win_lo != kNoBound && n_bnd <= bnd_cap && n_hi < K && K <= n_hi + n_bnd;
+
+  KeySource src;
+  src.ctl = &c; src.cap_r = cap_r; src.n_regions = regions;
+  src.lds = nullptr; src.flat = nullptr; src.regions = cand_key + (size_t)n * cap_total; src.count = n_tot;
+  uint32_t base, rank;
+  if (window) {
+    // the k-th score lies inside the window: select among the boundary list only
+    const uint32_t* list = bnd_key + (size_t)n * bnd_cap;
+    src.count = n_bnd;
+    if (s_keys != nullptr && n_bnd <= kLdsKeys) {
+      for (uint32_t i = tid; i < n_bnd; i += NT) s_keys[i] = list[i];
+      src.lds = s_keys;
+    } else {
+      src.flat = list;
+    }
+    base = win_lo;
+    rank = K - n_hi;
+  } else {
+    // all candidates; only scores >= the bound can hold the k-th (at least k do)
+    // (dense list: the 2k-th largest |a| when the list has 2k entries; a shorter
+    // list is the whole row, whose scores may all be damped)
+    base = SECOND ? (c.dense_total >= 2 * K ? c.f_tau : 0u) : c.tau_lo;
+    rank = K;
+  }
+  __syncthreads();
+  uint32_t budget, ties;
+  // (the key buffer in LDS is free for the gathering unless it holds the boundary list)
+  uint32_t* stash = (s_keys != nullptr && src.lds == nullptr) ? s_keys : nullptr;
+  const uint32_t tau = rel_select<NT>(src, base, rank, s_hist, s_w, s_out, stash, kLdsKeys, &budget, &ties);
+
+  if (tid == 0) {
+    c.tau = tau;
+    c.budget = budget;
+    c.n_gt = K - budget;
+    c.ties_total = ties;
+    c.used_window = window ? 1u : 0u;
+    // ---- bound and window of the next round
+    // density of scores per bit pattern just below / around tau
+    double dens;
+    if (window) dens = (double)n_bnd / (double)(win_hi - win_lo);
+    else dens = tau > base ? (double)(n_tot - K + 1) / (double)(tau - base) : 1.0;
+    if (dens < 1e-7) dens = 1e-7;
+    // After a failed speculation the history may say nothing about the next
+    // round.  The bound was too high (fewer than k valid candidates): the k-th
+    // score fell, which a drift never does - restart from this round's value.
+    // The bound was too low (overflow): a shock if the k-th score is more than
+    // twice what was expected; anything less can be the growth of the first
+    // rounds (the accumulated gradient of an unsent entry doubles from round 0
+    // to round 1, then grows by 3/2, 4/3, ...), an upward drift that was
+    // underestimated and that the extrapolation below keeps following.
+    bool shock = false;
+    if (SECOND && c.tau_lo != kNoBound) {
+      const uint32_t ref = c.centre != kNoBound ? c.centre : c.tau_prev;
+      if (!c.overflow) shock = true;
+      else if (ref != kNoBound && tau > ref && tau - ref > (1u << 23)) shock = true;
+    }
+    // the k-th score drifts from round to round: extrapolate linearly
+    int64_t drift = 0;
+    if (!shock && c.tau_prev != kNoBound) drift = (int64_t)tau - (int64_t)c.tau_prev;
+    if (drift > (1 << 22)) drift = 1 << 22;
+    if (drift < -(1 << 22)) drift = -(1 << 22);
+    int64_t centre = (int64_t)tau + drift;
+    if (centre < 0) centre = 0;
+    if (centre > 0x7F000000) centre = 0x7F000000;
+    // expected error of that prediction: how far this round's prediction was off
+    // if it was an extrapolation (two earlier rounds known), else half the drift
+    const uint32_t adrift = (uint32_t)(drift < 0 ? -drift : drift);
+    uint32_t err;
+    if (shock) err = kWinDefaultHalf;
+    else if (c.centre != kNoBound && c.extrapolated) err = tau > c.centre ? tau - c.centre : c.centre - tau;
+    else if (c.tau_prev != kNoBound) err = adrift / 2;
+    else err = kWinDefaultHalf;
+    if (!shock && (double)err < 0.7 * (double)c.err_prev) err = (uint32_t)(0.7 * (double)c.err_prev);
+    double half = 3.0 * (double)err + 1024.0;
+    const double by_count = 10000.0 / dens;                // at least about 20000 boundary entries
+    if (half < by_count) half = by_count;
+    const double cap_half = (double)bnd_cap / (4.0 * dens);
+    if (half > cap_half) half = cap_half;
+    if (half < (double)kWinMinHalf) half = (double)kWinMinHalf;
+    if (half > (double)kWinMaxHalf) half = (double)kWinMaxHalf;
+    const uint32_t h = (uint32_t)half;
+    // bound: below the (cautiously) predicted k-th score by a margin that aims at
+    // cand_target*k candidates and covers the prediction error.  An upward drift
+    // is only followed half way (it usually slows down; too low a bound merely
+    // costs candidates, too high a bound costs a dense selection).  After a
+    // failed speculation the margin grows if the bound was too high (fewer than
+    // k valid candidates) and shrinks if it was too low (overflow); it relaxes
+    // back afterwards.
+    float ms = c.margin_scale;
+    if (!(ms > 0.0f)) ms = 1.0f;
+    if (SECOND) {
+      if (c.overflow) ms = ms * 0.5f < 0.125f ? 0.125f : ms * 0.5f;
+      else if (c.tau_lo != kNoBound) ms = ms * 2.0f > 16.0f ? 16.0f : ms * 2.0f;
+    } else {
+      ms = ms > 1.0f ? 1.0f + (ms - 1.0f) * 0.7f : (ms * 1.3f > 1.0f ? 1.0f : ms * 1.3f);
+    }
+    c.margin_scale = ms;
+    double margin = ((double)cand_target - 1.0) * (double)K / dens;
+    if (margin < (double)err + 1024.0) margin = (double)err + 1024.0;
+    margin *= (double)ms;
+    if (margin > 16777216.0) margin = 16777216.0;
+    const int64_t anchor = drift > 0 ? (int64_t)tau + drift / 2 : centre;
+    int64_t lo = anchor - (int64_t)margin;
+    if (shock && c.dense_total >= 2 * K) {
+      // The dense selection's list is exactly the 2k entries of largest prior,
+      // ending at f_tau.  Whether the new level persists (the k-th score stays
+      // near tau) or the residuals of this round dominate the next one - after a
+      // single spike, or when the gradients have collapsed - so that its k-th
+      // score is this round's 2k-th, about f_tau: a bound half a list's spacing
+      // below f_tau holds about 2.5k candidates, inside the buffer, and at
+      // least k valid ones.
+      const double below = 0.5 * (double)(tau > c.f_tau ? tau - c.f_tau : 0u) * (double)(ms > 1.0f ? ms : 1.0f);
+      const int64_t lo2 = (int64_t)c.f_tau - (int64_t)(below < 16777216.0 ? below : 16777216.0) - 1024;
+      if (lo2 < lo) lo = lo2;
+    }
+    const bool speculate = (int64_t)n_tot >= (int64_t)((double)cand_target * (double)K) || !SECOND;
+    c.next_tau_lo = speculate ? (uint32_t)(lo > 0 ? lo : 0) : kNoBound;
+    c.next_win_lo = speculate ? (uint32_t)(centre > (int64_t)h ? centre - (int64_t)h : 0) : kNoBound;
+    c.next_win_hi = (uint32_t)centre + h;
+    c.tau_prev = tau;
+    c.centre = speculate ? (uint32_t)centre : kNoBound;
+    c.err_prev = err;
+    c.extrapolated = (speculate && drift != 0) ? 1u : 0u;
+  }
+}
+
+// grid (N), 1024 threads: the first selection of a round, for all workers.
+__global__ void __launch_bounds__(kScanBlock)
+k_select(WorkerCtl* ctl, GlobalCtl* gctl, const uint32_t* __restrict__ cand_key,
+         const uint32_t* __restrict__ bnd_key, int64_t k, uint32_t cap_r, uint32_t cap_total,
+         uint32_t regions, uint32_t bnd_cap, float cand_target, int force_dense) {
+  __shared__ uint32_t s_hist[kL1Bins];
+  __shared__ uint32_t s_keys[kLdsKeys];
+  __shared__ uint32_t s_w[16];
+  __shared__ uint32_t s_out[2];
+  select_worker<false, kScanBlock>(blockIdx.x, ctl, gctl, cand_key, bnd_key, k, cap_r, cap_total, regions,
+                                   bnd_cap, cand_target, force_dense, s_hist, s_keys, s_w, s_out);
+}
+
+// -------------------------------------------------------------- sampling ----
+// A round that starts without a bound from the previous one (round 0, after a
+// reset or set_state) gets one from a strided sample of a = eps + g: the level-1
+// histogram of the sample, from which k_sample_bound takes the bin edge above
+// which about 1.6k entries of the whole row are expected.  The bound is only a
+// guess - the selection verifies it like any other and falls back to the dense
+// selection if it was wrong.
+constexpr uint32_t kSampleMax = 1u << 18;     // sampled entries per worker (whole row if shorter)
+
+// grid (blocks, N).  Sample i is the group of 4 entries at 4*i*stride4.
+template <typename G>
+__global__ void __launch_bounds__(kBlock)
+k_sample_hist(const float* __restrict__ e, const G* __restrict__ g, const uint32_t* __restrict__ mask,
+              int64_t d, uint32_t nc, uint32_t* __restrict__ shist, uint32_t n_groups, uint32_t stride4,
+              int roots) {
+  __shared__ uint32_t s_hist[kL1Bins];
+  const uint32_t n = blockIdx.y, tid = threadIdx.x;
+  for (uint32_t i = tid; i < kL1Bins; i += kBlock) s_hist[i] = 0;
+  __syncthreads();
+  const size_t row = (size_t)n * (size_t)d;
+  const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
+  const bool vec = (d % 4 == 0) && (reinterpret_cast<uintptr_t>(g) % (4 * sizeof(G)) == 0);
+  for (uint32_t i = blockIdx.x * kBlock + tid; i < n_groups; i += gridDim.x * kBlock) {
+    const int64_t j0 = (int64_t)i * stride4 * 4;
+    if (vec && j0 + 4 <= d) {                           // one 128-bit load of the state, one of the gradients
+      const uint32_t mb = (mrow[j0 >> 5] >> (j0 & 31)) & 15u;
+      f32x4 ev = *reinterpret_cast<const f32x4*>(e + row + j0);
+      const f32x4 gv = grad4_at(g, row + j0);
+      if (mb & 1u) ev.x = 0.f;
+      if (mb & 2u) ev.y = 0.f;
+      if (mb & 4u) ev.z = 0.f;
+      if (mb & 8u) ev.w = 0.f;
+      const f32x4 a4 = ev + gv;
+      atomicAdd(&s_hist[prior_key(a4.x, roots) >> kL1Shift], 1u);
+      atomicAdd(&s_hist[prior_key(a4.y, roots) >> kL1Shift], 1u);
+      atomicAdd(&s_hist[prior_key(a4.z, roots) >> kL1Shift], 1u);
+      atomicAdd(&s_hist[prior_key(a4.w, roots) >> kL1Shift], 1u);
+      continue;
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int64_t j = j0 + q;
+      if (j < d) {
+        const uint32_t sent = (mrow[j >> 5] >> (j & 31)) & 1u;
+        const float a = (sent ? 0.0f : e[row + j]) + grad_at(g, row + j);
+        atomicAdd(&s_hist[prior_key(a, roots) >> kL1Shift], 1u);
+      }
+    }
+  }
+  __syncthreads();
+  uint32_t* gh = shist + (size_t)n * 3 * kL1Bins;
+  for (uint32_t i = tid; i < kL1Bins; i += kBlock) {
+    const uint32_t v = s_hist[i];
+    if (v) atomicAdd(&gh[i], v);
+  }
+}
+
+// grid (N), 1024 threads.  Sets this round's bound from the sample histogram.
+__global__ void __launch_bounds__(kScanBlock)
+k_sample_bound(WorkerCtl* ctl, const uint32_t* __restrict__ shist, int64_t d, int64_t k,
+               uint32_t n_sampled, int roots) {
+  __shared__ uint32_t s_hist[kL1Bins];
+  __shared__ uint32_t s_w[16];
+  __shared__ uint32_t s_out[2];
+  const uint32_t n = blockIdx.x, tid = threadIdx.x;
+  const uint32_t* gh = shist + (size_t)n * 3 * kL1Bins;
+  for (uint32_t i = tid; i < kL1Bins; i += kScanBlock) s_hist[i] = gh[i];
+  __syncthreads();
+  // sample rank that corresponds to about 1.6k entries of the row, plus four
+  // standard deviations of the sampling noise
+  const double frac = (double)n_sampled / (double)d;
+  double want = 1.6 * (double)k * frac;
+  want += 4.0 * sqrt(want) + 1.0;
+  const RankHit h = want < (double)n_sampled ? find_rank_desc<kScanBlock>(s_hist, kL1Bins, (uint32_t)want, s_w, s_out)
+                                            : RankHit{kNoBound, 0u};
+  if (tid == 0 && h.bin != kNoBound && h.bin > 0) {
+    ctl[n].tau_lo = h.bin << kL1Shift;
+    ctl[n].tau_lo_mag = magnitude_bound(h.bin << kL1Shift, roots);
+    ctl[n].win_lo = kNoBound;
+  }
+}
+
+// ---------------------------------------------------------- k_chunk_scan ----
+// One block of NT threads per worker.  Exclusive scans over the chunks of one worker:
+//   tie_off[c] = ties before chunk c;
+//   sel[c]     = gt[c] + clamp(budget - tie_off[c], 0, tie[c])   (lowest-index ties first);
+//   sel_off[c] = selected entries before chunk c  (nc+1 values).
+// DENSE: budget = f_budget, sel_off/sel go to ch_off/ch_cnt (placement of the
+// dense emission) and dense_total.  Otherwise budget = ctl.budget, sel_off goes
+// to the round's sel_off table and the total is checked against k.  tie_off is
+// written in both cases.
+// (No __restrict__ here and in select_worker: inside k_dense_all these arrays
+// are written by other blocks in the phase before.)
+template <bool DENSE, int NT>
+__device__ __forceinline__ void chunk_scan_worker(uint32_t n, WorkerCtl* ctl, const uint32_t* ch_gt,
+                                                  const uint32_t* ch_tie, uint32_t* out_off,
+                                                  uint32_t* out_cnt, uint32_t* out_tieoff, uint32_t nc,
+                                                  int64_t k, uint32_t* s_w /*[>= 2 * NT / 64]*/) {
+  constexpr uint32_t W = NT / 64;
+  const uint32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  WorkerCtl& c = ctl[n];
+  const uint32_t budget = DENSE ? c.f_budget : c.budget;
+  const uint32_t* gt = ch_gt + (size_t)n * nc;
+  const uint32_t* tie = ch_tie + (size_t)n * nc;
+  uint32_t* off = out_off + (size_t)n * (DENSE ? nc : nc + 1);
+  uint32_t* cnt = DENSE ? out_cnt + (size_t)n * nc : nullptr;
+  uint32_t* tof = out_tieoff + (size_t)n * nc;
+  // The ties taken before chunk c number min(budget, ties before c), so the two
+  // running sums of gt and tie give everything.  Every wave owns a contiguous
+  // run of 64-chunk tiles (coalesced loads): first its totals, then, after the
+  // waves' totals are placed, the running sums and the outputs.
+  const uint32_t tiles = (nc + 63) / 64;
+  const uint32_t per = (tiles + W - 1) / W;
+  const uint32_t t0 = wv * per < tiles ? wv * per : tiles;
+  const uint32_t t1 = t0 + per < tiles ? t0 + per : tiles;
+  uint32_t gsum = 0, tsum = 0;
+#pragma unroll 8
+  for (uint32_t t = t0; t < t1; ++t) {
+    const uint32_t ci = t * 64 + lane;
+    if (ci < nc) { gsum += gt[ci]; tsum += tie[ci]; }
+  }
+  for (int o = 32; o > 0; o >>= 1) { gsum += __shfl_down(gsum, o); tsum += __shfl_down(tsum, o); }
+  if (lane == 0) { s_w[wv] = gsum; s_w[W + wv] = tsum; }
+  __syncthreads();
+  uint32_t grun = 0, trun = 0, gtot = 0, ttot = 0;
+  for (uint32_t i = 0; i < W; ++i) {
+    const uint32_t g = s_w[i], t = s_w[W + i];
+    if (i < wv) { grun += g; trun += t; }
+    gtot += g; ttot += t;
+  }
+  __syncthreads();
+#pragma unroll 4
+  for (uint32_t t = t0; t < t1; ++t) {
+    const uint32_t ci = t * 64 + lane;
+    const uint32_t g = ci < nc ? gt[ci] : 0u, ti = ci < nc ? tie[ci] : 0u;
+    uint32_t gx = g, tx = ti;                            // inclusive running sums inside the tile
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t gy = __shfl_up(gx, o), ty = __shfl_up(tx, o);
+      if (lane >= (uint32_t)o) { gx += gy; tx += ty; }
+    }
+    const uint32_t g_before = grun + gx - g, t_before = trun + tx - ti;
+    if (ci < nc) {
+      const uint32_t taken_before = t_before < budget ? t_before : budget;
+      uint32_t take = 0;
+      if (t_before < budget) { take = budget - t_before; if (take > ti) take = ti; }
+      off[ci] = g_before + taken_before;
+      tof[ci] = t_before;
+      if (DENSE) cnt[ci] = g + take;
+    }
+    grun += __shfl(gx, 63);
+    trun += __shfl(tx, 63);
+  }
+  if (tid == 0) {
+    const uint32_t sel_run = gtot + (ttot < budget ? ttot : budget);
+    if (DENSE) c.dense_total = sel_run;
+    else {
+      off[nc] = sel_run;
+      if ((int64_t)sel_run != k) c.err |= 1u;
+    }
+  }
+}
+
+
+// grid (N), 1024 threads: the scan of the final compaction.
+__global__ void __launch_bounds__(kScanBlock)
+k_chunk_scan(WorkerCtl* ctl, const uint32_t* __restrict__ ch_gt, const uint32_t* __restrict__ ch_tie,
+             uint32_t* __restrict__ sel_off, uint32_t* __restrict__ tie_off, uint32_t nc, int64_t k) {
+  __shared__ uint32_t s_w[2 * kScanBlock / 64];
+  chunk_scan_worker<false, kScanBlock>(blockIdx.x, ctl, ch_gt, ch_tie, sel_off, nullptr, tie_off, nc, k, s_w);
+}
+
+}  // namespace rtk

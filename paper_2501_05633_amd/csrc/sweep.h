@@ -1,0 +1,209 @@
+// The dense sweep: per-round reset, ordered positions of flagged entries inside a chunk, and k_accum_emit.
+#pragma once
+#include "common.h"
+
+namespace rtk {
+
+// ---------------------------------------------------------------- k_begin ----
+__global__ void __launch_bounds__(kBlock)
+k_begin(WorkerCtl* ctl, GlobalCtl* gctl, int force_dense, int roots) {
+  const uint32_t n = blockIdx.x, tid = threadIdx.x;
+  if (n == 0 && tid == 0) gctl->any_dense = 0;
+  WorkerCtl& c = ctl[n];
+  if (tid < kMaxRegions) c.cursor[tid] = 0;
+  if (tid == 0) {
+    c.tau_lo = force_dense ? kNoBound : c.next_tau_lo;
+    c.tau_lo_mag = magnitude_bound(c.tau_lo, roots);
+    c.win_lo = force_dense ? kNoBound : c.next_win_lo;
+    c.win_hi = c.next_win_hi;
+    c.overflow = 0; c.need_dense = 0; c.n_cand = 0; c.n_valid = 0; c.n_hi = 0; c.n_bnd = 0;
+    c.dense_total = 0; c.used_window = 0;
+    c.tau = 0; c.n_gt = 0; c.budget = 0; c.ties_total = 0;
+    c.f_prefix = 0; c.f_krem = 0; c.f_tau = 0; c.f_budget = 0;
+  }
+}
+
+// ----------------------------------------------------- chunk in registers ----
+// A block of 256 threads holds one chunk of 4096 entries: wave v covers entries
+// [v*1024, v*1024+1024) of the chunk, iteration i the 256 entries after i*256,
+// lane l the four entries at l*4.  flags bit (i*4+c) marks entry (i, l, c).
+// ordered_positions gives every flagged entry its rank in ascending index order
+// within the block and returns the block's total.
+struct ChunkPos {
+  uint32_t lane_base[4];   // rank of the lane's first flagged entry of iteration i within the wave
+  uint32_t wave_base;      // flagged entries in lower waves
+  uint32_t total;          // flagged entries in the block
+};
+
+__device__ __forceinline__ ChunkPos ordered_positions(uint32_t flags, uint32_t* s_wtot /*[4]*/) {
+  const uint32_t tid = threadIdx.x, wv = tid >> 6;
+  ChunkPos cp;
+  uint32_t run = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    uint32_t below = 0, tot = 0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint64_t b = __ballot((flags >> (i * 4 + c)) & 1u);
+      below += lanes_below(b);
+      tot += (uint32_t)__popcll(b);
+    }
+    cp.lane_base[i] = run + below;
+    run += tot;
+  }
+  if ((tid & 63) == 0) s_wtot[wv] = run;
+  __syncthreads();
+  uint32_t wb = 0, total = 0;
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const uint32_t x = s_wtot[v];
+    if (v < (int)wv) wb += x;
+    total += x;
+  }
+  cp.wave_base = wb;
+  cp.total = total;
+  return cp;
+}
+
+// ---------------------------------------------------------- k_accum_emit ----
+// grid (nc, N).  VEC: d % 4 == 0 and 16-byte aligned rows.  The sweep touches
+// every byte exactly once, so it loads and stores with the non-temporal hint.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// Local gradients arrive as binary32 or as bfloat16 (the upper half of a
+// binary32 pattern: widening is exact, the arithmetic stays binary32).
+struct bf16_t { uint16_t bits; };
+__device__ __forceinline__ float grad_at(const float* g, size_t i) { return g[i]; }
+__device__ __forceinline__ float grad_at(const bf16_t* g, size_t i) {
+  return __uint_as_float((uint32_t)g[i].bits << 16);
+}
+// four consecutive gradients from an address aligned to the four of them
+__device__ __forceinline__ f32x4 grad4_at(const float* g, size_t i) {
+  return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(g + i));
+}
+__device__ __forceinline__ f32x4 grad4_at(const bf16_t* g, size_t i) {
+  const u32x2 w = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(g + i));
+  f32x4 r;
+  r.x = __uint_as_float(w.x << 16);
+  r.y = __uint_as_float(w.x & 0xFFFF0000u);
+  r.z = __uint_as_float(w.y << 16);
+  r.w = __uint_as_float(w.y & 0xFFFF0000u);
+  return r;
+}
+
+template <bool VEC, typename G>
+__global__ void __launch_bounds__(kBlock)
+k_accum_emit(float* __restrict__ e, const G* __restrict__ g, const uint32_t* __restrict__ mask,
+             const uint32_t* __restrict__ prev_sel_off, int64_t d, WorkerCtl* __restrict__ ctl,
+             int32_t* __restrict__ cand_idx,
+             float* __restrict__ cand_val, float* __restrict__ cand_prev, uint32_t* __restrict__ ch_off,
+             uint32_t* __restrict__ ch_cnt, uint32_t nc, uint32_t cap_r, uint32_t cap_total,
+             uint32_t regions) {
+  __shared__ uint32_t s_wtot[4];
+  __shared__ uint32_t s_base;
+  const uint32_t c = blockIdx.x, n = blockIdx.y;
+  const uint32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const size_t row = (size_t)n * (size_t)d;
+  const uint32_t tau_lo = ctl[n].tau_lo_mag;        // bound on |a|: the sweep never evaluates the prior
+  const int64_t base = (int64_t)c * kChunk + (int64_t)wv * 1024 + lane * 4;
+  float a[4][4];
+  float eo[4][4];       // what the state held: a^{t-1} where the entry was sent, the error elsewhere
+  uint32_t flags = 0;
+  // previous round's mask: the 4 bits of entries j0..j0+3 lie in one word
+  // (chunks from which nothing was sent have no mask bits: their words are not read)
+  const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
+  const bool sent_any = prev_sel_off[(size_t)n * (nc + 1) + c + 1] != prev_sel_off[(size_t)n * (nc + 1) + c];
+  uint32_t mb[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int64_t j0 = base + i * 256;
+    mb[i] = (sent_any && j0 < d) ? (mrow[j0 >> 5] >> (j0 & 31)) & 15u : 0u;
+  }
+  if (VEC) {
+    f32x4 ev[4], gv[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int64_t j0 = base + i * 256;
+      if (j0 < d) {
+        ev[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(e + row + j0));
+        gv[i] = grad4_at(g, row + j0);
+      } else {
+        ev[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        gv[i] = ev[i];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int64_t j0 = base + i * 256;
+      eo[i][0] = ev[i].x; eo[i][1] = ev[i].y; eo[i][2] = ev[i].z; eo[i][3] = ev[i].w;
+      f32x4 z4 = ev[i];
+      if (mb[i]) {                          // sent last round: the error restarts from zero
+        if (mb[i] & 1u) z4.x = 0.f;
+        if (mb[i] & 2u) z4.y = 0.f;
+        if (mb[i] & 4u) z4.z = 0.f;
+        if (mb[i] & 8u) z4.w = 0.f;
+      }
+      const f32x4 s4 = z4 + gv[i];
+      a[i][0] = s4.x; a[i][1] = s4.y; a[i][2] = s4.z; a[i][3] = s4.w;
+      if (j0 < d) {
+        __builtin_nontemporal_store(s4, reinterpret_cast<f32x4*>(e + row + j0));
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (key_of(a[i][q]) >= tau_lo) flags |= 1u << (i * 4 + q);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int64_t j = base + i * 256 + q;
+        a[i][q] = 0.f;
+        eo[i][q] = 0.f;
+        if (j < d) {
+          eo[i][q] = e[row + j];
+          const float eps = ((mb[i] >> q) & 1u) ? 0.f : eo[i][q];
+          a[i][q] = eps + grad_at(g, row + j);
+          e[row + j] = a[i][q];
+          if (key_of(a[i][q]) >= tau_lo) flags |= 1u << (i * 4 + q);
+        }
+      }
+    }
+  }
+  const ChunkPos cp = ordered_positions(flags, s_wtot);
+  const size_t tix = (size_t)n * nc + c;
+  if (cp.total == 0) {
+    if (tid == 0) { ch_off[tix] = 0; ch_cnt[tix] = 0; }
+    return;
+  }
+  if (tid == 0) {
+    const uint32_t r = c % regions;
+    const uint32_t off = atomicAdd(&ctl[n].cursor[r], cp.total);
+    uint32_t b = kNoBound;
+    if (off + cp.total <= cap_r) b = r * cap_r + off;
+    else ctl[n].overflow = 1;
+    s_base = b;
+    ch_off[tix] = (b == kNoBound) ? 0 : b;
+    ch_cnt[tix] = (b == kNoBound) ? 0 : cp.total;
+  }
+  __syncthreads();
+  const uint32_t b = s_base;
+  if (b == kNoBound || flags == 0) return;
+  const size_t out = (size_t)n * cap_total + b + cp.wave_base;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    uint32_t p = cp.lane_base[i];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if ((flags >> (i * 4 + q)) & 1u) {
+        cand_idx[out + p] = (int32_t)((uint32_t)(base + i * 256 + q) | (((mb[i] >> q) & 1u) ? kSentFlag : 0u));
+        cand_val[out + p] = a[i][q];
+        cand_prev[out + p] = eo[i][q];
+        ++p;
+      }
+    }
+  }
+}
+
+}  // namespace rtk
