@@ -328,3 +328,22 @@ def test_global_topk_on_cancelling_workers_and_ties():
         res_c = o.step_global(gg.cpu().numpy())
         _compare_exact(res_g, res_c, "ties round %d" % t)
     r.close()
+
+
+def test_first_row_of_the_papers_table_on_the_gpu():
+    # appendix table of accumulated gradients, iteration 1 (N = 2, J = 4, k = 3): the printed sparsified
+    # gradients and their average, for Top-k and RegTop-k alike
+    print("case table1", flush=True)
+    gold = _read_gold("table1_iteration1.txt")
+    target, s1, s2 = (np.array(gold[key]) for key in ("target", "sent1", "sent2"))
+    g = np.stack([s1, s2])
+    g[0, 2] = 2 * target[2] - s2[2]
+    g[1, 3] = 2 * target[3] - s1[3]
+    gt = torch.from_numpy(g.astype(f32)).to(DEV)
+    for mu in (0.0, 1.0):
+        r = binding.RegTopk(2, 4, 3, mu, device=DEV)
+        idx, val, agg = r.step(gt, None)
+        assert idx.cpu().tolist() == [[0, 1, 3], [0, 1, 2]]
+        np.testing.assert_allclose(val.cpu().numpy(), [[s1[0], s1[1], s1[3]], [s2[0], s2[1], s2[2]]], rtol=1e-6)
+        np.testing.assert_allclose(agg.cpu().numpy(), (s1 + s2) / 2, rtol=1e-6)
+        r.close()

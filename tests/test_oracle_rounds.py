@@ -225,6 +225,34 @@ def test_toy_example_closed_loop_stall():
     assert risk_reg < 0.5 * r0
 
 
+def _table1_gradients():
+    gold = _read_gold("table1_iteration1.txt")
+    target, s1, s2 = (np.array(gold[key]) for key in ("target", "sent1", "sent2"))
+    g = np.stack([s1, s2])
+    g[0, 2] = 2 * target[2] - s2[2]          # the dropped entries follow from the aggregation target
+    g[1, 3] = 2 * target[3] - s1[3]
+    return gold, target, s1, s2, g
+
+
+def test_first_row_of_the_papers_table_of_accumulated_gradients():
+    # The printed numbers are consistent with Top_3 per worker and averaging with omega = 1/2,
+    # and RegTop-k equals Top-k in the first iteration; the oracle reproduces the printed row.
+    gold, target, s1, s2, g = _table1_gradients()
+    np.testing.assert_allclose(g.mean(axis=0), target, atol=0.01)       # entries are printed with two decimals (rounded or cut)
+    assert abs(g[0, 2]) < np.abs(s1[[0, 1, 3]]).min() and abs(g[1, 3]) < np.abs(s2[[0, 1, 2]]).min()
+    for mu in (0.0, 1.0):
+        o = oracle.Oracle(2, 4, 3, mu)
+        idx, val, agg = o.step(g.astype(f32), None)
+        assert idx.tolist() == [[0, 1, 3], [0, 1, 2]]
+        ghat = np.zeros((2, 4))
+        for n in range(2):
+            ghat[n, idx[n]] = val[n]
+        np.testing.assert_allclose(ghat[0], s1, atol=1e-6)
+        np.testing.assert_allclose(ghat[1], s2, atol=1e-6)
+        np.testing.assert_allclose(agg, (s1 + s2) / 2, rtol=1e-6)
+        np.testing.assert_allclose(o.e, [[0, 0, g[0, 2], 0], [0, 0, 0, g[1, 3]]], rtol=1e-6)
+
+
 def test_power_of_two_scaling_and_sign_flip_keep_the_masks():
     rounds = _tiny_rounds(T=5)
     base = _run(oracle.Oracle(4, 2000, 20, 1.0), rounds)
