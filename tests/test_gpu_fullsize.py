@@ -79,3 +79,45 @@ def test_full_size_global_topk_rounds():
         assert np.array_equal(val.cpu().numpy().view(np.uint32), vc.view(np.uint32))
         np.testing.assert_allclose(agg.cpu().numpy(), ac, rtol=1e-6, atol=0)
     r.close()
+
+
+def test_maximum_row_length():
+    # d = 2^31 - 1, the largest the interface admits (indices are int32): one worker, two rounds.
+    # The CPU oracle would need tens of GB and minutes here, so the rounds are checked against what
+    # the definitions fix at any size: round 0 is plain Top-k; with a single worker every sent
+    # entry is a sole sender (distortion 0), so in round 1 its score is |a| * tanh(1/mu) and every
+    # other score is |a| -- the expected index sets follow from a library top-k over those scores.
+    from paper_2501_05633_amd import binding
+    d, k, mu = 2 ** 31 - 1, 4096 + 17, 1.0
+    print("case maximum row length d=%d" % d, flush=True)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(7)
+    r = binding.RegTopk(1, d, k, mu, device=DEV)
+    g0 = torch.randn(1, d, generator=gen, device=DEV)
+    idx0, val0, agg0 = r.step(g0, None)
+    torch.cuda.synchronize()
+    want0 = torch.topk(g0[0].abs(), k).indices.sort().values
+    assert torch.equal(idx0[0].long(), want0)
+    assert torch.equal(val0[0], g0[0][want0])
+    assert int(torch.count_nonzero(agg0)) == k and torch.equal(agg0[want0], val0[0])      # omega = 1
+    idx0 = idx0[0].long().clone()
+    agg0 = agg0.clone()
+    print("  round 0 ok", flush=True)
+    g1 = torch.randn(1, d, generator=gen, device=DEV)
+    idx1, val1, agg1 = r.step(g1, agg0)
+    torch.cuda.synchronize()
+    a = g0[0] + g1[0]                        # eps + g: eps = g0 off the first mask ...
+    a[idx0] = g1[0][idx0]                    # ... and 0 on it
+    del g0
+    score = a.abs()
+    f = torch.tensor(float(np.float32(np.tanh(1.0 / mu))), device=DEV)
+    score[idx0] = score[idx0] * f
+    want1 = torch.topk(score, k).indices.sort().values
+    assert torch.equal(idx1[0].long(), want1)
+    assert torch.equal(val1[0], a[want1])
+    assert int(torch.count_nonzero(agg1)) == k and torch.equal(agg1[want1], val1[0])
+    e, pidx, pval, t = r.get_state()
+    assert t == 2 and torch.equal(pidx[0].long(), want1)
+    a[want1] = 0.0
+    assert torch.equal(e[0], a)              # residual: a off the mask, 0 on it
+    r.close()
