@@ -81,7 +81,8 @@ Layout make_layout(int32_t N, int64_t d, int64_t k) {
   L.tie_off = take(nch * 4);
   for (int b = 0; b < 2; ++b) { L.sel_off[b] = take(((size_t)N * (L.nc + 1)) * 4); L.agg_hot[b] = take((size_t)L.nc * 4); }
   L.mask = take(nch * kChunkWords * 4);
-  L.bnd_cap = 262144;
+  // the boundary list never holds more than the candidate list does
+  L.bnd_cap = L.cap_total < 262144u ? L.cap_total : 262144u;
   L.bnd_key = take((size_t)N * L.bnd_cap * 4);
   L.fhist = take((size_t)N * 3 * kL1Bins * 4);
   L.ctl = take((size_t)N * sizeof(WorkerCtl));

@@ -231,6 +231,21 @@ def test_more_than_32_workers_and_odd_sizes():
     assert tol == 0
 
 
+def test_maximum_number_of_workers():
+    # N = 65535, the most the interface admits (grid dimension), on very short rows
+    N, d, k = 65535, 8, 2
+    print("case N=65535", flush=True)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(5)
+    shared = torch.randn(d, generator=gen, device=DEV)
+
+    def fn(t, agg):
+        return (shared + torch.randn(N, d, generator=gen, device=DEV)).contiguous()
+
+    stats, tol = run_both(N, d, k, 1.0, fn, 3, label="N=65535", check_overlap=True)
+    assert tol == 0
+
+
 def test_windowed_selection_with_many_ties_at_the_threshold():
     # Values on a coarse grid that hardly change from round to round: the k-th
     # score is predictable (windowed selection) and massively tied.
