@@ -5,45 +5,59 @@
 namespace rtk {
 
 // --------------------------------------------------------- k_chunk_count ----
-// grid (ceil(nc/4), N): one wave per chunk.  Candidates of the chunk with
-// score > tau and == tau.  Most chunks are empty and a few hold hundreds of
-// candidates, so a lane takes eight at a time with all loads in flight together.
+// Counting and compaction walk the candidate list chunk by chunk.  Most chunks
+// are empty and a few hold hundreds of candidates, and what bounds these
+// kernels is the number of waves that must each wait for two or three memory
+// round trips: so a wave takes four chunks at once, sixteen lanes each
+// (kChunksPerBlock chunks per block), and a lane takes eight candidates at a
+// time with all its loads in flight together.
 constexpr int kLaneBatch = 8;
+constexpr uint32_t kLanesPerChunk = 16;
+constexpr uint32_t kChunksPerWave = 64 / kLanesPerChunk;
+constexpr uint32_t kChunksPerBlock = (kBlock / 64) * kChunksPerWave;
+
+// grid (ceil(nc/kChunksPerBlock), N).  Candidates of the chunk with score > tau and == tau.
 __global__ void __launch_bounds__(kBlock)
 k_chunk_count(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ cand_key,
               const uint32_t* __restrict__ ch_off, const uint32_t* __restrict__ ch_cnt,
               uint32_t* __restrict__ ch_gt, uint32_t* __restrict__ ch_tie, uint32_t nc,
               uint32_t cap_total) {
-  const uint32_t n = blockIdx.y, lane = threadIdx.x & 63;
-  const uint32_t c = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (c >= nc) return;
-  const size_t tix = (size_t)n * nc + c;
+  const uint32_t n = blockIdx.y, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const uint32_t grp = lane / kLanesPerChunk, gl = lane % kLanesPerChunk;
+  const uint32_t c = (blockIdx.x * (kBlock / 64) + wv) * kChunksPerWave + grp;
+  const bool live = c < nc;
+  const size_t tix = (size_t)n * nc + (live ? c : 0);
   const uint32_t tau = ctl[n].tau;
-  const uint32_t off = ch_off[tix], cnt = ch_cnt[tix];
+  const uint32_t off = live ? ch_off[tix] : 0u, cnt = live ? ch_cnt[tix] : 0u;
   const uint32_t* key = cand_key + (size_t)n * cap_total + off;
   uint32_t gt = 0, tie = 0;
-  for (uint32_t p0 = 0; p0 < cnt; p0 += 64 * kLaneBatch) {
+  for (uint32_t p0 = 0; p0 < cnt; p0 += kLanesPerChunk * kLaneBatch) {   // trip count uniform within a group of lanes
     uint32_t kk[kLaneBatch];
 #pragma unroll
     for (int q = 0; q < kLaneBatch; ++q) {
-      const uint32_t p = p0 + q * 64 + lane;
+      const uint32_t p = p0 + q * kLanesPerChunk + gl;
       kk[q] = p < cnt ? key[p] : 0u;
     }
 #pragma unroll
     for (int q = 0; q < kLaneBatch; ++q) {
-      const bool in = p0 + q * 64 + lane < cnt;
+      const bool in = p0 + q * kLanesPerChunk + gl < cnt;
       gt += in && kk[q] > tau;
       tie += in && kk[q] == tau;
     }
   }
-  for (int o = 32; o > 0; o >>= 1) { gt += __shfl_down(gt, o); tie += __shfl_down(tie, o); }
-  if (lane == 0) { ch_gt[tix] = gt; ch_tie[tix] = tie; }
+  for (uint32_t o = kLanesPerChunk / 2; o > 0; o >>= 1) { gt += __shfl_xor(gt, o); tie += __shfl_xor(tie, o); }
+  if (live && gl == 0) { ch_gt[tix] = gt; ch_tie[tix] = tie; }
 }
 
 // ------------------------------------------------------------- k_compact ----
-// grid (ceil(nc/4), N): one wave per chunk.  Writes the selected pairs of the
-// chunk in index order at sel_off[c], and the chunk's words of the round's mask
-// (bit = entry selected).
+// grid (ceil(nc/(4 * 64 / LPC)), N), LPC lanes per chunk.  Writes the selected
+// pairs of the chunk in index order at sel_off[c], and the chunk's words of the
+// round's mask (bit = entry selected).  The ordered placement is a chain of
+// ballots over the chunk's candidates, so here the full chunks want more lanes
+// than the counting does.
+constexpr uint32_t kCompactLanes = 32;
+
+template <uint32_t LPC>
 __global__ void __launch_bounds__(kBlock)
 k_compact(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ cand_key,
           const int32_t* __restrict__ cand_idx, const float* __restrict__ cand_val,
@@ -52,68 +66,81 @@ k_compact(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ cand_k
           const uint32_t* __restrict__ tie_off, int32_t* __restrict__ out_idx,
           float* __restrict__ out_val, uint32_t* __restrict__ mask,
           int64_t k, uint32_t nc, uint32_t cap_total) {
-  __shared__ uint32_t s_m[4][kChunkWords];
+  constexpr uint32_t kCPW = 64 / LPC, kCPB = (kBlock / 64) * kCPW;
+  __shared__ uint32_t s_m[kCPB][kChunkWords];
+  constexpr uint32_t kWordsPerLane = kChunkWords / LPC;
   const uint32_t n = blockIdx.y, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const uint32_t c = blockIdx.x * 4 + wv;
+  const uint32_t grp = lane / LPC, gl = lane % LPC;
+  const uint32_t slot = wv * kCPW + grp;                       // this group's chunk inside the block
+  const uint32_t c = blockIdx.x * kCPB + slot;
   const bool live = c < nc;
-  s_m[wv][lane] = 0;
-  s_m[wv][lane + 64] = 0;
+#pragma unroll
+  for (uint32_t i = 0; i < kWordsPerLane; ++i) s_m[slot][gl * kWordsPerLane + i] = 0;
   __syncthreads();
-  uint32_t first = 0;
+  uint32_t first = 0, cnt = 0, off = 0, tie_run = 0;
   bool was_empty = true, is_empty = true;
   if (live) {
     const size_t tix = (size_t)n * nc + c;
     const size_t so = (size_t)n * (nc + 1) + c;
-    const uint32_t cnt = ch_cnt[tix];
-    const uint32_t off = ch_off[tix];
-    const uint32_t tau = ctl[n].tau, budget = ctl[n].budget;
-    const size_t cb = (size_t)n * cap_total + off;
+    cnt = ch_cnt[tix];
+    off = ch_off[tix];
     first = sel_off[so];
     was_empty = prev_sel_off[so + 1] == prev_sel_off[so];
     is_empty = sel_off[so + 1] == first;
-    uint32_t out = first;
-    uint32_t tie_run = tie_off[tix];
-    for (uint32_t p0 = 0; p0 < cnt; p0 += 64 * kLaneBatch) {
-      // keys, indices and values of eight candidates per lane, all loads in flight together
-      uint32_t kk[kLaneBatch], jj[kLaneBatch];
-      float vv[kLaneBatch];
+    tie_run = tie_off[tix];
+  }
+  const uint32_t tau = ctl[n].tau, budget = ctl[n].budget;
+  const size_t cb = (size_t)n * cap_total + off;
+  const uint64_t below_mask = (1ull << gl) - 1ull, group_bits = LPC == 64 ? ~0ull : (1ull << LPC) - 1ull;
+  const uint32_t gshift = grp * LPC;
+  uint32_t out = first;
+  for (uint32_t p0 = 0; p0 < cnt; p0 += LPC * kLaneBatch) {   // trip count uniform within a group of lanes
+    // keys, indices and values of eight candidates per lane, all loads in flight together
+    uint32_t kk[kLaneBatch], jj[kLaneBatch];
+    float vv[kLaneBatch];
 #pragma unroll
-      for (int q = 0; q < kLaneBatch; ++q) {
-        const uint32_t p = p0 + q * 64 + lane;
-        const bool in = p < cnt;
-        kk[q] = in ? cand_key[cb + p] : 0u;
-        jj[q] = in ? (uint32_t)cand_idx[cb + p] & ~kSentFlag : 0u;
-        vv[q] = in ? cand_val[cb + p] : 0.0f;
-      }
+    for (int q = 0; q < kLaneBatch; ++q) {
+      const uint32_t p = p0 + q * LPC + gl;
+      const bool in = p < cnt;
+      kk[q] = in ? cand_key[cb + p] : 0u;
+      jj[q] = in ? (uint32_t)cand_idx[cb + p] & ~kSentFlag : 0u;
+      vv[q] = in ? cand_val[cb + p] : 0.0f;
+    }
 #pragma unroll
-      for (int q = 0; q < kLaneBatch; ++q) {
-        if (p0 + q * 64 >= cnt) break;                       // uniform over the wave
-        const bool in = p0 + q * 64 + lane < cnt;
-        const bool is_tie = in && kk[q] == tau;
-        const uint64_t tb = __ballot(is_tie);
-        const bool take = in && (kk[q] > tau || (is_tie && tie_run + lanes_below(tb) < budget));
-        const uint64_t sb = __ballot(take);
-        if (take) {
-          const uint32_t o = out + lanes_below(sb);
-          if ((int64_t)o < k) {
-            out_idx[(size_t)n * k + o] = (int32_t)jj[q];
-            out_val[(size_t)n * k + o] = vv[q];
-            const uint32_t jl = jj[q] & (kChunk - 1);
-            atomicOr(&s_m[wv][jl >> 5], 1u << (jl & 31));
-          }
+    for (int q = 0; q < kLaneBatch; ++q) {
+      if (p0 + q * LPC >= cnt) break;                                    // uniform over the group
+      const bool in = p0 + q * LPC + gl < cnt;
+      const bool is_tie = in && kk[q] == tau;
+      // ballots span the wave; a group reads its own bits (the lanes of
+      // other groups that have left their loop contribute zeros)
+      const uint64_t tb = (__ballot(is_tie) >> gshift) & group_bits;
+      const bool take = in && (kk[q] > tau || (is_tie && tie_run + (uint32_t)__popcll(tb & below_mask) < budget));
+      const uint64_t sb = (__ballot(take) >> gshift) & group_bits;
+      if (take) {
+        const uint32_t o = out + (uint32_t)__popcll(sb & below_mask);
+        if ((int64_t)o < k) {
+          out_idx[(size_t)n * k + o] = (int32_t)jj[q];
+          out_val[(size_t)n * k + o] = vv[q];
+          const uint32_t jl = jj[q] & (kChunk - 1);
+          atomicOr(&s_m[slot][jl >> 5], 1u << (jl & 31));
         }
-        tie_run += (uint32_t)__popcll(tb);
-        out += (uint32_t)__popcll(sb);
       }
+      tie_run += (uint32_t)__popcll(tb);
+      out += (uint32_t)__popcll(sb);
     }
   }
   __syncthreads();
-  if (live) {
-    // a chunk without selected entries in the previous round has all-zero mask
-    // words already: nothing to write if it has none now either
-    if (!(was_empty && is_empty)) {
-      const size_t wbase = ((size_t)n * nc + c) * kChunkWords;
-      reinterpret_cast<uint2*>(mask + wbase)[lane] = make_uint2(s_m[wv][2 * lane], s_m[wv][2 * lane + 1]);
+  // a chunk without selected entries in the previous round has all-zero mask
+  // words already: nothing to write if it has none now either
+  if (live && !(was_empty && is_empty)) {
+    const size_t wbase = ((size_t)n * nc + c) * kChunkWords + gl * kWordsPerLane;
+    const uint32_t* m = &s_m[slot][gl * kWordsPerLane];
+    if (kWordsPerLane == 2) {
+      reinterpret_cast<uint2*>(mask + wbase)[0] = make_uint2(m[0], m[1]);
+    } else {
+#pragma unroll
+      for (uint32_t i = 0; i < kWordsPerLane / 4; ++i)
+        reinterpret_cast<uint4*>(mask + wbase)[i] = make_uint4(m[4 * i], m[4 * i + 1], m[4 * i + 2], m[4 * i + 3]);
     }
   }
 }

@@ -363,9 +363,11 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
 
   // ordered compaction, error update, aggregation
   if (ev) HIP_TRY(hipEventRecord(ev[2], s));
-  k_chunk_count<<<g_waves, kBlock, 0, s>>>(ctl, cand_key, ch_off, ch_cnt, ch_gt, ch_tie, nc, L.cap_total);
+  const dim3 g_groups((nc + kChunksPerBlock - 1) / kChunksPerBlock, N);
+  k_chunk_count<<<g_groups, kBlock, 0, s>>>(ctl, cand_key, ch_off, ch_cnt, ch_gt, ch_tie, nc, L.cap_total);
   k_chunk_scan<<<N, kScanBlock, 0, s>>>(ctl, ch_gt, ch_tie, sel_off, tie_off, nc, k);
-  k_compact<<<g_waves, kBlock, 0, s>>>(ctl, cand_key, cand_idx, cand_val, ch_off, ch_cnt, sel_off, prev_sel_off, tie_off, out_idx, out_val, mask, k, nc, L.cap_total);
+  constexpr uint32_t kCompactPerBlock = (kBlock / 64) * (64 / kCompactLanes);
+  k_compact<kCompactLanes><<<dim3((nc + kCompactPerBlock - 1) / kCompactPerBlock, N), kBlock, 0, s>>>(ctl, cand_key, cand_idx, cand_val, ch_off, ch_cnt, sel_off, prev_sel_off, tie_off, out_idx, out_val, mask, k, nc, L.cap_total);
   k_aggregate<<<nc, kBlock, 0, s>>>(out_idx, out_val, sel_off, agg, agg_hot, d, k, nc, N, omega);
   if (ev) { HIP_TRY(hipEventRecord(ev[3], s)); c->prof_rounds += 1; }
   HIP_TRY(hipGetLastError());
