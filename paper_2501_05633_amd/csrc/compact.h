@@ -16,12 +16,16 @@ constexpr uint32_t kLanesPerChunk = 16;
 constexpr uint32_t kChunksPerWave = 64 / kLanesPerChunk;
 constexpr uint32_t kChunksPerBlock = (kBlock / 64) * kChunksPerWave;
 
-// grid (ceil(nc/kChunksPerBlock), N).  Candidates of the chunk with score > tau and == tau.
+// grid (ceil(nc/kChunksPerBlock), N).  Candidates of the chunk with score > tau
+// and == tau, per chunk and summed over the block's chunks (blk_gt, blk_tie:
+// [N, gridDim.x]); the compaction builds its running sums from these two levels.
 __global__ void __launch_bounds__(kBlock)
 k_chunk_count(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ cand_key,
               const uint32_t* __restrict__ ch_off, const uint32_t* __restrict__ ch_cnt,
-              uint32_t* __restrict__ ch_gt, uint32_t* __restrict__ ch_tie, uint32_t nc,
+              uint32_t* __restrict__ ch_gt, uint32_t* __restrict__ ch_tie,
+              uint32_t* __restrict__ blk_gt, uint32_t* __restrict__ blk_tie, uint32_t nc,
               uint32_t cap_total) {
+  __shared__ uint32_t s_g[kBlock / 64], s_t[kBlock / 64];
   const uint32_t n = blockIdx.y, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const uint32_t grp = lane / kLanesPerChunk, gl = lane % kLanesPerChunk;
   const uint32_t c = (blockIdx.x * (kBlock / 64) + wv) * kChunksPerWave + grp;
@@ -47,6 +51,17 @@ k_chunk_count(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ ca
   }
   for (uint32_t o = kLanesPerChunk / 2; o > 0; o >>= 1) { gt += __shfl_xor(gt, o); tie += __shfl_xor(tie, o); }
   if (live && gl == 0) { ch_gt[tix] = gt; ch_tie[tix] = tie; }
+  // totals of the block: the groups' sums sit in their lane 0
+  uint32_t wg = gl == 0 ? gt : 0u, wt = gl == 0 ? tie : 0u;
+  for (int o = 32; o > 0; o >>= 1) { wg += __shfl_down(wg, o); wt += __shfl_down(wt, o); }
+  if (lane == 0) { s_g[wv] = wg; s_t[wv] = wt; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t bg = 0, bt = 0;
+    for (uint32_t i = 0; i < kBlock / 64; ++i) { bg += s_g[i]; bt += s_t[i]; }
+    blk_gt[(size_t)n * gridDim.x + blockIdx.x] = bg;
+    blk_tie[(size_t)n * gridDim.x + blockIdx.x] = bt;
+  }
 }
 
 // ------------------------------------------------------------- k_compact ----
@@ -54,20 +69,30 @@ k_chunk_count(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ ca
 // pairs of the chunk in index order at sel_off[c], and the chunk's words of the
 // round's mask (bit = entry selected).  The ordered placement is a chain of
 // ballots over the chunk's candidates, so here the full chunks want more lanes
-// than the counting does.
+// than the counting does.  Where a chunk's pairs go follows from two running
+// sums over the chunks before it, of the counts of scores > tau and == tau (the
+// ties taken before a chunk number min(budget, ties before it)): the block adds
+// up the counting blocks' totals before its own counting block, every group of
+// lanes the chunks before its own inside that block.  It also writes sel_off
+// (selected entries before each chunk; the last chunk adds the total).
 constexpr uint32_t kCompactLanes = 32;
 
 template <uint32_t LPC>
 __global__ void __launch_bounds__(kBlock)
-k_compact(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ cand_key,
+k_compact(WorkerCtl* ctl, const uint32_t* __restrict__ cand_key,
           const int32_t* __restrict__ cand_idx, const float* __restrict__ cand_val,
           const uint32_t* __restrict__ ch_off, const uint32_t* __restrict__ ch_cnt,
-          const uint32_t* __restrict__ sel_off, const uint32_t* __restrict__ prev_sel_off,
-          const uint32_t* __restrict__ tie_off, int32_t* __restrict__ out_idx,
+          const uint32_t* __restrict__ ch_gt, const uint32_t* __restrict__ ch_tie,
+          const uint32_t* __restrict__ blk_gt, const uint32_t* __restrict__ blk_tie, uint32_t n_blk,
+          uint32_t* __restrict__ sel_off, const uint32_t* __restrict__ prev_sel_off,
+          int32_t* __restrict__ out_idx,
           float* __restrict__ out_val, uint32_t* __restrict__ mask,
           int64_t k, uint32_t nc, uint32_t cap_total) {
   constexpr uint32_t kCPW = 64 / LPC, kCPB = (kBlock / 64) * kCPW;
+  static_assert(kChunksPerBlock % kCPB == 0, "a compaction block must lie inside one counting block");
+  static_assert(kChunksPerBlock <= LPC, "one load per lane must cover the chunks of a counting block");
   __shared__ uint32_t s_m[kCPB][kChunkWords];
+  __shared__ uint32_t s_g[kBlock / 64], s_t[kBlock / 64];
   constexpr uint32_t kWordsPerLane = kChunkWords / LPC;
   const uint32_t n = blockIdx.y, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const uint32_t grp = lane / LPC, gl = lane % LPC;
@@ -76,20 +101,47 @@ k_compact(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ cand_k
   const bool live = c < nc;
 #pragma unroll
   for (uint32_t i = 0; i < kWordsPerLane; ++i) s_m[slot][gl * kWordsPerLane + i] = 0;
-  __syncthreads();
-  uint32_t first = 0, cnt = 0, off = 0, tie_run = 0;
-  bool was_empty = true, is_empty = true;
+  // running sums, level 1: the counting blocks before this block's own
+  const uint32_t cblk = (blockIdx.x * kCPB) / kChunksPerBlock;           // the block's counting block
+  uint32_t bg = 0, bt = 0;
+  for (uint32_t i = threadIdx.x; i < cblk; i += kBlock) {
+    bg += blk_gt[(size_t)n * n_blk + i];
+    bt += blk_tie[(size_t)n * n_blk + i];
+  }
+  for (int o = 32; o > 0; o >>= 1) { bg += __shfl_down(bg, o); bt += __shfl_down(bt, o); }
+  if (lane == 0) { s_g[wv] = bg; s_t[wv] = bt; }
+  uint32_t cnt = 0, off = 0, my_gt = 0, my_tie = 0, in_g = 0, in_t = 0;
+  bool was_empty = true;
+  const size_t so = (size_t)n * (nc + 1) + (live ? c : 0);
   if (live) {
     const size_t tix = (size_t)n * nc + c;
-    const size_t so = (size_t)n * (nc + 1) + c;
     cnt = ch_cnt[tix];
     off = ch_off[tix];
-    first = sel_off[so];
+    my_gt = ch_gt[tix];
+    my_tie = ch_tie[tix];
     was_empty = prev_sel_off[so + 1] == prev_sel_off[so];
-    is_empty = sel_off[so + 1] == first;
-    tie_run = tie_off[tix];
+    // level 2: the chunks before this one inside the counting block (fewer than kChunksPerBlock <= LPC)
+    const uint32_t cfirst = cblk * kChunksPerBlock;
+    if (cfirst + gl < c) { in_g = ch_gt[(size_t)n * nc + cfirst + gl]; in_t = ch_tie[(size_t)n * nc + cfirst + gl]; }
   }
+  for (uint32_t o = LPC / 2; o > 0; o >>= 1) { in_g += __shfl_xor(in_g, o); in_t += __shfl_xor(in_t, o); }
+  __syncthreads();                                                       // mask words zeroed, block sums placed
+  uint32_t gt_before = in_g, tie_before = in_t;
+  for (uint32_t i = 0; i < kBlock / 64; ++i) { gt_before += s_g[i]; tie_before += s_t[i]; }
   const uint32_t tau = ctl[n].tau, budget = ctl[n].budget;
+  const uint32_t first = gt_before + (tie_before < budget ? tie_before : budget);
+  uint32_t my_take = 0;
+  if (tie_before < budget) { my_take = budget - tie_before; if (my_take > my_tie) my_take = my_tie; }
+  const uint32_t my_sel = my_gt + my_take;
+  const bool is_empty = my_sel == 0;
+  uint32_t tie_run = tie_before;
+  if (live && gl == 0) {
+    sel_off[so] = first;
+    if (c == nc - 1) {
+      sel_off[so + 1] = first + my_sel;
+      if ((int64_t)(first + my_sel) != k) atomicOr(&ctl[n].err, 1u);
+    }
+  }
   const size_t cb = (size_t)n * cap_total + off;
   const uint64_t below_mask = (1ull << gl) - 1ull, group_bits = LPC == 64 ? ~0ull : (1ull << LPC) - 1ull;
   const uint32_t gshift = grp * LPC;

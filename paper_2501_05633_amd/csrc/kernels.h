@@ -27,10 +27,11 @@
 //                   scores and the exact k-th score; one kernel with grid
 //                   barriers between its phases, which returns at once when no
 //                   worker is flagged
-//   k_chunk_count / k_chunk_scan / k_compact
+//   k_chunk_count / k_compact
 //                   ordered compaction of the selected (index, value) pairs,
-//                   lowest-index ties first; writes the round's mask (1 bit per
-//                   entry)
+//                   lowest-index ties first: per-chunk counts of scores above and
+//                   at the k-th, then placement from two levels of running sums;
+//                   writes the round's mask (1 bit per entry)
 //   k_aggregate     per 4096-entry tile: LDS accumulation of w*value in ascending
 //                   worker order, tile written once (zero fill included)
 //

@@ -41,7 +41,7 @@ size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 struct Layout {
   uint32_t nc, regions, cap_r, cap_total, bnd_cap;
   size_t e, out_idx[2], out_val[2], agg[2], cand_idx, cand_val, cand_key;
-  size_t ch_off, ch_cnt, ch_gt, ch_tie, tie_off, sel_off[2], agg_hot[2], mask, cand_prev, bnd_key, fhist, ctl, gctl, omega, total;
+  size_t ch_off, ch_cnt, ch_gt, ch_tie, tie_off, sel_off[2], agg_hot[2], mask, cand_prev, bnd_key, fhist, ctl, gctl, omega, blk_gt, blk_tie, total;
 };
 
 bool valid_sizes(int32_t N, int64_t d, int64_t k) {
@@ -88,6 +88,9 @@ Layout make_layout(int32_t N, int64_t d, int64_t k) {
   L.ctl = take((size_t)N * sizeof(WorkerCtl));
   L.gctl = take(sizeof(GlobalCtl));
   L.omega = take((size_t)N * 4);
+  const size_t nblk = (size_t)N * ((L.nc + kChunksPerBlock - 1) / kChunksPerBlock);
+  L.blk_gt = take(nblk * 4);
+  L.blk_tie = take(nblk * 4);
   L.total = o;
   return L;
 }
@@ -363,11 +366,15 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
 
   // ordered compaction, error update, aggregation
   if (ev) HIP_TRY(hipEventRecord(ev[2], s));
-  const dim3 g_groups((nc + kChunksPerBlock - 1) / kChunksPerBlock, N);
-  k_chunk_count<<<g_groups, kBlock, 0, s>>>(ctl, cand_key, ch_off, ch_cnt, ch_gt, ch_tie, nc, L.cap_total);
-  k_chunk_scan<<<N, kScanBlock, 0, s>>>(ctl, ch_gt, ch_tie, sel_off, tie_off, nc, k);
+  const uint32_t n_blk = (nc + kChunksPerBlock - 1) / kChunksPerBlock;
+  const dim3 g_groups(n_blk, N);
+  uint32_t* blk_gt = c->at<uint32_t>(L.blk_gt);
+  uint32_t* blk_tie = c->at<uint32_t>(L.blk_tie);
+  k_chunk_count<<<g_groups, kBlock, 0, s>>>(ctl, cand_key, ch_off, ch_cnt, ch_gt, ch_tie, blk_gt, blk_tie, nc, L.cap_total);
   constexpr uint32_t kCompactPerBlock = (kBlock / 64) * (64 / kCompactLanes);
-  k_compact<kCompactLanes><<<dim3((nc + kCompactPerBlock - 1) / kCompactPerBlock, N), kBlock, 0, s>>>(ctl, cand_key, cand_idx, cand_val, ch_off, ch_cnt, sel_off, prev_sel_off, tie_off, out_idx, out_val, mask, k, nc, L.cap_total);
+  k_compact<kCompactLanes><<<dim3((nc + kCompactPerBlock - 1) / kCompactPerBlock, N), kBlock, 0, s>>>(
+      ctl, cand_key, cand_idx, cand_val, ch_off, ch_cnt, ch_gt, ch_tie, blk_gt, blk_tie, n_blk, sel_off, prev_sel_off,
+      out_idx, out_val, mask, k, nc, L.cap_total);
   k_aggregate<<<nc, kBlock, 0, s>>>(out_idx, out_val, sel_off, agg, agg_hot, d, k, nc, N, omega);
   if (ev) { HIP_TRY(hipEventRecord(ev[3], s)); c->prof_rounds += 1; }
   HIP_TRY(hipGetLastError());

@@ -409,7 +409,9 @@ k_sample_bound(WorkerCtl* ctl, const uint32_t* __restrict__ shist, int64_t d, in
   }
 }
 
-// ---------------------------------------------------------- k_chunk_scan ----
+// ------------------------------------------------------------ chunk scan ----
+// (Used by the dense selection to place its emission; the compaction of the
+// round computes the same sums on the fly from two levels of partial sums.)
 // One block of NT threads per worker.  Exclusive scans over the chunks of one worker:
 //   tie_off[c] = ties before chunk c;
 //   sel[c]     = gt[c] + clamp(budget - tie_off[c], 0, tie[c])   (lowest-index ties first);
@@ -489,13 +491,5 @@ __device__ __forceinline__ void chunk_scan_worker(uint32_t n, WorkerCtl* ctl, co
   }
 }
 
-
-// grid (N), 1024 threads: the scan of the final compaction.
-__global__ void __launch_bounds__(kScanBlock)
-k_chunk_scan(WorkerCtl* ctl, const uint32_t* __restrict__ ch_gt, const uint32_t* __restrict__ ch_tie,
-             uint32_t* __restrict__ sel_off, uint32_t* __restrict__ tie_off, uint32_t nc, int64_t k) {
-  __shared__ uint32_t s_w[2 * kScanBlock / 64];
-  chunk_scan_worker<false, kScanBlock>(blockIdx.x, ctl, ch_gt, ch_tie, sel_off, nullptr, tie_off, nc, k, s_w);
-}
 
 }  // namespace rtk
