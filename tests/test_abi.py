@@ -57,3 +57,13 @@ def test_product_sources_do_not_touch_the_oracle():
             if f.endswith((".py", ".hip", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower() or f == "workloads.py", (dirpath, f)
+
+
+def test_header_is_plain_c(tmp_path):
+    # the boundary is a C ABI: the header must compile as C99 and as C++ on its own
+    import subprocess
+    hdr = os.path.join(ROOT, "include", "regtopk.h")
+    src = tmp_path / "use.c"
+    src.write_text('#include "%s"\nint main(void) { regtopk_result r; (void)r; return regtopk_last_error() == 0; }\n' % hdr)
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", str(src)])
+    subprocess.check_call(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", str(src)])
