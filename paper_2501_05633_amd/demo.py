@@ -48,8 +48,13 @@ def toy(iters: int = 120, mu: float = 1.0, eta: float = 0.9, device="cuda:0"):
     return out
 
 
-def linreg(S: float, mu: float, iters: int, N: int, J: int, device="cuda:0", every: int = 250, quiet=False):
-    wl = workloads.PaperLinReg(device, N=N, J=J, D=5 * J)
+def linreg(S: float, mu: float, iters: int, N: int, J: int, device="cuda:0", every: int = 250, quiet=False,
+           lowdim_seed=None):
+    if lowdim_seed is None:
+        wl = workloads.PaperLinReg(device, N=N, J=J, D=5 * J)
+    else:           # the low-dimensional study of the appendix: sigma^2 = 1, gradient without the 2/D_n
+        wl = workloads.PaperLinReg(device, N=N, J=J, D=5 * J, sigma2=1.0, normalised=False,
+                                   seed=workloads.BASE_SEED + 200 + lowdim_seed)
     k = max(1, int(round(S * J)))
     runs = {"dense": (0.0, J), "Top-k": (0.0, k), "RegTop-k": (mu, k), "global Top-k": (None, k)}
     res = {}
@@ -91,13 +96,17 @@ def main():
     l.add_argument("--iters", type=int, default=2500)
     l.add_argument("--N", type=int, default=20)
     l.add_argument("--J", type=int, default=100)
+    l.add_argument("--every", type=int, default=250, help="print the gaps every so many iterations")
+    l.add_argument("--lowdim", type=int, default=None, metavar="SEED",
+                   help="the appendix's low-dimensional study (use with --N 2 --J 4 --iters 60 --every 10): "
+                        "sigma^2 = 1 and the gradient X^T(X theta - y) without the factor 2/D_n")
     args = ap.parse_args()
     if not torch.cuda.is_available():
         raise SystemExit("demo: no GPU (the method runs only as HIP kernels)")
     if args.cmd == "toy":
         toy(args.iters, args.mu)
     else:
-        linreg(args.S, args.mu, args.iters, args.N, args.J)
+        linreg(args.S, args.mu, args.iters, args.N, args.J, every=args.every, lowdim_seed=args.lowdim)
 
 
 if __name__ == "__main__":

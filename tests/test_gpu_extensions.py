@@ -347,3 +347,26 @@ def test_first_row_of_the_papers_table_on_the_gpu():
         np.testing.assert_allclose(val.cpu().numpy(), [[s1[0], s1[1], s1[3]], [s2[0], s2[1], s2[2]]], rtol=1e-6)
         np.testing.assert_allclose(agg.cpu().numpy(), (s1 + s2) / 2, rtol=1e-6)
         r.close()
+
+
+@pytest.mark.parametrize("k,mu", [(3, 0.5), (2, 1.0), (3, 0.0)])
+def test_low_dimensional_study_on_the_gpu(k, mu):
+    # appendix "Closer Look at RegTop-k in Lower Dimensions" (N = 2, J = 4, D_n = 20), sample problem 2:
+    # sixty iterations of sparsified round + SGD update on the GPU, bit-equal to the oracle's loop;
+    # RegTop-k ends at the unsparsified run's gap, Top-k far above it
+    print("case lowdim k=%d mu=%g" % (k, mu), flush=True)
+    wl = workloads.PaperLinReg(DEV, N=2, J=4, D=20, sigma2=1.0, normalised=False, seed=workloads.BASE_SEED + 202)
+    theta_g = torch.zeros(4, device=DEV)
+    theta_c = np.zeros(4, dtype=f32)
+
+    def after(t, res_g, res_c):
+        nonlocal theta_c
+        binding.sgd_update(theta_g, res_g[2], wl.eta)
+        theta_c = orc.sgd_update(theta_c, res_c[2], wl.eta)
+        assert np.array_equal(theta_g.cpu().numpy().view(np.uint32), theta_c.view(np.uint32)), "theta differs at t=%d" % t
+
+    stats, tol = run_both(2, 4, k, mu, lambda t, agg: wl.grads(theta_g), 60, label="lowdim", on_round=after,
+                          check_state_every=20)
+    assert tol == 0
+    log_gap = float(np.log(wl.gap(theta_g)))
+    assert (log_gap < -9.0) if mu > 0 else (log_gap > -5.0)

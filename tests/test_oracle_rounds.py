@@ -308,3 +308,45 @@ def test_masks_of_different_workers_coordinate_under_the_regulariser():
 
     assert unanimous(1.0) > 70          # most of the 100 entries are kept or dropped by all workers
     assert unanimous(0.0) < 35          # plain Top-k: hardly any agreement
+
+
+def _lowdim_log_gap(seed, k, mu, T=60):
+    # the appendix's low-dimensional study: N = 2, J = 4, D_n = 20, U = 0, sigma^2 = h^2 = 1, eps^2 = 0.5,
+    # eta = 1e-2; gradient X^T (X theta - y), the scaling under which the unsparsified run decays at the
+    # rate of the curves plotted in the paper (about 0.8 per iteration at first, 0.86 later)
+    wl = workloads.PaperLinReg("cpu", N=2, J=4, D=20, sigma2=1.0, normalised=False,
+                               seed=workloads.BASE_SEED + 200 + seed)
+    o = oracle.Oracle(2, 4, k, mu)
+    theta, agg = np.zeros(4, dtype=f32), None
+    for _ in range(T):
+        g = wl.grads(torch.from_numpy(theta)).numpy()
+        _, _, agg = o.step(g, agg)
+        theta = oracle.sgd_update(theta, agg, wl.eta)
+    return float(np.log(wl.gap(torch.from_numpy(theta))))
+
+
+def test_low_dimensional_study_regtopk_tracks_the_unsparsified_run_where_topk_stalls():
+    # Figure "Optimality gap ... in the low-dimensional case with J = 4" and the text of the appendix: for
+    # S = 0.75 and S = 0.5 Top-k stays at a fixed distance from the optimum (log gap about -2.4 ... -3.4 after
+    # 60 iterations in the plotted sample problem) while RegTop-k follows the unsparsified run (about -9.3);
+    # for S = 0.25 neither converges.  One sample problem in full, then counts over ten problems.
+    gold = _read_gold("lowdim_figure.txt")
+    stall, track = -5.0, 1.0               # what "stalls" and "tracks" mean below; the plotted curves satisfy both
+    for S in ("S075", "S050"):
+        assert min(gold["topk_" + S]) > stall and max(gold["regtopk_" + S]) < min(gold["dense_" + S]) + track
+    assert min(gold["topk_S025"]) > stall and min(gold["regtopk_S025"]) > stall
+    first = gold["dense_S100_first"]
+    assert abs((first[1] - first[0]) - np.log(0.8)) < 0.01             # the step scaling used by _lowdim_log_gap
+    dense = _lowdim_log_gap(2, 4, 0.0)
+    assert dense < -9.0
+    for k in (3, 2):
+        assert _lowdim_log_gap(2, k, 0.0) > stall                      # Top-k stalls
+        for mu in (0.25, 0.5, 1.0):
+            assert _lowdim_log_gap(2, k, mu) < dense + track           # RegTop-k tracks the unsparsified run
+    assert _lowdim_log_gap(2, 1, 0.0) > stall and _lowdim_log_gap(2, 1, 1.0) > stall
+    tracked_reg = tracked_top = 0
+    for seed in range(10):
+        d = _lowdim_log_gap(seed, 4, 0.0)
+        tracked_top += _lowdim_log_gap(seed, 3, 0.0) < d + track
+        tracked_reg += min(_lowdim_log_gap(seed, 3, mu) for mu in (0.25, 0.5, 1.0, 2.0, 5.0)) < d + track
+    assert tracked_reg >= 8 and tracked_top <= 4                       # mu is tuned per problem, as in the paper
