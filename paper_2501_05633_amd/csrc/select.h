@@ -260,7 +260,7 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
     else if (c.centre != kNoBound && c.extrapolated) err = tau > c.centre ? tau - c.centre : c.centre - tau;
     else if (c.tau_prev != kNoBound) err = adrift / 2;
     else err = kWinDefaultHalf;
-    if (!shock && (double)err < 0.7 * (double)c.err_prev) err = (uint32_t)(0.7 * (double)c.err_prev);
+    if (!shock && (double)err < 0.5 * (double)c.err_prev) err = (uint32_t)(0.5 * (double)c.err_prev);
     double half = 3.0 * (double)err + 1024.0;
     const double by_count = 10000.0 / dens;                // at least about 20000 boundary entries
     if (half < by_count) half = by_count;
