@@ -197,12 +197,9 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
     // the k-th score lies inside the window: select among the boundary list only
     const uint32_t* list = bnd_key + (size_t)n * bnd_cap;
     src.count = n_bnd;
-    if (s_keys != nullptr && n_bnd <= kLdsKeys) {
-      for (uint32_t i = tid; i < n_bnd; i += NT) s_keys[i] = list[i];
-      src.lds = s_keys;
-    } else {
-      src.flat = list;
-    }
+    // (read from memory: after the first level only the keys of one bin remain, and those are
+    // gathered in LDS - copying the whole list there first is slower even when it fits)
+    src.flat = list;
     base = win_lo;
     rank = K - n_hi;
   } else {
