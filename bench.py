@@ -150,6 +150,7 @@ def main():
     for t in range(args.warmup):
         _, _, agg = r.step_global(grads[t % n_buf]) if glob else r.step(grads[t % n_buf], agg)
     torch.cuda.synchronize()
+    warm = [x[3] for x in r.timings(64)] if args.warmup else []     # whole-round event times of the warm-up rounds
     r.set_option(binding.OPT_PROFILE, 1)          # restart the event ring for the timed region
 
     t0 = time.perf_counter()
@@ -168,6 +169,13 @@ def main():
     tail_ms = sum(x[2] for x in stage) / len(stage)
     round_ms_events = sum(x[3] for x in stage) / len(stage)
 
+    # every round of the run by its own HIP events (round 0 has no history; the first rounds are
+    # slower while the k-th score still moves fast): round 0, and median / min / max of the others
+    all_rounds = (warm + [x[3] for x in stage])[-(args.warmup + args.steps):]
+    later = sorted(all_rounds[1:]) if len(all_rounds) > 1 else sorted(all_rounds)
+    round_ms = {"round0": all_rounds[0] if args.warmup and len(warm) == args.warmup else None,
+                "median_later_rounds": later[len(later) // 2], "min": later[0], "max": later[-1],
+                "rounds": len(all_rounds)}
     entries = N * d
     value = entries / (ms_per_step * 1e-3)
     sweep_bytes = (8 + g_bytes) * N * d           # read eps, read g, write eps
@@ -187,6 +195,7 @@ def main():
         "algorithmic_bytes_per_round": b_alg,
         "stage_ms": {"sweep": sweep_ms, "select": select_ms, "compact_aggregate": tail_ms,
                      "round_events": round_ms_events},
+        "round_ms_by_events": round_ms,
         "dense_fallback_workers_last_round": dense_rounds,
         "candidates_last_round": [w["n_candidates"] for w in st],
         "roofline": {"bound": "hbm", "kernel": "k_global_accum" if glob else "k_accum_emit", "achieved": achieved,
