@@ -17,11 +17,13 @@
 //                   above it are counted
 //   k_select        one block per worker: checks the speculation (no overflow and
 //                   >= k candidates scored >= tau_lo), then finds the k-th largest
-//                   score exactly - from the boundary list held in LDS when the
-//                   window contains it, otherwise by a three-level radix select
-//                   over all candidates - and derives next round's bound/window
-//   k_dense_all     for workers whose speculation failed (and in round 0): exact
-//                   radix select of the 2k largest |a| (a superset of the true
+//                   score exactly by a three-level radix select - over the boundary
+//                   list when the window contains it, otherwise over all
+//                   candidates - and derives next round's bound/window
+//   (k_sample_hist, k_sample_bound: a round without history - round 0, after a
+//                   reset - first takes its bound from a strided sample of a)
+//   k_dense_all     for workers whose speculation failed: exact radix select of
+//                   the 2k largest priors |a|^y (a superset of the true
 //                   top-k, see below), count, scan and an ordered emission of
 //                   exactly those entries as the candidate list, then their
 //                   scores and the exact k-th score; one kernel with grid
@@ -35,11 +37,11 @@
 //   k_aggregate     per 4096-entry tile: LDS accumulation of w*value in ascending
 //                   worker order, tile written once (zero fill included)
 //
-// Why 2k largest |a| suffice when the speculation fails: the score never
-// exceeds |a| and differs from it only on the k entries sent in the previous
-// round; among the 2k entries with the largest (|a|, lower index first) at
-// least k are therefore scored at their full |a|, and each of them beats every
-// entry outside that set.
+// Why the 2k largest priors suffice when the speculation fails: the score never
+// exceeds the prior p = |a|^y (y = 1 unless a variant is set) and differs from
+// it only on the k entries sent in the previous round; among the 2k entries
+// with the largest (p, lower index first) at least k are therefore scored at
+// their full p, and each of them beats every entry outside that set.
 #pragma once
 #include "common.h"
 #include "sweep.h"
