@@ -5,16 +5,17 @@
 namespace rtk {
 
 // ------------------------------------------------------------ dense path ----
-// The dense selection of the workers whose speculation failed (and of every
-// worker in round 0) runs as ONE kernel, k_dense_all, whose phases are
+// The dense selection of the workers whose speculation failed (or of every
+// worker when the option forces it) runs as ONE kernel, k_dense_all, whose phases are
 // separated by grid barriers: when no worker is flagged - the usual case - the
 // whole path costs a single launch that returns at once.  The grid is sized by
 // the host so that all blocks are resident together.
 //
 // Phases, for flagged workers only:
-//   clear histograms | 3 x (histogram of |a| bits, pick the bin of rank
-//   min(2k,d)) | per-chunk counts | chunk scan | ordered emission of the 2k
-//   largest |a| as the candidate list | scores | exact k-th score.
+//   clear histograms | 3 x (histogram of the prior's bits, every flagged
+//   worker fed by its own group of blocks; pick the bin of rank min(2k,d)) |
+//   per-chunk counts | chunk scan | ordered emission of the 2k largest priors
+//   as the candidate list | scores | exact k-th score.
 
 // Histogram level LEVEL of worker n's row; block b of G covers a strided share.
 template <int LEVEL, bool VEC>

@@ -155,7 +155,7 @@ __device__ __forceinline__ uint32_t rel_select(KeySource src, uint32_t base, uin
   return base + ((pb << 4) | hc.bin);
 }
 
-constexpr uint32_t kLdsKeys = 11264;    // boundary keys held in LDS (longer lists are read from memory)
+constexpr uint32_t kLdsKeys = 11264;    // LDS room for the keys of the bin chosen at the first level
 
 // SECOND = false: first invocation, all workers (validates the speculation).
 // SECOND = true : after the dense selection, flagged workers only.
