@@ -148,8 +148,8 @@ int regtopk_reset(regtopk_ctx* ctx, void* stream);
  * Before round 1 the previous lists are empty and pidx/pval are not written /
  * read.  Any of the output pointers of get_state may be NULL to skip it.
  * set_state enqueues a check that every row of pidx is strictly ascending and
- * within [0,d); a violation is reported by the next regtopk_get_stats /
- * regtopk_check (REGTOPK_BAD_STATE) and the following rounds are undefined. */
+ * within [0,d); a violation is reported by the next regtopk_get_stats
+ * (REGTOPK_BAD_STATE) and the following rounds are undefined. */
 int regtopk_get_state(regtopk_ctx* ctx, float* e_dev, int32_t* pidx_dev, float* pval_dev,
                       int64_t* t_host, void* stream);
 int regtopk_set_state(regtopk_ctx* ctx, const float* e_dev, const int32_t* pidx_dev,
