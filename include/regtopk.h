@@ -89,7 +89,8 @@ size_t regtopk_workspace_bytes(int32_t N, int64_t d, int64_t k);
 
 /* Creates a context: eps = 0, round counter 0, empty previous mask
  * (initialisation line of Algorithm 2).
- *   N >= 1 workers, 1 <= d < 2^31 entries per worker, 1 <= k <= d, mu >= 0.
+ *   1 <= N <= 65535 workers, 1 <= d < 2^31 entries per worker, 1 <= k <= d,
+ *   mu >= 0 and finite (REGTOPK_INVALID_ARG otherwise).
  * regtopk_create allocates its arena with hipMalloc on the current device and
  * frees it in regtopk_destroy.  regtopk_create_in uses caller-owned device
  * memory instead: arena_dev must be 256-byte aligned, at least
