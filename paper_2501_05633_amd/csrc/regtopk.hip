@@ -98,6 +98,7 @@ Layout make_layout(int32_t N, int64_t d, int64_t k) {
 }  // namespace
 
 constexpr int kProfRounds = 64;
+constexpr int kFreshRounds = 3;      // rounds that sample their bound after a start without history
 
 struct regtopk_ctx {
   int32_t N;
@@ -105,7 +106,7 @@ struct regtopk_ctx {
   float mu;
   int64_t t;
   bool have_prev;       // a previous mask exists (round >= 1 or set_state with t >= 1)
-  bool fresh;           // no bound carried over from a previous round: sample one
+  int fresh;            // rounds still to take their bound from a sample: no (reliable) bound is carried over yet
   bool owns_arena;
   int device;
   int dense_blocks;     // grid of the dense-selection kernel: all blocks resident together
@@ -140,7 +141,7 @@ int zero_state(regtopk_ctx* c, hipStream_t s) {
   HIP_TRY(hipGetLastError());
   c->t = 0;
   c->have_prev = false;
-  c->fresh = true;
+  c->fresh = kFreshRounds;
   return REGTOPK_OK;
 }
 
@@ -259,11 +260,11 @@ int regtopk_set_option(regtopk_ctx* c, int option, double value) {
     case REGTOPK_OPT_PRIOR_ROOTS:
       if (!(value == 0.0 || value == 1.0 || value == 2.0 || value == 3.0))
         return fail(REGTOPK_INVALID_ARG, "prior roots must be 0, 1, 2 or 3");
-      if ((int)value != c->prior_roots) { c->prior_roots = (int)value; c->reinit_ctl = true; c->fresh = true; }
+      if ((int)value != c->prior_roots) { c->prior_roots = (int)value; c->reinit_ctl = true; c->fresh = kFreshRounds; }
       return REGTOPK_OK;
     case REGTOPK_OPT_LIKELIHOOD:
       if (!(value == 0.0 || value == 1.0)) return fail(REGTOPK_INVALID_ARG, "likelihood must be 0 (tanh) or 1 (clipped linear)");
-      if ((int)value != c->likelihood) { c->likelihood = (int)value; c->reinit_ctl = true; c->fresh = true; }
+      if ((int)value != c->likelihood) { c->likelihood = (int)value; c->reinit_ctl = true; c->fresh = kFreshRounds; }
       return REGTOPK_OK;
     case REGTOPK_OPT_PROFILE:
       if (value != 0.0 && !c->profile) {
@@ -334,8 +335,11 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
     c->reinit_ctl = false;
   }
   k_begin<<<N, kBlock, 0, s>>>(ctl, gctl, c->force_dense, sk.roots);
-  if (c->fresh && !c->force_dense) {
-    // no bound from a previous round: take one from a strided sample of a = eps + g
+  if (c->fresh > 0 && !c->force_dense) {
+    // No bound from a previous round, or only the guess of a controller that has
+    // not seen two rounds yet (from an empty error state the k-th score grows by
+    // up to a factor of two in the second round and 3/2 in the third): take the
+    // bound from a strided sample of a = eps + g.
     const uint64_t groups_all = (uint64_t)((d + 3) / 4);
     const uint32_t n_groups = (uint32_t)(groups_all < kSampleMax / 4 ? groups_all : kSampleMax / 4);
     const uint32_t stride4 = (uint32_t)(groups_all / n_groups);
@@ -349,7 +353,7 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
     k_sample_hist<G><<<dim3(sample_blocks, N), kBlock, 0, s>>>(e, grads, mask, d, nc, fhist, n_groups, stride4, sk.roots);
     k_sample_bound<<<N, kScanBlock, 0, s>>>(ctl, fhist, d, k, (uint32_t)n_sampled, sk.roots);
   }
-  c->fresh = false;
+  if (c->fresh > 0) c->fresh -= 1;
   if (ev) HIP_TRY(hipEventRecord(ev[0], s));
   if (vec)
     k_accum_emit<true, G><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, prev_sel_off, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
@@ -442,7 +446,7 @@ int regtopk_step_global(regtopk_ctx* c, const float* grads, void* stream, regtop
   HIP_TRY(hipGetLastError());
   c->t += 1;
   c->have_prev = true;
-  c->fresh = true;               // bounds of earlier local rounds do not describe the next one
+  c->fresh = kFreshRounds;               // bounds of earlier local rounds do not describe the next one
   out->idx = c->at<int32_t>(L.out_idx[cur]);
   out->val = c->at<float>(L.out_val[cur]);
   out->agg = sel.agg;
@@ -479,7 +483,7 @@ int regtopk_set_state(regtopk_ctx* c, const float* e_dev, const int32_t* pidx_de
   k_init_ctl<<<c->N, 256, 0, s>>>(c->at<WorkerCtl>(c->L.ctl));     // no speculative bound: next round selects densely
   c->t = t;
   c->have_prev = t > 0;
-  c->fresh = true;
+  c->fresh = kFreshRounds;
   if (t == 0) {
     for (int b = 0; b < 2; ++b)
       k_fill_u32<<<256, 256, 0, s>>>(c->at<uint32_t>(c->L.sel_off[b]), (size_t)c->N * (c->L.nc + 1), 0u);

@@ -211,9 +211,11 @@ def test_score_variants(name, d, N, k, roots, likelihood, mu):
     assert tol == 0
     if name == "large_cnn":                       # the speculation also works in the transformed score space
         fallbacks = sum(w["used_dense"] for st in stats[2:] for w in st)
-        # (the eighth root packs the scores 8 times denser: while the k-th score still moves by
-        # tens of per cent per round one overflow of the candidate buffer may happen)
-        assert fallbacks == 0 if roots < 3 else fallbacks <= N
+        # (the first rounds take their bound from a sample; when the controller takes over, the k-th
+        # score still moves by tens of per cent per round and one overflow of the candidate buffer
+        # per worker may happen - more easily with a root prior, which packs the scores denser)
+        assert fallbacks <= N
+        assert all(w["used_dense"] == 0 for w in stats[-1])
 
 
 def test_score_variant_with_forced_dense_selection_and_ties():
