@@ -34,7 +34,7 @@ def algorithmic_bytes(N, d, k, g_bytes=4):
 # HBM bytes per launch of the sweep kernel measured with rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE (two runs), scaled by what the same counters read for
 # the 1 GiB reference copy; see profiles/regtopk_round_large_cnn_hbm_traffic.txt.
-MEASURED_SWEEP_TRAFFIC = {"large_cnn": 5020494530}
+MEASURED_SWEEP_TRAFFIC = {"large_cnn": 5020516937}
 
 
 def cpu_baseline(cfg, wl, rounds=3, workers=None, bf16=False, variant=(0, 0), glob=False):
