@@ -118,6 +118,11 @@ def main():
         print("bench.py: no GPU", file=sys.stderr)
         sys.exit(2)
     dev = torch.device("cuda:0")
+    if args.workload not in workloads.CONFIGS or workloads.CONFIGS[args.workload].kind == "linreg":
+        print("bench.py: --workload must be one of %s (the closed-loop linear regression is a parity case, "
+              "see tests/ and paper_2501_05633_amd.demo)" % ", ".join(
+                  n for n, c in workloads.CONFIGS.items() if c.kind != "linreg"), file=sys.stderr)
+        sys.exit(2)
     cfg = workloads.CONFIGS[args.workload]
     if args.mu is not None:
         cfg = workloads.scaled(cfg, d=cfg.d, k=cfg.k, mu=args.mu)
