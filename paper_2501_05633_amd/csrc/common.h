@@ -47,7 +47,7 @@ struct WorkerCtl {
   uint32_t f_krem;
   uint32_t f_tau;
   uint32_t f_budget;
-  uint32_t err;           // bit 0: selected count != k, bit 1: bad set_state input
+  uint32_t err;           // bit 0: selected count != k, bit 1: bad set_state input, bit 2: the dense selection of this worker was abandoned
   uint32_t tau_prev;      // k-th score of the previous round or kNoBound
   uint32_t centre;        // predicted k-th score of this round (window centre) or kNoBound
   uint32_t err_prev;      // |prediction error| of the previous round
@@ -132,32 +132,54 @@ struct GlobalCtl {
 };
 
 // Barrier across the (co-resident) blocks of the dense-selection kernel.  Every
-// wait is bounded: after kBarrierSpinLimit polls a block gives up, records the
-// fact and carries on, so the grid always drains.
+// wait is bounded: after kBarrierSpinLimit polls a block gives up and records
+// the fact in bar_err (and in *host_err, a word of pinned host memory that the
+// next regtopk_step looks at); the blocks still waiting see bar_err and leave as
+// well.  Returns false, to every thread of the block, when the barrier did not
+// complete: the caller must return without touching memory again, so the grid
+// always drains and nothing is computed from half-finished phases.
 constexpr uint32_t kBarrierSpinLimit = 1u << 22;
 
-__device__ __forceinline__ void grid_barrier(GlobalCtl* g, uint32_t nblocks) {
+__device__ __forceinline__ bool grid_barrier(GlobalCtl* g, uint32_t nblocks, uint32_t* host_err) {
+  __shared__ uint32_t s_ok;
   __syncthreads();
   if (threadIdx.x == 0) {
     __threadfence();
-    const uint32_t gen = __hip_atomic_load(&g->bar_gen, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
-    const uint32_t arrived = atomicAdd(&g->bar_count, 1u) + 1u;
-    if (arrived == nblocks) {
-      __hip_atomic_store(&g->bar_count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __threadfence();
-      atomicAdd(&g->bar_gen, 1u);
+    uint32_t ok = 1;
+    if (__hip_atomic_load(&g->bar_err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+      ok = 0;
     } else {
-      uint32_t spins = 0;
-      // relaxed polls with a pause: an acquiring load per poll makes the hundreds of waiting blocks
-      // slow down the few that work in the one-block-per-worker phases (the fence below orders the exit)
-      while (__hip_atomic_load(&g->bar_gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gen) {
-        __builtin_amdgcn_s_sleep(32);
-        if (++spins > kBarrierSpinLimit) { atomicOr(&g->bar_err, 1u); break; }
+      const uint32_t gen = __hip_atomic_load(&g->bar_gen, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+      const uint32_t arrived = atomicAdd(&g->bar_count, 1u) + 1u;
+      if (arrived == nblocks) {
+        __hip_atomic_store(&g->bar_count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __threadfence();
+        atomicAdd(&g->bar_gen, 1u);
+      } else {
+        uint32_t spins = 0;
+        // relaxed polls with a pause: an acquiring load per poll makes the hundreds of waiting blocks
+        // slow down the few that work in the one-block-per-worker phases (the fence below orders the exit)
+        while (__hip_atomic_load(&g->bar_gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gen) {
+          __builtin_amdgcn_s_sleep(32);
+          ++spins;
+          if ((spins & 63u) == 0 && __hip_atomic_load(&g->bar_err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+            ok = 0;                                      // another block gave up
+            break;
+          }
+          if (spins > kBarrierSpinLimit) {
+            atomicOr(&g->bar_err, 1u);
+            if (host_err) __hip_atomic_store(host_err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            ok = 0;
+            break;
+          }
+        }
       }
     }
+    s_ok = ok;
   }
   __syncthreads();
   __threadfence();
+  return s_ok != 0;
 }
 
 }  // namespace rtk

@@ -32,7 +32,8 @@ k_chunk_count(const WorkerCtl* __restrict__ ctl, const uint32_t* __restrict__ ca
   const bool live = c < nc;
   const size_t tix = (size_t)n * nc + (live ? c : 0);
   const uint32_t tau = ctl[n].tau;
-  const uint32_t off = live ? ch_off[tix] : 0u, cnt = live ? ch_cnt[tix] : 0u;
+  const bool abandoned = (ctl[n].err & 4u) != 0;     // dense selection given up: the lists are not to be read
+  const uint32_t off = live ? ch_off[tix] : 0u, cnt = (live && !abandoned) ? ch_cnt[tix] : 0u;
   const uint32_t* key = cand_key + (size_t)n * cap_total + off;
   uint32_t gt = 0, tie = 0;
   for (uint32_t p0 = 0; p0 < cnt; p0 += kLanesPerChunk * kLaneBatch) {   // trip count uniform within a group of lanes
@@ -115,7 +116,7 @@ k_compact(WorkerCtl* ctl, const uint32_t* __restrict__ cand_key,
   const size_t so = (size_t)n * (nc + 1) + (live ? c : 0);
   if (live) {
     const size_t tix = (size_t)n * nc + c;
-    cnt = ch_cnt[tix];
+    cnt = (ctl[n].err & 4u) ? 0u : ch_cnt[tix];       // nothing is read for a worker whose dense selection was given up
     off = ch_off[tix];
     my_gt = ch_gt[tix];
     my_tie = ch_tie[tix];
@@ -217,7 +218,12 @@ k_aggregate(const int32_t* __restrict__ out_idx, const float* __restrict__ out_v
   __shared__ float s_v[kAggStage];
   __shared__ uint32_t s_s0[32], s_pre[33];
   __shared__ float s_w[32];
+  __shared__ uint32_t s_hot;
   const uint32_t c = blockIdx.x, tid = threadIdx.x;
+  // agg_hot[c] tells whether this tile of the output buffer holds anything but
+  // zeros.  Only thread 0 touches the word: it hands the old value to the block
+  // through LDS here and stores the new one at the end.
+  if (tid == 0) s_hot = agg_hot[c];
   for (uint32_t i = tid; i < kChunk; i += kBlock) s_tile[i] = 0.0f;
   const int32_t jbase = (int32_t)(c << kChunkLog);
   uint32_t any_entries = 0;
@@ -265,9 +271,8 @@ k_aggregate(const int32_t* __restrict__ out_idx, const float* __restrict__ out_v
     }
   }
   __syncthreads();
-  // agg_hot[c] tells whether this tile of the output buffer holds anything but
-  // zeros: a tile no worker selected from is only written if it has to be cleared
-  const uint32_t was_hot = agg_hot[c];
+  // a tile no worker selected from is only written if it has to be cleared
+  const uint32_t was_hot = s_hot;
   if (!any_entries && !was_hot) return;
   if (tid == 0) agg_hot[c] = any_entries ? 1u : 0u;
   const int64_t j0 = (int64_t)c * kChunk;

@@ -282,6 +282,15 @@ __device__ __forceinline__ uint32_t flagged_worker(const WorkerCtl* ctl, int32_t
   return hit;
 }
 
+// A grid barrier did not complete (its blocks were not resident together within
+// the spin limit): the flagged workers' selection is abandoned.  Their error
+// bit makes the counting and compaction kernels skip them and regtopk_get_stats
+// fail; the host-visible word set by the barrier makes the next regtopk_step fail.
+__device__ __forceinline__ void dense_abandon(WorkerCtl* ctl, int32_t N) {
+  for (int32_t n = threadIdx.x; n < N; n += kBlock)
+    if (ctl[n].need_dense) atomicOr(&ctl[n].err, 4u);
+}
+
 // grid (G): G blocks resident together.  See the section header.
 template <bool VEC>
 __global__ void __launch_bounds__(kBlock)
@@ -291,7 +300,8 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
             uint32_t* cand_key,
             const uint32_t* bnd_key, const float* prev_val, const float* gprev, int64_t k, uint32_t nc,
             int32_t N, uint32_t cap_r, uint32_t cap_total, uint32_t regions, uint32_t bnd_cap,
-            const float* omega, float mu, int use_reg, float cand_target, ScoreKind sk) {
+            const float* omega, float mu, int use_reg, float cand_target, ScoreKind sk,
+            uint32_t* host_err) {
   if (gctl->any_dense == 0) return;
   const int roots = sk.roots;
   __shared__ uint32_t s_hist[kL1Bins];
@@ -304,7 +314,7 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
     uint32_t* fh = fhist + (size_t)n * 3 * kL1Bins;
     for (uint32_t i = b * kBlock + tid; i < 3 * kL1Bins; i += G * kBlock) fh[i] = 0;
   }
-  grid_barrier(gctl, G);
+  if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
 
   // The histogram passes give every flagged worker its own group of blocks (all
   // workers at once, each histogram fed by G / n_flagged blocks), so that the
@@ -320,42 +330,42 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
     const uint32_t n = r == grp ? first_worker : flagged_worker(ctl, N, r, &n_flagged, s_w, s_out);
     if (n < (uint32_t)N) dense_hist_worker<1, VEC>(n, sub, sub_cnt, a_rows, d, ctl, fhist, s_hist, roots);
   }
-  grid_barrier(gctl, G);
+  if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (int32_t n = b; n < N; n += G)
     if (ctl[n].need_dense) dense_scan_worker<1>(n, ctl, fhist, k, d, s_a, s_b);
-  grid_barrier(gctl, G);
+  if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (uint32_t r = grp; r < n_flagged; r += groups) {
     const uint32_t n = r == grp ? first_worker : flagged_worker(ctl, N, r, &n_flagged, s_w, s_out);
     if (n < (uint32_t)N) dense_hist_worker<2, VEC>(n, sub, sub_cnt, a_rows, d, ctl, fhist, s_hist, roots);
   }
-  grid_barrier(gctl, G);
+  if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (int32_t n = b; n < N; n += G)
     if (ctl[n].need_dense) dense_scan_worker<2>(n, ctl, fhist, k, d, s_a, s_b);
-  grid_barrier(gctl, G);
+  if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (uint32_t r = grp; r < n_flagged; r += groups) {
     const uint32_t n = r == grp ? first_worker : flagged_worker(ctl, N, r, &n_flagged, s_w, s_out);
     if (n < (uint32_t)N) dense_hist_worker<3, VEC>(n, sub, sub_cnt, a_rows, d, ctl, fhist, s_hist, roots);
   }
-  grid_barrier(gctl, G);
+  if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (int32_t n = b; n < N; n += G)
     if (ctl[n].need_dense) dense_scan_worker<3>(n, ctl, fhist, k, d, s_a, s_b);
-  grid_barrier(gctl, G);
+  if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
 
   for (int32_t n = 0; n < N; ++n) {
     if (!ctl[n].need_dense) continue;
     for (uint32_t c = b; c < nc; c += G) dense_count_chunk<VEC>(n, c, a_rows, d, ctl, ch_gt, ch_tie, nc, s_x, s_y, roots);
   }
-  grid_barrier(gctl, G);
+  if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (int32_t n = b; n < N; n += G)
     if (ctl[n].need_dense) chunk_scan_worker<true, kBlock>(n, ctl, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, nc, k, s_w);
-  grid_barrier(gctl, G);
+  if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (int32_t n = 0; n < N; ++n) {
     if (!ctl[n].need_dense) continue;
     for (uint32_t c = b; c < nc; c += G)
       dense_emit_chunk<VEC>(n, c, a_rows, mask, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, tie_off,
                             prev_sel_off, prev_val, k, nc, cap_total, s_x, s_y, s_a, s_b, roots);
   }
-  grid_barrier(gctl, G);
+  if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
 
   for (int32_t n = 0; n < N; ++n) {
     if (!ctl[n].need_dense) continue;
@@ -365,7 +375,7 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
     for (uint32_t p = b * kBlock + tid; p < total; p += G * kBlock)
       cand_key[cb + p] = score_entry((uint32_t)cand_idx[cb + p], cand_val[cb + p], cand_prev[cb + p], use_reg, gprev, w, mu, sk);
   }
-  grid_barrier(gctl, G);
+  if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (int32_t n = b; n < N; n += G)
     if (ctl[n].need_dense)
       select_worker<true, kBlock>(n, ctl, gctl, cand_key, bnd_key, k, cap_r, cap_total, regions, bnd_cap,

@@ -7,6 +7,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -38,6 +39,23 @@ int fail(int code, const char* fmt, ...) {
 constexpr size_t kAlign = 256;
 size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
+// The dense-selection kernel synchronises its blocks with grid barriers, so all
+// of them must be resident together.  Two such kernels that run at the same
+// time on one device (two contexts driven on two streams) could each be partly
+// resident and wait for each other, so the library keeps them apart: while more
+// than one context lives on a device, every launch of that kernel first waits
+// for the previous one of any other stream (an event per device, re-recorded
+// after each launch).  A lone context pays nothing.
+constexpr int kMaxDevices = 64;
+struct DeviceGate {
+  std::mutex m;
+  int live = 0;                 // user contexts alive on the device
+  hipEvent_t ev = nullptr;      // recorded after the last dense-selection launch
+  hipStream_t last = nullptr;   // its stream
+  bool recorded = false;
+};
+DeviceGate g_gate[kMaxDevices];
+
 struct Layout {
   uint32_t nc, regions, cap_r, cap_total, bnd_cap;
   size_t e, out_idx[2], out_val[2], agg[2], cand_idx, cand_val, cand_key;
@@ -48,22 +66,35 @@ bool valid_sizes(int32_t N, int64_t d, int64_t k) {
   return N >= 1 && N <= 65535 && d >= 1 && d < ((int64_t)1 << 31) && k >= 1 && k <= d;
 }
 
-Layout make_layout(int32_t N, int64_t d, int64_t k) {
+// Lays the arena out.  Every capacity is computed in 64 bits and checked before
+// it is narrowed; returns false (and leaves L.total at 0) when a piece would not
+// fit the 32-bit slot numbers the kernels use.
+bool make_layout(int32_t N, int64_t d, int64_t k, Layout* out) {
   Layout L{};
-  L.nc = (uint32_t)((d + kChunk - 1) / kChunk);
-  uint32_t R = L.nc / 64;
+  *out = L;
+  if (!valid_sizes(N, d, k)) return false;
+  const uint64_t nc = (uint64_t)((d + kChunk - 1) / kChunk);
+  uint64_t R = nc / 64;
   if (R < 1) R = 1;
   if (R > 32) R = 32;
-  L.regions = R;
   // Room for 4k candidates in total (the dense selection needs min(2k,d)),
-  // with a quarter of slack per region for uneven chunk populations.
+  // with a quarter of slack per region for uneven chunk populations -- but never
+  // more than the region's chunks hold entries (chunk c feeds region c % R),
+  // which no sweep can exceed.
   uint64_t want = (uint64_t)4 * (uint64_t)k;
   if (want < 1024) want = 1024;
   uint64_t per = (want + R - 1) / R;
   if (R > 1) per += per / 4;
   per = (per + 63) / 64 * 64;
+  const uint64_t region_max = (nc + R - 1) / R * (uint64_t)kChunk;
+  if (per > region_max) per = region_max;
+  const uint64_t cap_total = per * R;
+  const uint64_t need_dense = (uint64_t)(2 * k < d ? 2 * k : d);
+  if (cap_total > 0xFFFFFFFFull || cap_total < need_dense) return false;
+  L.nc = (uint32_t)nc;
+  L.regions = (uint32_t)R;
   L.cap_r = (uint32_t)per;
-  L.cap_total = (uint32_t)(per * R);
+  L.cap_total = (uint32_t)cap_total;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += up(bytes); return at; };
   const size_t nd = (size_t)N * (size_t)d, nk = (size_t)N * (size_t)k;
@@ -92,7 +123,8 @@ Layout make_layout(int32_t N, int64_t d, int64_t k) {
   L.blk_gt = take(nblk * 4);
   L.blk_tie = take(nblk * 4);
   L.total = o;
-  return L;
+  *out = L;
+  return true;
 }
 
 }  // namespace
@@ -118,6 +150,8 @@ struct regtopk_ctx {
   bool profile;                 // record stage events in every step
   hipEvent_t ev[kProfRounds][5];
   int64_t prof_rounds;          // steps recorded since profiling was switched on
+  uint32_t* host_err;   // pinned host word the dense-selection kernel sets when it abandons a round
+  bool internal;        // the selector of a global Top-k round: always driven on its owner's stream
   regtopk_ctx* gsel;    // global Top-k: a one-row context that selects over the unsparsified aggregate
   float* abar;          // global Top-k: that aggregate, [d]
   char* arena;
@@ -138,6 +172,7 @@ int zero_state(regtopk_ctx* c, hipStream_t s) {
   k_fill_u32<<<1024, 256, 0, s>>>(c->at<uint32_t>(c->L.mask), (size_t)c->N * c->L.nc * kChunkWords, 0u);
   k_init_ctl<<<c->N, 256, 0, s>>>(c->at<WorkerCtl>(c->L.ctl));
   k_fill_u32<<<1, 64, 0, s>>>(c->at<uint32_t>(c->L.gctl), sizeof(GlobalCtl) / 4, 0u);
+  k_fill_u32<<<1, 64, 0, s>>>(c->host_err, 1, 0u);      // (pinned host memory, cleared in stream order)
   HIP_TRY(hipGetLastError());
   c->t = 0;
   c->have_prev = false;
@@ -145,10 +180,20 @@ int zero_state(regtopk_ctx* c, hipStream_t s) {
   return REGTOPK_OK;
 }
 
+// Removes a context from its device's count of live contexts.
+void gate_leave(regtopk_ctx* c) {
+  if (c->internal || c->device < 0 || c->device >= kMaxDevices) return;
+  DeviceGate& g = g_gate[c->device];
+  std::lock_guard<std::mutex> lock(g.m);
+  g.live -= 1;
+}
+
 int create_common(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu, void* arena,
-                  size_t bytes, bool owns, hipStream_t s) {
+                  size_t bytes, bool owns, hipStream_t s, bool internal = false) {
   regtopk_ctx* c = new (std::nothrow) regtopk_ctx;
   if (!c) return fail(REGTOPK_NO_MEMORY, "out of host memory");
+  c->internal = internal;
+  c->host_err = nullptr;
   c->N = N; c->d = d; c->k = k; c->mu = mu;
   c->owns_arena = owns;
   c->force_dense = 0;
@@ -161,8 +206,7 @@ int create_common(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu, 
   c->profile = false;
   c->prof_rounds = 0;
   c->arena = static_cast<char*>(arena);
-  c->L = make_layout(N, d, k);
-  (void)bytes;
+  if (!make_layout(N, d, k, &c->L) || bytes < c->L.total) { delete c; return fail(REGTOPK_INVALID_ARG, "sizes have no valid layout"); }
   if (hipGetDevice(&c->device) != hipSuccess) { delete c; return fail(REGTOPK_HIP_ERROR, "hipGetDevice failed"); }
   int cus = 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess || cus < 1) {
@@ -172,17 +216,49 @@ int create_common(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu, 
   // All blocks of the dense-selection kernel must be resident together (it
   // synchronises them with grid barriers): stay one block per compute unit below
   // what the occupancy calculator allows, at most 3 per unit.
-  int per_cu = 0;
-  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_dense_all<true>, kBlock, 0) != hipSuccess || per_cu < 1) {
+  int per_cu = 0, per_cu_scalar = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_dense_all<true>, kBlock, 0) != hipSuccess || per_cu < 1 ||
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu_scalar, k_dense_all<false>, kBlock, 0) != hipSuccess || per_cu_scalar < 1) {
     delete c;
     return fail(REGTOPK_HIP_ERROR, "cannot query the occupancy of the dense-selection kernel");
   }
+  if (per_cu_scalar < per_cu) per_cu = per_cu_scalar;       // either instantiation may be the one launched
   per_cu = per_cu - 1 < 1 ? 1 : (per_cu - 1 > 3 ? 3 : per_cu - 1);
   c->dense_blocks = per_cu * cus;
+  if (c->device >= kMaxDevices) { delete c; return fail(REGTOPK_INVALID_ARG, "device index %d not supported", c->device); }
+  // one word of pinned host memory through which an abandoned dense selection reaches the next step
+  void* hp = nullptr;
+  if (hipHostMalloc(&hp, 64, hipHostMallocDefault) != hipSuccess) {
+    (void)hipGetLastError();
+    delete c;
+    return fail(REGTOPK_NO_MEMORY, "hipHostMalloc of the error word failed");
+  }
+  c->host_err = static_cast<uint32_t*>(hp);
+  *c->host_err = 0;
+  if (!internal) {
+    // from the second live context on, dense-selection launches are chained by the device's event;
+    // the launches made so far were not recorded, so let them finish first
+    DeviceGate& g = g_gate[c->device];
+    std::lock_guard<std::mutex> lock(g.m);
+    if (g.live >= 1) {
+      if (!g.ev && hipEventCreateWithFlags(&g.ev, hipEventDisableTiming) != hipSuccess) {
+        (void)hipHostFree(hp);
+        delete c;
+        return fail(REGTOPK_HIP_ERROR, "hipEventCreateWithFlags failed");
+      }
+      if (hipDeviceSynchronize() != hipSuccess) {
+        (void)hipHostFree(hp);
+        delete c;
+        return fail(REGTOPK_HIP_ERROR, "hipDeviceSynchronize failed");
+      }
+      g.recorded = false;
+    }
+    g.live += 1;
+  }
   k_fill_u32<<<1, 256, 0, s>>>(c->at<uint32_t>(c->L.omega), (size_t)N, __builtin_bit_cast(uint32_t, 1.0f / (float)N));
   int rc = zero_state(c, s);
   if (rc == REGTOPK_OK && hipStreamSynchronize(s) != hipSuccess) rc = fail(REGTOPK_HIP_ERROR, "zeroing the state failed");
-  if (rc != REGTOPK_OK) { delete c; return rc; }
+  if (rc != REGTOPK_OK) { gate_leave(c); (void)hipHostFree(c->host_err); delete c; return rc; }
   *out = c;
   return REGTOPK_OK;
 }
@@ -203,14 +279,16 @@ extern "C" {
 const char* regtopk_last_error(void) { return g_err; }
 
 size_t regtopk_workspace_bytes(int32_t N, int64_t d, int64_t k) {
-  if (!valid_sizes(N, d, k)) return 0;
-  return make_layout(N, d, k).total;
+  Layout L;
+  return make_layout(N, d, k, &L) ? L.total : 0;
 }
 
 int regtopk_create(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu) {
   int rc = check_create_args(out, N, d, k, mu);
   if (rc) return rc;
-  const size_t bytes = make_layout(N, d, k).total;
+  Layout L;
+  if (!make_layout(N, d, k, &L)) return fail(REGTOPK_INVALID_ARG, "sizes have no valid layout");
+  const size_t bytes = L.total;
   void* p = nullptr;
   if (hipMalloc(&p, bytes) != hipSuccess) {
     (void)hipGetLastError();
@@ -227,7 +305,9 @@ int regtopk_create_in(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float 
   if (rc) return rc;
   if (!arena_dev) return fail(REGTOPK_INVALID_ARG, "arena_dev is NULL");
   if (reinterpret_cast<uintptr_t>(arena_dev) % kAlign) return fail(REGTOPK_INVALID_ARG, "arena_dev must be 256-byte aligned");
-  const size_t need = make_layout(N, d, k).total;
+  Layout L;
+  if (!make_layout(N, d, k, &L)) return fail(REGTOPK_INVALID_ARG, "sizes have no valid layout");
+  const size_t need = L.total;
   if (arena_bytes < need) return fail(REGTOPK_NO_MEMORY, "arena has %zu bytes, %zu needed", arena_bytes, need);
   return create_common(out, N, d, k, mu, arena_dev, arena_bytes, false, static_cast<hipStream_t>(stream));
 }
@@ -240,6 +320,8 @@ int regtopk_destroy(regtopk_ctx* c) {
   if (c->gsel && regtopk_destroy(c->gsel) != REGTOPK_OK) rc = REGTOPK_HIP_ERROR;
   if (c->abar && hipFree(c->abar) != hipSuccess) rc = fail(REGTOPK_HIP_ERROR, "hipFree failed");
   if (c->owns_arena && hipFree(c->arena) != hipSuccess) rc = fail(REGTOPK_HIP_ERROR, "hipFree failed");
+  if (c->host_err && hipHostFree(c->host_err) != hipSuccess) rc = fail(REGTOPK_HIP_ERROR, "hipHostFree failed");
+  gate_leave(c);
   delete c;
   return rc;
 }
@@ -289,6 +371,9 @@ namespace {
 template <typename G>
 int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, regtopk_result* out) {
   if (!c || !grads || !out) return fail(REGTOPK_INVALID_ARG, "ctx, grads_dev and out must not be NULL");
+  if (*static_cast<volatile uint32_t*>(c->host_err) != 0)
+    return fail(REGTOPK_BAD_STATE, "an earlier round abandoned its dense selection (its blocks were not resident "
+                                   "together); the state is undefined until regtopk_reset or regtopk_set_state");
   const int use_reg = (c->have_prev && c->mu > 0.0f) ? 1 : 0;
   if (use_reg && !gprev) return fail(REGTOPK_INVALID_ARG, "prev_aggregate_dev is required after round 0 when mu > 0");
   if (reinterpret_cast<uintptr_t>(grads) % sizeof(G) || reinterpret_cast<uintptr_t>(gprev) % 4)
@@ -363,10 +448,25 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
   k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_prev, cand_key, bnd_key, gprev, d, L.cap_r, L.cap_total, L.bnd_cap, omega, c->mu, use_reg, sk);
   k_select<<<N, kScanBlock, 0, s>>>(ctl, gctl, cand_key, bnd_key, k, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->cand_target, c->force_dense);
   // dense selection for the workers whose speculation failed; returns at once if there is none
-  if (vec)
-    k_dense_all<true><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, prev_sel_off, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_prev, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, omega, c->mu, use_reg, c->cand_target, sk);
-  else
-    k_dense_all<false><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, prev_sel_off, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_prev, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, omega, c->mu, use_reg, c->cand_target, sk);
+  {
+    DeviceGate* gate = c->internal ? nullptr : &g_gate[c->device];
+    std::unique_lock<std::mutex> lock;
+    bool chain = false;
+    if (gate) {
+      lock = std::unique_lock<std::mutex>(gate->m);
+      chain = gate->live > 1;
+      if (chain && gate->recorded && gate->last != s) HIP_TRY(hipStreamWaitEvent(s, gate->ev, 0));
+    }
+    if (vec)
+      k_dense_all<true><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, prev_sel_off, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_prev, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, omega, c->mu, use_reg, c->cand_target, sk, c->host_err);
+    else
+      k_dense_all<false><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, prev_sel_off, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_prev, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, omega, c->mu, use_reg, c->cand_target, sk, c->host_err);
+    if (chain) {
+      HIP_TRY(hipEventRecord(gate->ev, s));
+      gate->last = s;
+      gate->recorded = true;
+    }
+  }
 
   // ordered compaction, error update, aggregation
   if (ev) HIP_TRY(hipEventRecord(ev[2], s));
@@ -406,8 +506,15 @@ int regtopk_step_global(regtopk_ctx* c, const float* grads, void* stream, regtop
   if (!c->gsel) {
     // first use: the selector over the aggregate (one row, plain Top-k) and the aggregate itself
     regtopk_ctx* g = nullptr;
-    int rc = regtopk_create(&g, 1, c->d, c->k, 0.0f);
-    if (rc != REGTOPK_OK) return rc;
+    Layout GL;
+    if (!make_layout(1, c->d, c->k, &GL)) return fail(REGTOPK_INVALID_ARG, "sizes have no valid layout");
+    void* ga = nullptr;
+    if (hipMalloc(&ga, GL.total) != hipSuccess) {
+      (void)hipGetLastError();
+      return fail(REGTOPK_NO_MEMORY, "hipMalloc of %zu bytes failed", GL.total);
+    }
+    int rc = create_common(&g, 1, c->d, c->k, 0.0f, ga, GL.total, true, s, true);
+    if (rc != REGTOPK_OK) { (void)hipFree(ga); return rc; }
     void* p = nullptr;
     if (hipMalloc(&p, (size_t)c->d * 4) != hipSuccess) {
       (void)hipGetLastError();
@@ -480,7 +587,9 @@ int regtopk_set_state(regtopk_ctx* c, const float* e_dev, const int32_t* pidx_de
   hipStream_t s = static_cast<hipStream_t>(stream);
   const size_t nd = (size_t)c->N * (size_t)c->d, nk = (size_t)c->N * (size_t)c->k;
   k_copy_u32<<<2048, 256, 0, s>>>(c->at<uint32_t>(c->L.e), reinterpret_cast<const uint32_t*>(e_dev), nd);
-  k_init_ctl<<<c->N, 256, 0, s>>>(c->at<WorkerCtl>(c->L.ctl));     // no speculative bound: next round selects densely
+  k_init_ctl<<<c->N, 256, 0, s>>>(c->at<WorkerCtl>(c->L.ctl));     // no bound is carried over: the next rounds sample theirs
+  k_fill_u32<<<1, 64, 0, s>>>(c->at<uint32_t>(c->L.gctl), sizeof(GlobalCtl) / 4, 0u);
+  k_fill_u32<<<1, 64, 0, s>>>(c->host_err, 1, 0u);
   c->t = t;
   c->have_prev = t > 0;
   c->fresh = kFreshRounds;

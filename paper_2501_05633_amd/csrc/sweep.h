@@ -8,7 +8,7 @@ namespace rtk {
 __global__ void __launch_bounds__(kBlock)
 k_begin(WorkerCtl* ctl, GlobalCtl* gctl, int force_dense, int roots) {
   const uint32_t n = blockIdx.x, tid = threadIdx.x;
-  if (n == 0 && tid == 0) gctl->any_dense = 0;
+  if (n == 0 && tid == 0) { gctl->any_dense = 0; gctl->bar_count = 0; }   // (arrivals of an abandoned barrier are dropped)
   WorkerCtl& c = ctl[n];
   if (tid < kMaxRegions) c.cursor[tid] = 0;
   if (tid == 0) {

@@ -42,6 +42,32 @@ def test_workspace_bytes_host_logic(lib):
     assert 16 * 25_600_000 * 4 < big < 3 * 16 * 25_600_000 * 4
 
 
+def test_workspace_bytes_grows_with_k_and_never_wraps(lib):
+    # the candidate capacity is a 32-bit slot count inside the kernels: for every k up to d = 2^31 - 1
+    # the layout must be computed without wrapping (it once was 4k + 25 % truncated to 32 bits)
+    N, d = 1, 2 ** 31 - 1
+    ks = [1, 1000, 10 ** 6, 10 ** 8, 5 * 10 ** 8, 8 * 10 ** 8, 858_993_459, 858_993_460, 9 * 10 ** 8,
+          10 ** 9, 2 ** 30, 2 ** 30 + 1, 2 * 10 ** 9, d - 1, d]
+    sizes = [binding.workspace_bytes(N, d, k) for k in ks]
+    assert all(b > 0 for b in sizes)
+    assert all(b1 >= b0 for b0, b1 in zip(sizes, sizes[1:])), list(zip(ks, sizes))
+    for k, b in zip(ks, sizes):
+        # state, double-buffered index/value lists, and four words per slot of a candidate list that
+        # holds at least the min(2k, d) entries of the dense selection
+        assert b >= 4 * N * d + 16 * N * k + 16 * N * min(2 * k, d), (k, b)
+    # k = d: every entry can be a candidate once; the arena stays a small multiple of the state
+    assert sizes[-1] <= 12 * 4 * N * d
+    for N, d in ((3, 4096 * 7 + 5), (16, 25_600_000), (4, 124_000_000), (5, 1), (2, 4096)):
+        prev = 0
+        for k in sorted({1, 2, d // 1000 + 1, d // 100 + 1, d // 10 + 1, d // 4, d // 4 + 1, d // 2 + 1, d - 1, d} - {0}):
+            if k > d:
+                continue
+            b = binding.workspace_bytes(N, d, k)
+            assert b >= prev and b >= 4 * N * d + 16 * N * k, (N, d, k, b)
+            assert b <= 12 * 4 * N * d + (1 << 22) * N, (N, d, k, b)
+            prev = b
+
+
 def test_product_path_refuses_to_run_without_gpu(lib):
     import torch
     if torch.cuda.is_available():

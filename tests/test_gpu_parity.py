@@ -43,7 +43,7 @@ def test_linear_regression_closed_loop():
             theta = theta - wl.eta * agg
         return wl.grads(theta)
 
-    stats, tol = run_both(cfg.N, cfg.d, cfg.k, cfg.mu, fn, 12, label="linreg", check_state_every=4)
+    stats, tol = run_both(cfg.N, cfg.d, cfg.k, cfg.mu, fn, cfg.T, label="linreg", check_state_every=10)
     assert tol == 0
 
 
@@ -285,4 +285,38 @@ def test_caller_owned_previous_aggregate_and_two_contexts_on_two_streams():
         torch.cuda.synchronize()
         for x, y, z in zip(r0, ra, rb):
             assert torch.equal(x, y) and torch.equal(x, z)
+    ref.close(); a.close(); b.close()
+
+
+def test_two_contexts_on_two_streams_with_the_dense_selection_forced():
+    # the dense selection synchronises its blocks with grid barriers; launches of different contexts
+    # on one device are kept apart by the library, so two streams that both take it in every round
+    # must give what a single context gives
+    cfg = workloads.scaled(workloads.CONFIGS["large_cnn"], d=300_000, N=2, k=3_000)
+    wl = workloads.Workload(cfg, DEV)
+    ref = binding.RegTopk(2, 300_000, 3_000, 1.0, device=DEV)
+    a = binding.RegTopk(2, 300_000, 3_000, 1.0, device=DEV)
+    b = binding.RegTopk(2, 300_000, 3_000, 1.0, device=DEV)
+    for r in (ref, a, b):
+        r.set_option(binding.OPT_FORCE_DENSE, 1)
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    agg_ref = agg_a = agg_b = None
+    for t in range(4):
+        print("  round %d" % t, flush=True)
+        g = wl.grads(t)
+        torch.cuda.synchronize()
+        r0 = [x.clone() for x in ref.step(g, agg_ref)]
+        agg_ref = r0[2]
+        torch.cuda.synchronize()
+        with torch.cuda.stream(sa):
+            ra = a.step(g, agg_a)
+            agg_a = ra[2].clone()
+        with torch.cuda.stream(sb):
+            rb = b.step(g, agg_b)
+            agg_b = rb[2].clone()
+        torch.cuda.synchronize()
+        for x, y, z in zip(r0, ra, rb):
+            assert torch.equal(x, y) and torch.equal(x, z)
+        for r in (a, b):
+            assert all(w["used_dense"] == 1 for w in r.stats())
     ref.close(); a.close(); b.close()

@@ -350,3 +350,24 @@ def test_low_dimensional_study_regtopk_tracks_the_unsparsified_run_where_topk_st
         tracked_top += _lowdim_log_gap(seed, 3, 0.0) < d + track
         tracked_reg += min(_lowdim_log_gap(seed, 3, mu) for mu in (0.25, 0.5, 1.0, 2.0, 5.0)) < d + track
     assert tracked_reg >= 8 and tracked_top <= 4                       # mu is tuned per problem, as in the paper
+
+
+def test_linear_regression_n20_what_the_oracle_reproduces_of_the_papers_claims():
+    # Section "Linear Regression Problem" (N = 20, J = 100, D_n = 500, eta = 1e-2, S = 0.6).
+    # Reproduced, and pinned here: with identical ground truths and no label noise (figure
+    # "Homogeneity vs heterogeneity", left) Top-k and RegTop-k both track the unsparsified run; with
+    # heterogeneous workers (sigma^2 = 5) Top-k stays at a fixed distance from the optimum, orders of
+    # magnitude above the unsparsified run.  NOT reproduced by this reading of Algorithm 2 for any mu
+    # on a grid 1e-3 .. 1e2 (oracle/linreg_study.py; table in the design document): RegTop-k reaching
+    # the unsparsified gap in the heterogeneous case -- that claim stays "parity unpinned".
+    from oracle import linreg_study as ls
+    T = 1500
+    dense_h = ls.run(0, 1.0, 0.0, homogeneous=True, T=T)
+    topk_h = ls.run(0, 0.6, 0.0, homogeneous=True, T=T)
+    reg_h = ls.run(0, 0.6, 1.0, homogeneous=True, T=T)
+    assert dense_h < 1e-3 and topk_h < 3 * dense_h and reg_h < 3 * dense_h, (dense_h, topk_h, reg_h)
+    dense = ls.run(0, 1.0, 0.0, T=T)
+    topk = ls.run(0, 0.6, 0.0, T=T)
+    assert dense < 1e-3 and topk > 100 * dense, (dense, topk)
+    # Top-k has stalled, not merely slowed down: 1000 more iterations change nothing
+    assert abs(ls.run(0, 0.6, 0.0, T=T + 1000) - topk) < 0.3 * topk
