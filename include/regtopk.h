@@ -176,6 +176,18 @@ int regtopk_set_weights(regtopk_ctx* ctx, const float* weights_host, void* strea
  * the first round.  Enqueued on `stream`. */
 int regtopk_mask_overlap(regtopk_ctx* ctx, int64_t* counts_dev, void* stream);
 
+/* regtopk_mask_overlap for callers that must not allocate or touch the context's
+ * scratch areas while they run: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same inputs, same result in
+ * counts_dev, but the per-block partial counts go to a 4 MiB array that is
+ * part of the library image on every GPU (no hipMalloc, hipFree or other
+ * allocating call is made, and the context's arena is only read).  Limits:
+ * N <= 1023 workers (REGTOPK_INVALID_ARG otherwise, with a message that says
+ * so), and the context's device must be current.  All calls on one GPU share
+ * that array: calls that overlap in time on one GPU (two streams) race and
+ * give undefined counts; calls on one stream, or ordered by events, are fine. */
+int regtopk_mask_overlap_static(regtopk_ctx* ctx, int64_t* counts_dev, void* stream);
+
 /* Model update of distributed SGD (paper: introduction, theta^{t+1} = theta^t -
  * eta^t g^t): theta_dev[j] <- theta_dev[j] - eta * g_dev[j] for j in [0,d),
  * binary32, the product rounded before the subtraction (no fused multiply-add).

@@ -22,7 +22,7 @@ SYMBOLS = [
     "regtopk_workspace_bytes", "regtopk_create", "regtopk_create_in", "regtopk_step", "regtopk_step_bf16", "regtopk_step_global",
     "regtopk_destroy", "regtopk_reset", "regtopk_get_state", "regtopk_set_state",
     "regtopk_get_stats", "regtopk_set_option", "regtopk_get_timings", "regtopk_tanh_f32",
-    "regtopk_copy_f32", "regtopk_set_weights", "regtopk_mask_overlap", "regtopk_sgd_update",
+    "regtopk_copy_f32", "regtopk_set_weights", "regtopk_mask_overlap", "regtopk_mask_overlap_static", "regtopk_sgd_update",
     "regtopk_last_error",
 ]
 
@@ -76,6 +76,7 @@ def load():
     lib.regtopk_tanh_f32.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
     lib.regtopk_set_weights.argtypes = [c_void_p, ctypes.POINTER(c_float), c_void_p]
     lib.regtopk_mask_overlap.argtypes = [c_void_p, c_void_p, c_void_p]
+    lib.regtopk_mask_overlap_static.argtypes = [c_void_p, c_void_p, c_void_p]
     lib.regtopk_sgd_update.argtypes = [c_void_p, c_void_p, c_float, c_int64, c_void_p]
     lib.regtopk_last_error.restype = c_char_p
     _lib = lib
@@ -213,6 +214,16 @@ class RegTopk:
         counts = torch.empty(self.N + 1, dtype=torch.int64, device=self.device)
         with torch.cuda.device(self.device):
             _check(self.lib.regtopk_mask_overlap(self._h, c_void_p(counts.data_ptr()), _stream_ptr(torch)))
+        return counts
+
+    def mask_overlap_static(self, counts):
+        """``mask_overlap`` into the caller's int64 [N+1] CUDA tensor through the entry point that allocates nothing."""
+        torch = self._torch
+        if counts.dtype != torch.int64 or counts.numel() != self.N + 1 or counts.device != self.device \
+                or not counts.is_contiguous():
+            raise ValueError("counts must be a contiguous int64 [N+1] tensor on %s" % self.device)
+        with torch.cuda.device(self.device):
+            _check(self.lib.regtopk_mask_overlap_static(self._h, c_void_p(counts.data_ptr()), _stream_ptr(torch)))
         return counts
 
     def set_option(self, option: int, value: float):

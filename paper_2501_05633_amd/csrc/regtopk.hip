@@ -56,6 +56,17 @@ struct DeviceGate {
 };
 DeviceGate g_gate[kMaxDevices];
 
+// Scratch of regtopk_mask_overlap_static: per-block histograms of the overlap
+// count, kStaticOverlapBlocks rows of kOverlapBins words (4 MiB).  Every GPU
+// holds its own copy of the array until the process ends.  In host code the
+// name `g_overlap_scratch` is only a handle for hipGetSymbolAddress; the
+// address the kernels get is looked up once per device and kept in
+// g_overlap_ptr.
+constexpr uint32_t kStaticOverlapBlocks = 1024;
+static __device__ __align__(256) uint32_t g_overlap_scratch[kStaticOverlapBlocks * kOverlapBins];
+std::mutex g_overlap_mutex;
+uint32_t* g_overlap_ptr[kMaxDevices] = {};
+
 struct Layout {
   uint32_t nc, regions, cap_r, cap_total, bnd_cap;
   size_t e, out_idx[2], out_val[2], agg[2], cand_idx, cand_val, cand_key;
@@ -670,6 +681,41 @@ int regtopk_mask_overlap(regtopk_ctx* c, int64_t* counts_dev, void* stream) {
   if (!staged) k_fill_u32<<<64, 256, 0, s>>>(reinterpret_cast<uint32_t*>(counts_dev), 2 * ((size_t)c->N + 1), 0u);
   k_mask_overlap<<<(uint32_t)blocks, kBlock, 0, s>>>(c->at<uint32_t>(c->L.mask), c->d, c->L.nc, c->N, planes, counts, partial);
   if (staged) k_overlap_sum<<<(uint32_t)c->N + 1u, kBlock, 0, s>>>(partial, (uint32_t)blocks, c->N, counts);
+  HIP_TRY(hipGetLastError());
+  return REGTOPK_OK;
+}
+
+int regtopk_mask_overlap_static(regtopk_ctx* c, int64_t* counts_dev, void* stream) {
+  if (!c || !counts_dev) return fail(REGTOPK_INVALID_ARG, "ctx and counts_dev must not be NULL");
+  if (reinterpret_cast<uintptr_t>(counts_dev) % 8) return fail(REGTOPK_INVALID_ARG, "counts_dev must be 8-byte aligned");
+  if ((uint32_t)c->N + 1u > kOverlapBins)
+    return fail(REGTOPK_INVALID_ARG, "regtopk_mask_overlap_static handles at most %u workers (N = %d); use regtopk_mask_overlap",
+                kOverlapBins - 1u, c->N);
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev != c->device) return fail(REGTOPK_INVALID_ARG, "the context lives on device %d, the current device is %d", c->device, dev);
+  uint32_t* scratch = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_overlap_mutex);
+    if (!g_overlap_ptr[dev]) {
+      void* p = nullptr;
+      HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(g_overlap_scratch)));     // this device's copy of the array
+      g_overlap_ptr[dev] = static_cast<uint32_t*>(p);
+    }
+    scratch = g_overlap_ptr[dev];
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int planes = 1;
+  while ((1 << planes) <= c->N) ++planes;
+  const size_t nw = (size_t)((c->d + 31) / 32);
+  size_t blocks = (nw + kBlock - 1) / kBlock;
+  if (blocks > kStaticOverlapBlocks) blocks = kStaticOverlapBlocks;
+  // Nothing has to be cleared: every block writes all N + 1 words of its row of the scratch before
+  // k_overlap_sum reads exactly those rows, so what an earlier call left behind is never read.
+  k_mask_overlap<<<(uint32_t)blocks, kBlock, 0, s>>>(c->at<uint32_t>(c->L.mask), c->d, c->L.nc, c->N, planes,
+                                                     reinterpret_cast<unsigned long long*>(counts_dev), scratch);
+  k_overlap_sum<<<(uint32_t)c->N + 1u, kBlock, 0, s>>>(scratch, (uint32_t)blocks, c->N,
+                                                      reinterpret_cast<unsigned long long*>(counts_dev));
   HIP_TRY(hipGetLastError());
   return REGTOPK_OK;
 }
