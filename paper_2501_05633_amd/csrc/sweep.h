@@ -95,7 +95,7 @@ __device__ __forceinline__ f32x4 grad4_at(const bf16_t* g, size_t i) {
 template <bool VEC, typename G>
 __global__ void __launch_bounds__(kBlock)
 k_accum_emit(float* __restrict__ e, const G* __restrict__ g, const uint32_t* __restrict__ mask,
-             const uint32_t* __restrict__ prev_sel_off, int64_t d, WorkerCtl* __restrict__ ctl,
+             int64_t d, WorkerCtl* __restrict__ ctl,
              int32_t* __restrict__ cand_idx,
              float* __restrict__ cand_val, float* __restrict__ cand_prev, uint32_t* __restrict__ ch_off,
              uint32_t* __restrict__ ch_cnt, uint32_t nc, uint32_t cap_r, uint32_t cap_total,
@@ -110,25 +110,22 @@ k_accum_emit(float* __restrict__ e, const G* __restrict__ g, const uint32_t* __r
   float a[4][4];
   float eo[4][4];       // what the state held: a^{t-1} where the entry was sent, the error elsewhere
   uint32_t flags = 0;
-  // previous round's mask: the 4 bits of entries j0..j0+3 lie in one word
-  // (chunks from which nothing was sent have no mask bits: their words are not read)
+  // previous round's mask: the 4 bits of entries j0..j0+3 lie in one word.  The
+  // words are read unconditionally, together with the state and the gradients
+  // (chunks from which nothing was sent hold zeros), so no load waits for another.
   const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
-  const bool sent_any = prev_sel_off[(size_t)n * (nc + 1) + c + 1] != prev_sel_off[(size_t)n * (nc + 1) + c];
   uint32_t mb[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int64_t j0 = base + i * 256;
-    mb[i] = (sent_any && j0 < d) ? (mrow[j0 >> 5] >> (j0 & 31)) & 15u : 0u;
-  }
   if (VEC) {
     f32x4 ev[4], gv[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int64_t j0 = base + i * 256;
       if (j0 < d) {
+        mb[i] = (mrow[j0 >> 5] >> (j0 & 31)) & 15u;
         ev[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(e + row + j0));
         gv[i] = grad4_at(g, row + j0);
       } else {
+        mb[i] = 0;
         ev[i] = f32x4{0.f, 0.f, 0.f, 0.f};
         gv[i] = ev[i];
       }
@@ -156,9 +153,11 @@ k_accum_emit(float* __restrict__ e, const G* __restrict__ g, const uint32_t* __r
   } else {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
+      const int64_t j0 = base + i * 256;
+      mb[i] = j0 < d ? (mrow[j0 >> 5] >> (j0 & 31)) & 15u : 0u;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int64_t j = base + i * 256 + q;
+        const int64_t j = j0 + q;
         a[i][q] = 0.f;
         eo[i][q] = 0.f;
         if (j < d) {
