@@ -54,6 +54,8 @@ struct WorkerCtl {
   float margin_scale;     // widens the bound's safety margin after a failed speculation
   uint32_t extrapolated;  // this round's prediction used the drift of two earlier rounds
   uint32_t tau_lo_mag;    // smallest |a| bit pattern whose prior reaches tau_lo (= tau_lo for the plain prior)
+  // diagnostics of the last completed round, copied before the counters are cleared for the next one
+  uint32_t snap_tau_lo, snap_n_cand, snap_used_dense, snap_overflow, snap_used_window, snap_n_bnd, snap_n_valid, snap_win_half;
   uint32_t pad[3];
   uint32_t cursor[kMaxRegions];
 };

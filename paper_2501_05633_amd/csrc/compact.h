@@ -80,7 +80,7 @@ constexpr uint32_t kCompactLanes = 32;
 
 template <uint32_t LPC>
 __global__ void __launch_bounds__(kBlock)
-k_compact(WorkerCtl* ctl, const uint32_t* __restrict__ cand_key,
+k_compact(WorkerCtl* ctl, GlobalCtl* gctl, const uint32_t* __restrict__ cand_key,
           const int32_t* __restrict__ cand_idx, const float* __restrict__ cand_val,
           const uint32_t* __restrict__ ch_off, const uint32_t* __restrict__ ch_cnt,
           const uint32_t* __restrict__ ch_gt, const uint32_t* __restrict__ ch_tie,
@@ -88,7 +88,7 @@ k_compact(WorkerCtl* ctl, const uint32_t* __restrict__ cand_key,
           uint32_t* __restrict__ sel_off, const uint32_t* __restrict__ prev_sel_off,
           int32_t* __restrict__ out_idx,
           float* __restrict__ out_val, uint32_t* __restrict__ mask,
-          int64_t k, uint32_t nc, uint32_t cap_total) {
+          int64_t k, uint32_t nc, uint32_t cap_total, int next_force_dense, int next_roots) {
   constexpr uint32_t kCPW = 64 / LPC, kCPB = (kBlock / 64) * kCPW;
   static_assert(kChunksPerBlock % kCPB == 0, "a compaction block must lie inside one counting block");
   static_assert(kChunksPerBlock <= LPC, "one load per lane must cover the chunks of a counting block");
@@ -183,6 +183,27 @@ k_compact(WorkerCtl* ctl, const uint32_t* __restrict__ cand_key,
     }
   }
   __syncthreads();
+  // The first block of a worker also prepares its control block for the next
+  // round (what k_begin does after a start without history): a snapshot of the
+  // round's diagnostics, cursors and counters cleared, the next bound and window
+  // loaded.  No later kernel of the round and no other block of this one reads
+  // what is cleared here (they read tau, budget and err).
+  if (blockIdx.x == 0) {
+    WorkerCtl& wc = ctl[n];
+    if (threadIdx.x < kMaxRegions) wc.cursor[threadIdx.x] = 0;
+    if (threadIdx.x == 0) {
+      wc.snap_tau_lo = wc.tau_lo;
+      wc.snap_n_cand = wc.need_dense ? wc.dense_total : wc.n_cand;
+      wc.snap_used_dense = wc.need_dense;
+      wc.snap_overflow = wc.overflow;
+      wc.snap_used_window = wc.used_window;
+      wc.snap_n_bnd = wc.n_bnd;
+      wc.snap_n_valid = wc.n_valid;
+      wc.snap_win_half = wc.win_lo == kNoBound ? 0u : (wc.win_hi - wc.win_lo) / 2;
+      begin_round(wc, next_force_dense, next_roots);
+      if (n == 0) { gctl->any_dense = 0; gctl->bar_count = 0; }
+    }
+  }
   // a chunk without selected entries in the previous round has all-zero mask
   // words already: nothing to write if it has none now either
   if (live && !(was_empty && is_empty)) {

@@ -157,6 +157,7 @@ struct regtopk_ctx {
   int prior_roots;      // prior |a|^(2^-prior_roots)
   int likelihood;       // 0 tanh, 1 clipped linear
   bool reinit_ctl;      // the score space changed: drop the bounds carried over from earlier rounds
+  bool need_begin;      // the control blocks are not prepared for the next round (k_begin must run)
   float cand_target;
   bool profile;                 // record stage events in every step
   hipEvent_t ev[kProfRounds][5];
@@ -188,6 +189,7 @@ int zero_state(regtopk_ctx* c, hipStream_t s) {
   c->t = 0;
   c->have_prev = false;
   c->fresh = kFreshRounds;
+  c->need_begin = true;
   return REGTOPK_OK;
 }
 
@@ -345,7 +347,10 @@ int regtopk_reset(regtopk_ctx* c, void* stream) {
 int regtopk_set_option(regtopk_ctx* c, int option, double value) {
   if (!c) return fail(REGTOPK_INVALID_ARG, "ctx is NULL");
   switch (option) {
-    case REGTOPK_OPT_FORCE_DENSE: c->force_dense = value != 0.0; return REGTOPK_OK;
+    case REGTOPK_OPT_FORCE_DENSE:
+      if ((value != 0.0) != (c->force_dense != 0)) c->need_begin = true;
+      c->force_dense = value != 0.0;
+      return REGTOPK_OK;
     case REGTOPK_OPT_CAND_TARGET:
       if (!(value > 1.0 && value <= 3.0)) return fail(REGTOPK_INVALID_ARG, "candidate target must be in (1, 3]");
       c->cand_target = (float)value;
@@ -429,8 +434,12 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
   if (c->reinit_ctl) {
     k_init_ctl<<<N, 256, 0, s>>>(ctl);
     c->reinit_ctl = false;
+    c->need_begin = true;
   }
-  k_begin<<<N, kBlock, 0, s>>>(ctl, gctl, c->force_dense, sk.roots);
+  if (c->need_begin) {          // otherwise the last kernel of the previous round has done this
+    k_begin<<<N, kBlock, 0, s>>>(ctl, gctl, c->force_dense, sk.roots);
+    c->need_begin = false;
+  }
   if (c->fresh > 0 && !c->force_dense) {
     // No bound from a previous round, or only the guess of a controller that has
     // not seen two rounds yet (from an empty error state the k-th score grows by
@@ -488,8 +497,8 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
   k_chunk_count<<<g_groups, kBlock, 0, s>>>(ctl, cand_key, ch_off, ch_cnt, ch_gt, ch_tie, blk_gt, blk_tie, nc, L.cap_total);
   constexpr uint32_t kCompactPerBlock = (kBlock / 64) * (64 / kCompactLanes);
   k_compact<kCompactLanes><<<dim3((nc + kCompactPerBlock - 1) / kCompactPerBlock, N), kBlock, 0, s>>>(
-      ctl, cand_key, cand_idx, cand_val, ch_off, ch_cnt, ch_gt, ch_tie, blk_gt, blk_tie, n_blk, sel_off, prev_sel_off,
-      out_idx, out_val, mask, k, nc, L.cap_total);
+      ctl, gctl, cand_key, cand_idx, cand_val, ch_off, ch_cnt, ch_gt, ch_tie, blk_gt, blk_tie, n_blk, sel_off, prev_sel_off,
+      out_idx, out_val, mask, k, nc, L.cap_total, c->force_dense, sk.roots);
   k_aggregate<<<nc, kBlock, 0, s>>>(out_idx, out_val, sel_off, agg, agg_hot, d, k, nc, N, omega);
   if (ev) { HIP_TRY(hipEventRecord(ev[3], s)); c->prof_rounds += 1; }
   HIP_TRY(hipGetLastError());
@@ -604,6 +613,7 @@ int regtopk_set_state(regtopk_ctx* c, const float* e_dev, const int32_t* pidx_de
   c->t = t;
   c->have_prev = t > 0;
   c->fresh = kFreshRounds;
+  c->need_begin = true;
   if (t == 0) {
     for (int b = 0; b < 2; ++b)
       k_fill_u32<<<256, 256, 0, s>>>(c->at<uint32_t>(c->L.sel_off[b]), (size_t)c->N * (c->L.nc + 1), 0u);
@@ -635,18 +645,18 @@ int regtopk_get_stats(regtopk_ctx* c, regtopk_worker_stats* st, void* stream) {
   uint32_t err = hg.bar_err ? 4u : 0u;
   for (int32_t n = 0; n < c->N; ++n) {
     const WorkerCtl& w = h[(size_t)n];
-    st[n].tau_lo_bits = w.tau_lo;
-    st[n].n_candidates = w.need_dense ? w.dense_total : w.n_cand;
-    st[n].used_dense = w.need_dense;
+    st[n].tau_lo_bits = w.snap_tau_lo;
+    st[n].n_candidates = w.snap_n_cand;
+    st[n].used_dense = w.snap_used_dense;
     st[n].tau_bits = w.tau;
     st[n].n_greater = w.n_gt;
     st[n].n_ties_taken = w.budget;
     st[n].n_ties_total = w.ties_total;
-    st[n].overflow = w.overflow;
-    st[n].used_window = w.used_window;
-    st[n].n_boundary = w.n_bnd;
-    st[n].n_valid = w.n_valid;
-    st[n].window_half = w.win_lo == kNoBound ? 0u : (w.win_hi - w.win_lo) / 2;
+    st[n].overflow = w.snap_overflow;
+    st[n].used_window = w.snap_used_window;
+    st[n].n_boundary = w.snap_n_bnd;
+    st[n].n_valid = w.snap_n_valid;
+    st[n].window_half = w.snap_win_half;
     err |= w.err;
   }
   if (err) return fail(REGTOPK_BAD_STATE, "device-side check failed (flags 0x%x)", err);
