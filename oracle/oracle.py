@@ -54,6 +54,8 @@ def _load():
     lib.rtk_oracle_set_weights.argtypes = [c.c_void_p, c.c_void_p]
     lib.rtk_oracle_mask_overlap.argtypes = [c.c_void_p, c.c_void_p]
     lib.rtk_oracle_sgd_update.argtypes = [c.c_void_p, c.c_void_p, c.c_float, c.c_int64]
+    lib.rtk_oracle_set_worker_k.restype = c.c_int
+    lib.rtk_oracle_set_worker_k.argtypes = [c.c_void_p, c.c_void_p]
     lib.rtk_oracle_set_score_variant.restype = c.c_int
     lib.rtk_oracle_set_score_variant.argtypes = [c.c_void_p, c.c_int, c.c_int]
     lib.rtk_oracle_likelihood_sent_kind.restype = c.c_float
@@ -134,6 +136,14 @@ class Oracle:
         if ws.shape != (self.N,):
             raise ValueError("weights must be [N]")
         self._lib.rtk_oracle_set_weights(self._h, ws.ctypes.data)
+
+    def set_worker_k(self, kn):
+        """Entries kept by each worker, k_n in [1, k]; the rest of a worker's output row is (-1, 0)."""
+        ks = np.ascontiguousarray(kn, dtype=np.int64)
+        if ks.shape != (self.N,):
+            raise ValueError("need N values")
+        if self._lib.rtk_oracle_set_worker_k(self._h, ks.ctypes.data) != 0:
+            raise ValueError("every k_n must be in [1, k]")
 
     def set_score_variant(self, sqrt_steps: int = 0, likelihood: int = 0):
         """Prior |a|^(2^-sqrt_steps) and likelihood kind (0 tanh, 1 clipped linear)."""

@@ -52,6 +52,11 @@
 //       sides of the parity check can take it bit for bit); besides tanh the
 //       likelihood may be the cumulative function of a uniform innovation,
 //       min(|1+Delta|/mu, 1).  The defaults (m = 0, tanh) are Algorithm 2.
+//   R18 Algorithm 2 is stated "at worker n" and its selector Top_k takes k as a
+//       parameter of that worker's sparsifier; the paper's experiments give all
+//       workers the same k.  Here worker n may be given its own k_n <= k: its
+//       mask has exactly k_n ones, its lists hold k_n pairs, and the rest of its
+//       row of the [N,k] outputs is filled with index -1 and value 0.
 
 #include <algorithm>
 #include <cmath>
@@ -67,6 +72,7 @@ struct Oracle {
     int64_t d, k;
     float mu;
     std::vector<float> w;        // [N] aggregation weights omega_n (R2)
+    std::vector<int64_t> kn;     // [N] entries kept by worker n, 1 <= k_n <= k (R18; default k)
     int sqrt_steps;              // prior |a|^y with y = 2^-sqrt_steps (R15)
     int likelihood;              // 0: tanh(x), 1: min(x, 1) (R15)
     int64_t t;       // rounds done so far
@@ -128,6 +134,7 @@ void* rtk_oracle_create(int32_t N, int64_t d, int64_t k, float mu) {
     Oracle* o = new Oracle;
     o->N = N; o->d = d; o->k = k; o->mu = mu;
     o->w.assign((size_t)N, 1.0f / (float)N);
+    o->kn.assign((size_t)N, k);
     o->t = 0;
     o->sqrt_steps = 0;
     o->likelihood = 0;
@@ -170,13 +177,14 @@ void rtk_oracle_step(void* h, const float* grads, const float* gprev,
                 f = likelihood_sent(a[j], ap[j], gprev[j], w, mu, o->likelihood);
             sc[j] = prior(a[j], o->sqrt_steps) * f;          // |a|^y . u(|1 + Delta|)
         }
-        topk_mask(sc, d, k, s);                              // s^t = Top_k(.)
+        topk_mask(sc, d, o->kn[(size_t)n], s);               // s^t = Top_k(.), k = k_n (R18)
         int64_t c = 0;
         for (int64_t j = 0; j < d; ++j) {
             gh[j] = (float)s[j] * a[j];                      // ghat = s . a
             e[j] = a[j] - gh[j];                             // eps^{t+1} = a - ghat
             if (s[j]) { idx[(size_t)n * k + c] = (int32_t)j; val[(size_t)n * k + c] = a[j]; ++c; }
         }
+        for (; c < k; ++c) { idx[(size_t)n * k + c] = -1; val[(size_t)n * k + c] = 0.0f; }   // unused rest of the row
         std::memcpy(ap, a, sizeof(float) * (size_t)d);       // keep a^{t} for round t+1
         std::memcpy(sp, s, (size_t)d);                       // keep s^{t}
     }
@@ -194,6 +202,16 @@ void rtk_oracle_step(void* h, const float* grads, const float* gprev,
 void rtk_oracle_set_weights(void* h, const float* w) {
     Oracle* o = (Oracle*)h;
     for (int32_t n = 0; n < o->N; ++n) o->w[(size_t)n] = w[n];
+}
+
+// Entries kept per worker (R18): k_n[0..N), each in [1, k].  Applies from the
+// next round on.  Returns 0 on success.
+int rtk_oracle_set_worker_k(void* h, const int64_t* kn) {
+    Oracle* o = (Oracle*)h;
+    for (int32_t n = 0; n < o->N; ++n)
+        if (kn[n] < 1 || kn[n] > o->k) return -1;
+    for (int32_t n = 0; n < o->N; ++n) o->kn[(size_t)n] = kn[n];
+    return 0;
 }
 
 // Score variant (R15): prior exponent y = 2^-sqrt_steps (0..3) and the kind of

@@ -367,3 +367,81 @@ def test_global_and_local_rounds_share_their_state():
     assert np.array_equal(sc[prev == 0], np.abs(a)[prev == 0])
     assert np.any(sc[prev == 1] < np.abs(a)[prev == 1])
     assert o.round == 2
+
+
+# ------------------------------------------------------------- per-worker k ----
+def _numpy_topk_sets(score, k):
+    """Indices of the k largest scores, lower index first among equals, ascending (full sort)."""
+    order = np.lexsort((np.arange(score.size), -score.astype(np.float64)))
+    return np.sort(order[:k])
+
+
+def test_equal_worker_k_is_the_scalar_k():
+    rounds = _rounds(5, 4, 1500, 30)
+    a, b = oracle.Oracle(4, 1500, 30, 1.0), oracle.Oracle(4, 1500, 30, 1.0)
+    b.set_worker_k([30, 30, 30, 30])
+    ga = gb = None
+    for g in rounds:
+        ia, va, ga = a.step(g, ga)
+        ib, vb, gb = b.step(g, gb)
+        assert np.array_equal(ia, ib) and np.array_equal(va, vb) and np.array_equal(ga, gb)
+        assert np.array_equal(a.e, b.e)
+
+
+def test_worker_k_without_regulariser_is_algorithm1_with_each_workers_own_k():
+    # mu = 0: every worker runs Algorithm 1 on its own, with its own k_n -- rebuilt here with a full
+    # sort; the unused rest of each output row is (-1, 0); the aggregate is the weighted sum of the lists.
+    N, d, k = 4, 700, 50
+    kn = [1, 17, 50, 33]
+    o = oracle.Oracle(N, d, k, 0.0)
+    o.set_worker_k(kn)
+    e = np.zeros((N, d), dtype=f32)
+    for g in _rounds(6, N, d, k):
+        idx, val, agg = o.step(g, None)
+        a = e + g
+        ref = np.zeros(d, dtype=f32)
+        for n in range(N):
+            want = _numpy_topk_sets(np.abs(a[n]), kn[n])
+            assert np.array_equal(idx[n, :kn[n]], want)
+            assert np.array_equal(val[n, :kn[n]], a[n, want])
+            assert np.all(idx[n, kn[n]:] == -1) and np.all(val[n, kn[n]:] == 0)
+            e[n] = a[n]
+            e[n, want] = 0
+            ref[want] = ref[want] + f32(1.0) / f32(N) * a[n, want]
+        assert np.array_equal(o.e, e)
+        assert np.array_equal(agg, ref)
+
+
+def test_worker_k_with_regulariser_selects_k_n_largest_scores_and_conserves():
+    N, d, k = 5, 900, 90
+    kn = [90, 1, 45, 10, 89]
+    o = oracle.Oracle(N, d, k, 0.9)
+    o.set_worker_k(kn)
+    agg = None
+    for g in _rounds(6, N, d, k):
+        e_before = o.e
+        idx, val, agg = o.step(g, agg)
+        sc, a, mask = o.score, o.a, o.mask
+        assert np.array_equal(a, e_before + g)
+        for n in range(N):
+            want = _numpy_topk_sets(sc[n], kn[n])           # brute force on the oracle's scores
+            assert np.array_equal(idx[n, :kn[n]], want)
+            assert int(mask[n].sum()) == kn[n]
+            sent = np.zeros(d, dtype=f32)
+            sent[want] = val[n, :kn[n]]
+            assert np.array_equal((sent + o.e[n]).view(np.uint32), a[n].view(np.uint32))   # a = ghat + eps
+    assert np.array_equal(o.mask_overlap(), np.bincount(o.mask.sum(0), minlength=N + 1))
+
+
+def test_a_worker_that_keeps_everything_has_no_error_and_k_n_is_checked():
+    N, d, k = 3, 120, 120
+    o = oracle.Oracle(N, d, k, 1.0)
+    o.set_worker_k([120, 5, 60])
+    agg = None
+    for g in _rounds(4, N, d, k):
+        idx, val, agg = o.step(g, agg)
+        assert np.array_equal(idx[0], np.arange(d)) and np.array_equal(val[0], g[0])   # eps_0 stays 0
+        assert not o.e[0].any()
+    for bad in ([0, 5, 5], [121, 5, 5], [5, 5]):
+        with pytest.raises(ValueError):
+            o.set_worker_k(bad)
