@@ -169,6 +169,20 @@ int regtopk_get_stats(regtopk_ctx* ctx, regtopk_worker_stats* stats_host, void* 
  * `stream`).  Weights survive regtopk_reset and set_state. */
 int regtopk_set_weights(regtopk_ctx* ctx, const float* weights_host, void* stream);
 
+/* Entries kept per worker (paper: Algorithm 2 is stated at worker n, and its
+ * selector Top_k takes k as a parameter of that worker's sparsifier; the
+ * paper's experiments give every worker the same k).  k_host[0..N) is HOST
+ * memory, 1 <= k_host[n] <= k of regtopk_create (REGTOPK_INVALID_ARG
+ * otherwise).  From the next round on worker n selects exactly k_host[n]
+ * entries.  Layout: the lists stay [N,k] row-major; row n holds its k_host[n]
+ * pairs first (indices ascending) and (-1, 0.0f) in the remaining positions;
+ * the same holds for pidx/pval of get_state / set_state.  Copies synchronously
+ * (waits for `stream`); survives regtopk_reset and set_state; the bounds
+ * carried over from earlier rounds are dropped.  regtopk_step_global shares
+ * one mask of k entries among all workers and returns REGTOPK_BAD_STATE while
+ * some worker's k differs from k. */
+int regtopk_set_worker_k(regtopk_ctx* ctx, const int64_t* k_host, void* stream);
+
 /* Agreement of the workers' masks in the last completed round (paper: appendix
  * subsection "Comparing Sparsification Masks"): counts_dev[c], c = 0..N, device
  * memory of N+1 int64 (8-byte aligned), receives the number of entries j in

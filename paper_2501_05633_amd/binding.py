@@ -22,7 +22,7 @@ SYMBOLS = [
     "regtopk_workspace_bytes", "regtopk_create", "regtopk_create_in", "regtopk_step", "regtopk_step_bf16", "regtopk_step_global",
     "regtopk_destroy", "regtopk_reset", "regtopk_get_state", "regtopk_set_state",
     "regtopk_get_stats", "regtopk_set_option", "regtopk_get_timings", "regtopk_tanh_f32",
-    "regtopk_copy_f32", "regtopk_set_weights", "regtopk_mask_overlap", "regtopk_mask_overlap_static", "regtopk_sgd_update",
+    "regtopk_copy_f32", "regtopk_set_weights", "regtopk_set_worker_k", "regtopk_mask_overlap", "regtopk_mask_overlap_static", "regtopk_sgd_update",
     "regtopk_last_error",
 ]
 
@@ -75,6 +75,7 @@ def load():
     lib.regtopk_copy_f32.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
     lib.regtopk_tanh_f32.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
     lib.regtopk_set_weights.argtypes = [c_void_p, ctypes.POINTER(c_float), c_void_p]
+    lib.regtopk_set_worker_k.argtypes = [c_void_p, ctypes.POINTER(c_int64), c_void_p]
     lib.regtopk_mask_overlap.argtypes = [c_void_p, c_void_p, c_void_p]
     lib.regtopk_mask_overlap_static.argtypes = [c_void_p, c_void_p, c_void_p]
     lib.regtopk_sgd_update.argtypes = [c_void_p, c_void_p, c_float, c_int64, c_void_p]
@@ -207,6 +208,15 @@ class RegTopk:
         arr = (c_float * self.N)(*ws)
         with self._torch.cuda.device(self.device):
             _check(self.lib.regtopk_set_weights(self._h, arr, _stream_ptr(self._torch)))
+
+    def set_worker_k(self, kn):
+        """Entries kept by each worker (N integers in [1, k]); unused list positions hold (-1, 0)."""
+        ks = [int(x) for x in kn]
+        if len(ks) != self.N:
+            raise ValueError("need N values")
+        arr = (c_int64 * self.N)(*ks)
+        with self._torch.cuda.device(self.device):
+            _check(self.lib.regtopk_set_worker_k(self._h, arr, _stream_ptr(self._torch)))
 
     def mask_overlap(self):
         """int64 [N+1] CUDA tensor: entry c = number of indices that exactly c workers selected last round."""

@@ -56,7 +56,8 @@ struct WorkerCtl {
   uint32_t tau_lo_mag;    // smallest |a| bit pattern whose prior reaches tau_lo (= tau_lo for the plain prior)
   // diagnostics of the last completed round, copied before the counters are cleared for the next one
   uint32_t snap_tau_lo, snap_n_cand, snap_used_dense, snap_overflow, snap_used_window, snap_n_bnd, snap_n_valid, snap_win_half;
-  uint32_t pad[3];
+  uint32_t f_want;        // entries the dense selection lists: k + k_prev (not clamped to d)
+  uint32_t pad[2];
   uint32_t cursor[kMaxRegions];
 };
 

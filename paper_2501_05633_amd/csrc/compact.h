@@ -88,7 +88,8 @@ k_compact(WorkerCtl* ctl, GlobalCtl* gctl, const uint32_t* __restrict__ cand_key
           uint32_t* __restrict__ sel_off, const uint32_t* __restrict__ prev_sel_off,
           int32_t* __restrict__ out_idx,
           float* __restrict__ out_val, uint32_t* __restrict__ mask,
-          int64_t k, uint32_t nc, uint32_t cap_total, int next_force_dense, int next_roots) {
+          int64_t k, const uint32_t* __restrict__ kn, uint32_t nc, uint32_t cap_total, int next_force_dense,
+          int next_roots) {
   constexpr uint32_t kCPW = 64 / LPC, kCPB = (kBlock / 64) * kCPW;
   static_assert(kChunksPerBlock % kCPB == 0, "a compaction block must lie inside one counting block");
   static_assert(kChunksPerBlock <= LPC, "one load per lane must cover the chunks of a counting block");
@@ -140,9 +141,12 @@ k_compact(WorkerCtl* ctl, GlobalCtl* gctl, const uint32_t* __restrict__ cand_key
     sel_off[so] = first;
     if (c == nc - 1) {
       sel_off[so + 1] = first + my_sel;
-      if ((int64_t)(first + my_sel) != k) atomicOr(&ctl[n].err, 1u);
+      if (first + my_sel != kn[n]) atomicOr(&ctl[n].err, 1u);
     }
   }
+  // a worker that keeps fewer than k entries: the rest of its row of the lists is (-1, 0)
+  if (live && c == nc - 1)
+    for (int64_t o = (int64_t)kn[n] + gl; o < k; o += LPC) { out_idx[(size_t)n * k + o] = -1; out_val[(size_t)n * k + o] = 0.0f; }
   const size_t cb = (size_t)n * cap_total + off;
   const uint64_t below_mask = (1ull << gl) - 1ull, group_bits = LPC == 64 ? ~0ull : (1ull << LPC) - 1ull;
   const uint32_t gshift = grp * LPC;

@@ -13,9 +13,11 @@ namespace rtk {
 //
 // Phases, for flagged workers only:
 //   clear histograms | 3 x (histogram of the prior's bits, every flagged
-//   worker fed by its own group of blocks; pick the bin of rank min(2k,d)) |
-//   per-chunk counts | chunk scan | ordered emission of the 2k largest priors
-//   as the candidate list | scores | exact k-th score.
+//   worker fed by its own group of blocks; pick the bin of rank
+//   min(k + k_prev, d)) | per-chunk counts | chunk scan | ordered emission of
+//   the k + k_prev largest priors as the candidate list | scores | exact k-th
+//   score.  (k_prev: entries the worker sent in the previous round; 2k when
+//   every round keeps k.)
 
 // Histogram level LEVEL of worker n's row; block b of G covers a strided share.
 template <int LEVEL, bool VEC>
@@ -63,12 +65,13 @@ __device__ __forceinline__ void dense_hist_worker(uint32_t n, uint32_t b, uint32
   __syncthreads();
 }
 
-// Level LEVEL of the radix select of rank min(2k, d) over the |a| bits of worker
-// n: finds, from the top bin downwards, the bin in which the cumulative count
-// reaches the wanted rank.  One block.
+// Level LEVEL of the radix select of rank min(k + k_prev, d) over the prior's
+// bits of worker n (k entries to keep now, k_prev entries sent in the previous
+// round): finds, from the top bin downwards, the bin in which the cumulative
+// count reaches the wanted rank.  One block.
 template <int LEVEL>
 __device__ __forceinline__ void dense_scan_worker(uint32_t n, WorkerCtl* ctl, const uint32_t* hist_all,
-                                                  int64_t k, int64_t d, uint32_t* s_sum,
+                                                  int64_t k, int64_t k_prev, int64_t d, uint32_t* s_sum,
                                                   uint32_t* s_scan) {
   constexpr uint32_t bins = LEVEL == 1 ? kL1Bins : (LEVEL == 2 ? kL2Bins : kL3Bins);
   constexpr uint32_t per = bins / kBlock;            // bins per thread (16, 8, 1)
@@ -76,8 +79,12 @@ __device__ __forceinline__ void dense_scan_worker(uint32_t n, WorkerCtl* ctl, co
   WorkerCtl& c = ctl[n];
   const uint32_t* h = hist_all + ((size_t)n * 3 + (LEVEL - 1)) * kL1Bins;
   uint32_t want;
-  if (LEVEL == 1) want = (uint32_t)(2 * k < d ? 2 * k : d);
-  else want = c.f_krem;
+  if (LEVEL == 1) {
+    want = (uint32_t)(k + k_prev < d ? k + k_prev : d);
+    if (tid == 0) c.f_want = (uint32_t)(k + k_prev);
+  } else {
+    want = c.f_krem;
+  }
   // thread t owns bins [bins-1-t*per .. bins-(t+1)*per], i.e. descending order
   uint32_t loc[per];
   uint32_t s = 0;
@@ -150,7 +157,7 @@ __device__ __forceinline__ void dense_count_chunk(uint32_t n, uint32_t c, const 
   __syncthreads();
 }
 
-// Chunk c of worker n: writes its share of the 2k largest |a| (ties: lowest
+// Chunk c of worker n: writes its share of the k + k_prev largest |a| (ties: lowest
 // indices) to the candidate list, in index order, at the offsets of the scan.
 // The sweep has overwritten the state by now, so the value sent in the previous
 // round is fetched from that round's list: its position there is the number of
@@ -298,7 +305,7 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
             GlobalCtl* gctl, uint32_t* fhist, uint32_t* ch_gt, uint32_t* ch_tie, uint32_t* ch_off,
             uint32_t* ch_cnt, uint32_t* tie_off, int32_t* cand_idx, float* cand_val, float* cand_prev,
             uint32_t* cand_key,
-            const uint32_t* bnd_key, const float* prev_val, const float* gprev, int64_t k, uint32_t nc,
+            const uint32_t* bnd_key, const float* prev_val, const float* gprev, int64_t k, const uint32_t* kn, uint32_t nc,
             int32_t N, uint32_t cap_r, uint32_t cap_total, uint32_t regions, uint32_t bnd_cap,
             const float* omega, float mu, int use_reg, float cand_target, ScoreKind sk,
             uint32_t* host_err) {
@@ -332,7 +339,7 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
   }
   if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (int32_t n = b; n < N; n += G)
-    if (ctl[n].need_dense) dense_scan_worker<1>(n, ctl, fhist, k, d, s_a, s_b);
+    if (ctl[n].need_dense) dense_scan_worker<1>(n, ctl, fhist, (int64_t)kn[n], (int64_t)prev_sel_off[(size_t)n * (nc + 1) + nc], d, s_a, s_b);
   if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (uint32_t r = grp; r < n_flagged; r += groups) {
     const uint32_t n = r == grp ? first_worker : flagged_worker(ctl, N, r, &n_flagged, s_w, s_out);
@@ -340,7 +347,7 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
   }
   if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (int32_t n = b; n < N; n += G)
-    if (ctl[n].need_dense) dense_scan_worker<2>(n, ctl, fhist, k, d, s_a, s_b);
+    if (ctl[n].need_dense) dense_scan_worker<2>(n, ctl, fhist, (int64_t)kn[n], (int64_t)prev_sel_off[(size_t)n * (nc + 1) + nc], d, s_a, s_b);
   if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (uint32_t r = grp; r < n_flagged; r += groups) {
     const uint32_t n = r == grp ? first_worker : flagged_worker(ctl, N, r, &n_flagged, s_w, s_out);
@@ -348,7 +355,7 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
   }
   if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (int32_t n = b; n < N; n += G)
-    if (ctl[n].need_dense) dense_scan_worker<3>(n, ctl, fhist, k, d, s_a, s_b);
+    if (ctl[n].need_dense) dense_scan_worker<3>(n, ctl, fhist, (int64_t)kn[n], (int64_t)prev_sel_off[(size_t)n * (nc + 1) + nc], d, s_a, s_b);
   if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
 
   for (int32_t n = 0; n < N; ++n) {
@@ -357,7 +364,7 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
   }
   if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (int32_t n = b; n < N; n += G)
-    if (ctl[n].need_dense) chunk_scan_worker<true, kBlock>(n, ctl, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, nc, k, s_w);
+    if (ctl[n].need_dense) chunk_scan_worker<true, kBlock>(n, ctl, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, nc, (int64_t)kn[n], s_w);
   if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (int32_t n = 0; n < N; ++n) {
     if (!ctl[n].need_dense) continue;
@@ -378,7 +385,7 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
   if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (int32_t n = b; n < N; n += G)
     if (ctl[n].need_dense)
-      select_worker<true, kBlock>(n, ctl, gctl, cand_key, bnd_key, k, cap_r, cap_total, regions, bnd_cap,
+      select_worker<true, kBlock>(n, ctl, gctl, cand_key, bnd_key, (int64_t)kn[n], cap_r, cap_total, regions, bnd_cap,
                                   cand_target, 0, s_hist, nullptr, s_w, s_out);
 }
 

@@ -253,10 +253,12 @@ __global__ void k_init_ctl(WorkerCtl* ctl) {
 // zero): state[n][pidx[n][i]] = pval[n][i].  Indices outside [0,d) are skipped
 // (k_check_ascending reports them).
 __global__ void k_scatter_prev(float* __restrict__ e, const int32_t* __restrict__ pidx,
-                               const float* __restrict__ pval, int64_t d, int64_t k, int32_t N) {
+                               const float* __restrict__ pval, int64_t d, int64_t k,
+                               const uint32_t* __restrict__ kn, int32_t N) {
   const size_t total = (size_t)N * (size_t)k;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
     const size_t n = i / (size_t)k;
+    if (i - n * (size_t)k >= kn[n]) continue;        // beyond the worker's own list length
     const int64_t j = pidx[i];
     if (j >= 0 && j < d) e[n * (size_t)d + (size_t)j] = pval[i];
   }
@@ -266,7 +268,7 @@ __global__ void k_scatter_prev(float* __restrict__ e, const int32_t* __restrict_
 // grid (ceil(nc/4), N): one wave per chunk.
 __global__ void __launch_bounds__(kBlock)
 k_build_mask(const int32_t* __restrict__ pidx, uint32_t* __restrict__ mask,
-             uint32_t* __restrict__ sel_off, int64_t k, uint32_t nc) {
+             uint32_t* __restrict__ sel_off, int64_t k, const uint32_t* __restrict__ kn, uint32_t nc) {
   __shared__ uint32_t s_m[4][kChunkWords];
   const uint32_t n = blockIdx.y, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const uint32_t c = blockIdx.x * 4 + wv;
@@ -278,14 +280,15 @@ k_build_mask(const int32_t* __restrict__ pidx, uint32_t* __restrict__ mask,
   if (live) {
     const int32_t* pi = pidx + (size_t)n * k;
     const int64_t t0 = (int64_t)c * kChunk, t1 = t0 + kChunk;
-    int64_t lo = 0, hi = k;
+    const int64_t len = (int64_t)kn[n];               // the worker's own list length
+    int64_t lo = 0, hi = len;
     while (lo < hi) { const int64_t mid = (lo + hi) >> 1; if ((int64_t)pi[mid] < t0) lo = mid + 1; else hi = mid; }
     first = (uint32_t)lo;
     if (lane == 0) {
       sel_off[(size_t)n * (nc + 1) + c] = first;
-      if (c == nc - 1) sel_off[(size_t)n * (nc + 1) + nc] = (uint32_t)k;
+      if (c == nc - 1) sel_off[(size_t)n * (nc + 1) + nc] = (uint32_t)len;
     }
-    for (int64_t p = lo + lane; p < k; p += 64) {
+    for (int64_t p = lo + lane; p < len; p += 64) {
       const int64_t j = pi[p];
       if (j >= t1 || j < t0) break;
       const uint32_t jl = (uint32_t)(j - t0);
@@ -311,10 +314,12 @@ __global__ void k_export_eps(float* __restrict__ dst, const float* __restrict__ 
 }
 
 // grid (blocks, N)
-__global__ void k_check_ascending(const int32_t* __restrict__ pidx, WorkerCtl* ctl, int64_t d, int64_t k) {
+__global__ void k_check_ascending(const int32_t* __restrict__ pidx, WorkerCtl* ctl, int64_t d, int64_t k,
+                                  const uint32_t* __restrict__ kn) {
   const uint32_t n = blockIdx.y;
   const int32_t* pi = pidx + (size_t)n * k;
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < k; i += (int64_t)gridDim.x * blockDim.x) {
+  const int64_t len = (int64_t)kn[n];
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < len; i += (int64_t)gridDim.x * blockDim.x) {
     const int32_t v = pi[i];
     if (v < 0 || (int64_t)v >= d || (i > 0 && pi[i - 1] >= v)) atomicOr(&ctl[n].err, 2u);
   }

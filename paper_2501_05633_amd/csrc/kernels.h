@@ -23,7 +23,8 @@
 //   (k_sample_hist, k_sample_bound: a round without history - round 0, after a
 //                   reset - first takes its bound from a strided sample of a)
 //   k_dense_all     for workers whose speculation failed: exact radix select of
-//                   the 2k largest priors |a|^y (a superset of the true
+//                   the k + k_prev largest priors |a|^y (k_prev entries were sent
+//                   in the previous round, normally k; a superset of the true
 //                   top-k, see below), count, scan and an ordered emission of
 //                   exactly those entries as the candidate list, then their
 //                   scores and the exact k-th score; one kernel with grid
@@ -37,11 +38,12 @@
 //   k_aggregate     per 4096-entry tile: LDS accumulation of w*value in ascending
 //                   worker order, tile written once (zero fill included)
 //
-// Why the 2k largest priors suffice when the speculation fails: the score never
-// exceeds the prior p = |a|^y (y = 1 unless a variant is set) and differs from
-// it only on the k entries sent in the previous round; among the 2k entries
-// with the largest (p, lower index first) at least k are therefore scored at
-// their full p, and each of them beats every entry outside that set.
+// Why the k + k_prev largest priors suffice when the speculation fails: the
+// score never exceeds the prior p = |a|^y (y = 1 unless a variant is set) and
+// differs from it only on the k_prev entries sent in the previous round; among
+// the k + k_prev entries with the largest (p, lower index first) at least k are
+// therefore scored at their full p, and each of them beats every entry outside
+// that set.
 #pragma once
 #include "common.h"
 #include "sweep.h"

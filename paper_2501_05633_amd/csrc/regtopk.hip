@@ -70,7 +70,7 @@ uint32_t* g_overlap_ptr[kMaxDevices] = {};
 struct Layout {
   uint32_t nc, regions, cap_r, cap_total, bnd_cap;
   size_t e, out_idx[2], out_val[2], agg[2], cand_idx, cand_val, cand_key;
-  size_t ch_off, ch_cnt, ch_gt, ch_tie, tie_off, sel_off[2], agg_hot[2], mask, cand_prev, bnd_key, fhist, ctl, gctl, omega, blk_gt, blk_tie, total;
+  size_t ch_off, ch_cnt, ch_gt, ch_tie, tie_off, sel_off[2], agg_hot[2], mask, cand_prev, bnd_key, fhist, ctl, gctl, omega, kn, blk_gt, blk_tie, total;
 };
 
 bool valid_sizes(int32_t N, int64_t d, int64_t k) {
@@ -130,6 +130,7 @@ bool make_layout(int32_t N, int64_t d, int64_t k, Layout* out) {
   L.ctl = take((size_t)N * sizeof(WorkerCtl));
   L.gctl = take(sizeof(GlobalCtl));
   L.omega = take((size_t)N * 4);
+  L.kn = take((size_t)N * 4);
   const size_t nblk = (size_t)N * ((L.nc + kChunksPerBlock - 1) / kChunksPerBlock);
   L.blk_gt = take(nblk * 4);
   L.blk_tie = take(nblk * 4);
@@ -163,6 +164,7 @@ struct regtopk_ctx {
   hipEvent_t ev[kProfRounds][5];
   int64_t prof_rounds;          // steps recorded since profiling was switched on
   uint32_t* host_err;   // pinned host word the dense-selection kernel sets when it abandons a round
+  bool uniform_k;       // every worker keeps k entries (no regtopk_set_worker_k with other values)
   bool internal;        // the selector of a global Top-k round: always driven on its owner's stream
   regtopk_ctx* gsel;    // global Top-k: a one-row context that selects over the unsparsified aggregate
   float* abar;          // global Top-k: that aggregate, [d]
@@ -269,6 +271,8 @@ int create_common(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu, 
     g.live += 1;
   }
   k_fill_u32<<<1, 256, 0, s>>>(c->at<uint32_t>(c->L.omega), (size_t)N, __builtin_bit_cast(uint32_t, 1.0f / (float)N));
+  k_fill_u32<<<1, 256, 0, s>>>(c->at<uint32_t>(c->L.kn), (size_t)N, (uint32_t)k);
+  c->uniform_k = true;
   int rc = zero_state(c, s);
   if (rc == REGTOPK_OK && hipStreamSynchronize(s) != hipSuccess) rc = fail(REGTOPK_HIP_ERROR, "zeroing the state failed");
   if (rc != REGTOPK_OK) { gate_leave(c); (void)hipHostFree(c->host_err); delete c; return rc; }
@@ -425,6 +429,7 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
   uint32_t* mask = c->at<uint32_t>(L.mask);
   float* cand_prev = c->at<float>(L.cand_prev);
   const float* omega = c->at<float>(L.omega);
+  const uint32_t* kn = c->at<uint32_t>(L.kn);
 
   const dim3 g_chunks(nc, N), g_waves((nc + 3) / 4, N);
   const dim3 g_score((L.cap_r + kScoreSlots - 1) / kScoreSlots, L.regions, N);
@@ -456,7 +461,7 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
     uint32_t sample_blocks = (n_groups + 4 * kBlock - 1) / (4 * kBlock);
     if (sample_blocks > 16) sample_blocks = 16;
     k_sample_hist<G><<<dim3(sample_blocks, N), kBlock, 0, s>>>(e, grads, mask, d, nc, fhist, n_groups, stride4, sk.roots);
-    k_sample_bound<<<N, kScanBlock, 0, s>>>(ctl, fhist, d, k, (uint32_t)n_sampled, sk.roots);
+    k_sample_bound<<<N, kScanBlock, 0, s>>>(ctl, fhist, d, kn, (uint32_t)n_sampled, sk.roots);
   }
   if (c->fresh > 0) c->fresh -= 1;
   if (ev) HIP_TRY(hipEventRecord(ev[0], s));
@@ -466,7 +471,7 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
     k_accum_emit<false, G><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   if (ev) HIP_TRY(hipEventRecord(ev[1], s));
   k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_prev, cand_key, bnd_key, gprev, d, L.cap_r, L.cap_total, L.bnd_cap, omega, c->mu, use_reg, sk);
-  k_select<<<N, kScanBlock, 0, s>>>(ctl, gctl, cand_key, bnd_key, k, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->cand_target, c->force_dense);
+  k_select<<<N, kScanBlock, 0, s>>>(ctl, gctl, cand_key, bnd_key, kn, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->cand_target, c->force_dense);
   // dense selection for the workers whose speculation failed; returns at once if there is none
   {
     DeviceGate* gate = c->internal ? nullptr : &g_gate[c->device];
@@ -478,9 +483,9 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
       if (chain && gate->recorded && gate->last != s) HIP_TRY(hipStreamWaitEvent(s, gate->ev, 0));
     }
     if (vec)
-      k_dense_all<true><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, prev_sel_off, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_prev, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, omega, c->mu, use_reg, c->cand_target, sk, c->host_err);
+      k_dense_all<true><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, prev_sel_off, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_prev, cand_key, bnd_key, prev_val, gprev, k, kn, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, omega, c->mu, use_reg, c->cand_target, sk, c->host_err);
     else
-      k_dense_all<false><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, prev_sel_off, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_prev, cand_key, bnd_key, prev_val, gprev, k, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, omega, c->mu, use_reg, c->cand_target, sk, c->host_err);
+      k_dense_all<false><<<c->dense_blocks, kBlock, 0, s>>>(e, mask, prev_sel_off, d, ctl, gctl, fhist, ch_gt, ch_tie, ch_off, ch_cnt, tie_off, cand_idx, cand_val, cand_prev, cand_key, bnd_key, prev_val, gprev, k, kn, nc, N, L.cap_r, L.cap_total, L.regions, L.bnd_cap, omega, c->mu, use_reg, c->cand_target, sk, c->host_err);
     if (chain) {
       HIP_TRY(hipEventRecord(gate->ev, s));
       gate->last = s;
@@ -498,7 +503,7 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
   constexpr uint32_t kCompactPerBlock = (kBlock / 64) * (64 / kCompactLanes);
   k_compact<kCompactLanes><<<dim3((nc + kCompactPerBlock - 1) / kCompactPerBlock, N), kBlock, 0, s>>>(
       ctl, gctl, cand_key, cand_idx, cand_val, ch_off, ch_cnt, ch_gt, ch_tie, blk_gt, blk_tie, n_blk, sel_off, prev_sel_off,
-      out_idx, out_val, mask, k, nc, L.cap_total, c->force_dense, sk.roots);
+      out_idx, out_val, mask, k, kn, nc, L.cap_total, c->force_dense, sk.roots);
   k_aggregate<<<nc, kBlock, 0, s>>>(out_idx, out_val, sel_off, agg, agg_hot, d, k, nc, N, omega);
   if (ev) { HIP_TRY(hipEventRecord(ev[3], s)); c->prof_rounds += 1; }
   HIP_TRY(hipGetLastError());
@@ -522,6 +527,7 @@ int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* s
 int regtopk_step_global(regtopk_ctx* c, const float* grads, void* stream, regtopk_result* out) {
   if (!c || !grads || !out) return fail(REGTOPK_INVALID_ARG, "ctx, grads_dev and out must not be NULL");
   if (reinterpret_cast<uintptr_t>(grads) % 4) return fail(REGTOPK_INVALID_ARG, "grads_dev must be 4-byte aligned");
+  if (!c->uniform_k) return fail(REGTOPK_BAD_STATE, "the global Top-k round shares one mask of k entries: per-worker k is set");
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (!c->gsel) {
     // first use: the selector over the aggregate (one row, plain Top-k) and the aggregate itself
@@ -625,10 +631,10 @@ int regtopk_set_state(regtopk_ctx* c, const float* e_dev, const int32_t* pidx_de
     k_copy_u32<<<512, 256, 0, s>>>(reinterpret_cast<uint32_t*>(pi), reinterpret_cast<const uint32_t*>(pidx_dev), nk);
     k_copy_u32<<<512, 256, 0, s>>>(c->at<uint32_t>(c->L.out_val[prv]), reinterpret_cast<const uint32_t*>(pval_dev), nk);
     const dim3 g((c->L.nc + 3) / 4, c->N);
-    k_build_mask<<<g, kBlock, 0, s>>>(pi, c->at<uint32_t>(c->L.mask), c->at<uint32_t>(c->L.sel_off[prv]), c->k, c->L.nc);
-    k_scatter_prev<<<512, 256, 0, s>>>(c->at<float>(c->L.e), pi, c->at<float>(c->L.out_val[prv]), c->d, c->k, c->N);
+    k_build_mask<<<g, kBlock, 0, s>>>(pi, c->at<uint32_t>(c->L.mask), c->at<uint32_t>(c->L.sel_off[prv]), c->k, c->at<uint32_t>(c->L.kn), c->L.nc);
+    k_scatter_prev<<<512, 256, 0, s>>>(c->at<float>(c->L.e), pi, c->at<float>(c->L.out_val[prv]), c->d, c->k, c->at<uint32_t>(c->L.kn), c->N);
     const dim3 g2(64, c->N);
-    k_check_ascending<<<g2, 256, 0, s>>>(pi, c->at<WorkerCtl>(c->L.ctl), c->d, c->k);
+    k_check_ascending<<<g2, 256, 0, s>>>(pi, c->at<WorkerCtl>(c->L.ctl), c->d, c->k, c->at<uint32_t>(c->L.kn));
   }
   HIP_TRY(hipGetLastError());
   return REGTOPK_OK;
@@ -670,6 +676,25 @@ int regtopk_set_weights(regtopk_ctx* c, const float* w_host, void* stream) {
   hipStream_t s = static_cast<hipStream_t>(stream);
   HIP_TRY(hipMemcpyAsync(c->at<float>(c->L.omega), w_host, (size_t)c->N * 4, hipMemcpyHostToDevice, s));
   HIP_TRY(hipStreamSynchronize(s));
+  return REGTOPK_OK;
+}
+
+int regtopk_set_worker_k(regtopk_ctx* c, const int64_t* k_host, void* stream) {
+  if (!c || !k_host) return fail(REGTOPK_INVALID_ARG, "ctx and k_host must not be NULL");
+  std::vector<uint32_t> v((size_t)c->N);
+  bool uniform = true;
+  for (int32_t n = 0; n < c->N; ++n) {
+    if (k_host[n] < 1 || k_host[n] > c->k)
+      return fail(REGTOPK_INVALID_ARG, "k of worker %d is %lld, outside [1, %lld]", n, (long long)k_host[n], (long long)c->k);
+    v[(size_t)n] = (uint32_t)k_host[n];
+    uniform = uniform && k_host[n] == c->k;
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  HIP_TRY(hipMemcpyAsync(c->at<uint32_t>(c->L.kn), v.data(), (size_t)c->N * 4, hipMemcpyHostToDevice, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  c->uniform_k = uniform;
+  c->reinit_ctl = true;                  // the bounds carried over belong to the old k
+  c->fresh = kFreshRounds;
   return REGTOPK_OK;
 }
 

@@ -204,9 +204,9 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
     rank = K - n_hi;
   } else {
     // all candidates; only scores >= the bound can hold the k-th (at least k do)
-    // (dense list: the 2k-th largest |a| when the list has 2k entries; a shorter
-    // list is the whole row, whose scores may all be damped)
-    base = SECOND ? (c.dense_total >= 2 * K ? c.f_tau : 0u) : c.tau_lo;
+    // (dense list: its smallest prior when the list has all the k + k_prev entries
+    // asked for; a shorter list is the whole row, whose scores may all be damped)
+    base = SECOND ? (c.dense_total >= c.f_want ? c.f_tau : 0u) : c.tau_lo;
     rank = K;
   }
   __syncthreads();
@@ -288,9 +288,9 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
     if (margin > 16777216.0) margin = 16777216.0;
     const int64_t anchor = drift > 0 ? (int64_t)tau + drift / 2 : centre;
     int64_t lo = anchor - (int64_t)margin;
-    if (shock && c.dense_total >= 2 * K) {
-      // The dense selection's list is exactly the 2k entries of largest prior,
-      // ending at f_tau.  Whether the new level persists (the k-th score stays
+    if (shock && c.dense_total >= c.f_want) {
+      // The dense selection's list is exactly the k + k_prev (normally 2k) entries of
+      // largest prior, ending at f_tau.  Whether the new level persists (the k-th score stays
       // near tau) or the residuals of this round dominate the next one - after a
       // single spike, or when the gradients have collapsed - so that its k-th
       // score is this round's 2k-th, about f_tau: a bound half a list's spacing
@@ -314,13 +314,13 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
 // grid (N), 1024 threads: the first selection of a round, for all workers.
 __global__ void __launch_bounds__(kScanBlock)
 k_select(WorkerCtl* ctl, GlobalCtl* gctl, const uint32_t* __restrict__ cand_key,
-         const uint32_t* __restrict__ bnd_key, int64_t k, uint32_t cap_r, uint32_t cap_total,
+         const uint32_t* __restrict__ bnd_key, const uint32_t* __restrict__ kn, uint32_t cap_r, uint32_t cap_total,
          uint32_t regions, uint32_t bnd_cap, float cand_target, int force_dense) {
   __shared__ uint32_t s_hist[kL1Bins];
   __shared__ uint32_t s_keys[kLdsKeys];
   __shared__ uint32_t s_w[16];
   __shared__ uint32_t s_out[2];
-  select_worker<false, kScanBlock>(blockIdx.x, ctl, gctl, cand_key, bnd_key, k, cap_r, cap_total, regions,
+  select_worker<false, kScanBlock>(blockIdx.x, ctl, gctl, cand_key, bnd_key, (int64_t)kn[blockIdx.x], cap_r, cap_total, regions,
                                    bnd_cap, cand_target, force_dense, s_hist, s_keys, s_w, s_out);
 }
 
@@ -383,12 +383,13 @@ k_sample_hist(const float* __restrict__ e, const G* __restrict__ g, const uint32
 
 // grid (N), 1024 threads.  Sets this round's bound from the sample histogram.
 __global__ void __launch_bounds__(kScanBlock)
-k_sample_bound(WorkerCtl* ctl, const uint32_t* __restrict__ shist, int64_t d, int64_t k,
+k_sample_bound(WorkerCtl* ctl, const uint32_t* __restrict__ shist, int64_t d, const uint32_t* __restrict__ kn,
                uint32_t n_sampled, int roots) {
   __shared__ uint32_t s_hist[kL1Bins];
   __shared__ uint32_t s_w[16];
   __shared__ uint32_t s_out[2];
   const uint32_t n = blockIdx.x, tid = threadIdx.x;
+  const int64_t k = (int64_t)kn[n];
   const uint32_t* gh = shist + (size_t)n * 3 * kL1Bins;
   for (uint32_t i = tid; i < kL1Bins; i += kScanBlock) s_hist[i] = gh[i];
   __syncthreads();

@@ -42,7 +42,7 @@ def ulp_threshold_ties(o: orc.Oracle, n: int, idx_gpu: np.ndarray, idx_cpu: np.n
     return int(only_gpu.size + only_cpu.size), near
 
 
-def compare_round(o: orc.Oracle, res_gpu, res_cpu, label=""):
+def compare_round(o: orc.Oracle, res_gpu, res_cpu, label="", worker_k=None):
     """Bit-exact index sets; values/aggregate within REL_TOL.  Returns the number
     of tolerated 1-ulp threshold ties (reported by the callers)."""
     idx_g, val_g, agg_g = (x.cpu().numpy() for x in res_gpu)
@@ -57,7 +57,9 @@ def compare_round(o: orc.Oracle, res_gpu, res_cpu, label=""):
             print("REPORT %s worker %d: %d mismatching indices, all within 1 ulp of the threshold" % (label, n, total))
         else:
             _rel_close(val_g[n], val_c[n], "%s val[%d]" % (label, n))
-        assert np.all(np.diff(idx_g[n].astype(np.int64)) > 0), "%s worker %d: indices not ascending" % (label, n)
+        kn = idx_g.shape[1] if worker_k is None else int(worker_k[n])
+        assert np.all(np.diff(idx_g[n, :kn].astype(np.int64)) > 0), "%s worker %d: indices not ascending" % (label, n)
+        assert np.all(idx_g[n, kn:] == -1) and np.all(val_g[n, kn:] == 0), "%s worker %d: rest of the row" % (label, n)
     if tolerated == 0:
         _rel_close(agg_g, agg_c, label + " agg")
     return tolerated
@@ -65,13 +67,15 @@ def compare_round(o: orc.Oracle, res_gpu, res_cpu, label=""):
 
 def run_both(N, d, k, mu, grads_fn, T, device="cuda:0", force_dense=False, closed_loop=None,
              label="", check_state_every=1, cand_target=None, weights=None, check_overlap=False,
-             on_round=None, grad_dtype=None, prior_roots=0, likelihood=0):
+             on_round=None, grad_dtype=None, prior_roots=0, likelihood=0, worker_k=None):
     """grads_fn(t, agg_prev_or_None) -> [N,d] float32 tensor on the GPU.
 
     Each side feeds its own aggregate back as g^{t-1}.  Returns per-round stats
     of the HIP path.  `weights`: aggregation weights omega_n for both sides;
     `check_overlap`: also compare the mask-overlap counts of every round;
     `on_round(t, res_gpu, res_cpu)`: hook after the comparison of round t;
+    `worker_k`: entries kept per worker (a list, or a function t -> list applied
+    before round t) for both sides;
     `grad_dtype`: torch.bfloat16 (or a function t -> dtype) rounds the generated
     gradients to bfloat16 first and hands the HIP path the 16-bit tensor, the
     oracle the same values widened to binary32.
@@ -94,7 +98,13 @@ def run_both(N, d, k, mu, grads_fn, T, device="cuda:0", force_dense=False, close
     agg_c = None
     stats = []
     tolerated = 0
+    kn_now = None
     for t in range(T):
+        kn_t = worker_k(t) if callable(worker_k) else (worker_k if t == 0 else None)
+        if kn_t is not None:
+            kn_now = [int(x) for x in kn_t]
+            o.set_worker_k(kn_now)
+            r.set_worker_k(kn_now)
         g = grads_fn(t, agg_g)
         assert g.is_cuda and g.dtype == torch.float32
         dt = grad_dtype(t) if callable(grad_dtype) else grad_dtype
@@ -106,7 +116,7 @@ def run_both(N, d, k, mu, grads_fn, T, device="cuda:0", force_dense=False, close
         res_c = o.step(g_host, agg_c)
         st = r.stats()
         stats.append(st)
-        tolerated += compare_round(o, res_g, res_c, "%s round %d" % (label, t))
+        tolerated += compare_round(o, res_g, res_c, "%s round %d" % (label, t), worker_k=kn_now)
         if check_overlap:
             ov_g = r.mask_overlap().cpu().numpy()
             assert np.array_equal(ov_g, o.mask_overlap()), "%s round %d: mask overlap %s vs %s" % (

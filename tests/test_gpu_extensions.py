@@ -372,3 +372,64 @@ def test_low_dimensional_study_on_the_gpu(k, mu):
     assert tol == 0
     log_gap = float(np.log(wl.gap(theta_g)))
     assert (log_gap < -9.0) if mu > 0 else (log_gap > -5.0)
+
+
+# ------------------------------------------------------------- per-worker k ----
+@pytest.mark.parametrize("case", ["mixed", "one_and_all", "changing", "dense"])
+def test_per_worker_k(case):
+    # worker n keeps its own k_n <= k entries (Algorithm 2 at worker n with that worker's Top_k);
+    # everything the round returns, the residual and the previous lists against the oracle
+    from tests.parity import run_both
+    kw = {}
+    if case == "mixed":
+        N, d, k, T = 5, 300_001, 3_000, 6
+        kn = [3_000, 1, 1_500, 17, 2_999]
+    elif case == "one_and_all":                 # k_n = 1 and k_n = d side by side
+        N, d, k, T = 4, 12_289, 12_289, 5
+        kn = [1, 12_289, 6_000, 12_288]
+    elif case == "changing":                    # k_n changes between rounds, up and down
+        N, d, k, T = 3, 200_000, 2_000, 8
+        kn = lambda t: {0: [2_000, 500, 1], 3: [100, 2_000, 1_000], 5: [1_000, 1_000, 1_000]}.get(t)
+    else:                                       # the dense selection with different k_n
+        N, d, k, T = 3, 150_000, 1_500, 5
+        kn = [1_500, 2, 700]
+        kw["force_dense"] = True
+    cfg = workloads.scaled(workloads.CONFIGS["large_cnn"], d=d, N=N, k=k)
+    wl = workloads.Workload(cfg, DEV)
+    print("case per-worker k %s" % case, flush=True)
+    stats, tol = run_both(N, d, k, 1.0, lambda t, agg: wl.grads(t), T, label="worker_k " + case, worker_k=kn,
+                          check_overlap=True, **kw)
+    assert tol == 0
+
+
+def test_per_worker_k_argument_checks_state_roundtrip_and_global_round():
+    N, d, k = 3, 50_000, 500
+    cfg = workloads.scaled(workloads.CONFIGS["large_cnn"], d=d, N=N, k=k)
+    wl = workloads.Workload(cfg, DEV)
+    r = binding.RegTopk(N, d, k, 1.0, device=DEV)
+    for bad in ([0, 5, 5], [501, 5, 5]):
+        with pytest.raises(binding.RegTopkError) as e:
+            r.set_worker_k(bad)
+        assert e.value.code == binding.INVALID_ARG
+    r.set_worker_k([500, 20, 250])
+    with pytest.raises(binding.RegTopkError) as e:
+        r.step_global(wl.grads(0))
+    assert e.value.code == binding.BAD_STATE
+    agg = None
+    for t in range(3):
+        idx, val, agg = r.step(wl.grads(t), agg)
+        agg = agg.clone()
+    # the state moved to a fresh context (same k_n) continues bit for bit
+    e_, pidx, pval, tt = r.get_state()
+    assert tt == 3 and bool((pidx[1, 20:] == -1).all()) and bool((pidx[2, 250:] == -1).all())
+    r2 = binding.RegTopk(N, d, k, 1.0, device=DEV)
+    r2.set_worker_k([500, 20, 250])
+    r2.set_state(e_, pidx, pval, tt)
+    g = wl.grads(3)
+    a = [x.clone() for x in r.step(g, agg)]
+    b = [x.clone() for x in r2.step(g, agg)]
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+    r.stats(); r2.stats()
+    r.close(); r2.close()

@@ -88,3 +88,43 @@ def test_random_small_configurations(block):
         r.stats()                                  # raises if a device-side consistency check failed
         r.close()
         o.close()
+
+
+@pytest.mark.parametrize("block", range(2))
+def test_random_configurations_with_per_worker_k(block):
+    # the same sweep with every worker keeping its own k_n (drawn per case, redrawn once mid-run)
+    rng = np.random.default_rng(20260105 + block)
+    for case in range(12):
+        N, d, k, mu, pattern, opts = _draw_case(rng)
+        if N == 1:
+            N = 4
+        label = "worker-k block %d case %d: N=%d d=%d k=%d mu=%g %s dense=%s" % (
+            block, case, N, d, k, mu, pattern, opts["force_dense"])
+        print(label, flush=True)
+        o = orc.Oracle(N, d, k, mu)
+        r = binding.RegTopk(N, d, k, mu, device=DEV)
+        if opts["force_dense"]:
+            r.set_option(binding.OPT_FORCE_DENSE, 1)
+        agg_g = agg_c = None
+        for t in range(5):
+            if t in (0, 3):
+                kn = [int(x) for x in rng.integers(1, k + 1, size=N)]
+                kn[int(rng.integers(N))] = k
+                kn[int(rng.integers(N))] = 1
+                o.set_worker_k(kn)
+                r.set_worker_k(kn)
+            g = torch.from_numpy(_grads(rng, pattern, N, d, t)).to(DEV)
+            res_g = r.step(g.contiguous(), agg_g)
+            res_c = o.step(g.cpu().numpy(), agg_c)
+            torch.cuda.synchronize()
+            idx, val, agg = (x.cpu().numpy() for x in res_g)
+            assert np.array_equal(idx, res_c[0]), label + " round %d: indices" % t
+            assert np.array_equal(val.view(np.uint32), res_c[1].view(np.uint32)), label + " round %d: values" % t
+            assert np.array_equal(agg.view(np.uint32), res_c[2].view(np.uint32)), label + " round %d: aggregate" % t
+            assert np.array_equal(r.mask_overlap().cpu().numpy(), o.mask_overlap()), label + " round %d: overlap" % t
+            agg_g, agg_c = res_g[2].clone(), res_c[2]
+        e = r.get_state()[0].cpu().numpy()
+        assert np.array_equal(e.view(np.uint32), o.e.view(np.uint32)), label + ": residual"
+        r.stats()
+        r.close()
+        o.close()
