@@ -133,9 +133,16 @@ int regtopk_step_bf16(regtopk_ctx* ctx, const uint16_t* grads_bf16_dev, const fl
  * abar is summed like the aggregate: from +0, + omega_n * a_n in ascending
  * worker order.  Shares the state with regtopk_step (rounds of both kinds may
  * alternate; a following regtopk_step regularises with this round's mask).
- * The first call allocates a selector context for one row of d entries and a
- * d-vector with hipMalloc (freed by regtopk_destroy); out->agg lives in that
- * selector and stays valid until the next regtopk_step_global. */
+ * The round needs a selector over one row of d entries, which lives in
+ * regtopk_global_workspace_bytes(d, k) bytes of device memory.  A context made
+ * by regtopk_create allocates them with hipMalloc on the first call (freed by
+ * regtopk_destroy).  A context made by regtopk_create_in never allocates: the
+ * caller hands the memory over once with regtopk_bind_global (256-byte aligned,
+ * must outlive the context; its contents are overwritten), otherwise
+ * regtopk_step_global returns REGTOPK_BAD_STATE.  out->agg lives in that memory
+ * and stays valid until the next regtopk_step_global. */
+size_t regtopk_global_workspace_bytes(int64_t d, int64_t k);
+int regtopk_bind_global(regtopk_ctx* ctx, void* mem_dev, size_t bytes, void* stream);
 int regtopk_step_global(regtopk_ctx* ctx, const float* grads_dev, void* stream, regtopk_result* out);
 
 int regtopk_destroy(regtopk_ctx* ctx);

@@ -20,6 +20,7 @@ OPT_FORCE_DENSE, OPT_CAND_TARGET, OPT_PROFILE, OPT_PRIOR_ROOTS, OPT_LIKELIHOOD =
 # every symbol include/regtopk.h declares
 SYMBOLS = [
     "regtopk_workspace_bytes", "regtopk_create", "regtopk_create_in", "regtopk_step", "regtopk_step_bf16", "regtopk_step_global",
+    "regtopk_global_workspace_bytes", "regtopk_bind_global",
     "regtopk_destroy", "regtopk_reset", "regtopk_get_state", "regtopk_set_state",
     "regtopk_get_stats", "regtopk_set_option", "regtopk_get_timings", "regtopk_tanh_f32",
     "regtopk_copy_f32", "regtopk_set_weights", "regtopk_set_worker_k", "regtopk_mask_overlap", "regtopk_mask_overlap_static", "regtopk_sgd_update",
@@ -64,6 +65,9 @@ def load():
     lib.regtopk_step.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, ctypes.POINTER(Result)]
     lib.regtopk_step_bf16.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, ctypes.POINTER(Result)]
     lib.regtopk_step_global.argtypes = [c_void_p, c_void_p, c_void_p, ctypes.POINTER(Result)]
+    lib.regtopk_global_workspace_bytes.restype = c_size_t
+    lib.regtopk_global_workspace_bytes.argtypes = [c_int64, c_int64]
+    lib.regtopk_bind_global.argtypes = [c_void_p, c_void_p, c_size_t, c_void_p]
     lib.regtopk_destroy.argtypes = [c_void_p]
     lib.regtopk_reset.argtypes = [c_void_p, c_void_p]
     lib.regtopk_get_state.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p,
@@ -136,6 +140,8 @@ class RegTopk:
         self.device = torch.device(device)
         self._h = c_void_p()
         self._arena = None
+        self._garena = None          # memory of the global Top-k round's selector (torch-owned arenas only)
+        self._own_arena = own_arena
         with torch.cuda.device(self.device):
             if own_arena:
                 _check(self.lib.regtopk_create(ctypes.byref(self._h), self.N, self.d, self.k, self.mu))
@@ -154,6 +160,7 @@ class RegTopk:
             self.lib.regtopk_destroy(self._h)
             self._h = c_void_p()
             self._arena = None
+            self._garena = None
 
     def __del__(self):
         try:
@@ -189,11 +196,17 @@ class RegTopk:
             raise ValueError("grads must be a contiguous float32 [N,d] tensor on %s" % self.device)
         res = Result()
         with torch.cuda.device(self.device):
+            if self._arena is not None and self._garena is None:
+                # the context lives in torch's memory, so the selector of the global round does too
+                nbytes = int(self.lib.regtopk_global_workspace_bytes(self.d, self.k))
+                self._garena = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+                aligned = (self._garena.data_ptr() + 255) // 256 * 256
+                _check(self.lib.regtopk_bind_global(self._h, c_void_p(aligned), nbytes, _stream_ptr(torch)))
             _check(self.lib.regtopk_step_global(self._h, c_void_p(grads.data_ptr()), _stream_ptr(torch),
                                                 ctypes.byref(res)))
         idx = _view(torch, res.idx, (self.N, self.k), torch.int32, self.device, self._arena)
         val = _view(torch, res.val, (self.N, self.k), torch.float32, self.device, self._arena)
-        agg = _view(torch, res.agg, (self.d,), torch.float32, self.device, None)
+        agg = _view(torch, res.agg, (self.d,), torch.float32, self.device, self._garena)
         return idx, val, agg
 
     def reset(self):

@@ -167,7 +167,6 @@ struct regtopk_ctx {
   bool uniform_k;       // every worker keeps k entries (no regtopk_set_worker_k with other values)
   bool internal;        // the selector of a global Top-k round: always driven on its owner's stream
   regtopk_ctx* gsel;    // global Top-k: a one-row context that selects over the unsparsified aggregate
-  float* abar;          // global Top-k: that aggregate, [d]
   char* arena;
   Layout L;
   template <typename T> T* at(size_t off) const { return reinterpret_cast<T*>(arena + off); }
@@ -216,7 +215,6 @@ int create_common(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu, 
   c->likelihood = 0;
   c->reinit_ctl = false;
   c->gsel = nullptr;
-  c->abar = nullptr;
   c->cand_target = 1.25f;
   c->profile = false;
   c->prof_rounds = 0;
@@ -335,7 +333,6 @@ int regtopk_destroy(regtopk_ctx* c) {
   if (c->profile)
     for (auto& row : c->ev) for (auto& e : row) (void)hipEventDestroy(e);
   if (c->gsel && regtopk_destroy(c->gsel) != REGTOPK_OK) rc = REGTOPK_HIP_ERROR;
-  if (c->abar && hipFree(c->abar) != hipSuccess) rc = fail(REGTOPK_HIP_ERROR, "hipFree failed");
   if (c->owns_arena && hipFree(c->arena) != hipSuccess) rc = fail(REGTOPK_HIP_ERROR, "hipFree failed");
   if (c->host_err && hipHostFree(c->host_err) != hipSuccess) rc = fail(REGTOPK_HIP_ERROR, "hipHostFree failed");
   gate_leave(c);
@@ -387,10 +384,12 @@ int regtopk_set_option(regtopk_ctx* c, int option, double value) {
 
 namespace {
 
-// One round; G is the element type of the local gradients.
+// One round; G is the element type of the local gradients.  pre: the state
+// already holds the accumulated values (the selector of a global Top-k round),
+// grads is not read.
 template <typename G>
-int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, regtopk_result* out) {
-  if (!c || !grads || !out) return fail(REGTOPK_INVALID_ARG, "ctx, grads_dev and out must not be NULL");
+int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, regtopk_result* out, bool pre = false) {
+  if (!c || (!grads && !pre) || !out) return fail(REGTOPK_INVALID_ARG, "ctx, grads_dev and out must not be NULL");
   if (*static_cast<volatile uint32_t*>(c->host_err) != 0)
     return fail(REGTOPK_BAD_STATE, "an earlier round abandoned its dense selection (its blocks were not resident "
                                    "together); the state is undefined until regtopk_reset or regtopk_set_state");
@@ -404,7 +403,7 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
   const int64_t d = c->d, k = c->k;
   const uint32_t nc = L.nc;
   const int cur = (int)(c->t & 1), prv = cur ^ 1;
-  const bool vec = (d % 4 == 0) && (reinterpret_cast<uintptr_t>(grads) % (4 * sizeof(G)) == 0);
+  const bool vec = (d % 4 == 0) && (pre || reinterpret_cast<uintptr_t>(grads) % (4 * sizeof(G)) == 0);
 
   WorkerCtl* ctl = c->at<WorkerCtl>(L.ctl);
   GlobalCtl* gctl = c->at<GlobalCtl>(L.gctl);
@@ -460,12 +459,17 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
     // of many blocks to the same few words queue up (about 12 ns each)
     uint32_t sample_blocks = (n_groups + 4 * kBlock - 1) / (4 * kBlock);
     if (sample_blocks > 16) sample_blocks = 16;
-    k_sample_hist<G><<<dim3(sample_blocks, N), kBlock, 0, s>>>(e, grads, mask, d, nc, fhist, n_groups, stride4, sk.roots);
+    if (pre) k_sample_hist_state<<<dim3(sample_blocks, N), kBlock, 0, s>>>(e, d, fhist, n_groups, stride4, sk.roots);
+    else k_sample_hist<G><<<dim3(sample_blocks, N), kBlock, 0, s>>>(e, grads, mask, d, nc, fhist, n_groups, stride4, sk.roots);
     k_sample_bound<<<N, kScanBlock, 0, s>>>(ctl, fhist, d, kn, (uint32_t)n_sampled, sk.roots);
   }
   if (c->fresh > 0) c->fresh -= 1;
   if (ev) HIP_TRY(hipEventRecord(ev[0], s));
-  if (vec)
+  if (pre && vec)
+    k_emit_only<true><<<g_chunks, kBlock, 0, s>>>(e, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
+  else if (pre)
+    k_emit_only<false><<<g_chunks, kBlock, 0, s>>>(e, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
+  else if (vec)
     k_accum_emit<true, G><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   else
     k_accum_emit<false, G><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
@@ -524,31 +528,49 @@ int regtopk_step(regtopk_ctx* c, const float* grads, const float* gprev, void* s
   return step_impl<float>(c, grads, gprev, stream, out);
 }
 
+// Makes the selector of the global Top-k rounds (one row of d entries, plain
+// Top-k) in `mem`.
+static int bind_global_impl(regtopk_ctx* c, void* mem, size_t bytes, bool owned, hipStream_t s) {
+  regtopk_ctx* g = nullptr;
+  int rc = create_common(&g, 1, c->d, c->k, 0.0f, mem, bytes, owned, s, true);
+  if (rc != REGTOPK_OK) return rc;
+  c->gsel = g;
+  return REGTOPK_OK;
+}
+
+size_t regtopk_global_workspace_bytes(int64_t d, int64_t k) {
+  Layout L;
+  return make_layout(1, d, k, &L) ? L.total : 0;
+}
+
+int regtopk_bind_global(regtopk_ctx* c, void* mem_dev, size_t bytes, void* stream) {
+  if (!c || !mem_dev) return fail(REGTOPK_INVALID_ARG, "ctx and mem_dev must not be NULL");
+  if (c->gsel) return fail(REGTOPK_BAD_STATE, "the global Top-k round already has its memory");
+  if (reinterpret_cast<uintptr_t>(mem_dev) % kAlign) return fail(REGTOPK_INVALID_ARG, "mem_dev must be 256-byte aligned");
+  const size_t need = regtopk_global_workspace_bytes(c->d, c->k);
+  if (bytes < need) return fail(REGTOPK_NO_MEMORY, "memory has %zu bytes, %zu needed", bytes, need);
+  return bind_global_impl(c, mem_dev, bytes, false, static_cast<hipStream_t>(stream));
+}
+
 int regtopk_step_global(regtopk_ctx* c, const float* grads, void* stream, regtopk_result* out) {
   if (!c || !grads || !out) return fail(REGTOPK_INVALID_ARG, "ctx, grads_dev and out must not be NULL");
   if (reinterpret_cast<uintptr_t>(grads) % 4) return fail(REGTOPK_INVALID_ARG, "grads_dev must be 4-byte aligned");
   if (!c->uniform_k) return fail(REGTOPK_BAD_STATE, "the global Top-k round shares one mask of k entries: per-worker k is set");
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (!c->gsel) {
-    // first use: the selector over the aggregate (one row, plain Top-k) and the aggregate itself
-    regtopk_ctx* g = nullptr;
-    Layout GL;
-    if (!make_layout(1, c->d, c->k, &GL)) return fail(REGTOPK_INVALID_ARG, "sizes have no valid layout");
+    // first use.  A context that owns its arena allocates the selector's memory as well; one that
+    // lives in the caller's memory never allocates: the caller binds the memory beforehand.
+    if (!c->owns_arena)
+      return fail(REGTOPK_BAD_STATE, "this context lives in caller-owned memory: give the global Top-k round its "
+                                     "memory with regtopk_bind_global first");
+    const size_t bytes = regtopk_global_workspace_bytes(c->d, c->k);
     void* ga = nullptr;
-    if (hipMalloc(&ga, GL.total) != hipSuccess) {
+    if (bytes == 0 || hipMalloc(&ga, bytes) != hipSuccess) {
       (void)hipGetLastError();
-      return fail(REGTOPK_NO_MEMORY, "hipMalloc of %zu bytes failed", GL.total);
+      return fail(REGTOPK_NO_MEMORY, "hipMalloc of %zu bytes failed", bytes);
     }
-    int rc = create_common(&g, 1, c->d, c->k, 0.0f, ga, GL.total, true, s, true);
+    int rc = bind_global_impl(c, ga, bytes, true, s);
     if (rc != REGTOPK_OK) { (void)hipFree(ga); return rc; }
-    void* p = nullptr;
-    if (hipMalloc(&p, (size_t)c->d * 4) != hipSuccess) {
-      (void)hipGetLastError();
-      (void)regtopk_destroy(g);
-      return fail(REGTOPK_NO_MEMORY, "hipMalloc of %zu bytes failed", (size_t)c->d * 4);
-    }
-    c->gsel = g;
-    c->abar = static_cast<float*>(p);
   }
   regtopk_ctx* g = c->gsel;
   const Layout& L = c->L;
@@ -559,22 +581,23 @@ int regtopk_step_global(regtopk_ctx* c, const float* grads, void* stream, regtop
   const uint32_t* prev_sel_off = c->at<uint32_t>(L.sel_off[prv]);
   hipEvent_t* ev = c->profile ? c->ev[c->prof_rounds % kProfRounds] : nullptr;
   if (ev) { HIP_TRY(hipEventRecord(ev[4], s)); HIP_TRY(hipEventRecord(ev[0], s)); }
-  if (vec) k_global_accum<true><<<L.nc, kBlock, 0, s>>>(e, grads, mask, prev_sel_off, c->d, L.nc, c->N, c->at<float>(L.omega), c->abar);
-  else k_global_accum<false><<<L.nc, kBlock, 0, s>>>(e, grads, mask, prev_sel_off, c->d, L.nc, c->N, c->at<float>(L.omega), c->abar);
+  // abar goes straight into the selector's state: its round neither adds nor stores anything
+  float* abar = g->at<float>(g->L.e);
+  const uint32_t acc_blocks = (uint32_t)((c->d + 4 * kGlobalBlock - 1) / (4 * kGlobalBlock));
+  if (vec) k_global_accum<true, kGlobalRows, kGlobalBlock><<<acc_blocks, kGlobalBlock, 0, s>>>(e, grads, mask, c->d, L.nc, c->N, c->at<float>(L.omega), abar);
+  else k_global_accum<false, 1, kGlobalBlock><<<acc_blocks, kGlobalBlock, 0, s>>>(e, grads, mask, c->d, L.nc, c->N, c->at<float>(L.omega), abar);
   if (ev) HIP_TRY(hipEventRecord(ev[1], s));
-  // the selector must see abar alone: its own error state restarts at zero every round
-  // (its bounds and window carry over: the k-th magnitude of abar moves slowly)
-  k_fill_u32<<<2048, 256, 0, s>>>(g->at<uint32_t>(g->L.e), (size_t)c->d, 0u);
   HIP_TRY(hipGetLastError());
   regtopk_result sel;
   const int gcur = (int)(g->t & 1);
-  int rc = regtopk_step(g, c->abar, nullptr, stream, &sel);
+  int rc = step_impl<float>(g, nullptr, nullptr, stream, &sel, true);
   if (rc != REGTOPK_OK) return rc;
   if (ev) HIP_TRY(hipEventRecord(ev[2], s));
-  const dim3 g_waves((L.nc + 3) / 4, c->N);
-  k_global_apply<<<g_waves, kBlock, 0, s>>>(e, sel.idx, g->at<uint32_t>(g->L.sel_off[gcur]), g->at<uint32_t>(g->L.mask),
-                                              prev_sel_off, c->at<int32_t>(L.out_idx[cur]), c->at<float>(L.out_val[cur]),
-                                              c->at<uint32_t>(L.sel_off[cur]), mask, c->d, c->k, L.nc);
+  const uint32_t entry_blocks = (uint32_t)((c->k + kBlock - 1) / kBlock);
+  k_global_apply<<<dim3(entry_blocks + (L.nc + 3) / 4, c->N), kBlock, 0, s>>>(
+      e, sel.idx, g->at<uint32_t>(g->L.sel_off[gcur]), g->at<uint32_t>(g->L.mask), prev_sel_off,
+      c->at<int32_t>(L.out_idx[cur]), c->at<float>(L.out_val[cur]), c->at<uint32_t>(L.sel_off[cur]), mask, c->d, c->k, L.nc,
+      entry_blocks);
   if (ev) { HIP_TRY(hipEventRecord(ev[3], s)); c->prof_rounds += 1; }
   HIP_TRY(hipGetLastError());
   c->t += 1;

@@ -381,6 +381,29 @@ k_sample_hist(const float* __restrict__ e, const G* __restrict__ g, const uint32
   }
 }
 
+// The same sample of a row whose state already holds the accumulated values.
+__global__ void __launch_bounds__(kBlock)
+k_sample_hist_state(const float* __restrict__ e, int64_t d, uint32_t* __restrict__ shist, uint32_t n_groups,
+                    uint32_t stride4, int roots) {
+  __shared__ uint32_t s_hist[kL1Bins];
+  const uint32_t n = blockIdx.y, tid = threadIdx.x;
+  for (uint32_t i = tid; i < kL1Bins; i += kBlock) s_hist[i] = 0;
+  __syncthreads();
+  const size_t row = (size_t)n * (size_t)d;
+  for (uint32_t i = blockIdx.x * kBlock + tid; i < n_groups; i += gridDim.x * kBlock) {
+    const int64_t j0 = (int64_t)i * stride4 * 4;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (j0 + q < d) atomicAdd(&s_hist[prior_key(e[row + j0 + q], roots) >> kL1Shift], 1u);
+  }
+  __syncthreads();
+  uint32_t* gh = shist + (size_t)n * 3 * kL1Bins;
+  for (uint32_t i = tid; i < kL1Bins; i += kBlock) {
+    const uint32_t v = s_hist[i];
+    if (v) atomicAdd(&gh[i], v);
+  }
+}
+
 // grid (N), 1024 threads.  Sets this round's bound from the sample histogram.
 __global__ void __launch_bounds__(kScanBlock)
 k_sample_bound(WorkerCtl* ctl, const uint32_t* __restrict__ shist, int64_t d, const uint32_t* __restrict__ kn,

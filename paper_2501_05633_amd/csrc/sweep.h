@@ -102,6 +102,54 @@ __device__ __forceinline__ f32x4 grad4_at(const bf16_t* g, size_t i) {
   return r;
 }
 
+// Appends the flagged entries of the block's chunk (flags bit i*4+q = entry
+// (i, lane, q), see ChunkPos) to worker n's candidate list, in index order: one
+// atomic per block reserves room in region c % regions.  a = accumulated
+// gradients, eo = what the state held, mb = previous-mask bits.  Called by all
+// threads of the block.
+__device__ __forceinline__ void emit_chunk(uint32_t flags, const float (&a)[4][4], const float (&eo)[4][4],
+                                           const uint32_t (&mb)[4], int64_t base, uint32_t n, uint32_t c,
+                                           WorkerCtl* __restrict__ ctl, int32_t* __restrict__ cand_idx,
+                                           float* __restrict__ cand_val, float* __restrict__ cand_prev,
+                                           uint32_t* __restrict__ ch_off, uint32_t* __restrict__ ch_cnt,
+                                           uint32_t nc, uint32_t cap_r, uint32_t cap_total, uint32_t regions,
+                                           uint32_t* s_wtot, uint32_t* s_base_p) {
+  const uint32_t tid = threadIdx.x;
+  const ChunkPos cp = ordered_positions(flags, s_wtot);
+  const size_t tix = (size_t)n * nc + c;
+  if (cp.total == 0) {
+    if (tid == 0) { ch_off[tix] = 0; ch_cnt[tix] = 0; }
+    return;
+  }
+  if (tid == 0) {
+    const uint32_t r = c % regions;
+    const uint32_t off = atomicAdd(&ctl[n].cursor[r], cp.total);
+    uint32_t b = kNoBound;
+    if (off + cp.total <= cap_r) b = r * cap_r + off;
+    else ctl[n].overflow = 1;
+    *s_base_p = b;
+    ch_off[tix] = (b == kNoBound) ? 0 : b;
+    ch_cnt[tix] = (b == kNoBound) ? 0 : cp.total;
+  }
+  __syncthreads();
+  const uint32_t b = *s_base_p;
+  if (b == kNoBound || flags == 0) return;
+  const size_t out = (size_t)n * cap_total + b + cp.wave_base;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    uint32_t p = cp.lane_base[i];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if ((flags >> (i * 4 + q)) & 1u) {
+        cand_idx[out + p] = (int32_t)((uint32_t)(base + i * 256 + q) | (((mb[i] >> q) & 1u) ? kSentFlag : 0u));
+        cand_val[out + p] = a[i][q];
+        cand_prev[out + p] = eo[i][q];
+        ++p;
+      }
+    }
+  }
+}
+
 template <bool VEC, typename G>
 __global__ void __launch_bounds__(kBlock)
 k_accum_emit(float* __restrict__ e, const G* __restrict__ g, const uint32_t* __restrict__ mask,
@@ -180,39 +228,50 @@ k_accum_emit(float* __restrict__ e, const G* __restrict__ g, const uint32_t* __r
       }
     }
   }
-  const ChunkPos cp = ordered_positions(flags, s_wtot);
-  const size_t tix = (size_t)n * nc + c;
-  if (cp.total == 0) {
-    if (tid == 0) { ch_off[tix] = 0; ch_cnt[tix] = 0; }
-    return;
-  }
-  if (tid == 0) {
-    const uint32_t r = c % regions;
-    const uint32_t off = atomicAdd(&ctl[n].cursor[r], cp.total);
-    uint32_t b = kNoBound;
-    if (off + cp.total <= cap_r) b = r * cap_r + off;
-    else ctl[n].overflow = 1;
-    s_base = b;
-    ch_off[tix] = (b == kNoBound) ? 0 : b;
-    ch_cnt[tix] = (b == kNoBound) ? 0 : cp.total;
-  }
-  __syncthreads();
-  const uint32_t b = s_base;
-  if (b == kNoBound || flags == 0) return;
-  const size_t out = (size_t)n * cap_total + b + cp.wave_base;
+  emit_chunk(flags, a, eo, mb, base, n, c, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, cap_r, cap_total, regions,
+             s_wtot, &s_base);
+}
+
+// ----------------------------------------------------------- k_emit_only ----
+// The sweep of a row whose state already holds the accumulated values (the
+// selector of the global Top-k round: k_global_accum leaves abar there): nothing
+// is added or stored, the entries with |a| >= the bound are emitted.  grid (nc, N).
+template <bool VEC>
+__global__ void __launch_bounds__(kBlock)
+k_emit_only(const float* __restrict__ e, int64_t d, WorkerCtl* __restrict__ ctl, int32_t* __restrict__ cand_idx,
+            float* __restrict__ cand_val, float* __restrict__ cand_prev, uint32_t* __restrict__ ch_off,
+            uint32_t* __restrict__ ch_cnt, uint32_t nc, uint32_t cap_r, uint32_t cap_total, uint32_t regions) {
+  __shared__ uint32_t s_wtot[4];
+  __shared__ uint32_t s_base;
+  const uint32_t c = blockIdx.x, n = blockIdx.y;
+  const uint32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const size_t row = (size_t)n * (size_t)d;
+  const uint32_t tau_lo = ctl[n].tau_lo_mag;
+  const int64_t base = (int64_t)c * kChunk + (int64_t)wv * 1024 + lane * 4;
+  float a[4][4], eo[4][4];
+  uint32_t mb[4] = {0u, 0u, 0u, 0u};
+  uint32_t flags = 0;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    uint32_t p = cp.lane_base[i];
+    const int64_t j0 = base + i * 256;
+    f32x4 v = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (VEC) {
+      if (j0 < d) v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(e + row + j0));
+    } else {
+      if (j0 < d) v.x = e[row + j0];
+      if (j0 + 1 < d) v.y = e[row + j0 + 1];
+      if (j0 + 2 < d) v.z = e[row + j0 + 2];
+      if (j0 + 3 < d) v.w = e[row + j0 + 3];
+    }
+    a[i][0] = v.x; a[i][1] = v.y; a[i][2] = v.z; a[i][3] = v.w;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      if ((flags >> (i * 4 + q)) & 1u) {
-        cand_idx[out + p] = (int32_t)((uint32_t)(base + i * 256 + q) | (((mb[i] >> q) & 1u) ? kSentFlag : 0u));
-        cand_val[out + p] = a[i][q];
-        cand_prev[out + p] = eo[i][q];
-        ++p;
-      }
+      eo[i][q] = 0.f;
+      if (j0 + q < d && key_of(a[i][q]) >= tau_lo) flags |= 1u << (i * 4 + q);
     }
   }
+  emit_chunk(flags, a, eo, mb, base, n, c, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, cap_r, cap_total, regions,
+             s_wtot, &s_base);
 }
 
 }  // namespace rtk

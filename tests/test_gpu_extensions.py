@@ -433,3 +433,28 @@ def test_per_worker_k_argument_checks_state_roundtrip_and_global_round():
         assert torch.equal(x, y)
     r.stats(); r2.stats()
     r.close(); r2.close()
+
+
+def test_global_round_memory_of_a_context_in_caller_owned_memory():
+    # a context that lives in the caller's arena never allocates: the global Top-k round refuses to
+    # run until its memory is bound, and then gives what a library-owned context gives
+    import ctypes
+    N, d, k = 3, 40_000, 400
+    cfg = workloads.scaled(workloads.CONFIGS["large_cnn"], d=d, N=N, k=k)
+    wl = workloads.Workload(cfg, DEV)
+    own = binding.RegTopk(N, d, k, 1.0, device=DEV, own_arena=True)
+    ext = binding.RegTopk(N, d, k, 1.0, device=DEV)
+    g = wl.grads(0)
+    res = binding.Result()
+    rc = ext.lib.regtopk_step_global(ext._h, ctypes.c_void_p(g.data_ptr()),
+                                     ctypes.c_void_p(torch.cuda.current_stream().cuda_stream), ctypes.byref(res))
+    assert rc == binding.BAD_STATE and b"regtopk_bind_global" in ext.lib.regtopk_last_error()
+    assert int(ext.lib.regtopk_global_workspace_bytes(d, k)) == binding.workspace_bytes(1, d, k)
+    for t in range(3):
+        g = wl.grads(t)
+        a = [x.clone() for x in own.step_global(g)]
+        b = [x.clone() for x in ext.step_global(g)]
+        torch.cuda.synchronize()
+        for x, y in zip(a, b):
+            assert torch.equal(x, y)
+    own.close(); ext.close()
