@@ -92,11 +92,39 @@ __device__ __forceinline__ uint32_t rel_select(KeySource src, uint32_t base, uin
   const uint32_t tid = threadIdx.x;
   uint32_t want = rank;
   RankHit ha{0u, 0u};
+  // A short contiguous list (the boundary list, normally) is read from memory
+  // once, all loads of a thread in flight together, and kept in registers for
+  // every pass below.
+  constexpr uint32_t kRegVec = 8;
+  uint4 rk[kRegVec];
+  uint32_t rtail = 0, n4 = 0, rem = 0;
+  bool in_regs = src.flat != nullptr && src.lds == nullptr && src.count <= 4u * kRegVec * (uint32_t)NT;
+  if (in_regs) {
+    n4 = src.count / 4;
+    rem = src.count - 4 * n4;
+    const uint4* b4 = reinterpret_cast<const uint4*>(src.flat);
+#pragma unroll
+    for (uint32_t q = 0; q < kRegVec; ++q) {
+      const uint32_t i = tid + q * NT;
+      rk[q] = i < n4 ? b4[i] : make_uint4(0u, 0u, 0u, 0u);
+    }
+    if (tid < rem) rtail = src.flat[n4 * 4 + tid];
+  }
+  auto each_key = [&](auto f) {
+    if (in_regs) {
+#pragma unroll
+      for (uint32_t q = 0; q < kRegVec; ++q)
+        if (tid + q * NT < n4) { f(rk[q].x); f(rk[q].y); f(rk[q].z); f(rk[q].w); }
+      if (tid < rem) f(rtail);
+    } else {
+      for_each_key<NT>(src, f);
+    }
+  };
   for (int guard = 0; guard < 64; ++guard) {
     for (uint32_t i = tid; i < kL1Bins; i += NT) s_hist[i] = 0;
     __syncthreads();
     uint32_t over = 0;
-    for_each_key<NT>(src, [&](uint32_t key) {
+    each_key([&](uint32_t key) {
       if (key < base) return;
       const uint32_t rel = key - base;
       if (rel >> 25) ++over;
@@ -115,24 +143,25 @@ __device__ __forceinline__ uint32_t rel_select(KeySource src, uint32_t base, uin
   want -= ha.above;
   const uint32_t pa = ha.bin;
   // the keys of that bin are usually few: gather them in LDS once, so that the
-  // two finer levels need no further pass over memory
+  // two finer levels need no further pass over the whole list
   const uint32_t in_bin = s_hist[pa];
   __syncthreads();
   if (!src.lds && s_stash != nullptr && in_bin <= stash_cap) {
     if (tid == 0) s_out[0] = 0;
     __syncthreads();
-    for_each_key<NT>(src, [&](uint32_t key) {
+    each_key([&](uint32_t key) {
       if (key < base) return;
       if (((key - base) >> 13) == pa) s_stash[atomicAdd(&s_out[0], 1u)] = key;
     });
     __syncthreads();
     src.lds = s_stash;
     src.count = in_bin;
+    in_regs = false;
     __syncthreads();
   }
   for (uint32_t i = tid; i < 512; i += NT) s_hist[i] = 0;
   __syncthreads();
-  for_each_key<NT>(src, [&](uint32_t key) {
+  each_key([&](uint32_t key) {
     if (key < base) return;
     const uint32_t rel = key - base;
     if ((rel >> 13) == pa) atomicAdd(&s_hist[(rel >> 4) & 511u], 1u);
@@ -143,7 +172,7 @@ __device__ __forceinline__ uint32_t rel_select(KeySource src, uint32_t base, uin
   const uint32_t pb = (pa << 9) | hb.bin;
   if (tid < 16) s_hist[tid] = 0;
   __syncthreads();
-  for_each_key<NT>(src, [&](uint32_t key) {
+  each_key([&](uint32_t key) {
     if (key < base) return;
     const uint32_t rel = key - base;
     if ((rel >> 4) == pb) atomicAdd(&s_hist[rel & 15u], 1u);
@@ -168,22 +197,38 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
                                               uint32_t* s_hist, uint32_t* s_keys, uint32_t* s_w,
                                               uint32_t* s_out) {
   const uint32_t tid = threadIdx.x;
-  WorkerCtl& c = ctl[n];
+  // The worker's control block is read once, by the block together, into LDS:
+  // the many fields consulted below (most of them by thread 0 alone, one after
+  // the other) then cost no memory round trip each.  Results are stored to the
+  // block in memory (w).
+  __shared__ WorkerCtl s_ctl;
+  WorkerCtl& w = ctl[n];
+  __syncthreads();            // (a caller's loop: thread 0 may still be reading the copy of the worker before)
+  {
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(&w);
+    uint32_t* dst = reinterpret_cast<uint32_t*>(&s_ctl);
+    for (uint32_t i = tid; i < sizeof(WorkerCtl) / 4; i += NT) dst[i] = src[i];
+  }
+  __syncthreads();
+  const WorkerCtl& c = s_ctl;
   if (SECOND && !c.need_dense) return;
   const uint32_t K = (uint32_t)k;
   uint32_t n_tot = 0;
   if (!SECOND) {
     for (uint32_t r = 0; r < regions; ++r) n_tot += region_limit(c, r, cap_r);
     const bool need = force_dense || c.overflow || c.tau_lo == kNoBound || c.n_valid < K;
-    if (tid == 0) {
-      c.n_cand = n_tot;
-      c.need_dense = need ? 1u : 0u;
-      if (need) atomicOr(&gctl->any_dense, 1u);
+    if (need) {
+      if (tid == 0) {
+        w.n_cand = n_tot;
+        w.need_dense = 1u;
+        atomicOr(&gctl->any_dense, 1u);
+      }
+      return;
     }
-    if (need) return;
+    // (n_cand and need_dense = 0 are stored with the other results at the end: a store ahead of
+    // the barriers below would make the first of them wait for it)
   } else {
     n_tot = c.dense_total;
-    if (tid == 0) c.n_cand = n_tot;
   }
   const uint32_t win_lo = c.win_lo, win_hi = c.win_hi;
   const uint32_t n_hi = c.n_hi, n_bnd = c.n_bnd;
@@ -216,11 +261,13 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
   const uint32_t tau = rel_select<NT>(src, base, rank, s_hist, s_w, s_out, stash, kLdsKeys, &budget, &ties);
 
   if (tid == 0) {
-    c.tau = tau;
-    c.budget = budget;
-    c.n_gt = K - budget;
-    c.ties_total = ties;
-    c.used_window = window ? 1u : 0u;
+    w.n_cand = n_tot;
+    if (!SECOND) w.need_dense = 0u;
+    w.tau = tau;
+    w.budget = budget;
+    w.n_gt = K - budget;
+    w.ties_total = ties;
+    w.used_window = window ? 1u : 0u;
     // ---- bound and window of the next round
     // density of scores per bit pattern just below / around tau
     double dens;
@@ -281,7 +328,7 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
     } else {
       ms = ms > 1.0f ? 1.0f + (ms - 1.0f) * 0.7f : (ms * 1.3f > 1.0f ? 1.0f : ms * 1.3f);
     }
-    c.margin_scale = ms;
+    w.margin_scale = ms;
     double margin = ((double)cand_target - 1.0) * (double)K / dens;
     if (margin < (double)err + 1024.0) margin = (double)err + 1024.0;
     margin *= (double)ms;
@@ -301,13 +348,13 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
       if (lo2 < lo) lo = lo2;
     }
     const bool speculate = (int64_t)n_tot >= (int64_t)((double)cand_target * (double)K) || !SECOND;
-    c.next_tau_lo = speculate ? (uint32_t)(lo > 0 ? lo : 0) : kNoBound;
-    c.next_win_lo = speculate ? (uint32_t)(centre > (int64_t)h ? centre - (int64_t)h : 0) : kNoBound;
-    c.next_win_hi = (uint32_t)centre + h;
-    c.tau_prev = tau;
-    c.centre = speculate ? (uint32_t)centre : kNoBound;
-    c.err_prev = err;
-    c.extrapolated = (speculate && drift != 0) ? 1u : 0u;
+    w.next_tau_lo = speculate ? (uint32_t)(lo > 0 ? lo : 0) : kNoBound;
+    w.next_win_lo = speculate ? (uint32_t)(centre > (int64_t)h ? centre - (int64_t)h : 0) : kNoBound;
+    w.next_win_hi = (uint32_t)centre + h;
+    w.tau_prev = tau;
+    w.centre = speculate ? (uint32_t)centre : kNoBound;
+    w.err_prev = err;
+    w.extrapolated = (speculate && drift != 0) ? 1u : 0u;
   }
 }
 

@@ -128,11 +128,13 @@ __device__ __forceinline__ void emit_chunk(uint32_t flags, const float (&a)[4][4
     if (off + cp.total <= cap_r) b = r * cap_r + off;
     else ctl[n].overflow = 1;
     *s_base_p = b;
-    ch_off[tix] = (b == kNoBound) ? 0 : b;
-    ch_cnt[tix] = (b == kNoBound) ? 0 : cp.total;
   }
   __syncthreads();
   const uint32_t b = *s_base_p;
+  if (tid == 0) {                        // (stored after the barrier, which would otherwise wait for these stores)
+    ch_off[tix] = (b == kNoBound) ? 0 : b;
+    ch_cnt[tix] = (b == kNoBound) ? 0 : cp.total;
+  }
   if (b == kNoBound || flags == 0) return;
   const size_t out = (size_t)n * cap_total + b + cp.wave_base;
 #pragma unroll
