@@ -16,6 +16,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "regtopk_oracle.cpp")
 _LIB = os.path.join(_HERE, "libregtopk_oracle.so")
+# tests/test_oracle_mutations.py points this at a deliberately broken build to show that the pins notice
+_LIB_OVERRIDE = os.environ.get("REGTOPK_ORACLE_LIB")
 _lib = None
 
 # No FMA contraction, no fast-math: every operation is a single IEEE rounding.
@@ -38,7 +40,7 @@ def _load():
     global _lib
     if _lib is not None:
         return _lib
-    lib = ctypes.CDLL(build())
+    lib = ctypes.CDLL(_LIB_OVERRIDE or build())
     c = ctypes
     lib.rtk_oracle_create.restype = c.c_void_p
     lib.rtk_oracle_create.argtypes = [c.c_int32, c.c_int64, c.c_int64, c.c_float]

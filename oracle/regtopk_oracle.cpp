@@ -62,6 +62,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstring>
+#include <limits>
 #include <numeric>
 #include <vector>
 
@@ -85,7 +86,13 @@ struct Oracle {
     std::vector<float> ghat;     // [N*d] sparsified gradient of the last round
 };
 
-// tanh step: correctly rounded binary32 tanh (see header).
+// tanh step: correctly rounded binary32 tanh (see header).  Rounding the
+// extended-precision value once more to binary32 gives the correctly rounded
+// result only if the intermediate carries far more than 24 bits: the x87 format
+// (64-bit significand) does, a long double that is binary64 would not be
+// trusted here.
+static_assert(std::numeric_limits<long double>::digits >= 64,
+              "the oracle's tanh needs a long double with a 64-bit significand (x87 extended precision)");
 float tanh32(float x) {
     return (float)tanhl((long double)x);
 }

@@ -371,3 +371,41 @@ def test_linear_regression_n20_what_the_oracle_reproduces_of_the_papers_claims()
     assert dense < 1e-3 and topk > 100 * dense, (dense, topk)
     # Top-k has stalled, not merely slowed down: 1000 more iterations change nothing
     assert abs(ls.run(0, 0.6, 0.0, T=T + 1000) - topk) < 0.3 * topk
+
+
+def test_round_level_wiring_of_the_distortion_sole_sender_and_two_senders():
+    # Which quantities the round hands to the distortion: g^{t-1} (the aggregate), a^{t-1} (what the
+    # worker sent then) and a^t (its new accumulated gradient) -- with gradients that change between
+    # the rounds, so that a^{t-1} != a^t on the sent entries.
+    # (1) One worker: every sent entry had a sole sender, the aggregate there is omega * a^{t-1}
+    #     exactly, the distortion is 0 and the score is |a^t| * tanh(1/mu); unsent entries score |a^t|.
+    mu = 0.7
+    rng = np.random.default_rng(5)
+    g0 = rng.standard_normal((1, 12)).astype(np.float32)
+    g1 = rng.standard_normal((1, 12)).astype(np.float32)
+    o = oracle.Oracle(1, 12, 4, mu)
+    idx0, val0, agg0 = o.step(g0, None)
+    o.step(g1, agg0)
+    a1, sc1 = o.a[0], o.score[0]
+    f = np.float32(oracle.tanh32(np.float32(1.0) / np.float32(mu)))
+    sent = np.zeros(12, dtype=bool)
+    sent[idx0[0]] = True
+    assert np.array_equal(a1[sent], g1[0][sent]) and np.array_equal(a1[~sent], (g0 + g1)[0][~sent])
+    assert np.array_equal(sc1[sent], np.abs(a1[sent]) * f)
+    assert np.array_equal(sc1[~sent], np.abs(a1[~sent]))
+    # (2) Two workers that both sent entry 0 in round 0: Delta_1 = (g^0 - w v_1) / (w a_1^1) with
+    #     g^0 = w v_1 + w v_2, evaluated here in 200-bit arithmetic from the binary32 inputs.
+    import mpmath
+    mpmath.mp.prec = 200
+    g0 = np.array([[4.0, 0.1, 0.2], [3.0, 0.3, -0.1]], dtype=np.float32)
+    g1 = np.array([[1.7, 0.05, 0.1], [-2.2, 0.2, 0.3]], dtype=np.float32)
+    o = oracle.Oracle(2, 3, 1, mu)
+    idx0, val0, agg0 = o.step(g0, None)
+    assert idx0.tolist() == [[0], [0]]
+    o.step(g1, agg0)
+    w = mpmath.mpf(0.5)
+    for n in range(2):
+        a_now = mpmath.mpf(float(g1[n, 0]))                      # the error was cleared on the sent entry
+        delta = (mpmath.mpf(float(agg0[0])) - w * mpmath.mpf(float(g0[n, 0]))) / (w * a_now)
+        want = abs(a_now) * mpmath.tanh(abs(1 + delta) / mpmath.mpf(float(np.float32(mu))))
+        assert abs(mpmath.mpf(float(o.score[n, 0])) - want) <= 4e-7 * want, (n, o.score[n, 0], want)
