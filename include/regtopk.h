@@ -10,7 +10,8 @@
  *        score_j = |a_j| * tanh(|1 + Delta_j| / mu)   for j sent in the previous round,
  *        score_j = |a_j|                              otherwise (constant C = 1),
  *        Delta_j = (gprev_j - w a^{t-1}_j) / (w a^t_j),  w = omega_n (1/N unless set)
- *        (paper: posterior-distortion equation, label eq:Delta_def; likelihood
+ *        (paper: definition of the posterior distortion Delta in the subsection
+ *        "Characterizing the Likelihood"; likelihood
  *        with tanh in the section "RegTop-k Algorithm"; Algorithm 2 mask line);
  *   3. exact Top_k of the score, exactly k entries, the lower index winning
  *        among equal scores (paper: Top_k selector of the subsection "Top-k:
@@ -52,7 +53,7 @@ extern "C" {
 
 #define REGTOPK_OK            0
 #define REGTOPK_INVALID_ARG  -1   /* bad size, null pointer, misaligned pointer, mu < 0 or NaN */
-#define REGTOPK_BAD_STATE    -2   /* e.g. set_state with indices that are not ascending */
+#define REGTOPK_BAD_STATE    -2   /* e.g. set_state with indices that are not ascending; a round that was given up */
 #define REGTOPK_HIP_ERROR    -3   /* a HIP call or kernel launch failed */
 #define REGTOPK_NO_MEMORY    -4   /* arena too small / allocation failed */
 
@@ -84,7 +85,9 @@ typedef struct {
   uint32_t window_half;   /* half width of that window in binary32 bit patterns (0 = none) */
 } regtopk_worker_stats;
 
-/* Bytes of device memory a context needs for (N, d, k).  0 on invalid sizes. */
+/* Bytes of device memory a context needs for (N, d, k): the state of Algorithm 2
+ * for N workers (eps, previous lists), the outputs and the kernels' work areas.
+ * 0 on invalid sizes. */
 size_t regtopk_workspace_bytes(int32_t N, int64_t d, int64_t k);
 
 /* Creates a context: eps = 0, round counter 0, empty previous mask
@@ -108,7 +111,17 @@ int regtopk_create_in(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float 
  *                      the `agg` pointer of the previous result); read only;
  *                      ignored (may be NULL) in round 0 and when mu == 0.
  * Rows are read with 128-bit loads when d is a multiple of 4 and grads_dev is
- * 16-byte aligned, otherwise with scalar loads. */
+ * 16-byte aligned, otherwise with scalar loads.
+ * When a worker's speculative bound fails, its exact selection runs in a kernel
+ * whose blocks synchronise with each other and must all be resident on the GPU
+ * together.  The library never lets two such kernels of one process run at the
+ * same time on a device (launches of different contexts are chained by an
+ * event).  If the blocks still do not become resident together within a bounded
+ * wait (another process saturating the same GPU), the kernel gives the round
+ * up rather than compute from half-finished phases: the workers concerned are
+ * flagged, regtopk_get_stats returns REGTOPK_BAD_STATE, and so does every
+ * regtopk_step called after the kernel has run, until regtopk_reset or
+ * regtopk_set_state; the lists of that round are undefined. */
 int regtopk_step(regtopk_ctx* ctx, const float* grads_dev, const float* prev_aggregate_dev,
                  void* stream, regtopk_result* out);
 
@@ -147,10 +160,15 @@ int regtopk_step_global(regtopk_ctx* ctx, const float* grads_dev, void* stream, 
 
 int regtopk_destroy(regtopk_ctx* ctx);
 
-/* Back to the state after create (eps = 0, round 0, no previous mask). */
+/* Back to the state after create: eps = 0, round 0, no previous mask (paper:
+ * initialisation line of Algorithm 2).  Enqueued on `stream`. */
 int regtopk_reset(regtopk_ctx* ctx, void* stream);
 
-/* Copies the persistent state out / in (device buffers of the caller):
+/* Copies the persistent state out / in (device buffers of the caller).  The
+ * state is what Algorithm 2 carries from round to round at worker n: the
+ * sparsification error eps_n, the previous mask s_n^{t-1} and the accumulated
+ * gradient a_n^{t-1} on that mask (as index and value lists), and the round
+ * counter:
  *   e_dev [N,d] error eps, pidx_dev [N,k] / pval_dev [N,k] previous round's
  *   selected indices (ascending) and values, *t_host the round counter.
  * Before round 1 the previous lists are empty and pidx/pval are not written /
@@ -238,6 +256,16 @@ int regtopk_set_option(regtopk_ctx* ctx, int option, double value);
  * + 3 the whole round.  Waits for the recorded events. */
 int regtopk_get_timings(regtopk_ctx* ctx, float* out_host, int32_t max_rounds, int32_t* n_rounds);
 
+/* Text of the last error on the calling thread ("" if none). */
+const char* regtopk_last_error(void);
+
+/* ------------------------------------------------------------------------
+ * Test and profiling hooks.  Not part of the method's interface: the tests use
+ * the first to compare the tanh step exhaustively, the benchmark launches the
+ * second once as the dispatch of known size against which hardware traffic
+ * counters are scaled.
+ * ------------------------------------------------------------------------ */
+
 /* The tanh step alone: y[i] = tanh(x[i]) correctly rounded to binary32 for
  * x[i] >= 0 (device buffers of n floats).  Test hook for the exhaustive
  * comparison of that step. */
@@ -247,9 +275,6 @@ int regtopk_tanh_f32(const float* x_dev, float* y_dev, int64_t n, void* stream);
  * written): the known-size reference dispatch against which hardware traffic
  * counters are scaled when profiling. */
 int regtopk_copy_f32(float* dst_dev, const float* src_dev, int64_t n, void* stream);
-
-/* Text of the last error on the calling thread ("" if none). */
-const char* regtopk_last_error(void);
 
 #ifdef __cplusplus
 }

@@ -13,8 +13,8 @@
 //   * Algorithm 1 / the Top_k selector defined in the subsection "Top-k:
 //     Classical Sparsification Scheme": mask with exactly k ones on the k
 //     largest magnitudes.
-//   * The posterior-distortion equation (label eq:Delta_def) in "Characterizing
-//     the Likelihood".
+//   * The definition of the posterior distortion Delta in the subsection
+//     "Characterizing the Likelihood".
 //   * The likelihood with tanh and the constant C = 1 (Section "RegTop-k
 //     Algorithm", display after the cumulative function u_mu, and its footnote).
 //   * The aggregation equation g^t = sum_n omega_n ghat_n^t right after
