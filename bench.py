@@ -31,10 +31,20 @@ def algorithmic_bytes(N, d, k, g_bytes=4):
     return (8 + g_bytes) * N * d + 4 * d + 28 * N * k
 
 
-# HBM bytes per launch of the sweep kernel measured with rocprofv3 --pmc
-# FETCH_SIZE / WRITE_SIZE (two runs), scaled by what the same counters read for
-# the 1 GiB reference copy; see profiles/regtopk_round_large_cnn_hbm_traffic.txt.
-MEASURED_SWEEP_TRAFFIC = {"large_cnn": 5020516937}
+def measured_traffic(workload, mode):
+    """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc
+    FETCH_SIZE / WRITE_SIZE (two runs, scaled by what the same counters read for the
+    1 GiB reference copy), read from the committed summary of that profile -- not
+    measured by this run.  None if there is no summary for the workload."""
+    name = {"regtopk": "regtopk_round_%s_hbm_traffic.txt", "global": "regtopk_global_round_%s_hbm_traffic.txt"}[mode] % workload
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        for line in open(path):
+            if line.strip().startswith("dominant kernel traffic per launch:"):
+                return int(line.split(":")[1].split()[0]), "profiles/" + name
+    except (OSError, ValueError):
+        pass
+    return None, None
 
 
 def cpu_baseline(cfg, wl, rounds=3, workers=None, bf16=False, variant=(0, 0), glob=False):
@@ -184,6 +194,11 @@ def main():
     entries = N * d
     value = entries / (ms_per_step * 1e-3)
     sweep_bytes = (8 + g_bytes) * N * d           # read eps, read g, write eps
+    if glob:
+        sweep_bytes += 4 * d                      # the accumulation also writes the unsparsified aggregate
+    traffic, traffic_src = (None, None)
+    if args.grad_dtype == "f32" and args.prior_roots == 0 and args.likelihood == 0 and not args.force_dense:
+        traffic, traffic_src = measured_traffic(cfg.name, args.mode)
     achieved = sweep_bytes / (sweep_ms * 1e-3) / 1e9
     b_alg = algorithmic_bytes(N, d, k, g_bytes)
     out = {
@@ -203,10 +218,10 @@ def main():
         "round_ms_by_events": round_ms,
         "dense_fallback_workers_last_round": dense_rounds,
         "candidates_last_round": [w["n_candidates"] for w in st],
-        "roofline": {"bound": "hbm", "kernel": "k_global_accum" if glob else "k_accum_emit", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "k_global_accum" if glob else "k_accum_emit_vec", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "algorithmic_bytes_per_launch": sweep_bytes, "avg_launch_ms": sweep_ms,
-                     "traffic": MEASURED_SWEEP_TRAFFIC.get(cfg.name) if args.grad_dtype == "f32" and not glob else None},
+                     "traffic": traffic, "traffic_source": traffic_src},
     }
     out["extras"] = time_extras(torch, binding, r, agg, N, d)
     r.close()

@@ -470,9 +470,9 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
   else if (pre)
     k_emit_only<false><<<g_chunks, kBlock, 0, s>>>(e, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   else if (vec)
-    k_accum_emit<true, G><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
+    k_accum_emit_vec<G, kSweepNI><<<g_chunks, 1024 / kSweepNI, 0, s>>>(e, grads, mask, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   else
-    k_accum_emit<false, G><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
+    k_accum_emit<G><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   if (ev) HIP_TRY(hipEventRecord(ev[1], s));
   k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_prev, cand_key, bnd_key, gprev, d, L.cap_r, L.cap_total, L.bnd_cap, omega, c->mu, use_reg, sk);
   k_select<<<N, kScanBlock, 0, s>>>(ctl, gctl, cand_key, bnd_key, kn, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->cand_target, c->force_dense);
