@@ -247,7 +247,10 @@ int regtopk_sgd_update(float* theta_dev, const float* g_dev, float eta, int64_t 
 #define REGTOPK_OPT_PRIOR_ROOTS   4  /* value m in {0,1,2,3}: prior |a|^y with y = 2^-m, evaluated as m correctly
                                         rounded binary32 square roots of |a| */
 #define REGTOPK_OPT_LIKELIHOOD    5  /* 0: tanh(|1+Delta|/mu);  1: min(|1+Delta|/mu, 1), the cumulative function
-                                        of an innovation uniform on [0, mu] */
+                                        of an innovation uniform on [0, mu];  2: erf(|1+Delta|/mu) correctly
+                                        rounded to binary32, the cumulative function of a Gaussian innovation of
+                                        standard deviation mu/sqrt(2) with the constants dropped as the paper
+                                        drops them for tanh (1/2 (1 + erf) -> erf) */
 int regtopk_set_option(regtopk_ctx* ctx, int option, double value);
 
 /* Stage times of the last n <= min(max_rounds, 64) profiled rounds, oldest
@@ -261,15 +264,17 @@ const char* regtopk_last_error(void);
 
 /* ------------------------------------------------------------------------
  * Test and profiling hooks.  Not part of the method's interface: the tests use
- * the first to compare the tanh step exhaustively, the benchmark launches the
- * second once as the dispatch of known size against which hardware traffic
+ * the first two to compare the tanh and erf steps exhaustively, the benchmark
+ * launches the third once as the dispatch of known size against which hardware traffic
  * counters are scaled.
  * ------------------------------------------------------------------------ */
 
 /* The tanh step alone: y[i] = tanh(x[i]) correctly rounded to binary32 for
  * x[i] >= 0 (device buffers of n floats).  Test hook for the exhaustive
- * comparison of that step. */
+ * comparison of that step.  regtopk_erf_f32: the same for the erf step of
+ * REGTOPK_OPT_LIKELIHOOD 2. */
 int regtopk_tanh_f32(const float* x_dev, float* y_dev, int64_t n, void* stream);
+int regtopk_erf_f32(const float* x_dev, float* y_dev, int64_t n, void* stream);
 
 /* Plain copy dst[i] = src[i] of n floats by one kernel (n*4 bytes read, n*4
  * written): the known-size reference dispatch against which hardware traffic

@@ -70,6 +70,9 @@ def _load():
     lib.rtk_oracle_likelihood_sent.argtypes = [c.c_float] * 5
     lib.rtk_oracle_topk_mask.argtypes = [c.c_void_p, c.c_int64, c.c_int64, c.c_void_p]
     lib.rtk_oracle_tanh32_array.argtypes = [c.c_void_p, c.c_void_p, c.c_int64]
+    lib.rtk_oracle_erf32.restype = c.c_float
+    lib.rtk_oracle_erf32.argtypes = [c.c_float]
+    lib.rtk_oracle_erf32_array.argtypes = [c.c_void_p, c.c_void_p, c.c_int64]
     _lib = lib
     return lib
 
@@ -148,9 +151,9 @@ class Oracle:
             raise ValueError("every k_n must be in [1, k]")
 
     def set_score_variant(self, sqrt_steps: int = 0, likelihood: int = 0):
-        """Prior |a|^(2^-sqrt_steps) and likelihood kind (0 tanh, 1 clipped linear)."""
+        """Prior |a|^(2^-sqrt_steps) and likelihood kind (0 tanh, 1 clipped linear, 2 erf)."""
         if self._lib.rtk_oracle_set_score_variant(self._h, int(sqrt_steps), int(likelihood)) != 0:
-            raise ValueError("sqrt_steps must be 0..3 and likelihood 0 or 1")
+            raise ValueError("sqrt_steps must be 0..3 and likelihood 0, 1 or 2")
 
     def mask_overlap(self) -> np.ndarray:
         """counts[c] = number of entries selected by exactly c workers in the last round."""
@@ -193,6 +196,17 @@ def tanh32_array(x) -> np.ndarray:
     xs = _f32(x).ravel()
     out = np.empty_like(xs)
     _load().rtk_oracle_tanh32_array(xs.ctypes.data, out.ctypes.data, xs.size)
+    return out
+
+
+def erf32(x: float) -> float:
+    return float(_load().rtk_oracle_erf32(float(np.float32(x))))
+
+
+def erf32_array(x) -> np.ndarray:
+    xs = _f32(x).ravel()
+    out = np.empty_like(xs)
+    _load().rtk_oracle_erf32_array(xs.ctypes.data, out.ctypes.data, xs.size)
     return out
 
 

@@ -51,7 +51,10 @@
 //       successive correctly rounded binary32 square roots of |a| (so that both
 //       sides of the parity check can take it bit for bit); besides tanh the
 //       likelihood may be the cumulative function of a uniform innovation,
-//       min(|1+Delta|/mu, 1).  The defaults (m = 0, tanh) are Algorithm 2.
+//       min(|1+Delta|/mu, 1), or of a Gaussian one with the constants dropped
+//       as the paper drops them for tanh, erf(|1+Delta|/mu) (correctly rounded
+//       binary32, realised like tanh).  The defaults (m = 0, tanh) are
+//       Algorithm 2.
 //   R18 Algorithm 2 is stated "at worker n" and its selector Top_k takes k as a
 //       parameter of that worker's sparsifier; the paper's experiments give all
 //       workers the same k.  Here worker n may be given its own k_n <= k: its
@@ -97,6 +100,12 @@ float tanh32(float x) {
     return (float)tanhl((long double)x);
 }
 
+// erf step of the Gaussian likelihood (R15): correctly rounded binary32 erf,
+// realised the same way.
+float erf32(float x) {
+    return (float)erfl((long double)x);
+}
+
 // Likelihood factor for an entry that WAS sent in the previous round
 // (Algorithm 2, distortion line and the tanh in the mask line).  R4, R7.
 float likelihood_sent(float a_now, float a_before, float g_before, float w, float mu, int kind = 0) {
@@ -108,6 +117,7 @@ float likelihood_sent(float a_now, float a_before, float g_before, float w, floa
     float x = r / mu;
     if (x != x) return 1.0f;
     if (kind == 1) return x < 1.0f ? x : 1.0f;   // uniform innovation on [0, mu]
+    if (kind == 2) return erf32(x);              // Gaussian innovation
     return tanh32(x);
 }
 
@@ -222,10 +232,10 @@ int rtk_oracle_set_worker_k(void* h, const int64_t* kn) {
 }
 
 // Score variant (R15): prior exponent y = 2^-sqrt_steps (0..3) and the kind of
-// likelihood (0 tanh, 1 clipped linear).  Returns 0 on success.
+// likelihood (0 tanh, 1 clipped linear, 2 erf).  Returns 0 on success.
 int rtk_oracle_set_score_variant(void* h, int sqrt_steps, int likelihood) {
     Oracle* o = (Oracle*)h;
-    if (sqrt_steps < 0 || sqrt_steps > 3 || likelihood < 0 || likelihood > 1) return -1;
+    if (sqrt_steps < 0 || sqrt_steps > 3 || likelihood < 0 || likelihood > 2) return -1;
     o->sqrt_steps = sqrt_steps;
     o->likelihood = likelihood;
     return 0;
@@ -317,6 +327,10 @@ void rtk_oracle_topk_mask(const float* score, int64_t d, int64_t k, uint8_t* mas
 }
 void rtk_oracle_tanh32_array(const float* x, float* y, int64_t n) {
     for (int64_t i = 0; i < n; ++i) y[i] = tanh32(x[i]);
+}
+float rtk_oracle_erf32(float x) { return erf32(x); }
+void rtk_oracle_erf32_array(const float* x, float* y, int64_t n) {
+    for (int64_t i = 0; i < n; ++i) y[i] = erf32(x[i]);
 }
 
 }  // extern "C"

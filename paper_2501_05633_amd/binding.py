@@ -22,7 +22,7 @@ SYMBOLS = [
     "regtopk_workspace_bytes", "regtopk_create", "regtopk_create_in", "regtopk_step", "regtopk_step_bf16", "regtopk_step_global",
     "regtopk_global_workspace_bytes", "regtopk_bind_global",
     "regtopk_destroy", "regtopk_reset", "regtopk_get_state", "regtopk_set_state",
-    "regtopk_get_stats", "regtopk_set_option", "regtopk_get_timings", "regtopk_tanh_f32",
+    "regtopk_get_stats", "regtopk_set_option", "regtopk_get_timings", "regtopk_tanh_f32", "regtopk_erf_f32",
     "regtopk_copy_f32", "regtopk_set_weights", "regtopk_set_worker_k", "regtopk_mask_overlap", "regtopk_mask_overlap_static", "regtopk_sgd_update",
     "regtopk_last_error",
 ]
@@ -78,6 +78,7 @@ def load():
     lib.regtopk_get_timings.argtypes = [c_void_p, ctypes.POINTER(c_float), c_int32, ctypes.POINTER(c_int32)]
     lib.regtopk_copy_f32.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
     lib.regtopk_tanh_f32.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
+    lib.regtopk_erf_f32.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
     lib.regtopk_set_weights.argtypes = [c_void_p, ctypes.POINTER(c_float), c_void_p]
     lib.regtopk_set_worker_k.argtypes = [c_void_p, ctypes.POINTER(c_int64), c_void_p]
     lib.regtopk_mask_overlap.argtypes = [c_void_p, c_void_p, c_void_p]
@@ -311,6 +312,16 @@ def tanh_f32(x):
     with torch.cuda.device(x.device):
         _check(load().regtopk_tanh_f32(c_void_p(x.data_ptr()), c_void_p(y.data_ptr()), x.numel(),
                                        _stream_ptr(torch)))
+    return y
+
+
+def erf_f32(x):
+    """erf step alone on a CUDA float32 tensor (test hook)."""
+    import torch
+    y = torch.empty_like(x)
+    with torch.cuda.device(x.device):
+        _check(load().regtopk_erf_f32(c_void_p(x.data_ptr()), c_void_p(y.data_ptr()), x.numel(),
+                                      _stream_ptr(torch)))
     return y
 
 

@@ -362,7 +362,8 @@ int regtopk_set_option(regtopk_ctx* c, int option, double value) {
       if ((int)value != c->prior_roots) { c->prior_roots = (int)value; c->reinit_ctl = true; c->fresh = kFreshRounds; }
       return REGTOPK_OK;
     case REGTOPK_OPT_LIKELIHOOD:
-      if (!(value == 0.0 || value == 1.0)) return fail(REGTOPK_INVALID_ARG, "likelihood must be 0 (tanh) or 1 (clipped linear)");
+      if (!(value == 0.0 || value == 1.0 || value == 2.0))
+        return fail(REGTOPK_INVALID_ARG, "likelihood must be 0 (tanh), 1 (clipped linear) or 2 (erf)");
       if ((int)value != c->likelihood) { c->likelihood = (int)value; c->reinit_ctl = true; c->fresh = kFreshRounds; }
       return REGTOPK_OK;
     case REGTOPK_OPT_PROFILE:
@@ -816,6 +817,14 @@ int regtopk_copy_f32(float* dst_dev, const float* src_dev, int64_t n, void* stre
   if (n == 0) return REGTOPK_OK;
   k_copy_u32<<<2048, 256, 0, static_cast<hipStream_t>(stream)>>>(reinterpret_cast<uint32_t*>(dst_dev),
                                                                    reinterpret_cast<const uint32_t*>(src_dev), (size_t)n);
+  HIP_TRY(hipGetLastError());
+  return REGTOPK_OK;
+}
+
+int regtopk_erf_f32(const float* x_dev, float* y_dev, int64_t n, void* stream) {
+  if (n < 0 || (n > 0 && (!x_dev || !y_dev))) return fail(REGTOPK_INVALID_ARG, "bad arguments");
+  if (n == 0) return REGTOPK_OK;
+  k_erf<<<2048, 256, 0, static_cast<hipStream_t>(stream)>>>(x_dev, y_dev, n);
   HIP_TRY(hipGetLastError());
   return REGTOPK_OK;
 }

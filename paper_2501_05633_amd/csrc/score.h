@@ -16,11 +16,12 @@ __device__ __forceinline__ float likelihood_sent(float a_now, float a_before, fl
   const float x = __fdiv_rn(r, mu);
   if (x != x) return 1.0f;
   if (kind == 1) return x < 1.0f ? x : 1.0f;     // cumulative function of a uniform innovation
+  if (kind == 2) return erf_f32_cr(x);           // of a Gaussian innovation (constants dropped as for tanh)
   return tanh_f32_cr(x);
 }
 
 // What the score variants need: the number of square roots of the prior and
-// the kind of likelihood (0 tanh, 1 clipped linear).
+// the kind of likelihood (0 tanh, 1 clipped linear, 2 erf).
 struct ScoreKind { int roots, likelihood; };
 
 // Score bits of one candidate: index word `raw` with the sent flag, value a,

@@ -1,4 +1,5 @@
-// tanh of a non-negative binary32 argument, rounded correctly to binary32.
+// tanh (and, further down, erf) of a non-negative binary32 argument, rounded
+// correctly to binary32.
 //
 // The selection score needs tanh to be the same function on every machine, so
 // it is defined as the correctly rounded value and computed here from IEEE
@@ -72,6 +73,21 @@ __device__ __forceinline__ dd dd_div(dd a, dd b) {
 #define RTK_LN2_C 0x1.7b57a079a1934p-111
 #define RTK_LOG2E 0x1.71547652b82fep+0
 
+// One rounding of a positive double-double value hi + lo to binary32.
+__device__ __forceinline__ float dd_round_f32(dd y) {
+  float f = (float)y.hi;
+  const double fl = (double)f;
+  const double diff = (y.hi - fl) + y.lo;
+  if (diff > 0.0) {
+    float up = __uint_as_float(__float_as_uint(f) + 1u);
+    if (diff > 0.5 * ((double)up - fl)) f = up;
+  } else if (diff < 0.0) {
+    float dn = __uint_as_float(__float_as_uint(f) - 1u);
+    if (-diff > 0.5 * (fl - (double)dn)) f = dn;
+  }
+  return f;
+}
+
 // Slow, ~100-bit evaluation (only reached for arguments whose tanh lies
 // extremely close to the midpoint of two binary32 numbers).
 __device__ __noinline__ float tanh_f32_dd(float xf) {
@@ -100,18 +116,7 @@ __device__ __noinline__ float tanh_f32_dd(float xf) {
   const double sc = ldexp(1.0, (int)n);
   dd E = dd_add_d(dd_mul_d(q, sc), sc - 1.0);
   dd y = dd_div(E, dd_add_d(E, 2.0));
-  // one rounding of hi + lo to binary32 (the argument is positive here)
-  float f = (float)y.hi;
-  const double fl = (double)f;
-  const double diff = (y.hi - fl) + y.lo;
-  if (diff > 0.0) {
-    float up = __uint_as_float(__float_as_uint(f) + 1u);
-    if (diff > 0.5 * ((double)up - fl)) f = up;
-  } else if (diff < 0.0) {
-    float dn = __uint_as_float(__float_as_uint(f) - 1u);
-    if (-diff > 0.5 * (fl - (double)dn)) f = dn;
-  }
-  return f;
+  return dd_round_f32(y);
 }
 
 __device__ __forceinline__ float tanh_f32_cr(float xf) {
@@ -141,6 +146,91 @@ __device__ __forceinline__ float tanh_f32_cr(float xf) {
   const float hi = (float)(y * (1.0 + 0x1p-47));
   if (lo == hi) return lo;
   return tanh_f32_dd(xf);
+}
+
+// ------------------------------------------------------------------- erf ----
+// erf of a non-negative binary32 argument, rounded correctly to binary32 (the
+// likelihood of a Gaussian innovation).  From binary64 operations only:
+//
+//   erf(x) = (2/sqrt(pi)) exp(-x^2) sum_{n>=0} 2^n x^(2n+1) / (1*3*5*...*(2n+1)),
+//
+// a series of positive terms (no cancellation; at most 63 terms up to the
+// saturation point), with exp(-x^2) from the same argument reduction and
+// Taylor polynomial as above (x^2 is exact in binary64).  The binary64 result
+// carries a relative error below 2^-45; when rounding it to binary32 could
+// depend on that error the evaluation is repeated in double-double arithmetic.
+#define RTK_2_SQRTPI_HI 0x1.20dd750429b6dp+0
+#define RTK_2_SQRTPI_LO 0x1.1ae3a914fed80p-56
+
+__device__ __noinline__ float erf_f32_dd(float xf) {
+  const double x = (double)xf;
+  const double t = -(x * x);                               // exact
+  const double n = rint(t * RTK_LOG2E);
+  dd r = dd_two_prod(-n, RTK_LN2_A);
+  r = dd_add_d(r, t);
+  r = dd_add(r, dd_two_prod(-n, RTK_LN2_B));
+  r = dd_add_d(r, -n * RTK_LN2_C);
+  dd s = {r.hi * 0.00390625, r.lo * 0.00390625};
+  dd h = {1.0, 0.0};
+  for (int kk = 12; kk >= 2; --kk) {
+    dd kd = {(double)kk, 0.0};
+    h = dd_add_d(dd_div(dd_mul(s, h), kd), 1.0);
+  }
+  dd q = dd_mul(s, h);
+  for (int i = 0; i < 8; ++i) {
+    dd q2 = dd_mul(q, q);
+    q = dd_add(dd_mul_d(q, 2.0), q2);
+  }
+  const double sc = ldexp(1.0, (int)n);
+  dd ex = dd_mul_d(dd_add_d(q, 1.0), sc);                  // exp(-x^2)
+  const dd x2 = {2.0 * x * x, 0.0};                        // exact
+  dd term = {x, 0.0}, sum = {x, 0.0};
+  for (int kk = 1; kk < 160; ++kk) {                       // (about 100 terms at the saturation point)
+    dd kd = {(double)(2 * kk + 1), 0.0};
+    term = dd_div(dd_mul(term, x2), kd);
+    sum = dd_add(sum, term);
+    if (term.hi < sum.hi * 0x1p-100) break;
+  }
+  const dd c = {RTK_2_SQRTPI_HI, RTK_2_SQRTPI_LO};
+  return dd_round_f32(dd_mul(dd_mul(c, ex), sum));
+}
+
+__device__ __forceinline__ float erf_f32_cr(float xf) {
+  if (!(xf < 3.92f)) return 1.0f;          // erf(x) >= 1 - 2^-25 from x = 3.9193 on
+  if (xf == 0.0f) return 0.0f;
+  const double x = (double)xf;
+  const double t = -(x * x);               // exact
+  const double n = rint(t * RTK_LOG2E);
+  double r = __fma_rn(-n, RTK_LN2_A, t);
+  r = __fma_rn(-n, RTK_LN2_B, r);
+  double p = 1.0 / 87178291200.0;                       // 1/14!
+  p = __fma_rn(p, r, 1.0 / 6227020800.0);
+  p = __fma_rn(p, r, 1.0 / 479001600.0);
+  p = __fma_rn(p, r, 1.0 / 39916800.0);
+  p = __fma_rn(p, r, 1.0 / 3628800.0);
+  p = __fma_rn(p, r, 1.0 / 362880.0);
+  p = __fma_rn(p, r, 1.0 / 40320.0);
+  p = __fma_rn(p, r, 1.0 / 5040.0);
+  p = __fma_rn(p, r, 1.0 / 720.0);
+  p = __fma_rn(p, r, 1.0 / 120.0);
+  p = __fma_rn(p, r, 1.0 / 24.0);
+  p = __fma_rn(p, r, 1.0 / 6.0);
+  p = __fma_rn(p, r, 0.5);
+  const double q = __fma_rn(r * r, p, r);               // expm1(r)
+  const double sc = ldexp(1.0, (int)n);
+  const double ex = __fma_rn(sc, q, sc);                // exp(-x^2)
+  const double x2 = 2.0 * x * x;
+  double term = x, sum = x;
+  for (int kk = 1; kk < 96; ++kk) {
+    term = term * x2 / (double)(2 * kk + 1);
+    sum += term;
+    if (term < sum * 0x1p-60) break;
+  }
+  const double y = RTK_2_SQRTPI_HI * ex * sum;
+  const float lo = (float)(y * (1.0 - 0x1p-43));
+  const float hi = (float)(y * (1.0 + 0x1p-43));
+  if (lo == hi) return lo;
+  return erf_f32_dd(xf);
 }
 
 }  // namespace rtk

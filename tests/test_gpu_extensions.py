@@ -242,9 +242,9 @@ def test_switching_the_variant_between_rounds():
     with pytest.raises(binding.RegTopkError):
         r.set_option(binding.OPT_PRIOR_ROOTS, 4)
     with pytest.raises(binding.RegTopkError):
-        r.set_option(binding.OPT_LIKELIHOOD, 2)
+        r.set_option(binding.OPT_LIKELIHOOD, 3)
     agg_g = agg_c = None
-    for t, (roots, lk) in enumerate([(0, 0), (0, 0), (1, 0), (1, 0), (1, 1), (0, 0), (0, 0)]):
+    for t, (roots, lk) in enumerate([(0, 0), (0, 0), (1, 0), (1, 0), (1, 1), (0, 2), (0, 2), (2, 2), (0, 0), (0, 0)]):
         o.set_score_variant(roots, lk)
         r.set_option(binding.OPT_PRIOR_ROOTS, roots)
         r.set_option(binding.OPT_LIKELIHOOD, lk)

@@ -24,7 +24,7 @@ def _draw_case(rng):
     opts = {
         "weights": rng.dirichlet(np.ones(N)).astype(f32) if rng.random() < 0.3 else None,
         "roots": int(rng.choice([0, 0, 0, 1, 2])),
-        "likelihood": int(rng.choice([0, 0, 1])),
+        "likelihood": int(rng.choice([0, 0, 1, 2])),
         "force_dense": bool(rng.random() < 0.2),
         "bf16": bool(rng.random() < 0.25),
         "kinds": "".join(rng.choice(list("LLLG"), size=4)),

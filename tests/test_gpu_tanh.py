@@ -1,6 +1,7 @@
 """The tanh step of the HIP path against the oracle's, for EVERY binary32
 argument from 0 up to beyond the saturation point (about 1.09e9 values), plus
-arguments above it.  Both must be the correctly rounded binary32 tanh."""
+arguments above it.  Both must be the correctly rounded binary32 tanh.  The
+same for the erf step of the Gaussian likelihood (saturation at 3.9192)."""
 import concurrent.futures as cf
 
 import numpy as np
@@ -14,10 +15,10 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def _oracle_parallel(x: np.ndarray, threads=16) -> np.ndarray:
+def _oracle_parallel(x: np.ndarray, threads=16, fn=None) -> np.ndarray:
     parts = np.array_split(x, threads)
     with cf.ThreadPoolExecutor(threads) as ex:      # ctypes releases the GIL
-        outs = list(ex.map(orc.tanh32_array, parts))
+        outs = list(ex.map(fn or orc.tanh32_array, parts))
     return np.concatenate(outs)
 
 
@@ -47,3 +48,31 @@ def test_tanh_above_saturation_and_specials():
     want = orc.tanh32_array(x.cpu().numpy())
     assert np.array_equal(y.view(np.uint32), want.view(np.uint32))
     assert y[4] == 1.0 and y[8] == 1.0 and y[9] == 0.0
+
+
+def test_erf_exhaustive_up_to_saturation():
+    hi = int(np.float32(3.93).view(np.uint32))
+    slab = 1 << 26
+    mismatches = 0
+    for lo in range(0, hi + 1, slab):
+        n = min(slab, hi + 1 - lo)
+        bits = torch.arange(lo, lo + n, dtype=torch.int64, device=DEV).to(torch.int32)
+        x = bits.view(torch.float32)
+        y = binding.erf_f32(x).cpu().numpy()
+        want = _oracle_parallel(x.cpu().numpy(), fn=orc.erf32_array)
+        bad = np.flatnonzero(y.view(np.uint32) != want.view(np.uint32))
+        if bad.size:
+            print("erf slab %#x: %d mismatches, first x=%r got=%r want=%r" % (
+                lo, bad.size, x[int(bad[0])].item(), y[bad[0]], want[bad[0]]), flush=True)
+        mismatches += bad.size
+        print("erf slab %#x done" % lo, flush=True)
+    assert mismatches == 0
+
+
+def test_erf_above_saturation_and_specials():
+    x = torch.tensor([3.9192, 3.919206, 3.92, 3.93, 4.0, 10.0, 88.0, 1e10, 3.4e38, float("inf"), 0.0, 1e-45, 1e-38, 1e-20],
+                     dtype=torch.float32, device=DEV)
+    y = binding.erf_f32(x).cpu().numpy()
+    want = orc.erf32_array(x.cpu().numpy())
+    assert np.array_equal(y.view(np.uint32), want.view(np.uint32))
+    assert y[0] < 1.0 and y[2] == 1.0 and y[9] == 1.0 and y[10] == 0.0

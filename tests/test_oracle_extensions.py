@@ -171,7 +171,7 @@ def test_default_variant_is_algorithm_2():
     with pytest.raises(ValueError):
         b.set_score_variant(4, 0)
     with pytest.raises(ValueError):
-        b.set_score_variant(0, 2)
+        b.set_score_variant(0, 3)
 
 
 def test_prior_is_the_correctly_rounded_root():
@@ -292,6 +292,74 @@ def test_clipped_linear_rounds_keep_the_invariants():
             assert msk[n].sum() == k and sc[n][msk[n] == 1].min() >= sc[n][msk[n] == 0].max()
             assert np.array_equal(a[n][idx[n]], val[n]) and np.all(e[n][idx[n]] == 0)
     assert damped > 0
+
+
+def test_erf_is_correctly_rounded_on_samples_and_specials():
+    # the erf step of the Gaussian likelihood: nearest binary32 to the exact erf (200-bit reference)
+    mpmath.mp.prec = 200
+    rng = np.random.default_rng(41)
+    xs = np.concatenate([rng.uniform(0, 4.2, 3000), 10.0 ** rng.uniform(-44, 0.6, 3000)]).astype(f32)
+    got = oracle.erf32_array(xs)
+    for x, y in zip(xs, got):
+        exact = mpmath.erf(mpmath.mpf(float(x)))
+        lo, hi = np.nextafter(y, f32(-1)), np.nextafter(y, f32(2))
+        assert abs(mpmath.mpf(float(y)) - exact) <= abs(mpmath.mpf(float(lo)) - exact), x
+        assert abs(mpmath.mpf(float(y)) - exact) <= abs(mpmath.mpf(float(hi)) - exact), x
+    assert oracle.erf32(0.0) == 0.0 and oracle.erf32(3.9192) < 1.0 and oracle.erf32(3.92) == 1.0
+    assert oracle.erf32(100.0) == 1.0 and oracle.erf32(float("inf")) == 1.0
+    assert oracle.erf32(1e-45) == float(f32(1e-45))          # 2/sqrt(pi) * the smallest denormal rounds to it
+
+
+def test_gaussian_likelihood():
+    # cumulative function of a Gaussian innovation, constants dropped: erf(|1 + Delta| / mu)
+    mpmath.mp.prec = 200
+    rng = np.random.default_rng(43)
+    for _ in range(300):
+        a_now, a_bef, g_bef = (f32(x) for x in rng.standard_normal(3))
+        w, mu = f32(rng.uniform(0.02, 1.0)), f32(rng.uniform(0.05, 5.0))
+        got = oracle.likelihood_sent_kind(a_now, a_bef, g_bef, w, mu, 2)
+        m = mpmath.mpf
+        den = m(float(w)) * m(float(a_now))
+        num = m(float(g_bef)) - m(float(w)) * m(float(a_bef))
+        x = abs(1 + num / den) / m(float(mu))
+        want = mpmath.erf(x)
+        # five roundings of the argument, conditioned by 1/|den| through the sum 1 + Delta; erf'(x) x <= erf(x)
+        cond = (abs(num / den) + 1) / max(abs(1 + num / den), m(2) ** -60)
+        tol = float(want) * 2.0 ** -23 * (3 + 3 * float(cond)) + 1e-30
+        assert abs(got - float(want)) <= tol, (a_now, a_bef, g_bef, w, mu, got, float(want))
+        assert 0.0 <= got <= 1.0
+    assert oracle.likelihood_sent_kind(2.0, 2.0, 0.0, 0.5, 1.0, 2) == 0.0                       # cancelled entry
+    assert oracle.likelihood_sent_kind(2.0, 2.0, 1.0, 0.5, 4.0, 2) == oracle.erf32(0.25)        # sole sender: Delta = 0
+    assert oracle.likelihood_sent_kind(2.0, 2.0, 1.0, 0.5, 0.125, 2) == 1.0                     # saturation
+    assert oracle.likelihood_sent_kind(0.0, 2.0, 1.0, 0.5, 1.0, 2) == 1.0                       # zero denominator
+    vals = [oracle.likelihood_sent_kind(1.0, 1.0, g, 1.0, 2.0, 2) for g in np.linspace(0.0, 9.0, 60)]
+    assert all(b >= a for a, b in zip(vals, vals[1:])) and vals[0] == 0.0 and vals[-1] == 1.0
+    # it is neither of the other two
+    assert oracle.likelihood_sent_kind(1.3, 0.7, 0.2, 0.25, 0.9, 2) not in (
+        oracle.likelihood_sent_kind(1.3, 0.7, 0.2, 0.25, 0.9, 0), oracle.likelihood_sent_kind(1.3, 0.7, 0.2, 0.25, 0.9, 1))
+
+
+def test_gaussian_likelihood_rounds_keep_the_invariants_and_use_erf():
+    N, d, k, mu = 4, 3000, 60, 2.0
+    o = oracle.Oracle(N, d, k, mu)
+    o.set_score_variant(0, 2)
+    agg = None
+    checked = 0
+    for t, g in enumerate(_rounds(5, N, d, k)):
+        prev_mask = o.mask if t else np.zeros((N, d), dtype=np.uint8)
+        a_prev = o.a
+        agg_prev = agg
+        idx, val, agg = o.step(g, agg)
+        sc, a, msk, e = o.score, o.a, o.mask, o.e
+        assert np.all(sc <= np.abs(a)) and np.array_equal(sc[prev_mask == 0], np.abs(a)[prev_mask == 0])
+        for n in range(N):
+            assert msk[n].sum() == k and sc[n][msk[n] == 1].min() >= sc[n][msk[n] == 0].max()
+            assert np.array_equal(a[n][idx[n]], val[n]) and np.all(e[n][idx[n]] == 0)
+            for j in np.flatnonzero(prev_mask[n])[:5]:         # the round's score is |a| times the step's factor
+                fct = oracle.likelihood_sent_kind(a[n, j], a_prev[n, j], agg_prev[j], f32(1.0) / f32(N), mu, 2)
+                assert sc[n, j] == f32(abs(a[n, j])) * f32(fct)
+                checked += 1
+    assert checked > 0
 
 
 # ------------------------------------------------------------ global Top-k ----

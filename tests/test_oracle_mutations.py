@@ -33,6 +33,7 @@ MUTATIONS = [
     ("per-worker k ignored", "topk_mask(sc, d, o->kn[(size_t)n], s);", "topk_mask(sc, d, k, s);"),
     ("sent value weighted by omega", "val[(size_t)n * k + c] = a[j]; ++c; }\n        }\n        for (; c < k; ++c)", "val[(size_t)n * k + c] = w * a[j]; ++c; }\n        }\n        for (; c < k; ++c)"),
     ("tanh replaced by the clipped line", "    return tanh32(x);\n}\n\n// Prior", "    return x < 1.0f ? x : 1.0f;\n}\n\n// Prior"),
+    ("Gaussian likelihood evaluated with tanh", "if (kind == 2) return erf32(x);", "if (kind == 2) return tanh32(x);"),
     ("one square root too many in the prior", "for (int i = 0; i < m; ++i) p = std::sqrt(p);", "for (int i = 0; i <= m; ++i) p = std::sqrt(p);"),
     ("global Top-k over the last worker's values instead of the aggregate", "mag[(size_t)j] = std::fabs(acc);", "mag[(size_t)j] = std::fabs(o->a[(size_t)(o->N - 1) * d + j]);"),
 ]
