@@ -47,7 +47,7 @@ def measured_traffic(workload, mode):
     return None, None
 
 
-def cpu_baseline(cfg, wl, rounds=3, workers=None, bf16=False, variant=(0, 0), glob=False):
+def cpu_baseline(cfg, wl, rounds=3, workers=None, bf16=False, variant=(0, 0), glob=False, exponent=1.0):
     """The oracle, unchanged, single-threaded, on a bounded sample: the first
     `workers` rows of the same workload for `rounds` rounds."""
     workers = cfg.N if workers is None else workers
@@ -56,6 +56,8 @@ def cpu_baseline(cfg, wl, rounds=3, workers=None, bf16=False, variant=(0, 0), gl
     from oracle import oracle as orc
     o = orc.Oracle(workers, cfg.d, cfg.k, cfg.mu)
     o.set_score_variant(*variant)
+    if exponent != 1.0:
+        o.set_prior_exponent(exponent)
     agg = None
     elapsed = 0.0
     for t in range(rounds):
@@ -107,7 +109,8 @@ def main():
     ap.add_argument("--grad-dtype", choices=["f32", "bf16"], default="f32",
                     help="storage type of the local gradients (bf16: widened exactly, arithmetic stays f32)")
     ap.add_argument("--prior-roots", type=int, default=0, help="score variant: prior |a|^(2^-m)")
-    ap.add_argument("--likelihood", type=int, default=0, help="score variant: 0 tanh, 1 clipped linear")
+    ap.add_argument("--prior-exponent", type=float, default=1.0, help="score variant: prior |a|^y with a general 0 < y <= 1")
+    ap.add_argument("--likelihood", type=int, default=0, help="score variant: 0 tanh, 1 clipped linear, 2 erf")
     ap.add_argument("--mode", choices=["regtopk", "global"], default="regtopk",
                     help="global: the genie-aided global Top-k baseline instead of the RegTop-k round")
     ap.add_argument("--force-dense", action="store_true",
@@ -159,6 +162,8 @@ def main():
     r.set_option(binding.OPT_FORCE_DENSE, 1 if args.force_dense else 0)
     r.set_option(binding.OPT_PRIOR_ROOTS, args.prior_roots)
     r.set_option(binding.OPT_LIKELIHOOD, args.likelihood)
+    if args.prior_exponent != 1.0:
+        r.set_option(binding.OPT_PRIOR_EXPONENT, args.prior_exponent)
     agg = None
     dense_rounds = 0
     glob = args.mode == "global"
@@ -197,7 +202,8 @@ def main():
     if glob:
         sweep_bytes += 4 * d                      # the accumulation also writes the unsparsified aggregate
     traffic, traffic_src = (None, None)
-    if args.grad_dtype == "f32" and args.prior_roots == 0 and args.likelihood == 0 and not args.force_dense:
+    if args.grad_dtype == "f32" and args.prior_roots == 0 and args.prior_exponent == 1.0 and args.likelihood == 0 \
+            and not args.force_dense:
         traffic, traffic_src = measured_traffic(cfg.name, args.mode)
     achieved = sweep_bytes / (sweep_ms * 1e-3) / 1e9
     b_alg = algorithmic_bytes(N, d, k, g_bytes)
@@ -210,7 +216,7 @@ def main():
         "config": {"workload": "%s: N=%d workers, d=%d, k=%d, mu=%g, per-layer scales, %s entries, "
                                "30%% shared component" % (cfg.name, N, d, k, cfg.mu, cfg.marginal),
                    "N": N, "d": d, "k": k, "mu": cfg.mu, "rounds_resident": n_buf,
-                   "grad_dtype": args.grad_dtype, "prior_roots": args.prior_roots, "likelihood": args.likelihood, "mode": args.mode, "force_dense": args.force_dense},
+                   "grad_dtype": args.grad_dtype, "prior_roots": args.prior_roots, "prior_exponent": args.prior_exponent, "likelihood": args.likelihood, "mode": args.mode, "force_dense": args.force_dense},
         "hbm_frac_round": b_alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "algorithmic_bytes_per_round": b_alg,
         "stage_ms": {"sweep": sweep_ms, "select": select_ms, "compact_aggregate": tail_ms,
@@ -229,7 +235,8 @@ def main():
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, wl, bf16=args.grad_dtype == "bf16",
-                                           variant=(args.prior_roots, args.likelihood), glob=glob)
+                                           variant=(args.prior_roots, args.likelihood), glob=glob,
+                                           exponent=args.prior_exponent)
     print(json.dumps(out))
 
 

@@ -246,6 +246,9 @@ int regtopk_sgd_update(float* theta_dev, const float* g_dev, float eta, int64_t 
  * rounds are dropped. */
 #define REGTOPK_OPT_PRIOR_ROOTS   4  /* value m in {0,1,2,3}: prior |a|^y with y = 2^-m, evaluated as m correctly
                                         rounded binary32 square roots of |a| */
+#define REGTOPK_OPT_PRIOR_EXPONENT 6 /* value y in (0, 1]: prior |a|^y with a general binary32 exponent, defined as
+                                        the correctly rounded binary32 value of the real power (y = 1: Algorithm
+                                        2).  Replaces a setting of REGTOPK_OPT_PRIOR_ROOTS and is replaced by one. */
 #define REGTOPK_OPT_LIKELIHOOD    5  /* 0: tanh(|1+Delta|/mu);  1: min(|1+Delta|/mu, 1), the cumulative function
                                         of an innovation uniform on [0, mu];  2: erf(|1+Delta|/mu) correctly
                                         rounded to binary32, the cumulative function of a Gaussian innovation of
@@ -264,8 +267,8 @@ const char* regtopk_last_error(void);
 
 /* ------------------------------------------------------------------------
  * Test and profiling hooks.  Not part of the method's interface: the tests use
- * the first two to compare the tanh and erf steps exhaustively, the benchmark
- * launches the third once as the dispatch of known size against which hardware traffic
+ * the first three to compare the tanh, erf and power steps with the oracle's,
+ * the benchmark launches the last once as the dispatch of known size against which hardware traffic
  * counters are scaled.
  * ------------------------------------------------------------------------ */
 
@@ -275,6 +278,9 @@ const char* regtopk_last_error(void);
  * REGTOPK_OPT_LIKELIHOOD 2. */
 int regtopk_tanh_f32(const float* x_dev, float* y_dev, int64_t n, void* stream);
 int regtopk_erf_f32(const float* x_dev, float* y_dev, int64_t n, void* stream);
+/* out[i] = x[i]^y correctly rounded to binary32 for x[i] >= 0 and 0 < y < 1: the prior of
+ * REGTOPK_OPT_PRIOR_EXPONENT alone. */
+int regtopk_pow_f32(const float* x_dev, float y, float* out_dev, int64_t n, void* stream);
 
 /* Plain copy dst[i] = src[i] of n floats by one kernel (n*4 bytes read, n*4
  * written): the known-size reference dispatch against which hardware traffic

@@ -62,6 +62,11 @@ def _load():
     lib.rtk_oracle_set_score_variant.argtypes = [c.c_void_p, c.c_int, c.c_int]
     lib.rtk_oracle_likelihood_sent_kind.restype = c.c_float
     lib.rtk_oracle_likelihood_sent_kind.argtypes = [c.c_float] * 5 + [c.c_int]
+    lib.rtk_oracle_set_prior_exponent.restype = c.c_int
+    lib.rtk_oracle_set_prior_exponent.argtypes = [c.c_void_p, c.c_float]
+    lib.rtk_oracle_prior_pow.restype = c.c_float
+    lib.rtk_oracle_prior_pow.argtypes = [c.c_float, c.c_float]
+    lib.rtk_oracle_prior_pow_array.argtypes = [c.c_void_p, c.c_float, c.c_void_p, c.c_int64]
     lib.rtk_oracle_prior.restype = c.c_float
     lib.rtk_oracle_prior.argtypes = [c.c_float, c.c_int]
     lib.rtk_oracle_tanh32.restype = c.c_float
@@ -155,6 +160,11 @@ class Oracle:
         if self._lib.rtk_oracle_set_score_variant(self._h, int(sqrt_steps), int(likelihood)) != 0:
             raise ValueError("sqrt_steps must be 0..3 and likelihood 0, 1 or 2")
 
+    def set_prior_exponent(self, y: float):
+        """Prior |a|^y with a general exponent 0 < y <= 1 (replaces the square-root variant)."""
+        if self._lib.rtk_oracle_set_prior_exponent(self._h, float(np.float32(y))) != 0:
+            raise ValueError("the exponent must be in (0, 1]")
+
     def mask_overlap(self) -> np.ndarray:
         """counts[c] = number of entries selected by exactly c workers in the last round."""
         counts = np.zeros(self.N + 1, dtype=np.int64)
@@ -224,6 +234,17 @@ def likelihood_sent_kind(a_now, a_before, g_before, w, mu, kind: int) -> float:
 
 def prior(a, sqrt_steps: int) -> float:
     return float(_load().rtk_oracle_prior(float(np.float32(a)), int(sqrt_steps)))
+
+
+def prior_pow(a, y: float) -> float:
+    return float(_load().rtk_oracle_prior_pow(float(np.float32(a)), float(np.float32(y))))
+
+
+def prior_pow_array(x, y: float) -> np.ndarray:
+    xs = _f32(x).ravel()
+    out = np.empty_like(xs)
+    _load().rtk_oracle_prior_pow_array(xs.ctypes.data, float(np.float32(y)), out.ctypes.data, xs.size)
+    return out
 
 
 def topk_mask(score, k: int) -> np.ndarray:

@@ -49,7 +49,10 @@
 //       sentence that other cumulative functions u_mu may replace tanh:
 //       the prior |a|^y is offered for y = 2^-m, m = 0..3, and evaluated as m
 //       successive correctly rounded binary32 square roots of |a| (so that both
-//       sides of the parity check can take it bit for bit); besides tanh the
+//       sides of the parity check can take it bit for bit), and for a general
+//       binary32 exponent 0 < y < 1 as the correctly rounded binary32 value of
+//       the real power (realised by powl in x87 extended precision, rounded
+//       once); besides tanh the
 //       likelihood may be the cumulative function of a uniform innovation,
 //       min(|1+Delta|/mu, 1), or of a Gaussian one with the constants dropped
 //       as the paper drops them for tanh, erf(|1+Delta|/mu) (correctly rounded
@@ -78,6 +81,7 @@ struct Oracle {
     std::vector<float> w;        // [N] aggregation weights omega_n (R2)
     std::vector<int64_t> kn;     // [N] entries kept by worker n, 1 <= k_n <= k (R18; default k)
     int sqrt_steps;              // prior |a|^y with y = 2^-sqrt_steps (R15)
+    float exponent;              // or, when != 1, prior |a|^exponent (R15); sqrt_steps is then 0
     int likelihood;              // 0: tanh(x), 1: min(x, 1) (R15)
     int64_t t;       // rounds done so far
     std::vector<float> e;        // [N*d] sparsification error eps_n
@@ -128,6 +132,12 @@ float prior(float a, int m) {
     return p;
 }
 
+// Prior |a|^y for a general exponent 0 < y < 1: the real power rounded once to
+// binary32 (R15).
+float prior_pow(float a, float y) {
+    return (float)powl((long double)std::fabs(a), (long double)y);
+}
+
 // Top_k selector: mask with exactly k ones on the k largest scores, lower index
 // first among equal scores (R1).  Scores are non-negative and never NaN here.
 void topk_mask(const float* score, int64_t d, int64_t k, uint8_t* mask) {
@@ -154,6 +164,7 @@ void* rtk_oracle_create(int32_t N, int64_t d, int64_t k, float mu) {
     o->kn.assign((size_t)N, k);
     o->t = 0;
     o->sqrt_steps = 0;
+    o->exponent = 1.0f;
     o->likelihood = 0;
     size_t nd = (size_t)N * (size_t)d;
     o->e.assign(nd, 0.0f);           // eps^0 = 0
@@ -192,7 +203,8 @@ void rtk_oracle_step(void* h, const float* grads, const float* gprev,
             float f = 1.0f;                                  // C = 1 (R3)
             if (mu != 0.0f && sp[j])                         // R5, R6
                 f = likelihood_sent(a[j], ap[j], gprev[j], w, mu, o->likelihood);
-            sc[j] = prior(a[j], o->sqrt_steps) * f;          // |a|^y . u(|1 + Delta|)
+            const float pr = o->exponent != 1.0f ? prior_pow(a[j], o->exponent) : prior(a[j], o->sqrt_steps);
+            sc[j] = pr * f;                                  // |a|^y . u(|1 + Delta|)
         }
         topk_mask(sc, d, o->kn[(size_t)n], s);               // s^t = Top_k(.), k = k_n (R18)
         int64_t c = 0;
@@ -237,7 +249,18 @@ int rtk_oracle_set_score_variant(void* h, int sqrt_steps, int likelihood) {
     Oracle* o = (Oracle*)h;
     if (sqrt_steps < 0 || sqrt_steps > 3 || likelihood < 0 || likelihood > 2) return -1;
     o->sqrt_steps = sqrt_steps;
+    o->exponent = 1.0f;
     o->likelihood = likelihood;
+    return 0;
+}
+
+// General prior exponent 0 < y <= 1 (R15); y = 1 is Algorithm 2.  Replaces the
+// square-root variant.  Returns 0 on success.
+int rtk_oracle_set_prior_exponent(void* h, float y) {
+    Oracle* o = (Oracle*)h;
+    if (!(y > 0.0f && y <= 1.0f)) return -1;
+    o->exponent = y;
+    o->sqrt_steps = 0;
     return 0;
 }
 
@@ -322,6 +345,10 @@ float rtk_oracle_likelihood_sent_kind(float a_now, float a_before, float g_befor
     return likelihood_sent(a_now, a_before, g_before, w, mu, kind);
 }
 float rtk_oracle_prior(float a, int sqrt_steps) { return prior(a, sqrt_steps); }
+float rtk_oracle_prior_pow(float a, float y) { return prior_pow(a, y); }
+void rtk_oracle_prior_pow_array(const float* x, float y, float* out, int64_t n) {
+    for (int64_t i = 0; i < n; ++i) out[i] = prior_pow(x[i], y);
+}
 void rtk_oracle_topk_mask(const float* score, int64_t d, int64_t k, uint8_t* mask) {
     topk_mask(score, d, k, mask);
 }

@@ -15,14 +15,14 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libregtopk.so")
 
 OK, INVALID_ARG, BAD_STATE, HIP_ERROR, NO_MEMORY = 0, -1, -2, -3, -4
-OPT_FORCE_DENSE, OPT_CAND_TARGET, OPT_PROFILE, OPT_PRIOR_ROOTS, OPT_LIKELIHOOD = 1, 2, 3, 4, 5
+OPT_FORCE_DENSE, OPT_CAND_TARGET, OPT_PROFILE, OPT_PRIOR_ROOTS, OPT_LIKELIHOOD, OPT_PRIOR_EXPONENT = 1, 2, 3, 4, 5, 6
 
 # every symbol include/regtopk.h declares
 SYMBOLS = [
     "regtopk_workspace_bytes", "regtopk_create", "regtopk_create_in", "regtopk_step", "regtopk_step_bf16", "regtopk_step_global",
     "regtopk_global_workspace_bytes", "regtopk_bind_global",
     "regtopk_destroy", "regtopk_reset", "regtopk_get_state", "regtopk_set_state",
-    "regtopk_get_stats", "regtopk_set_option", "regtopk_get_timings", "regtopk_tanh_f32", "regtopk_erf_f32",
+    "regtopk_get_stats", "regtopk_set_option", "regtopk_get_timings", "regtopk_tanh_f32", "regtopk_erf_f32", "regtopk_pow_f32",
     "regtopk_copy_f32", "regtopk_set_weights", "regtopk_set_worker_k", "regtopk_mask_overlap", "regtopk_mask_overlap_static", "regtopk_sgd_update",
     "regtopk_last_error",
 ]
@@ -79,6 +79,7 @@ def load():
     lib.regtopk_copy_f32.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
     lib.regtopk_tanh_f32.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
     lib.regtopk_erf_f32.argtypes = [c_void_p, c_void_p, c_int64, c_void_p]
+    lib.regtopk_pow_f32.argtypes = [c_void_p, c_float, c_void_p, c_int64, c_void_p]
     lib.regtopk_set_weights.argtypes = [c_void_p, ctypes.POINTER(c_float), c_void_p]
     lib.regtopk_set_worker_k.argtypes = [c_void_p, ctypes.POINTER(c_int64), c_void_p]
     lib.regtopk_mask_overlap.argtypes = [c_void_p, c_void_p, c_void_p]
@@ -313,6 +314,16 @@ def tanh_f32(x):
         _check(load().regtopk_tanh_f32(c_void_p(x.data_ptr()), c_void_p(y.data_ptr()), x.numel(),
                                        _stream_ptr(torch)))
     return y
+
+
+def pow_f32(x, y: float):
+    """x**y correctly rounded, on a CUDA float32 tensor of non-negative values (test hook)."""
+    import torch
+    out = torch.empty_like(x)
+    with torch.cuda.device(x.device):
+        _check(load().regtopk_pow_f32(c_void_p(x.data_ptr()), float(y), c_void_p(out.data_ptr()), x.numel(),
+                                      _stream_ptr(torch)))
+    return out
 
 
 def erf_f32(x):

@@ -68,10 +68,16 @@ __device__ __forceinline__ uint32_t lanes_below(uint64_t ballot) {
 
 __device__ __forceinline__ uint32_t key_of(float a) { return __float_as_uint(a) & 0x7FFFFFFFu; }
 
-// Prior |a|^y for y = 2^-roots, roots = 0..3 (appendix remark on sub-linear
-// scaling): `roots` correctly rounded binary32 square roots of |a|.
+// Prior |a|^y (appendix remark on sub-linear scaling).  `roots` is the prior's
+// code: 0..3 = that many correctly rounded binary32 square roots of |a|
+// (y = 2^-roots); a negative value = minus the bit pattern of a binary32
+// exponent 0 < y < 1, the prior then being the correctly rounded |a|^y.
+__host__ __device__ __forceinline__ int prior_code_of_exponent(float y) {
+  return -(int)__builtin_bit_cast(uint32_t, y);
+}
 __device__ __forceinline__ float prior_of(float a, int roots) {
   float p = fabsf(a);
+  if (roots < 0) return pow_f32_cr(p, __uint_as_float((uint32_t)(-roots)));
   for (int i = 0; i < roots; ++i) p = sqrtf(p);      // correctly rounded (the __fsqrt_rn intrinsic is the approximate one here)
   return p;
 }

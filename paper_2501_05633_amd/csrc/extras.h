@@ -348,6 +348,11 @@ __global__ void k_tanh(const float* __restrict__ x, float* __restrict__ y, int64
     y[i] = tanh_f32_cr(x[i]);
 }
 
+__global__ void k_pow(const float* __restrict__ x, float y, float* __restrict__ out, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+    out[i] = pow_f32_cr(x[i], y);
+}
+
 __global__ void k_erf(const float* __restrict__ x, float* __restrict__ y, int64_t n) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
     y[i] = erf_f32_cr(x[i]);

@@ -155,7 +155,7 @@ struct regtopk_ctx {
   int device;
   int dense_blocks;     // grid of the dense-selection kernel: all blocks resident together
   int force_dense;
-  int prior_roots;      // prior |a|^(2^-prior_roots)
+  int prior_roots;      // prior's code: 0..3 square roots, or negative for a general exponent (prior_of)
   int likelihood;       // 0 tanh, 1 clipped linear
   bool reinit_ctl;      // the score space changed: drop the bounds carried over from earlier rounds
   bool need_begin;      // the control blocks are not prepared for the next round (k_begin must run)
@@ -361,6 +361,13 @@ int regtopk_set_option(regtopk_ctx* c, int option, double value) {
         return fail(REGTOPK_INVALID_ARG, "prior roots must be 0, 1, 2 or 3");
       if ((int)value != c->prior_roots) { c->prior_roots = (int)value; c->reinit_ctl = true; c->fresh = kFreshRounds; }
       return REGTOPK_OK;
+    case REGTOPK_OPT_PRIOR_EXPONENT: {
+      const float y = (float)value;
+      if (!(y > 0.0f && y <= 1.0f)) return fail(REGTOPK_INVALID_ARG, "prior exponent must be in (0, 1]");
+      const int code = y == 1.0f ? 0 : prior_code_of_exponent(y);
+      if (code != c->prior_roots) { c->prior_roots = code; c->reinit_ctl = true; c->fresh = kFreshRounds; }
+      return REGTOPK_OK;
+    }
     case REGTOPK_OPT_LIKELIHOOD:
       if (!(value == 0.0 || value == 1.0 || value == 2.0))
         return fail(REGTOPK_INVALID_ARG, "likelihood must be 0 (tanh), 1 (clipped linear) or 2 (erf)");
@@ -817,6 +824,14 @@ int regtopk_copy_f32(float* dst_dev, const float* src_dev, int64_t n, void* stre
   if (n == 0) return REGTOPK_OK;
   k_copy_u32<<<2048, 256, 0, static_cast<hipStream_t>(stream)>>>(reinterpret_cast<uint32_t*>(dst_dev),
                                                                    reinterpret_cast<const uint32_t*>(src_dev), (size_t)n);
+  HIP_TRY(hipGetLastError());
+  return REGTOPK_OK;
+}
+
+int regtopk_pow_f32(const float* x_dev, float y, float* out_dev, int64_t n, void* stream) {
+  if (n < 0 || (n > 0 && (!x_dev || !out_dev)) || !(y > 0.0f && y < 1.0f)) return fail(REGTOPK_INVALID_ARG, "bad arguments");
+  if (n == 0) return REGTOPK_OK;
+  k_pow<<<2048, 256, 0, static_cast<hipStream_t>(stream)>>>(x_dev, y, out_dev, n);
   HIP_TRY(hipGetLastError());
   return REGTOPK_OK;
 }

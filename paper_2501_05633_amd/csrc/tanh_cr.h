@@ -233,4 +233,113 @@ __device__ __forceinline__ float erf_f32_cr(float xf) {
   return erf_f32_dd(xf);
 }
 
+// ------------------------------------------------------------------- pow ----
+// x^y for a non-negative binary32 x and a binary32 exponent 0 < y < 1, rounded
+// correctly to binary32 (the prior |a|^y with a general exponent).  From
+// binary64 operations only:
+//
+//   x = m 2^e with sqrt(1/2) <= m < sqrt(2),  ln m = 2 atanh(s), s = (m-1)/(m+1)
+//   (|s| <= 0.1716: twelve terms of the odd series),  L = y (e ln2 + ln m),
+//   x^y = exp(L) by the argument reduction and Taylor polynomial used above.
+//
+// |L| stays below 104, so the binary64 result carries a relative error below
+// 2^-44; when rounding it to binary32 could depend on that error the evaluation
+// is repeated in double-double arithmetic.
+__device__ __forceinline__ void split_m_e(float xf, double* m, int* e) {
+  // xf > 0, finite (denormals included): exact in binary64
+  const double x = (double)xf;
+  int ex;
+  double mm = frexp(x, &ex);                 // x = mm 2^ex, 0.5 <= mm < 1
+  if (mm < 0x1.6a09e667f3bcdp-1) { mm *= 2.0; ex -= 1; }
+  *m = mm;
+  *e = ex;
+}
+
+__device__ __noinline__ float pow_f32_dd(float xf, float yf) {
+  double m; int e;
+  split_m_e(xf, &m, &e);
+  // s = (m - 1) / (m + 1) in double-double (m - 1 and m + 1 are exact sums of two doubles)
+  const dd sn = dd_two_sum(m, -1.0), sd = dd_two_sum(m, 1.0);
+  const dd sv = dd_div(sn, sd);
+  const dd s2 = dd_mul(sv, sv);
+  dd acc = {0.0, 0.0};
+  for (int kk = 23; kk >= 1; --kk) {                        // sum_{k>=1} s^(2k) / (2k+1), nested
+    dd kd = {(double)(2 * kk + 1), 0.0};
+    dd one_over = dd_div(dd{1.0, 0.0}, kd);
+    acc = dd_mul(s2, dd_add(one_over, acc));
+  }
+  dd lnm = dd_mul_d(dd_mul(sv, dd_add_d(acc, 1.0)), 2.0);    // 2 s (1 + s^2/3 + s^4/5 + ...)
+  const double ed = (double)e;
+  dd lnx = dd_two_prod(ed, RTK_LN2_A);
+  lnx = dd_add(lnx, dd_two_prod(ed, RTK_LN2_B));
+  lnx = dd_add_d(lnx, ed * RTK_LN2_C);
+  lnx = dd_add(lnx, lnm);
+  const dd L = dd_mul_d(lnx, (double)yf);
+  const double n = rint(L.hi * RTK_LOG2E);
+  dd r = dd_two_prod(-n, RTK_LN2_A);
+  r = dd_add(r, L);
+  r = dd_add(r, dd_two_prod(-n, RTK_LN2_B));
+  r = dd_add_d(r, -n * RTK_LN2_C);
+  dd sq = {r.hi * 0.00390625, r.lo * 0.00390625};
+  dd h = {1.0, 0.0};
+  for (int kk = 12; kk >= 2; --kk) {
+    dd kd = {(double)kk, 0.0};
+    h = dd_add_d(dd_div(dd_mul(sq, h), kd), 1.0);
+  }
+  dd q = dd_mul(sq, h);
+  for (int i = 0; i < 8; ++i) {
+    dd q2 = dd_mul(q, q);
+    q = dd_add(dd_mul_d(q, 2.0), q2);
+  }
+  const double sc = ldexp(1.0, (int)n);
+  return dd_round_f32(dd_mul_d(dd_add_d(q, 1.0), sc));
+}
+
+__device__ __forceinline__ float pow_f32_cr(float xf, float yf) {
+  if (xf == 0.0f) return 0.0f;
+  double m; int e;
+  split_m_e(xf, &m, &e);
+  const double sv = (m - 1.0) / (m + 1.0);
+  const double s2 = sv * sv;
+  double p = 1.0 / 25.0;
+  p = __fma_rn(p, s2, 1.0 / 23.0);
+  p = __fma_rn(p, s2, 1.0 / 21.0);
+  p = __fma_rn(p, s2, 1.0 / 19.0);
+  p = __fma_rn(p, s2, 1.0 / 17.0);
+  p = __fma_rn(p, s2, 1.0 / 15.0);
+  p = __fma_rn(p, s2, 1.0 / 13.0);
+  p = __fma_rn(p, s2, 1.0 / 11.0);
+  p = __fma_rn(p, s2, 1.0 / 9.0);
+  p = __fma_rn(p, s2, 1.0 / 7.0);
+  p = __fma_rn(p, s2, 1.0 / 5.0);
+  p = __fma_rn(p, s2, 1.0 / 3.0);
+  const double lnm = 2.0 * __fma_rn(sv * s2, p, sv);        // 2 atanh(s)
+  const double ed = (double)e;
+  const double lnx = __fma_rn(ed, RTK_LN2_A, __fma_rn(ed, RTK_LN2_B, lnm));
+  const double L = (double)yf * lnx;
+  const double n = rint(L * RTK_LOG2E);
+  double r = __fma_rn(-n, RTK_LN2_A, L);
+  r = __fma_rn(-n, RTK_LN2_B, r);
+  double pe = 1.0 / 87178291200.0;                      // 1/14!
+  pe = __fma_rn(pe, r, 1.0 / 6227020800.0);
+  pe = __fma_rn(pe, r, 1.0 / 479001600.0);
+  pe = __fma_rn(pe, r, 1.0 / 39916800.0);
+  pe = __fma_rn(pe, r, 1.0 / 3628800.0);
+  pe = __fma_rn(pe, r, 1.0 / 362880.0);
+  pe = __fma_rn(pe, r, 1.0 / 40320.0);
+  pe = __fma_rn(pe, r, 1.0 / 5040.0);
+  pe = __fma_rn(pe, r, 1.0 / 720.0);
+  pe = __fma_rn(pe, r, 1.0 / 120.0);
+  pe = __fma_rn(pe, r, 1.0 / 24.0);
+  pe = __fma_rn(pe, r, 1.0 / 6.0);
+  pe = __fma_rn(pe, r, 0.5);
+  const double q = __fma_rn(r * r, pe, r);              // expm1(r)
+  const double sc = ldexp(1.0, (int)n);
+  const double y = __fma_rn(sc, q, sc);                 // exp(L)
+  const float lo = (float)(y * (1.0 - 0x1p-42));
+  const float hi = (float)(y * (1.0 + 0x1p-42));
+  if (lo == hi) return lo;
+  return pow_f32_dd(xf, yf);
+}
+
 }  // namespace rtk

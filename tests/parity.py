@@ -67,7 +67,7 @@ def compare_round(o: orc.Oracle, res_gpu, res_cpu, label="", worker_k=None):
 
 def run_both(N, d, k, mu, grads_fn, T, device="cuda:0", force_dense=False, closed_loop=None,
              label="", check_state_every=1, cand_target=None, weights=None, check_overlap=False,
-             on_round=None, grad_dtype=None, prior_roots=0, likelihood=0, worker_k=None):
+             on_round=None, grad_dtype=None, prior_roots=0, likelihood=0, worker_k=None, prior_exponent=None):
     """grads_fn(t, agg_prev_or_None) -> [N,d] float32 tensor on the GPU.
 
     Each side feeds its own aggregate back as g^{t-1}.  Returns per-round stats
@@ -91,6 +91,9 @@ def run_both(N, d, k, mu, grads_fn, T, device="cuda:0", force_dense=False, close
         o.set_score_variant(prior_roots, likelihood)
         r.set_option(binding.OPT_PRIOR_ROOTS, prior_roots)
         r.set_option(binding.OPT_LIKELIHOOD, likelihood)
+    if prior_exponent is not None:
+        o.set_prior_exponent(prior_exponent)
+        r.set_option(binding.OPT_PRIOR_EXPONENT, float(np.float32(prior_exponent)))
     if weights is not None:
         o.set_weights(np.asarray(weights, dtype=np.float32))
         r.set_weights([float(np.float32(x)) for x in weights])

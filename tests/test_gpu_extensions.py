@@ -458,3 +458,29 @@ def test_global_round_memory_of_a_context_in_caller_owned_memory():
         for x, y in zip(a, b):
             assert torch.equal(x, y)
     own.close(); ext.close()
+
+
+@pytest.mark.parametrize("y,lk,dense", [(0.7, 0, False), (1.0 / 3.0, 2, False), (0.9, 1, True), (0.05, 0, False)])
+def test_general_prior_exponent_rounds(y, lk, dense):
+    # prior |a|^y with a general exponent (appendix remark on sub-linear scaling), every round against the oracle
+    N, d, k = 4, 250_003, 2_500
+    cfg = workloads.scaled(workloads.CONFIGS["large_cnn"], d=d, N=N, k=k)
+    wl = workloads.Workload(cfg, DEV)
+    print("case exponent y=%g likelihood=%d dense=%s" % (y, lk, dense), flush=True)
+    stats, tol = run_both(N, d, k, 0.8, lambda t, agg: wl.grads(t), 7, label="exponent %g" % y, prior_exponent=y,
+                          likelihood=lk, force_dense=dense, check_state_every=3)
+    assert tol == 0
+    if not dense:
+        assert any(all(w["used_dense"] == 0 for w in st) for st in stats[1:])      # the speculative path carried rounds
+
+
+def test_prior_exponent_option_replaces_roots_and_is_checked():
+    r = binding.RegTopk(2, 1000, 10, 1.0, device=DEV)
+    for bad in (0.0, -1.0, 1.5):
+        with pytest.raises(binding.RegTopkError) as e:
+            r.set_option(binding.OPT_PRIOR_EXPONENT, bad)
+        assert e.value.code == binding.INVALID_ARG
+    r.set_option(binding.OPT_PRIOR_ROOTS, 2)
+    r.set_option(binding.OPT_PRIOR_EXPONENT, 0.5)
+    r.set_option(binding.OPT_PRIOR_EXPONENT, 1.0)
+    r.close()

@@ -24,6 +24,7 @@ def _draw_case(rng):
     opts = {
         "weights": rng.dirichlet(np.ones(N)).astype(f32) if rng.random() < 0.3 else None,
         "roots": int(rng.choice([0, 0, 0, 1, 2])),
+        "exponent": float(rng.choice([1.0, 1.0, 1.0, 0.8, 0.35])),
         "likelihood": int(rng.choice([0, 0, 1, 2])),
         "force_dense": bool(rng.random() < 0.2),
         "bf16": bool(rng.random() < 0.25),
@@ -59,6 +60,9 @@ def test_random_small_configurations(block):
         o.set_score_variant(opts["roots"], opts["likelihood"])
         r.set_option(binding.OPT_PRIOR_ROOTS, opts["roots"])
         r.set_option(binding.OPT_LIKELIHOOD, opts["likelihood"])
+        if opts["exponent"] != 1.0 and opts["roots"] == 0:
+            o.set_prior_exponent(opts["exponent"])
+            r.set_option(binding.OPT_PRIOR_EXPONENT, opts["exponent"])
         if opts["force_dense"]:
             r.set_option(binding.OPT_FORCE_DENSE, 1)
         if opts["weights"] is not None:

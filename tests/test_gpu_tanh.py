@@ -76,3 +76,32 @@ def test_erf_above_saturation_and_specials():
     want = orc.erf32_array(x.cpu().numpy())
     assert np.array_equal(y.view(np.uint32), want.view(np.uint32))
     assert y[0] < 1.0 and y[2] == 1.0 and y[9] == 1.0 and y[10] == 0.0
+
+
+@pytest.mark.parametrize("y", [0.9, 0.75, 0.5, 1.0 / 3.0, 0.1, 0.999, 1e-3])
+def test_power_on_a_dense_sample_of_all_positive_arguments(y):
+    # the general-exponent prior |a|^y: every 37th binary32 bit pattern from 0 to the largest finite
+    # value (57 million arguments per exponent, denormals included), plus the neighbourhood of 1
+    y = float(np.float32(y))
+    top = int(np.float32(3.4e38).view(np.uint32))
+    slab = 1 << 30
+    mismatches = 0
+    for lo in range(0, top, slab):
+        bits = torch.arange(lo, min(lo + slab, top), 37, dtype=torch.int64, device=DEV).to(torch.int32)
+        x = bits.view(torch.float32)
+        got = binding.pow_f32(x, y).cpu().numpy()
+        xs = x.cpu().numpy()
+        parts = np.array_split(xs, 16)
+        with cf.ThreadPoolExecutor(16) as ex:
+            want = np.concatenate(list(ex.map(lambda p: orc.prior_pow_array(p, y), parts)))
+        bad = np.flatnonzero(got.view(np.uint32) != want.view(np.uint32))
+        if bad.size:
+            print("y=%r slab %#x: %d mismatches, first x=%r got=%r want=%r" % (
+                y, lo, bad.size, xs[bad[0]], got[bad[0]], want[bad[0]]), flush=True)
+        mismatches += bad.size
+        print("pow y=%r slab %#x done" % (y, lo), flush=True)
+    one = int(np.float32(1.0).view(np.uint32))
+    x = torch.arange(one - 200000, one + 200000, dtype=torch.int64, device=DEV).to(torch.int32).view(torch.float32)
+    got = binding.pow_f32(x, y).cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), orc.prior_pow_array(x.cpu().numpy(), y).view(np.uint32))
+    assert mismatches == 0

@@ -247,6 +247,64 @@ def test_exponent_half_commutes_with_scaling_by_four():
         assert np.array_equal(va * f32(16.0), vb) and np.array_equal(ga * f32(16.0), gb)
 
 
+def test_general_exponent_prior_is_the_correctly_rounded_power():
+    # |a|^y for a general binary32 y in (0, 1): nearest binary32 to the exact power (200-bit reference);
+    # for y = 1/2 it is the correctly rounded square root, i.e. the m = 1 variant, by another route
+    mpmath.mp.prec = 200
+    rng = np.random.default_rng(51)
+    for y in (0.9, 0.75, 0.5, f32(1.0) / f32(3.0), 0.1, 0.999, 1e-3):
+        y = f32(y)
+        xs = np.concatenate([np.abs(rng.standard_normal(400)), 10.0 ** rng.uniform(-44.9, 38.5, 400)]).astype(f32)
+        got = oracle.prior_pow_array(xs, y)
+        for x, p in zip(xs, got):
+            exact = mpmath.mpf(float(x)) ** mpmath.mpf(float(y))
+            lo, hi = np.nextafter(p, f32(0)), np.nextafter(p, f32(np.inf))
+            assert abs(mpmath.mpf(float(p)) - exact) <= abs(mpmath.mpf(float(lo)) - exact), (x, y)
+            assert abs(mpmath.mpf(float(p)) - exact) <= abs(mpmath.mpf(float(hi)) - exact), (x, y)
+    xs = np.concatenate([np.abs(rng.standard_normal(3000)), 10.0 ** rng.uniform(-44.9, 38.5, 3000)]).astype(f32)
+    assert np.array_equal(oracle.prior_pow_array(xs, 0.5), np.array([oracle.prior(x, 1) for x in xs], dtype=f32))
+    assert oracle.prior_pow(0.0, 0.3) == 0.0 and oracle.prior_pow(1.0, 0.3) == 1.0 and oracle.prior_pow(-8.0, f32(1.0) / f32(3.0)) == 2.0
+
+
+def test_general_exponent_rounds():
+    N, d, k, mu, y = 4, 3000, 60, 1.5, f32(0.7)
+    rounds = _rounds(5, N, d, k)
+    o = oracle.Oracle(N, d, k, mu)
+    o.set_prior_exponent(y)
+    agg = None
+    for t, g in enumerate(rounds):
+        prev_mask = o.mask if t else np.zeros((N, d), dtype=np.uint8)
+        a_prev, agg_prev = o.a, agg
+        idx, val, agg = o.step(g, agg)
+        sc, a, msk, e = o.score, o.a, o.mask, o.e
+        pr = oracle.prior_pow_array(a.ravel(), y).reshape(N, d)
+        assert np.array_equal(sc[prev_mask == 0], pr[prev_mask == 0]) and np.all(sc <= pr)
+        for n in range(N):
+            assert msk[n].sum() == k and sc[n][msk[n] == 1].min() >= sc[n][msk[n] == 0].max()
+            assert np.array_equal(a[n][idx[n]], val[n]) and np.all(e[n][idx[n]] == 0)
+            for j in np.flatnonzero(prev_mask[n])[:5]:
+                fct = oracle.likelihood_sent_kind(a[n, j], a_prev[n, j], agg_prev[j], f32(1.0) / f32(N), mu, 0)
+                assert sc[n, j] == pr[n, j] * f32(fct)
+    # with the regulariser off the exponent does not change what is selected (the remark's statement;
+    # continuous data, no ties), y = 1 is Algorithm 2, and the argument is checked
+    p0, p1, p2 = oracle.Oracle(N, d, k, 0.0), oracle.Oracle(N, d, k, 0.0), oracle.Oracle(N, d, k, mu)
+    p1.set_prior_exponent(y)
+    p2.set_prior_exponent(0.3)
+    p2.set_prior_exponent(1.0)
+    ref = oracle.Oracle(N, d, k, mu)
+    g2 = gr = None
+    for g in rounds:
+        i0, v0, _ = p0.step(g, None)
+        i1, v1, _ = p1.step(g, None)
+        assert np.array_equal(i0, i1) and np.array_equal(v0, v1)
+        i2, v2, g2 = p2.step(g, g2)
+        ir, vr, gr = ref.step(g, gr)
+        assert np.array_equal(i2, ir) and np.array_equal(g2, gr)
+    for bad in (0.0, -0.5, 1.5, float("nan")):
+        with pytest.raises(ValueError):
+            o.set_prior_exponent(bad)
+
+
 def test_clipped_linear_likelihood():
     # cumulative function of a uniform innovation: min(|1 + Delta| / mu, 1)
     mpmath.mp.prec = 200

@@ -34,6 +34,7 @@ MUTATIONS = [
     ("sent value weighted by omega", "val[(size_t)n * k + c] = a[j]; ++c; }\n        }\n        for (; c < k; ++c)", "val[(size_t)n * k + c] = w * a[j]; ++c; }\n        }\n        for (; c < k; ++c)"),
     ("tanh replaced by the clipped line", "    return tanh32(x);\n}\n\n// Prior", "    return x < 1.0f ? x : 1.0f;\n}\n\n// Prior"),
     ("Gaussian likelihood evaluated with tanh", "if (kind == 2) return erf32(x);", "if (kind == 2) return tanh32(x);"),
+    ("general exponent ignored", "const float pr = o->exponent != 1.0f ? prior_pow(a[j], o->exponent) : prior(a[j], o->sqrt_steps);", "const float pr = prior(a[j], o->sqrt_steps);"),
     ("one square root too many in the prior", "for (int i = 0; i < m; ++i) p = std::sqrt(p);", "for (int i = 0; i <= m; ++i) p = std::sqrt(p);"),
     ("global Top-k over the last worker's values instead of the aggregate", "mag[(size_t)j] = std::fabs(acc);", "mag[(size_t)j] = std::fabs(o->a[(size_t)(o->N - 1) * d + j]);"),
 ]
