@@ -41,7 +41,7 @@ def test_full_size_rounds(name):
     print("window half widths (worker 0):", [h[0] for h in halves], flush=True)
 
 
-@pytest.mark.parametrize("what", ["mu=0.1", "mu=10", "bf16", "roots=1,clipped", "weights"])
+@pytest.mark.parametrize("what", ["mu=0.1", "mu=10", "bf16", "roots=1,clipped", "exponent=0.7,erf", "weights"])
 def test_full_size_variants_of_the_target_workload(what):
     # the other ways the target workload (N = 16, d = 25.6M, k = 256k) is run: the mu sweep of the
     # benchmark list, bfloat16 gradients, a score variant, general weights -- two or three rounds each
@@ -56,6 +56,11 @@ def test_full_size_variants_of_the_target_workload(what):
         kw["grad_dtype"] = torch.bfloat16
     elif what == "roots=1,clipped":
         kw.update(prior_roots=1, likelihood=1)
+    elif what == "exponent=0.7,erf":
+        # (two of the sixteen workers: the oracle's extended-precision power costs 0.3 us per entry)
+        kw.update(prior_exponent=0.7, likelihood=2)
+        cfg = workloads.scaled(cfg, d=cfg.d, N=2, k=cfg.k)
+        wl = workloads.Workload(cfg, DEV)
     elif what == "weights":
         kw["weights"] = np.random.default_rng(2).dirichlet(np.full(cfg.N, 4.0)).astype(np.float32)
 
@@ -63,7 +68,7 @@ def test_full_size_variants_of_the_target_workload(what):
         print("  round %d" % t, flush=True)
         return wl.grads(t)
 
-    T = 2 if what in ("mu=10", "weights") else 3
+    T = 2 if what in ("mu=10", "weights", "exponent=0.7,erf") else 3
     stats, tol = run_both(cfg.N, cfg.d, cfg.k, mu, fn, T, label="large_cnn " + what, check_state_every=T - 1, **kw)
     assert tol == 0
 
