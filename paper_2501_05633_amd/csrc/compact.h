@@ -88,8 +88,7 @@ k_compact(WorkerCtl* ctl, GlobalCtl* gctl, const uint32_t* __restrict__ cand_key
           uint32_t* __restrict__ sel_off, const uint32_t* __restrict__ prev_sel_off,
           int32_t* __restrict__ out_idx,
           float* __restrict__ out_val, uint32_t* __restrict__ mask,
-          int64_t k, const uint32_t* __restrict__ kn, uint32_t nc, uint32_t cap_total, int next_force_dense,
-          int next_roots) {
+          int64_t k, const uint32_t* __restrict__ kn, uint32_t nc, uint32_t cap_total, int next_force_dense) {
   constexpr uint32_t kCPW = 64 / LPC, kCPB = (kBlock / 64) * kCPW;
   static_assert(kChunksPerBlock % kCPB == 0, "a compaction block must lie inside one counting block");
   static_assert(kChunksPerBlock <= LPC, "one load per lane must cover the chunks of a counting block");
@@ -204,7 +203,7 @@ k_compact(WorkerCtl* ctl, GlobalCtl* gctl, const uint32_t* __restrict__ cand_key
       wc.snap_n_bnd = wc.n_bnd;
       wc.snap_n_valid = wc.n_valid;
       wc.snap_win_half = wc.win_lo == kNoBound ? 0u : (wc.win_hi - wc.win_lo) / 2;
-      begin_round(wc, next_force_dense, next_roots);
+      begin_round(wc, next_force_dense);
       if (n == 0) { gctl->any_dense = 0; gctl->bar_count = 0; }
     }
   }

@@ -386,7 +386,7 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
   for (int32_t n = b; n < N; n += G)
     if (ctl[n].need_dense)
       select_worker<true, kBlock>(n, ctl, gctl, cand_key, bnd_key, (int64_t)kn[n], cap_r, cap_total, regions, bnd_cap,
-                                  cand_target, 0, s_hist, nullptr, s_w, s_out);
+                                  cand_target, 0, roots, s_hist, nullptr, s_w, s_out);
 }
 
 }  // namespace rtk

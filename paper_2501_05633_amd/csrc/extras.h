@@ -261,7 +261,7 @@ __global__ void k_init_ctl(WorkerCtl* ctl) {
   __syncthreads();
   if (threadIdx.x == 0) {
     WorkerCtl& c = ctl[blockIdx.x];
-    c.tau_lo = kNoBound; c.tau_lo_mag = kNoBound; c.next_tau_lo = kNoBound; c.win_lo = kNoBound; c.next_win_lo = kNoBound;
+    c.tau_lo = kNoBound; c.tau_lo_mag = kNoBound; c.next_tau_lo = kNoBound; c.next_tau_lo_mag = kNoBound; c.win_lo = kNoBound; c.next_win_lo = kNoBound;
     c.tau_prev = kNoBound; c.centre = kNoBound; c.margin_scale = 1.0f;
   }
 }

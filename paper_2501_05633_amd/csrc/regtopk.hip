@@ -449,7 +449,7 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
     c->need_begin = true;
   }
   if (c->need_begin) {          // otherwise the last kernel of the previous round has done this
-    k_begin<<<N, kBlock, 0, s>>>(ctl, gctl, c->force_dense, sk.roots);
+    k_begin<<<N, kBlock, 0, s>>>(ctl, gctl, c->force_dense);
     c->need_begin = false;
   }
   if (c->fresh > 0 && !c->force_dense) {
@@ -482,8 +482,11 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
   else
     k_accum_emit<G><<<g_chunks, kBlock, 0, s>>>(e, grads, mask, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, nc, L.cap_r, L.cap_total, L.regions);
   if (ev) HIP_TRY(hipEventRecord(ev[1], s));
-  k_score<<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_prev, cand_key, bnd_key, gprev, d, L.cap_r, L.cap_total, L.bnd_cap, omega, c->mu, use_reg, sk);
-  k_select<<<N, kScanBlock, 0, s>>>(ctl, gctl, cand_key, bnd_key, kn, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->cand_target, c->force_dense);
+  if (sk.roots == 0 && sk.likelihood == 0)
+    k_score<false><<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_prev, cand_key, bnd_key, gprev, d, L.cap_r, L.cap_total, L.bnd_cap, omega, c->mu, use_reg, sk);
+  else
+    k_score<true><<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_prev, cand_key, bnd_key, gprev, d, L.cap_r, L.cap_total, L.bnd_cap, omega, c->mu, use_reg, sk);
+  k_select<<<N, kScanBlock, 0, s>>>(ctl, gctl, cand_key, bnd_key, kn, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->cand_target, c->force_dense, sk.roots);
   // dense selection for the workers whose speculation failed; returns at once if there is none
   {
     DeviceGate* gate = c->internal ? nullptr : &g_gate[c->device];
@@ -515,7 +518,7 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
   constexpr uint32_t kCompactPerBlock = (kBlock / 64) * (64 / kCompactLanes);
   k_compact<kCompactLanes><<<dim3((nc + kCompactPerBlock - 1) / kCompactPerBlock, N), kBlock, 0, s>>>(
       ctl, gctl, cand_key, cand_idx, cand_val, ch_off, ch_cnt, ch_gt, ch_tie, blk_gt, blk_tie, n_blk, sel_off, prev_sel_off,
-      out_idx, out_val, mask, k, kn, nc, L.cap_total, c->force_dense, sk.roots);
+      out_idx, out_val, mask, k, kn, nc, L.cap_total, c->force_dense);
   k_aggregate<<<nc, kBlock, 0, s>>>(out_idx, out_val, sel_off, agg, agg_hot, d, k, nc, N, omega);
   if (ev) { HIP_TRY(hipEventRecord(ev[3], s)); c->prof_rounds += 1; }
   HIP_TRY(hipGetLastError());

@@ -39,13 +39,19 @@ __device__ __forceinline__ uint32_t score_entry(uint32_t raw, float a, float a_b
 // one region of the speculative candidate list, eight per thread.
 constexpr int kScoreSlots = 2048;
 
+// VARIANTS = false: the score of Algorithm 2 (plain prior, tanh) only -- the
+// code of the other priors and likelihoods (double-precision power and erf)
+// would otherwise cost this kernel registers, and with them resident waves, in
+// every round.
+template <bool VARIANTS>
 __global__ void __launch_bounds__(kBlock)
 k_score(WorkerCtl* __restrict__ ctl, const int32_t* __restrict__ cand_idx,
         const float* __restrict__ cand_val, const float* __restrict__ cand_prev,
         uint32_t* __restrict__ cand_key, uint32_t* __restrict__ bnd_key,
         const float* __restrict__ gprev, int64_t d, uint32_t cap_r,
         uint32_t cap_total, uint32_t bnd_cap, const float* __restrict__ omega, float mu, int use_reg,
-        ScoreKind sk) {
+        ScoreKind sk_in) {
+  const ScoreKind sk = VARIANTS ? sk_in : ScoreKind{0, 0};
   __shared__ uint32_t s_stage[kScoreSlots];
   __shared__ uint32_t s_cnt[3];       // boundary entries, valid, above window
   __shared__ uint32_t s_base;

@@ -193,7 +193,7 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
                                               const uint32_t* cand_key,
                                               const uint32_t* bnd_key, int64_t k,
                                               uint32_t cap_r, uint32_t cap_total, uint32_t regions,
-                                              uint32_t bnd_cap, float cand_target, int force_dense,
+                                              uint32_t bnd_cap, float cand_target, int force_dense, int roots,
                                               uint32_t* s_hist, uint32_t* s_keys, uint32_t* s_w,
                                               uint32_t* s_out) {
   const uint32_t tid = threadIdx.x;
@@ -348,7 +348,9 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
       if (lo2 < lo) lo = lo2;
     }
     const bool speculate = (int64_t)n_tot >= (int64_t)((double)cand_target * (double)K) || !SECOND;
-    w.next_tau_lo = speculate ? (uint32_t)(lo > 0 ? lo : 0) : kNoBound;
+    const uint32_t nlo = speculate ? (uint32_t)(lo > 0 ? lo : 0) : kNoBound;
+    w.next_tau_lo = nlo;
+    w.next_tau_lo_mag = magnitude_bound(nlo, roots);
     w.next_win_lo = speculate ? (uint32_t)(centre > (int64_t)h ? centre - (int64_t)h : 0) : kNoBound;
     w.next_win_hi = (uint32_t)centre + h;
     w.tau_prev = tau;
@@ -362,13 +364,13 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
 __global__ void __launch_bounds__(kScanBlock)
 k_select(WorkerCtl* ctl, GlobalCtl* gctl, const uint32_t* __restrict__ cand_key,
          const uint32_t* __restrict__ bnd_key, const uint32_t* __restrict__ kn, uint32_t cap_r, uint32_t cap_total,
-         uint32_t regions, uint32_t bnd_cap, float cand_target, int force_dense) {
+         uint32_t regions, uint32_t bnd_cap, float cand_target, int force_dense, int roots) {
   __shared__ uint32_t s_hist[kL1Bins];
   __shared__ uint32_t s_keys[kLdsKeys];
   __shared__ uint32_t s_w[16];
   __shared__ uint32_t s_out[2];
   select_worker<false, kScanBlock>(blockIdx.x, ctl, gctl, cand_key, bnd_key, (int64_t)kn[blockIdx.x], cap_r, cap_total, regions,
-                                   bnd_cap, cand_target, force_dense, s_hist, s_keys, s_w, s_out);
+                                   bnd_cap, cand_target, force_dense, roots, s_hist, s_keys, s_w, s_out);
 }
 
 // -------------------------------------------------------------- sampling ----

@@ -7,10 +7,12 @@ namespace rtk {
 // ---------------------------------------------------------------- k_begin ----
 // Start of a round for one worker (one thread; the cursors are cleared by the
 // caller): this round's bound and window from what the last selection left,
-// counters cleared.
-__device__ __forceinline__ void begin_round(WorkerCtl& c, int force_dense, int roots) {
+// counters cleared.  (The bound on |a| that goes with the score bound was computed
+// by the selection that left it: for a root or power prior that is a binary search
+// through the prior, too heavy for the kernels that call this.)
+__device__ __forceinline__ void begin_round(WorkerCtl& c, int force_dense) {
   c.tau_lo = force_dense ? kNoBound : c.next_tau_lo;
-  c.tau_lo_mag = magnitude_bound(c.tau_lo, roots);
+  c.tau_lo_mag = force_dense ? kNoBound : c.next_tau_lo_mag;
   c.win_lo = force_dense ? kNoBound : c.next_win_lo;
   c.win_hi = c.next_win_hi;
   c.overflow = 0; c.need_dense = 0; c.n_cand = 0; c.n_valid = 0; c.n_hi = 0; c.n_bnd = 0;
@@ -21,13 +23,13 @@ __device__ __forceinline__ void begin_round(WorkerCtl& c, int force_dense, int r
 // after a start without history (create, reset, set_state) or a change of an
 // option the preparation depends on.
 __global__ void __launch_bounds__(kBlock)
-k_begin(WorkerCtl* ctl, GlobalCtl* gctl, int force_dense, int roots) {
+k_begin(WorkerCtl* ctl, GlobalCtl* gctl, int force_dense) {
   const uint32_t n = blockIdx.x, tid = threadIdx.x;
   if (n == 0 && tid == 0) { gctl->any_dense = 0; gctl->bar_count = 0; }   // (arrivals of an abandoned barrier are dropped)
   WorkerCtl& c = ctl[n];
   if (tid < kMaxRegions) c.cursor[tid] = 0;
   if (tid == 0) {
-    begin_round(c, force_dense, roots);
+    begin_round(c, force_dense);
     c.tau = 0; c.n_gt = 0; c.budget = 0; c.ties_total = 0;
     c.f_prefix = 0; c.f_krem = 0; c.f_tau = 0; c.f_budget = 0;
   }
