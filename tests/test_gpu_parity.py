@@ -320,3 +320,16 @@ def test_two_contexts_on_two_streams_with_the_dense_selection_forced():
         for r in (a, b):
             assert all(w["used_dense"] == 1 for w in r.stats())
     ref.close(); a.close(); b.close()
+
+
+def test_sixty_rounds_of_the_scaled_down_target_workload():
+    # a long horizon: the controller's window narrows to its minimum and the speculative bound follows
+    # the slowly drifting k-th score for dozens of rounds; every round is compared
+    cfg = workloads.scaled(workloads.CONFIGS["large_cnn"], d=1_000_000, N=4, k=10_000)
+    print("case 60 rounds", flush=True)
+    stats, tol = run_both(4, 1_000_000, 10_000, 1.0, _wl_fn(cfg), 60, label="60 rounds", check_state_every=20)
+    assert tol == 0
+    dense = _used_dense(stats)
+    window = [[w["used_window"] for w in st] for st in stats]
+    assert sum(sum(r) for r in dense[10:]) == 0
+    assert sum(sum(r) for r in window[10:]) >= 4 * 45          # the window holds the k-th score in nearly every round
