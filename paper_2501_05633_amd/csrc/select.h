@@ -53,7 +53,7 @@ struct KeySource {
 };
 
 // Calls f(key) for every key of the source; memory is read 128 bits at a time,
-// two loads in flight per thread.
+// eight loads in flight per thread.
 template <int NT, typename F>
 __device__ __forceinline__ void for_each_key(const KeySource& src, F f) {
   const uint32_t tid = threadIdx.x;
@@ -68,11 +68,22 @@ __device__ __forceinline__ void for_each_key(const KeySource& src, F f) {
     const uint4* b4 = reinterpret_cast<const uint4*>(base);
     const uint32_t n4 = lim / 4;
     uint32_t i = tid;
-    for (; i + NT < n4; i += 2 * NT) {
-      const uint4 x = b4[i], y = b4[i + NT];
-      f(x.x); f(x.y); f(x.z); f(x.w); f(y.x); f(y.y); f(y.z); f(y.w);
+    constexpr uint32_t kFlight = 8;                    // 128-bit loads of a thread in flight together
+    for (; i + (kFlight - 1) * NT < n4; i += kFlight * NT) {
+      uint4 x[kFlight];
+#pragma unroll
+      for (uint32_t u = 0; u < kFlight; ++u) x[u] = b4[i + u * NT];
+#pragma unroll
+      for (uint32_t u = 0; u < kFlight; ++u) { f(x[u].x); f(x[u].y); f(x[u].z); f(x[u].w); }
     }
-    if (i < n4) { const uint4 x = b4[i]; f(x.x); f(x.y); f(x.z); f(x.w); }
+    {
+      uint4 x[kFlight];
+#pragma unroll
+      for (uint32_t u = 0; u < kFlight; ++u) x[u] = i + u * NT < n4 ? b4[i + u * NT] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+      for (uint32_t u = 0; u < kFlight; ++u)
+        if (i + u * NT < n4) { f(x[u].x); f(x[u].y); f(x[u].z); f(x[u].w); }
+    }
     if (tid < lim - n4 * 4) f(base[n4 * 4 + tid]);
   }
 }
