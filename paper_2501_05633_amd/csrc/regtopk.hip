@@ -457,18 +457,21 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
     // not seen two rounds yet (from an empty error state the k-th score grows by
     // up to a factor of two in the second round and 3/2 in the third): take the
     // bound from a strided sample of a = eps + g.
-    const uint64_t groups_all = (uint64_t)((d + 3) / 4);
-    const uint32_t n_groups = (uint32_t)(groups_all < kSampleMax / 4 ? groups_all : kSampleMax / 4);
-    const uint32_t stride4 = (uint32_t)(groups_all / n_groups);
-    uint64_t n_sampled = (uint64_t)n_groups * 4;
-    if (n_sampled > (uint64_t)d) n_sampled = (uint64_t)d;
+    const uint64_t lines_all = (uint64_t)((d + 31) / 32);
+    const uint32_t n_lines = (uint32_t)(lines_all < kSampleMax / 32 ? lines_all : kSampleMax / 32);
+    const uint32_t line_stride = (uint32_t)(lines_all / n_lines);
+    const uint32_t n_groups = n_lines * 8;
+    // every sample line is whole except, possibly, the last line of the row
+    const uint64_t last_start = (uint64_t)(n_lines - 1) * line_stride * 32;
+    const uint64_t last_len = (uint64_t)d - last_start < 32 ? (uint64_t)d - last_start : 32;
+    const uint64_t n_sampled = (uint64_t)(n_lines - 1) * 32 + last_len;
     k_fill_u32<<<64, 256, 0, s>>>(fhist, (size_t)N * 3 * kL1Bins, 0u);
-    // few blocks per worker: every block ends with one global add per occupied histogram bin, and adds
-    // of many blocks to the same few words queue up (about 12 ns each)
+    // a bounded number of blocks per worker: every block ends with one global add per occupied histogram
+    // bin, and adds of many blocks to the same few words queue up (about 12 ns each)
     uint32_t sample_blocks = (n_groups + 4 * kBlock - 1) / (4 * kBlock);
-    if (sample_blocks > 16) sample_blocks = 16;
-    if (pre) k_sample_hist_state<<<dim3(sample_blocks, N), kBlock, 0, s>>>(e, d, fhist, n_groups, stride4, sk.roots);
-    else k_sample_hist<G><<<dim3(sample_blocks, N), kBlock, 0, s>>>(e, grads, mask, d, nc, fhist, n_groups, stride4, sk.roots);
+    if (sample_blocks > 64) sample_blocks = 64;
+    if (pre) k_sample_hist_state<<<dim3(sample_blocks, N), kBlock, 0, s>>>(e, d, fhist, n_groups, line_stride, sk.roots);
+    else k_sample_hist<G><<<dim3(sample_blocks, N), kBlock, 0, s>>>(e, grads, mask, d, nc, fhist, n_groups, line_stride, sk.roots);
     k_sample_bound<<<N, kScanBlock, 0, s>>>(ctl, fhist, d, kn, (uint32_t)n_sampled, sk.roots);
   }
   if (c->fresh > 0) c->fresh -= 1;
