@@ -58,6 +58,9 @@ struct WorkerCtl {
   uint32_t snap_tau_lo, snap_n_cand, snap_used_dense, snap_overflow, snap_used_window, snap_n_bnd, snap_n_valid, snap_win_half;
   uint32_t f_want;        // entries the dense selection lists: k + k_prev (not clamped to d)
   uint32_t next_tau_lo_mag; // next_tau_lo as a bound on |a| (its pre-image under the prior), set with it
+  uint32_t err_hi;        // largest |prediction error| of the recent rounds (decays by a fifth per round)
+  uint32_t pred_x;        // what the linear extrapolation predicted for this round, or kNoBound
+  float acc_x, acc_l;     // decayed sums of the errors of the extrapolation / of "same as last round"
   uint32_t pad[1];
   uint32_t cursor[kMaxRegions];
 };

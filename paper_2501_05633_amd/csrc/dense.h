@@ -12,7 +12,7 @@ namespace rtk {
 // the host so that all blocks are resident together.
 //
 // Phases, for flagged workers only:
-//   clear histograms | 3 x (histogram of the prior's bits, every flagged
+//   3 x (histogram of the prior's bits, every flagged
 //   worker fed by its own group of blocks; pick the bin of rank
 //   min(k + k_prev, d)) | per-chunk counts | chunk scan | ordered emission of
 //   the k + k_prev largest priors as the candidate list | scores | exact k-th
@@ -115,46 +115,55 @@ __device__ __forceinline__ void dense_scan_worker(uint32_t n, WorkerCtl* ctl, co
   __syncthreads();
 }
 
-// Chunk c of worker n: entries with |a| bits > f_tau and == f_tau.
+// The chunks c = first, first + stride, ... of worker n, one per WAVE (no block barrier): entries
+// with prior bits > f_tau and == f_tau.  A lane keeps eight 128-bit loads in flight: the few
+// resident waves of this kernel must cover the memory latency themselves.
 template <bool VEC>
-__device__ __forceinline__ void dense_count_chunk(uint32_t n, uint32_t c, const float* a, int64_t d,
-                                                  const WorkerCtl* ctl, uint32_t* ch_gt,
-                                                  uint32_t* ch_tie, uint32_t nc, uint32_t* s_gt,
-                                                  uint32_t* s_tie, int roots) {
-  const uint32_t tid = threadIdx.x;
+__device__ __forceinline__ void dense_count_chunks(uint32_t n, uint32_t first, uint32_t stride, const float* a,
+                                                   int64_t d, const WorkerCtl* ctl, uint32_t* ch_gt,
+                                                   uint32_t* ch_tie, uint32_t nc, int roots) {
+  const uint32_t lane = threadIdx.x & 63;
   const uint32_t tau = ctl[n].f_tau;
   const float* row = a + (size_t)n * (size_t)d;
-  uint32_t gt = 0, tie = 0;
-  if (VEC) {
+  for (uint32_t c = first; c < nc; c += stride) {
+    uint32_t gt = 0, tie = 0;
+    const int64_t c0 = (int64_t)c * kChunk;
+    if (VEC) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int64_t j = (int64_t)c * kChunk + (i * kBlock + tid) * 4;
-      if (j < d) {
-        const float4 v = *reinterpret_cast<const float4*>(row + j);
-        const uint32_t k0 = prior_key(v.x, roots), k1 = prior_key(v.y, roots), k2 = prior_key(v.z, roots),
-                       k3 = prior_key(v.w, roots);
-        gt += (k0 > tau) + (k1 > tau) + (k2 > tau) + (k3 > tau);
-        tie += (k0 == tau) + (k1 == tau) + (k2 == tau) + (k3 == tau);
+      for (int h = 0; h < 2; ++h) {
+        float4 v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int64_t j = c0 + ((h * 8 + i) * 64 + lane) * 4;
+          v[i] = j < d ? *reinterpret_cast<const float4*>(row + j) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int64_t j = c0 + ((h * 8 + i) * 64 + lane) * 4;
+          if (j < d) {
+            const uint32_t k0 = prior_key(v[i].x, roots), k1 = prior_key(v[i].y, roots), k2 = prior_key(v[i].z, roots),
+                           k3 = prior_key(v[i].w, roots);
+            gt += (k0 > tau) + (k1 > tau) + (k2 > tau) + (k3 > tau);
+            tie += (k0 == tau) + (k1 == tau) + (k2 == tau) + (k3 == tau);
+          }
+        }
+      }
+    } else {
+      for (int i = 0; i < 64; ++i) {
+        const int64_t j = c0 + i * 64 + lane;
+        if (j < d) {
+          const uint32_t key = prior_key(row[j], roots);
+          gt += key > tau;
+          tie += key == tau;
+        }
       }
     }
-  } else {
-    for (int i = 0; i < 16; ++i) {
-      const int64_t j = (int64_t)c * kChunk + i * kBlock + tid;
-      if (j < d) {
-        const uint32_t key = prior_key(row[j], roots);
-        gt += key > tau;
-        tie += key == tau;
-      }
+    for (int o = 32; o > 0; o >>= 1) { gt += __shfl_down(gt, o); tie += __shfl_down(tie, o); }
+    if (lane == 0) {
+      ch_gt[(size_t)n * nc + c] = gt;
+      ch_tie[(size_t)n * nc + c] = tie;
     }
   }
-  for (int o = 32; o > 0; o >>= 1) { gt += __shfl_down(gt, o); tie += __shfl_down(tie, o); }
-  if ((tid & 63) == 0) { s_gt[tid >> 6] = gt; s_tie[tid >> 6] = tie; }
-  __syncthreads();
-  if (tid == 0) {
-    ch_gt[(size_t)n * nc + c] = s_gt[0] + s_gt[1] + s_gt[2] + s_gt[3];
-    ch_tie[(size_t)n * nc + c] = s_tie[0] + s_tie[1] + s_tie[2] + s_tie[3];
-  }
-  __syncthreads();
 }
 
 // Chunk c of worker n: writes its share of the k + k_prev largest |a| (ties: lowest
@@ -299,8 +308,14 @@ __device__ __forceinline__ void dense_abandon(WorkerCtl* ctl, int32_t N) {
 }
 
 // grid (G): G blocks resident together.  See the section header.
+// The kernel is compiled for four waves per SIMD (128 registers; the double-double
+// code of the score variants spills a little): left to itself the compiler takes
+// 173 registers, which halves the resident blocks -- and the grid is one block per
+// compute unit less than fit, so one block per unit instead of three.  The passes
+// over the rows are bound by how many loads the resident waves keep in flight
+// (all 16 workers of the target workload: 5.5 ms at one block per unit, 3.9 ms at three).
 template <bool VEC>
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(4, 4)))
 k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_off, int64_t d, WorkerCtl* ctl,
             GlobalCtl* gctl, uint32_t* fhist, uint32_t* ch_gt, uint32_t* ch_tie, uint32_t* ch_off,
             uint32_t* ch_cnt, uint32_t* tie_off, int32_t* cand_idx, float* cand_val, float* cand_prev,
@@ -316,13 +331,7 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
   __shared__ uint32_t s_w[16], s_out[2], s_x[4], s_y[4];
   const uint32_t b = blockIdx.x, G = gridDim.x, tid = threadIdx.x;
 
-  for (int32_t n = 0; n < N; ++n) {
-    if (!ctl[n].need_dense) continue;
-    uint32_t* fh = fhist + (size_t)n * 3 * kL1Bins;
-    for (uint32_t i = b * kBlock + tid; i < 3 * kL1Bins; i += G * kBlock) fh[i] = 0;
-  }
-  if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
-
+  // (k_select has cleared the histograms of the workers it flagged)
   // The histogram passes give every flagged worker its own group of blocks (all
   // workers at once, each histogram fed by G / n_flagged blocks), so that the
   // blocks' final adds do not all queue on the same few words.
@@ -360,7 +369,7 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
 
   for (int32_t n = 0; n < N; ++n) {
     if (!ctl[n].need_dense) continue;
-    for (uint32_t c = b; c < nc; c += G) dense_count_chunk<VEC>(n, c, a_rows, d, ctl, ch_gt, ch_tie, nc, s_x, s_y, roots);
+    dense_count_chunks<VEC>(n, b * (kBlock / 64) + (tid >> 6), G * (kBlock / 64), a_rows, d, ctl, ch_gt, ch_tie, nc, roots);
   }
   if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (int32_t n = b; n < N; n += G)

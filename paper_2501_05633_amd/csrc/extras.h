@@ -262,7 +262,7 @@ __global__ void k_init_ctl(WorkerCtl* ctl) {
   if (threadIdx.x == 0) {
     WorkerCtl& c = ctl[blockIdx.x];
     c.tau_lo = kNoBound; c.tau_lo_mag = kNoBound; c.next_tau_lo = kNoBound; c.next_tau_lo_mag = kNoBound; c.win_lo = kNoBound; c.next_win_lo = kNoBound;
-    c.tau_prev = kNoBound; c.centre = kNoBound; c.margin_scale = 1.0f;
+    c.tau_prev = kNoBound; c.centre = kNoBound; c.pred_x = kNoBound; c.margin_scale = 1.0f;
   }
 }
 

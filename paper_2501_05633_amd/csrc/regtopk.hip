@@ -489,7 +489,7 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
     k_score<false><<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_prev, cand_key, bnd_key, gprev, d, L.cap_r, L.cap_total, L.bnd_cap, omega, c->mu, use_reg, sk);
   else
     k_score<true><<<g_score, kBlock, 0, s>>>(ctl, cand_idx, cand_val, cand_prev, cand_key, bnd_key, gprev, d, L.cap_r, L.cap_total, L.bnd_cap, omega, c->mu, use_reg, sk);
-  k_select<<<N, kScanBlock, 0, s>>>(ctl, gctl, cand_key, bnd_key, kn, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->cand_target, c->force_dense, sk.roots);
+  k_select<<<N, kScanBlock, 0, s>>>(ctl, gctl, cand_key, bnd_key, kn, L.cap_r, L.cap_total, L.regions, L.bnd_cap, c->cand_target, c->force_dense, sk.roots, fhist);
   // dense selection for the workers whose speculation failed; returns at once if there is none
   {
     DeviceGate* gate = c->internal ? nullptr : &g_gate[c->device];

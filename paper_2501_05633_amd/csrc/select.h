@@ -199,8 +199,9 @@ constexpr uint32_t kLdsKeys = 11264;    // LDS room for the keys of the bin chos
 
 // SECOND = false: first invocation, all workers (validates the speculation).
 // SECOND = true : after the dense selection, flagged workers only.
+// Returns true (to every thread) if it flagged the worker for the dense selection.
 template <bool SECOND, int NT>
-__device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, GlobalCtl* gctl,
+__device__ __forceinline__ bool select_worker(uint32_t n, WorkerCtl* ctl, GlobalCtl* gctl,
                                               const uint32_t* cand_key,
                                               const uint32_t* bnd_key, int64_t k,
                                               uint32_t cap_r, uint32_t cap_total, uint32_t regions,
@@ -222,7 +223,7 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
   }
   __syncthreads();
   const WorkerCtl& c = s_ctl;
-  if (SECOND && !c.need_dense) return;
+  if (SECOND && !c.need_dense) return false;
   const uint32_t K = (uint32_t)k;
   uint32_t n_tot = 0;
   if (!SECOND) {
@@ -234,7 +235,7 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
         w.need_dense = 1u;
         atomicOr(&gctl->any_dense, 1u);
       }
-      return;
+      return true;
     }
     // (n_cand and need_dense = 0 are stored with the other results at the end: a store ahead of
     // the barriers below would make the first of them wait for it)
@@ -299,23 +300,44 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
       if (!c.overflow) shock = true;
       else if (ref != kNoBound && tau > ref && tau - ref > (1u << 23)) shock = true;
     }
-    // the k-th score drifts from round to round: extrapolate linearly
+    // The k-th score drifts from round to round: extrapolate linearly -- unless
+    // "same as last round" has been the better prediction lately (gradients whose
+    // scale jitters from round to round: extrapolating doubles such noise).
     int64_t drift = 0;
     if (!shock && c.tau_prev != kNoBound) drift = (int64_t)tau - (int64_t)c.tau_prev;
     if (drift > (1 << 22)) drift = 1 << 22;
     if (drift < -(1 << 22)) drift = -(1 << 22);
+    float acc_x = 0.0f, acc_l = 0.0f;
+    if (!shock && c.tau_prev != kNoBound && c.pred_x != kNoBound) {
+      const uint32_t ex = tau > c.pred_x ? tau - c.pred_x : c.pred_x - tau;
+      const uint32_t el = tau > c.tau_prev ? tau - c.tau_prev : c.tau_prev - tau;
+      acc_x = 0.7f * c.acc_x + (float)ex;
+      acc_l = 0.7f * c.acc_l + (float)el;
+    }
+    w.acc_x = acc_x;
+    w.acc_l = acc_l;
+    const int64_t px = (int64_t)tau + drift;
+    w.pred_x = (!shock && c.tau_prev != kNoBound) ? (uint32_t)(px < 0 ? 0 : (px > 0x7F000000 ? 0x7F000000 : px)) : kNoBound;
+    const bool have_two = !shock && c.tau_prev != kNoBound;      // the prediction rests on two observed rounds
+    const int64_t seen_drift = drift;
+    if (acc_l < acc_x) drift = 0;
     int64_t centre = (int64_t)tau + drift;
     if (centre < 0) centre = 0;
     if (centre > 0x7F000000) centre = 0x7F000000;
     // expected error of that prediction: how far this round's prediction was off
-    // if it was an extrapolation (two earlier rounds known), else half the drift
-    const uint32_t adrift = (uint32_t)(drift < 0 ? -drift : drift);
+    // if it rested on two earlier rounds, else half the drift
+    const uint32_t adrift = (uint32_t)(seen_drift < 0 ? -seen_drift : seen_drift);
     uint32_t err;
     if (shock) err = kWinDefaultHalf;
     else if (c.centre != kNoBound && c.extrapolated) err = tau > c.centre ? tau - c.centre : c.centre - tau;
     else if (c.tau_prev != kNoBound) err = adrift / 2;
     else err = kWinDefaultHalf;
     if (!shock && (double)err < 0.5 * (double)c.err_prev) err = (uint32_t)(0.5 * (double)c.err_prev);
+    // volatility: the largest error of the recent rounds.  The last error alone says little about
+    // the next when the scale of the gradients jitters; the bound's margin below covers this one.
+    uint32_t err_hi = shock ? err : (uint32_t)(0.8 * (double)c.err_hi);
+    if (err_hi < err) err_hi = err;
+    w.err_hi = err_hi;
     double half = 3.0 * (double)err + 1024.0;
     const double by_count = 10000.0 / dens;                // at least about 20000 boundary entries
     if (half < by_count) half = by_count;
@@ -341,7 +363,7 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
     }
     w.margin_scale = ms;
     double margin = ((double)cand_target - 1.0) * (double)K / dens;
-    if (margin < (double)err + 1024.0) margin = (double)err + 1024.0;
+    if (margin < 1.5 * (double)err_hi + 1024.0) margin = 1.5 * (double)err_hi + 1024.0;
     margin *= (double)ms;
     if (margin > 16777216.0) margin = 16777216.0;
     const int64_t anchor = drift > 0 ? (int64_t)tau + drift / 2 : centre;
@@ -367,21 +389,30 @@ __device__ __forceinline__ void select_worker(uint32_t n, WorkerCtl* ctl, Global
     w.tau_prev = tau;
     w.centre = speculate ? (uint32_t)centre : kNoBound;
     w.err_prev = err;
-    w.extrapolated = (speculate && drift != 0) ? 1u : 0u;
+    w.extrapolated = (speculate && have_two && seen_drift != 0) ? 1u : 0u;
   }
+  return false;
 }
 
 // grid (N), 1024 threads: the first selection of a round, for all workers.
 __global__ void __launch_bounds__(kScanBlock)
 k_select(WorkerCtl* ctl, GlobalCtl* gctl, const uint32_t* __restrict__ cand_key,
          const uint32_t* __restrict__ bnd_key, const uint32_t* __restrict__ kn, uint32_t cap_r, uint32_t cap_total,
-         uint32_t regions, uint32_t bnd_cap, float cand_target, int force_dense, int roots) {
+         uint32_t regions, uint32_t bnd_cap, float cand_target, int force_dense, int roots,
+         uint32_t* __restrict__ fhist) {
   __shared__ uint32_t s_hist[kL1Bins];
   __shared__ uint32_t s_keys[kLdsKeys];
   __shared__ uint32_t s_w[16];
   __shared__ uint32_t s_out[2];
-  select_worker<false, kScanBlock>(blockIdx.x, ctl, gctl, cand_key, bnd_key, (int64_t)kn[blockIdx.x], cap_r, cap_total, regions,
-                                   bnd_cap, cand_target, force_dense, roots, s_hist, s_keys, s_w, s_out);
+  const bool flagged = select_worker<false, kScanBlock>(blockIdx.x, ctl, gctl, cand_key, bnd_key, (int64_t)kn[blockIdx.x], cap_r,
+                                                        cap_total, regions, bnd_cap, cand_target, force_dense, roots,
+                                                        s_hist, s_keys, s_w, s_out);
+  // a worker handed to the dense selection gets its three histograms cleared here, which saves that
+  // kernel a phase and a grid barrier
+  if (flagged) {
+    uint32_t* fh = fhist + (size_t)blockIdx.x * 3 * kL1Bins;
+    for (uint32_t i = threadIdx.x; i < 3 * kL1Bins; i += kScanBlock) fh[i] = 0;
+  }
 }
 
 // -------------------------------------------------------------- sampling ----
