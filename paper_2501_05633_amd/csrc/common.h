@@ -43,8 +43,10 @@ struct WorkerCtl {
   uint32_t n_gt;          // candidates with score > tau
   uint32_t budget;        // ties to take, lowest indices first
   uint32_t ties_total;
-  uint32_t f_prefix;      // radix-select state of the dense selection over |a| bits
-  uint32_t f_krem;
+  uint32_t f_prefix;      // radix-select state of the dense selection over the prior's bits: bin chosen at
+  uint32_t f_krem;        //   level 1 and the rank wanted inside it
+  uint32_t f_prefix2;     //   the same after level 2 (the bins of levels 1 and 2 joined).  One pair per level:
+  uint32_t f_krem2;       //   several blocks store a level's (identical) result, none updates a pair in place
   uint32_t f_tau;
   uint32_t f_budget;
   uint32_t err;           // bit 0: selected count != k, bit 1: bad set_state input, bit 2: the dense selection of this worker was abandoned
@@ -188,10 +190,14 @@ __device__ __forceinline__ bool grid_barrier(GlobalCtl* g, uint32_t nblocks, uin
         }
       }
     }
+    // The acquiring fence (it drops what this compute unit's L1 and this XCD's L2 hold of other XCDs'
+    // lines) is issued once, by this thread, before the block's own barrier hands its effect to the
+    // other waves: the fences of a device's blocks queue up (about 0.1 us per block and barrier for a
+    // fence per wave, 0.06 us for one per block; 768 blocks).
+    __threadfence();
     s_ok = ok;
   }
   __syncthreads();
-  __threadfence();
   return s_ok != 0;
 }
 

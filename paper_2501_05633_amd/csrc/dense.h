@@ -28,7 +28,7 @@ __device__ __forceinline__ void dense_hist_worker(uint32_t n, uint32_t b, uint32
   constexpr uint32_t bins = LEVEL == 1 ? kL1Bins : (LEVEL == 2 ? kL2Bins : kL3Bins);
   for (uint32_t i = tid; i < bins; i += kBlock) s_hist[i] = 0;
   __syncthreads();
-  const uint32_t prefix = ctl[n].f_prefix;
+  const uint32_t prefix = LEVEL == 2 ? ctl[n].f_prefix : (LEVEL == 3 ? ctl[n].f_prefix2 : 0u);
   const float* row = a + (size_t)n * (size_t)d;
   auto put = [&](float v) {
     const uint32_t key = prior_key(v, roots);
@@ -68,7 +68,9 @@ __device__ __forceinline__ void dense_hist_worker(uint32_t n, uint32_t b, uint32
 // Level LEVEL of the radix select of rank min(k + k_prev, d) over the prior's
 // bits of worker n (k entries to keep now, k_prev entries sent in the previous
 // round): finds, from the top bin downwards, the bin in which the cumulative
-// count reaches the wanted rank.  One block.
+// count reaches the wanted rank.  One block; levels 1 and 2 are run by every
+// block that is about to feed the worker's next histogram (they all find and
+// store the same result), which saves a grid barrier per level.
 template <int LEVEL>
 __device__ __forceinline__ void dense_scan_worker(uint32_t n, WorkerCtl* ctl, const uint32_t* hist_all,
                                                   int64_t k, int64_t k_prev, int64_t d, uint32_t* s_sum,
@@ -83,7 +85,7 @@ __device__ __forceinline__ void dense_scan_worker(uint32_t n, WorkerCtl* ctl, co
     want = (uint32_t)(k + k_prev < d ? k + k_prev : d);
     if (tid == 0) c.f_want = (uint32_t)(k + k_prev);
   } else {
-    want = c.f_krem;
+    want = LEVEL == 2 ? c.f_krem : c.f_krem2;
   }
   // thread t owns bins [bins-1-t*per .. bins-(t+1)*per], i.e. descending order
   uint32_t loc[per];
@@ -106,8 +108,8 @@ __device__ __forceinline__ void dense_scan_worker(uint32_t n, WorkerCtl* ctl, co
         const uint32_t bin = bins - 1 - (tid * per + q);
         const uint32_t krem = want - run;            // rank wanted inside this bin
         if (LEVEL == 1) { c.f_prefix = bin; c.f_krem = krem; }
-        else if (LEVEL == 2) { c.f_prefix = (c.f_prefix << 11) | bin; c.f_krem = krem; }
-        else { c.f_tau = (c.f_prefix << 8) | bin; c.f_budget = krem; }
+        else if (LEVEL == 2) { c.f_prefix2 = (c.f_prefix << 11) | bin; c.f_krem2 = krem; }
+        else { c.f_tau = (c.f_prefix2 << 8) | bin; c.f_budget = krem; }
       }
       run += loc[q];
     }
@@ -347,20 +349,20 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
     if (n < (uint32_t)N) dense_hist_worker<1, VEC>(n, sub, sub_cnt, a_rows, d, ctl, fhist, s_hist, roots);
   }
   if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
-  for (int32_t n = b; n < N; n += G)
-    if (ctl[n].need_dense) dense_scan_worker<1>(n, ctl, fhist, (int64_t)kn[n], (int64_t)prev_sel_off[(size_t)n * (nc + 1) + nc], d, s_a, s_b);
-  if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (uint32_t r = grp; r < n_flagged; r += groups) {
     const uint32_t n = r == grp ? first_worker : flagged_worker(ctl, N, r, &n_flagged, s_w, s_out);
-    if (n < (uint32_t)N) dense_hist_worker<2, VEC>(n, sub, sub_cnt, a_rows, d, ctl, fhist, s_hist, roots);
+    if (n < (uint32_t)N) {
+      dense_scan_worker<1>(n, ctl, fhist, (int64_t)kn[n], (int64_t)prev_sel_off[(size_t)n * (nc + 1) + nc], d, s_a, s_b);
+      dense_hist_worker<2, VEC>(n, sub, sub_cnt, a_rows, d, ctl, fhist, s_hist, roots);
+    }
   }
   if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
-  for (int32_t n = b; n < N; n += G)
-    if (ctl[n].need_dense) dense_scan_worker<2>(n, ctl, fhist, (int64_t)kn[n], (int64_t)prev_sel_off[(size_t)n * (nc + 1) + nc], d, s_a, s_b);
-  if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (uint32_t r = grp; r < n_flagged; r += groups) {
     const uint32_t n = r == grp ? first_worker : flagged_worker(ctl, N, r, &n_flagged, s_w, s_out);
-    if (n < (uint32_t)N) dense_hist_worker<3, VEC>(n, sub, sub_cnt, a_rows, d, ctl, fhist, s_hist, roots);
+    if (n < (uint32_t)N) {
+      dense_scan_worker<2>(n, ctl, fhist, (int64_t)kn[n], (int64_t)prev_sel_off[(size_t)n * (nc + 1) + nc], d, s_a, s_b);
+      dense_hist_worker<3, VEC>(n, sub, sub_cnt, a_rows, d, ctl, fhist, s_hist, roots);
+    }
   }
   if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (int32_t n = b; n < N; n += G)

@@ -31,7 +31,7 @@ k_begin(WorkerCtl* ctl, GlobalCtl* gctl, int force_dense) {
   if (tid == 0) {
     begin_round(c, force_dense);
     c.tau = 0; c.n_gt = 0; c.budget = 0; c.ties_total = 0;
-    c.f_prefix = 0; c.f_krem = 0; c.f_tau = 0; c.f_budget = 0;
+    c.f_prefix = 0; c.f_krem = 0; c.f_prefix2 = 0; c.f_krem2 = 0; c.f_tau = 0; c.f_budget = 0;
   }
 }
 
