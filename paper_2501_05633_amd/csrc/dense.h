@@ -174,11 +174,16 @@ __device__ __forceinline__ void dense_count_chunks(uint32_t n, uint32_t first, u
 // round is fetched from that round's list: its position there is the number of
 // mask bits before the entry (prev_sel_off[c] of them in lower chunks; s_mw /
 // s_rk, 128 words each, hold the chunk's mask words and their running counts).
+// The caller has found the chunk's count non-zero.  Everything else the chunk
+// needs from memory (offsets, mask words, the entries) is loaded at the top,
+// before the first barrier, so that the few resident blocks of this kernel wait
+// for memory twice per chunk (these loads, then the previous values), not once
+// per step.
 template <bool VEC>
 __device__ __forceinline__ void dense_emit_chunk(uint32_t n, uint32_t c, const float* a_rows,
                                                  const uint32_t* mask, int64_t d, const WorkerCtl* ctl,
                                                  int32_t* cand_idx, float* cand_val, float* cand_prev,
-                                                 const uint32_t* ch_off, const uint32_t* ch_cnt,
+                                                 const uint32_t* ch_off,
                                                  const uint32_t* tie_off, const uint32_t* prev_sel_off,
                                                  const float* prev_val, int64_t k, uint32_t nc,
                                                  uint32_t cap_total, uint32_t* s_wtot, uint32_t* s_ttot,
@@ -186,27 +191,14 @@ __device__ __forceinline__ void dense_emit_chunk(uint32_t n, uint32_t c, const f
   const uint32_t tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const uint32_t* mrow = mask + (size_t)n * nc * kChunkWords;
   const size_t tix = (size_t)n * nc + c;
-  if (ch_cnt[tix] == 0) return;
-  if (tid < kChunkWords) s_mw[tid] = mrow[(size_t)c * kChunkWords + tid];
-  __syncthreads();
-  if (tid < 64) {                                    // wave 0: running count of mask bits, two words per lane
-    const uint32_t c0 = (uint32_t)__popc(s_mw[2 * tid]), c1 = (uint32_t)__popc(s_mw[2 * tid + 1]);
-    uint32_t x = c0 + c1;
-    for (int o = 1; o < 64; o <<= 1) {
-      const uint32_t y = __shfl_up(x, o);
-      if (tid >= (uint32_t)o) x += y;
-    }
-    const uint32_t before = prev_sel_off[(size_t)n * (nc + 1) + c] + x - (c0 + c1);
-    s_rk[2 * tid] = before;
-    s_rk[2 * tid + 1] = before + c0;
-  }
-  __syncthreads();
-  const float* pv = prev_val + (size_t)n * k;
+  const uint32_t mword = tid < kChunkWords ? mrow[(size_t)c * kChunkWords + tid] : 0u;
+  const uint32_t sent_before = prev_sel_off[(size_t)n * (nc + 1) + c];
+  const uint32_t tie_before = tie_off[tix];          // ties in lower chunks
+  const uint32_t first_slot = ch_off[tix];
   const uint32_t tau = ctl[n].f_tau, budget = ctl[n].f_budget;
   const size_t row = (size_t)n * (size_t)d;
   const int64_t base = (int64_t)c * kChunk + (int64_t)wv * 1024 + lane * 4;
   float a[4][4];
-  uint32_t gtf = 0, tief = 0;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int64_t j0 = base + i * 256;
@@ -218,6 +210,24 @@ __device__ __forceinline__ void dense_emit_chunk(uint32_t n, uint32_t c, const f
 #pragma unroll
       for (int q = 0; q < 4; ++q) a[i][q] = (j0 + q < d) ? a_rows[row + j0 + q] : 0.f;
     }
+  }
+  if (tid < kChunkWords) s_mw[tid] = mword;
+  __syncthreads();
+  if (tid < 64) {                                    // wave 0: running count of mask bits, two words per lane
+    const uint32_t c0 = (uint32_t)__popc(s_mw[2 * tid]), c1 = (uint32_t)__popc(s_mw[2 * tid + 1]);
+    uint32_t x = c0 + c1;
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t y = __shfl_up(x, o);
+      if (tid >= (uint32_t)o) x += y;
+    }
+    const uint32_t before = sent_before + x - (c0 + c1);
+    s_rk[2 * tid] = before;
+    s_rk[2 * tid + 1] = before + c0;
+  }
+  uint32_t gtf = 0, tief = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int64_t j0 = base + i * 256;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       if (j0 + q < d) {
@@ -228,7 +238,7 @@ __device__ __forceinline__ void dense_emit_chunk(uint32_t n, uint32_t c, const f
     }
   }
   // rank of every tie within the chunk (index order) decides which ties are taken
-  const uint32_t tie_before = tie_off[tix];          // ties in lower chunks
+  // (the barrier inside also publishes s_rk)
   ChunkPos tp = ordered_positions(tief, s_ttot);
   uint32_t flags = gtf;
 #pragma unroll
@@ -242,9 +252,9 @@ __device__ __forceinline__ void dense_emit_chunk(uint32_t n, uint32_t c, const f
       }
     }
   }
-  __syncthreads();
   const ChunkPos cp = ordered_positions(flags, s_wtot);
-  const size_t out = (size_t)n * cap_total + ch_off[tix] + cp.wave_base;
+  const float* pv = prev_val + (size_t)n * k;
+  const size_t out = (size_t)n * cap_total + first_slot + cp.wave_base;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     uint32_t p = cp.lane_base[i];
@@ -379,9 +389,15 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
   if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (int32_t n = 0; n < N; ++n) {
     if (!ctl[n].need_dense) continue;
-    for (uint32_t c = b; c < nc; c += G)
-      dense_emit_chunk<VEC>(n, c, a_rows, mask, d, ctl, cand_idx, cand_val, cand_prev, ch_off, ch_cnt, tie_off,
-                            prev_sel_off, prev_val, k, nc, cap_total, s_x, s_y, s_a, s_b, roots);
+    // (the count of the block's next chunk is fetched while the current one is emitted)
+    uint32_t cnt = b < nc ? ch_cnt[(size_t)n * nc + b] : 0u;
+    for (uint32_t c = b; c < nc; c += G) {
+      const uint32_t cnt_next = c + G < nc ? ch_cnt[(size_t)n * nc + c + G] : 0u;
+      if (cnt)
+        dense_emit_chunk<VEC>(n, c, a_rows, mask, d, ctl, cand_idx, cand_val, cand_prev, ch_off, tie_off,
+                              prev_sel_off, prev_val, k, nc, cap_total, s_x, s_y, s_a, s_b, roots);
+      cnt = cnt_next;
+    }
   }
   if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
 
