@@ -362,8 +362,24 @@ __device__ __forceinline__ bool select_worker(uint32_t n, WorkerCtl* ctl, Global
       ms = ms > 1.0f ? 1.0f + (ms - 1.0f) * 0.7f : (ms * 1.3f > 1.0f ? 1.0f : ms * 1.3f);
     }
     w.margin_scale = ms;
-    double margin = ((double)cand_target - 1.0) * (double)K / dens;
+    const double by_target = ((double)cand_target - 1.0) * (double)K / dens;
+    double margin = by_target;
     if (margin < 1.5 * (double)err_hi + 1024.0) margin = 1.5 * (double)err_hi + 1024.0;
+    // ... but not so far down that the candidates would outgrow their buffer (room for 4k and some
+    // slack): the number of entries above a bound grows like an exponential of the distance in bit
+    // patterns (a power of the magnitude), whose rate two counts of this round give -- k entries
+    // above tau and `above_ref` above `ref`, the bound (or the end of the dense selection's list).
+    // The volatility term is cut off where that model expects 2.2k candidates (it underestimates:
+    // the rate grows further down; a cut at 3k overflowed in the first rounds of the cnn workload).
+    {
+      const uint32_t ref = SECOND ? c.f_tau : c.tau_lo;
+      const double above_ref = SECOND ? (double)c.dense_total : (double)c.n_valid;
+      if (ref != kNoBound && tau > ref && above_ref > 1.02 * (double)K) {
+        const double reach = (double)(tau - ref) * log(2.2) / log(above_ref / (double)K);
+        const double most = reach > by_target ? reach : by_target;
+        if (margin > most) margin = most;
+      }
+    }
     margin *= (double)ms;
     if (margin > 16777216.0) margin = 16777216.0;
     const int64_t anchor = drift > 0 ? (int64_t)tau + drift / 2 : centre;
