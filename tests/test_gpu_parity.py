@@ -217,6 +217,29 @@ def test_scale_shocks_force_both_kinds_of_failed_speculation():
     assert all(x == 0 for x in dense[-1])
 
 
+def test_jitter_of_the_gradient_scale_per_worker_and_round():
+    # Every worker's gradients are scaled by its own factor, drawn anew in every round: uniform in
+    # [0.7, 1.3] for 16 rounds, then log-normal (sigma 0.5) for 10.  The k-th score then moves by
+    # more than any margin of a steady run; whatever mix of kept and failed speculations results,
+    # every round matches the oracle, and under the milder jitter the speculation mostly holds.
+    cfg = workloads.scaled(workloads.CONFIGS["large_cnn"], d=600_000, N=4, k=6_000)
+    wl = workloads.Workload(cfg, DEV)
+    gen = torch.Generator().manual_seed(77)
+    T = 26
+    uni = 0.7 + 0.6 * torch.rand(T, 4, generator=gen)
+    logn = torch.exp(0.5 * torch.randn(T, 4, generator=gen))
+    factors = torch.where(torch.arange(T)[:, None] < 16, uni, logn)
+
+    def fn(t, agg):
+        return (wl.grads(t) * factors[t].to(DEV)[:, None]).contiguous()
+
+    stats, tol = run_both(4, 600_000, 6_000, 1.0, fn, T, label="jitter", check_state_every=5)
+    assert tol == 0
+    dense = _used_dense(stats)
+    print("dense per round:", [sum(x) for x in dense], flush=True)
+    assert sum(sum(x) for x in dense[6:16]) <= 8          # of 40 worker-rounds under the uniform jitter
+
+
 def test_more_than_32_workers_and_odd_sizes():
     # 33 workers (two batches in the aggregation), d a multiple of 4 but not of 4096
     N, d, k = 33, 70_004, 350
