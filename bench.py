@@ -171,7 +171,10 @@ def main():
         _, _, agg = r.step_global(grads[t % n_buf]) if glob else r.step(grads[t % n_buf], agg)
     torch.cuda.synchronize()
     warm = [x[3] for x in r.timings(64)] if args.warmup else []     # whole-round event times of the warm-up rounds
-    r.set_option(binding.OPT_PROFILE, 1)          # restart the event ring for the timed region
+    # The timed region records only the two events around the dominant kernel (profile level 2): every
+    # event keeps the next kernel from starting back to back (about 4 us each), and the five events of
+    # the full stage breakdown would add some 20 us to every timed round.
+    r.set_option(binding.OPT_PROFILE, 2)
 
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -181,17 +184,25 @@ def main():
     t1 = time.perf_counter()
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    stage = r.timings(64)
+    sweep_ms = sum(x[0] for x in r.timings(64)) / args.steps
     st = r.stats()
     dense_rounds = sum(w["used_dense"] for w in st)
-    sweep_ms = sum(x[0] for x in stage) / len(stage)
+    cands = [w["n_candidates"] for w in st]
+
+    # stage breakdown: as many rounds again, after the timed region, with all five events per round
+    r.set_option(binding.OPT_PROFILE, 1)
+    for i in range(args.steps):
+        t = args.warmup + args.steps + i
+        _, _, agg = r.step_global(grads[t % n_buf]) if glob else r.step(grads[t % n_buf], agg)
+    torch.cuda.synchronize()
+    stage = r.timings(64)
     select_ms = sum(x[1] for x in stage) / len(stage)
     tail_ms = sum(x[2] for x in stage) / len(stage)
     round_ms_events = sum(x[3] for x in stage) / len(stage)
 
-    # every round of the run by its own HIP events (round 0 has no history; the first rounds are
-    # slower while the k-th score still moves fast): round 0, and median / min / max of the others
-    all_rounds = (warm + [x[3] for x in stage])[-(args.warmup + args.steps):]
+    # every fully instrumented round of the run by its own HIP events (round 0 has no history; the first
+    # rounds are slower while the k-th score still moves fast): round 0, and median / min / max of the others
+    all_rounds = warm + [x[3] for x in stage]
     later = sorted(all_rounds[1:]) if len(all_rounds) > 1 else sorted(all_rounds)
     round_ms = {"round0": all_rounds[0] if args.warmup and len(warm) == args.warmup else None,
                 "median_later_rounds": later[len(later) // 2], "min": later[0], "max": later[-1],
@@ -220,10 +231,12 @@ def main():
         "hbm_frac_round": b_alg / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "algorithmic_bytes_per_round": b_alg,
         "stage_ms": {"sweep": sweep_ms, "select": select_ms, "compact_aggregate": tail_ms,
-                     "round_events": round_ms_events},
+                     "round_events": round_ms_events,
+                     "source": "sweep: the timed rounds; the others: as many rounds after the timed region, "
+                               "recorded with five events per round (about 20 us more per round)"},
         "round_ms_by_events": round_ms,
         "dense_fallback_workers_last_round": dense_rounds,
-        "candidates_last_round": [w["n_candidates"] for w in st],
+        "candidates_last_round": cands,
         "roofline": {"bound": "hbm", "kernel": "k_global_accum" if glob else "k_accum_emit_vec", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "algorithmic_bytes_per_launch": sweep_bytes, "avg_launch_ms": sweep_ms,

@@ -237,8 +237,11 @@ int regtopk_sgd_update(float* theta_dev, const float* g_dev, float eta, int64_t 
 /* Options (tuning and test hooks). */
 #define REGTOPK_OPT_FORCE_DENSE   1  /* value != 0: never speculate, always run the dense selection */
 #define REGTOPK_OPT_CAND_TARGET   2  /* speculative pass aims at value*k candidates (1 < value <= 3; default 1.25) */
-#define REGTOPK_OPT_PROFILE       3  /* value != 0: record HIP events on the step's stream around the stages of every
-                                        step (resets the recorded rounds); 0 switches it off */
+#define REGTOPK_OPT_PROFILE       3  /* 1: record HIP events on the step's stream around the stages of every step
+                                        (five events; each keeps the next kernel from starting back to back,
+                                        about 4 us, so a profiled round is some 20 us longer);  2: only the two
+                                        events around the dense sweep kernel;  0 switches it off.  Every setting
+                                        resets the recorded rounds. */
 /* Score variants (paper: remark on sub-linear scaling in the appendix, score
  * |a|^y * u(|1 + Delta|) with y <= 1; sentence after the tanh likelihood that
  * other cumulative functions u_mu are admissible).  Defaults are Algorithm 2.
@@ -259,7 +262,8 @@ int regtopk_set_option(regtopk_ctx* ctx, int option, double value);
 /* Stage times of the last n <= min(max_rounds, 64) profiled rounds, oldest
  * first, in milliseconds: out_host[4*i + 0] the dense sweep kernel (accumulate + emit),
  * + 1 scoring and selection, + 2 compaction, error update and aggregation,
- * + 3 the whole round.  Waits for the recorded events. */
+ * + 3 the whole round (the last three are 0 for rounds recorded at profile
+ * level 2).  Waits for the recorded events. */
 int regtopk_get_timings(regtopk_ctx* ctx, float* out_host, int32_t max_rounds, int32_t* n_rounds);
 
 /* Text of the last error on the calling thread ("" if none). */

@@ -160,7 +160,8 @@ struct regtopk_ctx {
   bool reinit_ctl;      // the score space changed: drop the bounds carried over from earlier rounds
   bool need_begin;      // the control blocks are not prepared for the next round (k_begin must run)
   float cand_target;
-  bool profile;                 // record stage events in every step
+  int profile;                  // 0 off, 1 record the stage events in every step, 2 only those around the sweep
+  int ev_level[kProfRounds];    // level at which a round of the ring was recorded
   hipEvent_t ev[kProfRounds][5];
   int64_t prof_rounds;          // steps recorded since profiling was switched on
   uint32_t* host_err;   // pinned host word the dense-selection kernel sets when it abandons a round
@@ -216,7 +217,7 @@ int create_common(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu, 
   c->reinit_ctl = false;
   c->gsel = nullptr;
   c->cand_target = 1.25f;
-  c->profile = false;
+  c->profile = 0;
   c->prof_rounds = 0;
   c->arena = static_cast<char*>(arena);
   if (!make_layout(N, d, k, &c->L) || bytes < c->L.total) { delete c; return fail(REGTOPK_INVALID_ARG, "sizes have no valid layout"); }
@@ -374,14 +375,16 @@ int regtopk_set_option(regtopk_ctx* c, int option, double value) {
       if ((int)value != c->likelihood) { c->likelihood = (int)value; c->reinit_ctl = true; c->fresh = kFreshRounds; }
       return REGTOPK_OK;
     case REGTOPK_OPT_PROFILE:
+      if (!(value == 0.0 || value == 1.0 || value == 2.0)) return fail(REGTOPK_INVALID_ARG, "profile level must be 0, 1 or 2");
       if (value != 0.0 && !c->profile) {
-        for (auto& row : c->ev) for (auto& e : row) HIP_TRY(hipEventCreate(&e));
-        c->profile = true;
+        // timing only: without the system-scope fence an event otherwise carries (a write-back and
+        // invalidation of the caches, which the kernels after it pay for)
+        for (auto& row : c->ev) for (auto& e : row) HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableSystemFence));
       }
       if (value == 0.0 && c->profile) {
         for (auto& row : c->ev) for (auto& e : row) (void)hipEventDestroy(e);
-        c->profile = false;
       }
+      c->profile = (int)value;
       c->prof_rounds = 0;
       return REGTOPK_OK;
     default: return fail(REGTOPK_INVALID_ARG, "unknown option %d", option);
@@ -441,7 +444,9 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
   const dim3 g_chunks(nc, N), g_waves((nc + 3) / 4, N);
   const dim3 g_score((L.cap_r + kScoreSlots - 1) / kScoreSlots, L.regions, N);
   hipEvent_t* ev = c->profile ? c->ev[c->prof_rounds % kProfRounds] : nullptr;
-  if (ev) HIP_TRY(hipEventRecord(ev[4], s));
+  const bool ev_all = c->profile == 1;              // else only ev[0], ev[1] around the sweep
+  if (ev) c->ev_level[c->prof_rounds % kProfRounds] = c->profile;
+  if (ev && ev_all) HIP_TRY(hipEventRecord(ev[4], s));
   const ScoreKind sk{c->prior_roots, c->likelihood};
   if (c->reinit_ctl) {
     k_init_ctl<<<N, 256, 0, s>>>(ctl);
@@ -512,7 +517,7 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
   }
 
   // ordered compaction, error update, aggregation
-  if (ev) HIP_TRY(hipEventRecord(ev[2], s));
+  if (ev && ev_all) HIP_TRY(hipEventRecord(ev[2], s));
   const uint32_t n_blk = (nc + kChunksPerBlock - 1) / kChunksPerBlock;
   const dim3 g_groups(n_blk, N);
   uint32_t* blk_gt = c->at<uint32_t>(L.blk_gt);
@@ -523,7 +528,8 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
       ctl, gctl, cand_key, cand_idx, cand_val, ch_off, ch_cnt, ch_gt, ch_tie, blk_gt, blk_tie, n_blk, sel_off, prev_sel_off,
       out_idx, out_val, mask, k, kn, nc, L.cap_total, c->force_dense);
   k_aggregate<<<nc, kBlock, 0, s>>>(out_idx, out_val, sel_off, agg, agg_hot, d, k, nc, N, omega);
-  if (ev) { HIP_TRY(hipEventRecord(ev[3], s)); c->prof_rounds += 1; }
+  if (ev && ev_all) HIP_TRY(hipEventRecord(ev[3], s));
+  if (ev) c->prof_rounds += 1;
   HIP_TRY(hipGetLastError());
 
   c->t += 1;
@@ -594,7 +600,10 @@ int regtopk_step_global(regtopk_ctx* c, const float* grads, void* stream, regtop
   uint32_t* mask = c->at<uint32_t>(L.mask);
   const uint32_t* prev_sel_off = c->at<uint32_t>(L.sel_off[prv]);
   hipEvent_t* ev = c->profile ? c->ev[c->prof_rounds % kProfRounds] : nullptr;
-  if (ev) { HIP_TRY(hipEventRecord(ev[4], s)); HIP_TRY(hipEventRecord(ev[0], s)); }
+  const bool ev_all = c->profile == 1;
+  if (ev) c->ev_level[c->prof_rounds % kProfRounds] = c->profile;
+  if (ev && ev_all) HIP_TRY(hipEventRecord(ev[4], s));
+  if (ev) HIP_TRY(hipEventRecord(ev[0], s));
   // abar goes straight into the selector's state: its round neither adds nor stores anything
   float* abar = g->at<float>(g->L.e);
   const uint32_t acc_blocks = (uint32_t)((c->d + 4 * kGlobalBlock - 1) / (4 * kGlobalBlock));
@@ -606,13 +615,14 @@ int regtopk_step_global(regtopk_ctx* c, const float* grads, void* stream, regtop
   const int gcur = (int)(g->t & 1);
   int rc = step_impl<float>(g, nullptr, nullptr, stream, &sel, true);
   if (rc != REGTOPK_OK) return rc;
-  if (ev) HIP_TRY(hipEventRecord(ev[2], s));
+  if (ev && ev_all) HIP_TRY(hipEventRecord(ev[2], s));
   const uint32_t entry_blocks = (uint32_t)((c->k + kBlock - 1) / kBlock);
   k_global_apply<<<dim3(entry_blocks + (L.nc + 3) / 4, c->N), kBlock, 0, s>>>(
       e, sel.idx, g->at<uint32_t>(g->L.sel_off[gcur]), g->at<uint32_t>(g->L.mask), prev_sel_off,
       c->at<int32_t>(L.out_idx[cur]), c->at<float>(L.out_val[cur]), c->at<uint32_t>(L.sel_off[cur]), mask, c->d, c->k, L.nc,
       entry_blocks);
-  if (ev) { HIP_TRY(hipEventRecord(ev[3], s)); c->prof_rounds += 1; }
+  if (ev && ev_all) HIP_TRY(hipEventRecord(ev[3], s));
+  if (ev) c->prof_rounds += 1;
   HIP_TRY(hipGetLastError());
   c->t += 1;
   c->have_prev = true;
@@ -815,11 +825,15 @@ int regtopk_get_timings(regtopk_ctx* c, float* out, int32_t max_rounds, int32_t*
   for (int64_t i = 0; i < have; ++i) {
     const int64_t r = c->prof_rounds - have + i;      // oldest first
     hipEvent_t* ev = c->ev[r % kProfRounds];
-    HIP_TRY(hipEventSynchronize(ev[3]));
+    const bool all = c->ev_level[r % kProfRounds] == 1;
+    HIP_TRY(hipEventSynchronize(all ? ev[3] : ev[1]));
     HIP_TRY(hipEventElapsedTime(&out[i * 4 + 0], ev[0], ev[1]));
-    HIP_TRY(hipEventElapsedTime(&out[i * 4 + 1], ev[1], ev[2]));
-    HIP_TRY(hipEventElapsedTime(&out[i * 4 + 2], ev[2], ev[3]));
-    HIP_TRY(hipEventElapsedTime(&out[i * 4 + 3], ev[4], ev[3]));
+    out[i * 4 + 1] = out[i * 4 + 2] = out[i * 4 + 3] = 0.0f;
+    if (all) {
+      HIP_TRY(hipEventElapsedTime(&out[i * 4 + 1], ev[1], ev[2]));
+      HIP_TRY(hipEventElapsedTime(&out[i * 4 + 2], ev[2], ev[3]));
+      HIP_TRY(hipEventElapsedTime(&out[i * 4 + 3], ev[4], ev[3]));
+    }
   }
   *n_rounds = (int32_t)have;
   return REGTOPK_OK;

@@ -484,3 +484,35 @@ def test_prior_exponent_option_replaces_roots_and_is_checked():
     r.set_option(binding.OPT_PRIOR_EXPONENT, 0.5)
     r.set_option(binding.OPT_PRIOR_EXPONENT, 1.0)
     r.close()
+
+
+def test_stage_timings_at_both_profile_levels():
+    # level 1 records the events around every stage of a round, level 2 only those around the
+    # dense sweep; a change of level restarts the record; without profiling there are no timings
+    N, d, k = 4, 400_000, 4_000
+    cfg = workloads.scaled(workloads.CONFIGS["large_cnn"], d=d, N=N, k=k)
+    wl = workloads.Workload(cfg, DEV)
+    r = binding.RegTopk(N, d, k, 1.0, device=DEV)
+    with pytest.raises(binding.RegTopkError):
+        r.timings()
+    with pytest.raises(binding.RegTopkError):
+        r.set_option(binding.OPT_PROFILE, 3)
+    agg = None
+    r.set_option(binding.OPT_PROFILE, 1)
+    for t in range(3):
+        _, _, agg = r.step(wl.grads(t), agg)
+    full = r.timings()
+    assert len(full) == 3
+    for sweep, select, tail, total in full:
+        assert sweep > 0 and select > 0 and tail > 0 and total >= sweep + select + tail - 1e-3
+    r.set_option(binding.OPT_PROFILE, 2)
+    for t in range(3, 5):
+        _, _, agg = r.step(wl.grads(t), agg)
+    light = r.timings()
+    assert len(light) == 2
+    for sweep, select, tail, total in light:
+        assert sweep > 0 and select == 0 and tail == 0 and total == 0
+    r.set_option(binding.OPT_PROFILE, 0)
+    with pytest.raises(binding.RegTopkError):
+        r.timings()
+    r.close()
