@@ -412,8 +412,10 @@ k_dense_all(const float* a_rows, const uint32_t* mask, const uint32_t* prev_sel_
   if (!grid_barrier(gctl, G, host_err)) { dense_abandon(ctl, N); return; }
   for (int32_t n = b; n < N; n += G)
     if (ctl[n].need_dense)
+      // (the finer levels of the selection use the first 512 words of the histogram's LDS; the rest
+      // of it takes the keys of the bin chosen at the first level, which saves two passes over the list)
       select_worker<true, kBlock>(n, ctl, gctl, cand_key, bnd_key, (int64_t)kn[n], cap_r, cap_total, regions, bnd_cap,
-                                  cand_target, 0, roots, s_hist, nullptr, s_w, s_out);
+                                  cand_target, 0, roots, s_hist, s_hist + 512, kL1Bins - 512, s_w, s_out);
 }
 
 }  // namespace rtk

@@ -206,8 +206,8 @@ __device__ __forceinline__ bool select_worker(uint32_t n, WorkerCtl* ctl, Global
                                               const uint32_t* bnd_key, int64_t k,
                                               uint32_t cap_r, uint32_t cap_total, uint32_t regions,
                                               uint32_t bnd_cap, float cand_target, int force_dense, int roots,
-                                              uint32_t* s_hist, uint32_t* s_keys, uint32_t* s_w,
-                                              uint32_t* s_out) {
+                                              uint32_t* s_hist, uint32_t* s_keys, uint32_t keys_cap,
+                                              uint32_t* s_w, uint32_t* s_out) {
   const uint32_t tid = threadIdx.x;
   // The worker's control block is read once, by the block together, into LDS:
   // the many fields consulted below (most of them by thread 0 alone, one after
@@ -270,7 +270,7 @@ __device__ __forceinline__ bool select_worker(uint32_t n, WorkerCtl* ctl, Global
   uint32_t budget, ties;
   // (the key buffer in LDS is free for the gathering unless it holds the boundary list)
   uint32_t* stash = (s_keys != nullptr && src.lds == nullptr) ? s_keys : nullptr;
-  const uint32_t tau = rel_select<NT>(src, base, rank, s_hist, s_w, s_out, stash, kLdsKeys, &budget, &ties);
+  const uint32_t tau = rel_select<NT>(src, base, rank, s_hist, s_w, s_out, stash, keys_cap, &budget, &ties);
 
   if (tid == 0) {
     w.n_cand = n_tot;
@@ -422,7 +422,7 @@ k_select(WorkerCtl* ctl, GlobalCtl* gctl, const uint32_t* __restrict__ cand_key,
   __shared__ uint32_t s_out[2];
   const bool flagged = select_worker<false, kScanBlock>(blockIdx.x, ctl, gctl, cand_key, bnd_key, (int64_t)kn[blockIdx.x], cap_r,
                                                         cap_total, regions, bnd_cap, cand_target, force_dense, roots,
-                                                        s_hist, s_keys, s_w, s_out);
+                                                        s_hist, s_keys, kLdsKeys, s_w, s_out);
   // a worker handed to the dense selection gets its three histograms cleared here, which saves that
   // kernel a phase and a grid barrier
   if (flagged) {
