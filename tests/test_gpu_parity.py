@@ -240,6 +240,30 @@ def test_jitter_of_the_gradient_scale_per_worker_and_round():
     assert sum(sum(x) for x in dense[6:16]) <= 8          # of 40 worker-rounds under the uniform jitter
 
 
+def test_eighty_rounds_of_jitter_shocks_and_spikes():
+    # a long run in which everything that can upset the speculation happens again and again:
+    # log-normal jitter of every worker's scale, collapses and explosions of all workers'
+    # gradients, spikes of single workers -- every round against the oracle
+    N, d, k, T = 3, 300_000, 3_000, 80
+    cfg = workloads.scaled(workloads.CONFIGS["large_cnn"], d=d, N=N, k=k)
+    wl = workloads.Workload(cfg, DEV)
+    gen = torch.Generator().manual_seed(1)
+    f = torch.exp(0.4 * torch.randn(T, N, generator=gen))
+    for t in range(10, T, 17):
+        f[t] *= [1e-3, 50.0, 0.05, 300.0][(t // 17) % 4]
+    for t in range(5, T, 13):
+        f[t, t % N] *= 20.0
+
+    def fn(t, agg):
+        return (wl.grads(t) * f[t].to(DEV)[:, None]).contiguous()
+
+    stats, tol = run_both(N, d, k, 1.0, fn, T, label="soak", check_state_every=10)
+    assert tol == 0
+    dense = [sum(x) for x in _used_dense(stats)]
+    print("dense selections per round:", dense, flush=True)
+    assert 0 < sum(dense) < T * N // 3          # both paths are exercised, the speculation mostly holds
+
+
 def test_more_than_32_workers_and_odd_sizes():
     # 33 workers (two batches in the aggregation), d a multiple of 4 but not of 4096
     N, d, k = 33, 70_004, 350
