@@ -8,7 +8,7 @@ mu = 1 (the "large CNN-sized" configuration, 20 rounds from a zero error
 state): rounds 0..W-1 are the warm-up, rounds W..W+K-1 are timed.  Prints ONE
 JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--mu MU] [--grad-dtype f32|bf16]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--mu MU] [--k K] [--grad-dtype f32|bf16]
 """
 from __future__ import annotations
 
@@ -106,6 +106,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="large_cnn")
     ap.add_argument("--mu", type=float, default=None)
+    ap.add_argument("--k", type=int, default=None, help="entries kept per worker, if not the workload's own")
     ap.add_argument("--grad-dtype", choices=["f32", "bf16"], default="f32",
                     help="storage type of the local gradients (bf16: widened exactly, arithmetic stays f32)")
     ap.add_argument("--prior-roots", type=int, default=0, help="score variant: prior |a|^(2^-m)")
@@ -139,6 +140,8 @@ def main():
     cfg = workloads.CONFIGS[args.workload]
     if args.mu is not None:
         cfg = workloads.scaled(cfg, d=cfg.d, k=cfg.k, mu=args.mu)
+    if args.k is not None:
+        cfg = workloads.scaled(cfg, d=cfg.d, k=args.k)
     N, d, k = cfg.N, cfg.d, cfg.k
     wl = workloads.Workload(cfg, dev)
 
@@ -214,7 +217,7 @@ def main():
         sweep_bytes += 4 * d                      # the accumulation also writes the unsparsified aggregate
     traffic, traffic_src = (None, None)
     if args.grad_dtype == "f32" and args.prior_roots == 0 and args.prior_exponent == 1.0 and args.likelihood == 0 \
-            and not args.force_dense:
+            and not args.force_dense and args.k is None:
         traffic, traffic_src = measured_traffic(cfg.name, args.mode)
     achieved = sweep_bytes / (sweep_ms * 1e-3) / 1e9
     b_alg = algorithmic_bytes(N, d, k, g_bytes)
