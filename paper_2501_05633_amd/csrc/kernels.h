@@ -3,6 +3,8 @@
 // Data flow of one round (all N workers batched; rows of length d):
 //
 //   k_begin         reset counters, load this round's speculative bound and window
+//                   (only after a start without history: otherwise the compaction
+//                   of the round before has prepared the control blocks)
 //   k_accum_emit    a = eps + g written over eps (the one dense read/write sweep);
 //                   eps is taken as 0 where the previous round's mask bit is set
 //                   (the sent entries are never zeroed in memory: one bit per
@@ -21,7 +23,8 @@
 //                   list when the window contains it, otherwise over all
 //                   candidates - and derives next round's bound/window
 //   (k_sample_hist, k_sample_bound: a round without history - round 0, after a
-//                   reset - first takes its bound from a strided sample of a)
+//                   reset - first takes its bound from a sample of a: whole
+//                   128-byte lines at a fixed stride)
 //   k_dense_all     for workers whose speculation failed: exact radix select of
 //                   the k + k_prev largest priors |a|^y (k_prev entries were sent
 //                   in the previous round, normally k; a superset of the true
