@@ -174,9 +174,10 @@ def main():
         _, _, agg = r.step_global(grads[t % n_buf]) if glob else r.step(grads[t % n_buf], agg)
     torch.cuda.synchronize()
     warm = [x[3] for x in r.timings(64)] if args.warmup else []     # whole-round event times of the warm-up rounds
-    # The timed region records only the two events around the dominant kernel (profile level 2): every
-    # event keeps the next kernel from starting back to back (about 4 us each), and the five events of
-    # the full stage breakdown would add some 20 us to every timed round.
+    # The timed region records only the two events of the dominant kernel (profile level 2; they travel
+    # with the kernel's own dispatch): an event recorded between two kernels keeps the second from
+    # starting back to back (about 4 us each), and those of the full stage breakdown would add some
+    # 10 us to every timed round.
     r.set_option(binding.OPT_PROFILE, 2)
 
     t0 = time.perf_counter()
@@ -192,7 +193,7 @@ def main():
     dense_rounds = sum(w["used_dense"] for w in st)
     cands = [w["n_candidates"] for w in st]
 
-    # stage breakdown: as many rounds again, after the timed region, with all five events per round
+    # stage breakdown: as many rounds again, after the timed region, with all stage events
     r.set_option(binding.OPT_PROFILE, 1)
     for i in range(args.steps):
         t = args.warmup + args.steps + i
@@ -236,7 +237,7 @@ def main():
         "stage_ms": {"sweep": sweep_ms, "select": select_ms, "compact_aggregate": tail_ms,
                      "round_events": round_ms_events,
                      "source": "sweep: the timed rounds; the others: as many rounds after the timed region, "
-                               "recorded with five events per round (about 20 us more per round)"},
+                               "recorded with all stage events (about 10 us more per round)"},
         "round_ms_by_events": round_ms,
         "dense_fallback_workers_last_round": dense_rounds,
         "candidates_last_round": cands,

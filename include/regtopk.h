@@ -237,11 +237,13 @@ int regtopk_sgd_update(float* theta_dev, const float* g_dev, float eta, int64_t 
 /* Options (tuning and test hooks). */
 #define REGTOPK_OPT_FORCE_DENSE   1  /* value != 0: never speculate, always run the dense selection */
 #define REGTOPK_OPT_CAND_TARGET   2  /* speculative pass aims at value*k candidates (1 < value <= 3; default 1.25) */
-#define REGTOPK_OPT_PROFILE       3  /* 1: record HIP events on the step's stream around the stages of every step
-                                        (five events; each keeps the next kernel from starting back to back,
-                                        about 4 us, so a profiled round is some 20 us longer);  2: only the two
-                                        events around the dense sweep kernel;  0 switches it off.  Every setting
-                                        resets the recorded rounds. */
+#define REGTOPK_OPT_PROFILE       3  /* 1: HIP events on the step's stream around the stages of every step (an
+                                        event recorded between two kernels keeps the second from starting back
+                                        to back, about 4 us; the two events of the dense sweep kernel travel
+                                        with its own dispatch instead, the other three are recorded: a profiled
+                                        round is some 10 us longer);  2: only the two events of the dense sweep
+                                        kernel (about 3 us);  0 switches it off.  Every setting resets the
+                                        recorded rounds. */
 /* Score variants (paper: remark on sub-linear scaling in the appendix, score
  * |a|^y * u(|1 + Delta|) with y <= 1; sentence after the tanh likelihood that
  * other cumulative functions u_mu are admissible).  Defaults are Algorithm 2.
