@@ -99,7 +99,10 @@ size_t regtopk_workspace_bytes(int32_t N, int64_t d, int64_t k);
  * memory instead: arena_dev must be 256-byte aligned, at least
  * regtopk_workspace_bytes(N,d,k) long, and must outlive the context; its
  * contents are overwritten.  Both zero the state (create_in on `stream`, a
- * hipStream_t, NULL = default stream) and wait for that to finish. */
+ * hipStream_t, NULL = default stream) and wait for that to finish.
+ * The context belongs to the device that is current at creation: every later
+ * call that enqueues work for it must be made with that device current
+ * (REGTOPK_INVALID_ARG otherwise; nothing is enqueued). */
 int regtopk_create(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu);
 int regtopk_create_in(regtopk_ctx** out, int32_t N, int64_t d, int64_t k, float mu,
                       void* arena_dev, size_t arena_bytes, void* stream);

@@ -37,6 +37,16 @@ int fail(int code, const char* fmt, ...) {
       return fail(REGTOPK_HIP_ERROR, "%s failed: %s", #expr, hipGetErrorString(e_));    \
   } while (0)
 
+// Work of a context is enqueued on the device it was created on: the calling
+// thread's current device must be that one (its memory is not another device's).
+#define DEVICE_TRY(c)                                                                    \
+  do {                                                                                  \
+    int dev_ = -1;                                                                      \
+    HIP_TRY(hipGetDevice(&dev_));                                                       \
+    if (dev_ != (c)->device)                                                            \
+      return fail(REGTOPK_INVALID_ARG, "the context lives on device %d, the current device is %d", (c)->device, dev_); \
+  } while (0)
+
 constexpr size_t kAlign = 256;
 size_t up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -344,6 +354,7 @@ int regtopk_destroy(regtopk_ctx* c) {
 
 int regtopk_reset(regtopk_ctx* c, void* stream) {
   if (!c) return fail(REGTOPK_INVALID_ARG, "ctx is NULL");
+  DEVICE_TRY(c);
   return zero_state(c, static_cast<hipStream_t>(stream));
 }
 
@@ -402,6 +413,7 @@ namespace {
 template <typename G>
 int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, regtopk_result* out, bool pre = false) {
   if (!c || (!grads && !pre) || !out) return fail(REGTOPK_INVALID_ARG, "ctx, grads_dev and out must not be NULL");
+  DEVICE_TRY(c);
   if (*static_cast<volatile uint32_t*>(c->host_err) != 0)
     return fail(REGTOPK_BAD_STATE, "an earlier round abandoned its dense selection (its blocks were not resident "
                                    "together); the state is undefined until regtopk_reset or regtopk_set_state");
@@ -574,6 +586,7 @@ size_t regtopk_global_workspace_bytes(int64_t d, int64_t k) {
 int regtopk_bind_global(regtopk_ctx* c, void* mem_dev, size_t bytes, void* stream) {
   if (!c || !mem_dev) return fail(REGTOPK_INVALID_ARG, "ctx and mem_dev must not be NULL");
   if (c->gsel) return fail(REGTOPK_BAD_STATE, "the global Top-k round already has its memory");
+  DEVICE_TRY(c);
   if (reinterpret_cast<uintptr_t>(mem_dev) % kAlign) return fail(REGTOPK_INVALID_ARG, "mem_dev must be 256-byte aligned");
   const size_t need = regtopk_global_workspace_bytes(c->d, c->k);
   if (bytes < need) return fail(REGTOPK_NO_MEMORY, "memory has %zu bytes, %zu needed", bytes, need);
@@ -584,6 +597,7 @@ int regtopk_step_global(regtopk_ctx* c, const float* grads, void* stream, regtop
   if (!c || !grads || !out) return fail(REGTOPK_INVALID_ARG, "ctx, grads_dev and out must not be NULL");
   if (reinterpret_cast<uintptr_t>(grads) % 4) return fail(REGTOPK_INVALID_ARG, "grads_dev must be 4-byte aligned");
   if (!c->uniform_k) return fail(REGTOPK_BAD_STATE, "the global Top-k round shares one mask of k entries: per-worker k is set");
+  DEVICE_TRY(c);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (!c->gsel) {
     // first use.  A context that owns its arena allocates the selector's memory as well; one that
@@ -647,6 +661,7 @@ int regtopk_step_bf16(regtopk_ctx* c, const uint16_t* grads, const float* gprev,
 
 int regtopk_get_state(regtopk_ctx* c, float* e_dev, int32_t* pidx_dev, float* pval_dev, int64_t* t_host, void* stream) {
   if (!c) return fail(REGTOPK_INVALID_ARG, "ctx is NULL");
+  DEVICE_TRY(c);
   hipStream_t s = static_cast<hipStream_t>(stream);
   const size_t nd = (size_t)c->N * (size_t)c->d, nk = (size_t)c->N * (size_t)c->k;
   (void)nd;
@@ -665,6 +680,7 @@ int regtopk_set_state(regtopk_ctx* c, const float* e_dev, const int32_t* pidx_de
   if (!c || !e_dev) return fail(REGTOPK_INVALID_ARG, "ctx and e_dev must not be NULL");
   if (t < 0) return fail(REGTOPK_INVALID_ARG, "t must be >= 0");
   if (t > 0 && (!pidx_dev || !pval_dev)) return fail(REGTOPK_INVALID_ARG, "previous lists are required when t > 0");
+  DEVICE_TRY(c);
   hipStream_t s = static_cast<hipStream_t>(stream);
   const size_t nd = (size_t)c->N * (size_t)c->d, nk = (size_t)c->N * (size_t)c->k;
   k_copy_u32<<<2048, 256, 0, s>>>(c->at<uint32_t>(c->L.e), reinterpret_cast<const uint32_t*>(e_dev), nd);
@@ -697,6 +713,7 @@ int regtopk_set_state(regtopk_ctx* c, const float* e_dev, const int32_t* pidx_de
 
 int regtopk_get_stats(regtopk_ctx* c, regtopk_worker_stats* st, void* stream) {
   if (!c || !st) return fail(REGTOPK_INVALID_ARG, "ctx and stats_host must not be NULL");
+  DEVICE_TRY(c);
   hipStream_t s = static_cast<hipStream_t>(stream);
   std::vector<WorkerCtl> h((size_t)c->N);
   GlobalCtl hg;
@@ -726,6 +743,7 @@ int regtopk_get_stats(regtopk_ctx* c, regtopk_worker_stats* st, void* stream) {
 
 int regtopk_set_weights(regtopk_ctx* c, const float* w_host, void* stream) {
   if (!c || !w_host) return fail(REGTOPK_INVALID_ARG, "ctx and weights_host must not be NULL");
+  DEVICE_TRY(c);
   for (int32_t n = 0; n < c->N; ++n)
     if (!std::isfinite(w_host[n])) return fail(REGTOPK_INVALID_ARG, "weight %d is not finite", n);
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -736,6 +754,7 @@ int regtopk_set_weights(regtopk_ctx* c, const float* w_host, void* stream) {
 
 int regtopk_set_worker_k(regtopk_ctx* c, const int64_t* k_host, void* stream) {
   if (!c || !k_host) return fail(REGTOPK_INVALID_ARG, "ctx and k_host must not be NULL");
+  DEVICE_TRY(c);
   std::vector<uint32_t> v((size_t)c->N);
   bool uniform = true;
   for (int32_t n = 0; n < c->N; ++n) {
@@ -756,6 +775,7 @@ int regtopk_set_worker_k(regtopk_ctx* c, const int64_t* k_host, void* stream) {
 int regtopk_mask_overlap(regtopk_ctx* c, int64_t* counts_dev, void* stream) {
   if (!c || !counts_dev) return fail(REGTOPK_INVALID_ARG, "ctx and counts_dev must not be NULL");
   if (reinterpret_cast<uintptr_t>(counts_dev) % 8) return fail(REGTOPK_INVALID_ARG, "counts_dev must be 8-byte aligned");
+  DEVICE_TRY(c);
   hipStream_t s = static_cast<hipStream_t>(stream);
   int planes = 1;
   while ((1 << planes) <= c->N) ++planes;             // column sums reach N
