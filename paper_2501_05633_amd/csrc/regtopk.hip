@@ -489,7 +489,8 @@ int step_impl(regtopk_ctx* c, const G* grads, const float* gprev, void* stream, 
     uint32_t sample_blocks = (n_groups + 4 * kBlock - 1) / (4 * kBlock);
     if (sample_blocks > 64) sample_blocks = 64;
     if (pre) k_sample_hist_state<<<dim3(sample_blocks, N), kBlock, 0, s>>>(e, d, fhist, n_groups, line_stride, sk.roots);
-    else k_sample_hist<G><<<dim3(sample_blocks, N), kBlock, 0, s>>>(e, grads, mask, d, nc, fhist, n_groups, line_stride, sk.roots);
+    else if (sk.roots == 0) k_sample_hist<G, true><<<dim3(sample_blocks, N), kBlock, 0, s>>>(e, grads, mask, d, nc, fhist, n_groups, line_stride, 0);
+    else k_sample_hist<G, false><<<dim3(sample_blocks, N), kBlock, 0, s>>>(e, grads, mask, d, nc, fhist, n_groups, line_stride, sk.roots);
     k_sample_bound<<<N, kScanBlock, 0, s>>>(ctl, fhist, d, kn, (uint32_t)n_sampled, sk.roots);
   }
   if (c->fresh > 0) c->fresh -= 1;

@@ -443,19 +443,21 @@ constexpr uint32_t kSampleMax = 1u << 18;     // sampled entries per worker (who
 // The sample is made of whole 32-entry lines (128 bytes of the state, of the
 // gradients, and one mask word): memory hands out nothing smaller, and scattered
 // groups of four cost eight times the traffic for the same number of entries
-// (78 us against 23 us for the target workload's 16 x 2^18 entries).  Line l of
+// (78 us against 16 us for the target workload's 16 x 2^18 entries).  Line l of
 // the sample is line l * line_stride of the row; sample group i is the group
 // i % 8 of sample line i / 8.
 __device__ __forceinline__ int64_t sample_group_start(uint32_t i, uint32_t line_stride) {
   return (int64_t)(i >> 3) * line_stride * 32 + (int64_t)(i & 7u) * 4;
 }
 
-// grid (blocks, N).
-template <typename G>
+// grid (blocks, N).  PLAIN: the prior of Algorithm 2 (|a| itself) -- an instantiation without the
+// code of the other priors, whose registers would halve the resident waves.
+template <typename G, bool PLAIN>
 __global__ void __launch_bounds__(kBlock)
 k_sample_hist(const float* __restrict__ e, const G* __restrict__ g, const uint32_t* __restrict__ mask,
               int64_t d, uint32_t nc, uint32_t* __restrict__ shist, uint32_t n_groups, uint32_t line_stride,
-              int roots) {
+              int roots_in) {
+  const int roots = PLAIN ? 0 : roots_in;
   __shared__ uint32_t s_hist[kL1Bins];
   const uint32_t n = blockIdx.y, tid = threadIdx.x;
   for (uint32_t i = tid; i < kL1Bins; i += kBlock) s_hist[i] = 0;
