@@ -41,10 +41,11 @@ def test_full_size_rounds(name):
     print("window half widths (worker 0):", [h[0] for h in halves], flush=True)
 
 
-@pytest.mark.parametrize("what", ["mu=0.1", "mu=10", "bf16", "roots=1,clipped", "exponent=0.7,erf", "weights"])
+@pytest.mark.parametrize("what", ["mu=0.1", "mu=10", "bf16", "roots=1,clipped", "exponent=0.7,erf", "weights", "dense"])
 def test_full_size_variants_of_the_target_workload(what):
     # the other ways the target workload (N = 16, d = 25.6M, k = 256k) is run: the mu sweep of the
-    # benchmark list, bfloat16 gradients, a score variant, general weights -- two or three rounds each
+    # benchmark list, bfloat16 gradients, a score variant, general weights, the dense selection forced
+    # for all sixteen workers (every block of its kernel at work on all of the chip) -- two or three rounds each
     cfg = workloads.CONFIGS["large_cnn"]
     wl = workloads.Workload(cfg, DEV)
     print("case full size large_cnn %s" % what, flush=True)
@@ -63,6 +64,8 @@ def test_full_size_variants_of_the_target_workload(what):
         wl = workloads.Workload(cfg, DEV)
     elif what == "weights":
         kw["weights"] = np.random.default_rng(2).dirichlet(np.full(cfg.N, 4.0)).astype(np.float32)
+    elif what == "dense":
+        kw["force_dense"] = True
 
     def fn(t, agg):
         print("  round %d" % t, flush=True)
